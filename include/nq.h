@@ -1,0 +1,229 @@
+/*
+ * nq.h -- C ABI of the NestQuant nested-integer library for AMD MI355X (gfx950).
+ *
+ * The library implements the data-parallel hot path of "NestQuant: Post-Training
+ * Integer-Nesting Quantization for On-Device DNN" (arXiv 2506.17870):
+ *   - integer weight decomposition of INT-n weights into a higher-bit part
+ *     w_high (h bits) and a lower-bit part w_low (l bits), n = h + l
+ *     (Sec. 3.2.1, Eq. 4 and Eq. 5);
+ *   - packing of the two parts into two separately stored pages
+ *     (Sec. 3.3.4, "Packed-Bit Tensors", "Storing & Scheduling");
+ *   - switching: page the lower-bit page out (downgrade) or in (upgrade)
+ *     (Sec. 3.2.3, Sec. 3.3);
+ *   - inference in full-bit mode, weights recomposed on the fly as
+ *     w_high * 2^l + w_low and dequantised with the scale s (Eq. 2, Eq. 4), or in
+ *     part-bit mode, w_high alone with the scale s * 2^l (Eq. 8), as a GEMM or an
+ *     implicit-GEMM convolution with int8 activations (Sec. 4.2), int32
+ *     accumulation and a fused fp32 dequantisation epilogue.
+ *
+ * Conventions
+ *   - Every pointer whose name starts with d_ is DEVICE memory, h_ is HOST memory.
+ *     All memory is owned by the caller; the library allocates no device memory.
+ *   - Every call that takes a `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) only enqueues work on it and returns; results are ready when
+ *     that stream reaches the end of the enqueued work.
+ *   - Functions return NQ_OK or an error; on error nothing was enqueued.  Nothing
+ *     throws or aborts.  Arguments are checked on the host before any launch.
+ *   - Weights are W[N][K] row major, N = output channels, K = reduction length.
+ *     For a convolution K = KH*KW*Cin ordered (kh, kw, ci), i.e. the weight tensor
+ *     is [Cout][KH][KW][Cin]; activations are NHWC int8.
+ *   - Supported nestings: n_bits in {8, 6}, 1 <= l_bits <= n_bits - 2 (so h >= 2),
+ *     which covers the paper's INT(8|h), h in 3..7, and INT(6|h), h in 3..5
+ *     (Sec. 3.3.1).  INT-n weights arrive as int8 values inside [-2^(n-1), 2^(n-1)-1];
+ *     the range is the caller's promise and is not checked on the device.
+ *   - K must not exceed NQ_MAX_K, so that |acc| <= K * 2^14 fits an int32.
+ */
+#ifndef NQ_H
+#define NQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NQ_MAX_K 65536
+
+typedef enum {
+    NQ_OK = 0,
+    NQ_ERR_INVALID_ARG = 1,  /* NULL pointer, negative size, bad enum value           */
+    NQ_ERR_UNSUPPORTED = 2,  /* (n_bits, l_bits), format or layout outside the above   */
+    NQ_ERR_SHAPE = 3,        /* sizes inconsistent with each other or above the limits */
+    NQ_ERR_ALIGN = 4,        /* a packed page is not 16-byte aligned                   */
+    NQ_ERR_NOT_RESIDENT = 5, /* full-bit call while the lower-bit page is paged out    */
+    NQ_ERR_RANGE = 6,        /* a buffer is smaller than the layout needs              */
+    NQ_ERR_HIP = 7           /* the HIP runtime reported an error                      */
+} nq_status;
+
+/* How w_low is stored (Sec. 3.2.3 Eq. 9 and Sec. 3.3.3).
+ * NQ_LOW_UNSIGNED_L: the bit-wise split of Eq. 4: w_high = w_int >> l (arithmetic),
+ *   w_low = the low l bits of the two's-complement code, in [0, 2^l - 1]; recomposition
+ *   is exact for every INT-n value.
+ * NQ_LOW_SIGNED_L1: the paper's extra-1-bit compensation, signed (l+1) bits, needed when
+ *   w_high was rounded by something other than the shift. */
+typedef enum { NQ_LOW_UNSIGNED_L = 0, NQ_LOW_SIGNED_L1 = 1 } nq_low_format;
+
+/* Page layouts.
+ * NQ_LAYOUT_DENSE: exactly k bits per element on the shape padded to N%32 == 0,
+ *   K%64 == 0 (zero fields in the padding).  Tiles of 32 rows x 64 columns, row-block
+ *   major, each k*256 bytes.  Inside a tile, dword (i, slot) is at dword offset
+ *   i*64 + slot, i in [0,k), slot = 32*g + r with r the row in the tile and g the half
+ *   of the 64 columns.  The slot's 32 columns are c = 32*g + 4*j + b (j in [0,8) the
+ *   position, b in [0,4) the byte lane); byte b of dword (i, slot) is byte B_i of the
+ *   group (slot, b), which stores the fields F_0..F_7 of positions 0..7:
+ *     higher-bit page ("carrier"): with s = 8-k, bits [7..s] of B_i hold F_i for i < k;
+ *       the low s bits of B_0, B_1, ... in this order, least significant first, form a
+ *       string of k*s bits holding F_k, ..., F_7 one after the other, LSB first;
+ *     lower-bit page ("bit string"): B_0..B_{k-1} read as one little-endian string of
+ *       8k bits hold F_j in bits [j*k, (j+1)*k).
+ *   A field is the value modulo 2^k.
+ * NQ_LAYOUT_PAPER_U64: the paper's packed-bit tensor (Sec. 3.3.4): 64/k (integer
+ *   division) fields per unsigned 64-bit word, field j in bits [j*k, (j+1)*k), spare top
+ *   bits zero, each row starts a new word, the last word of a row zero padded.  This
+ *   layout can be packed and unpacked; the GEMM/convolution kernels read NQ_LAYOUT_DENSE. */
+typedef enum { NQ_LAYOUT_DENSE = 0, NQ_LAYOUT_PAPER_U64 = 1 } nq_layout;
+
+typedef struct {
+    int32_t n_bits;     /* n: 8 or 6                                  */
+    int32_t l_bits;     /* l: 1 .. n-2; h = n - l                     */
+    int32_t low_format; /* nq_low_format                              */
+    int32_t layout;     /* nq_layout                                  */
+} nq_cfg;
+
+/* One nested weight matrix: two pages plus the per-channel scale (Sec. 3.3.4: the model
+ * file keeps w_high and w_low under separate names).  A plain descriptor filled by the
+ * caller; the library owns none of the memory it points to, only `low_event`. */
+typedef struct {
+    nq_cfg cfg;
+    int64_t N, K;
+    const void *d_high;     /* device, packed higher-bit page, 16-byte aligned            */
+    uint64_t high_bytes;    /* >= nq_packed_bytes(N, K, h, layout)                        */
+    void *d_low;            /* device slot of the lower-bit page, 16-byte aligned; its    */
+                            /* contents count only while low_resident != 0                */
+    uint64_t low_bytes;     /* >= nq_packed_bytes(N, K, l, layout)                        */
+    const void *h_low;      /* host master copy of the lower-bit page ("storage");        */
+                            /* pinned memory makes nq_page_in_low asynchronous            */
+    const float *d_scale;   /* device, fp32[N], per-output-channel scale s                */
+    int32_t low_resident;   /* set by nq_page_in_low, cleared by nq_page_out_low; a       */
+                            /* caller that wrote d_low on the device may set it itself    */
+    int32_t low_event_armed;/* internal: low_event has been recorded                      */
+    void *low_event;        /* internal: hipEvent_t made by nq_weight_init                */
+} nq_weight;
+
+/* Fused epilogue of the GEMM / convolution (Eq. 2 and Eq. 8), fp32, in this order with
+ * one rounding per step and no fused multiply-add:
+ *   c = act_scale * scale[n];  part-bit only: c = c * 2^l  (exact)
+ *   y = (float)acc * c
+ *   y = y + bias[n]                              if d_bias
+ *   y = y + residual_scale * (float)residual[m][n]   if d_residual
+ *   y = max(y, 0)                                if relu
+ *   out_int8 == 0: Y[m][n] = y (fp32)
+ *   out_int8 != 0: Y[m][n] = (int8) clamp(round_half_even(y * inv_out_scale), -128, 127)
+ * d_acc_dump, if not NULL, also receives the raw int32 accumulators [M][N] (the sum over
+ * k of x * w_full in full-bit mode, of x * w_high in part-bit mode). */
+typedef struct {
+    float act_scale;
+    const float *d_bias;        /* device fp32[N] or NULL          */
+    const int8_t *d_residual;   /* device int8[M][N] or NULL       */
+    float residual_scale;
+    int32_t relu;
+    int32_t out_int8;
+    float inv_out_scale;
+    int32_t *d_acc_dump;        /* device int32[M][N] or NULL      */
+} nq_epilogue;
+
+/* NHWC convolution, groups = 1, dilation = 1, zero padding.
+ * Ho = (H + 2*pad - KH)/stride + 1, Wo likewise; the GEMM view has M = B*Ho*Wo rows. */
+typedef struct {
+    int64_t B, H, W, Cin, Cout;
+    int32_t KH, KW, stride, pad;
+} nq_conv_shape;
+
+/* ---- housekeeping ------------------------------------------------------------------ */
+int nq_version(void);
+const char *nq_status_string(int status);
+
+/* Bytes of one packed page of `field_bits`-bit fields for an N x K matrix in `layout`
+ * (DENSE: ceil(N/32)*32 * ceil(K/64)*64 * field_bits / 8; PAPER_U64: N * ceil(K/(64/k)) * 8).
+ * Returns 0 for invalid arguments (field_bits outside 1..8 for PAPER_U64, 1..7 for DENSE). */
+size_t nq_packed_bytes(int64_t N, int64_t K, int field_bits, int layout);
+
+/* ---- decomposition and packing ----------------------------------------------------- */
+/* Eq. 4 / Eq. 5 (BitShift): d_high[i] = d_w_int[i] >> l (arithmetic shift, i.e. floor),
+ * d_low[i] = d_w_int[i] - d_high[i] * 2^l in [0, 2^l - 1].  Elementwise over N*K int8.
+ * In, out: device int8[N*K], caller owned.  Only NQ_LOW_UNSIGNED_L. */
+nq_status nq_decompose(const int8_t *d_w_int, int64_t N, int64_t K, const nq_cfg *cfg,
+                       int8_t *d_high, int8_t *d_low, void *stream);
+
+/* Sec. 3.3.4: pack unpacked parts into pages of cfg->layout.  d_high holds values in the
+ * INT-h range, d_low values in [0, 2^l - 1], both int8[N][K].  Either input/output pair may
+ * be NULL to pack only the other page.  Pages: device, 16-byte aligned, at least
+ * nq_packed_bytes(...) bytes; every byte of that size is written (padding as zero). */
+nq_status nq_pack(const int8_t *d_high, const int8_t *d_low, int64_t N, int64_t K,
+                  const nq_cfg *cfg, void *d_packed_high, void *d_packed_low, void *stream);
+
+/* Alg. 1 step 2 (w_low = w_int - w_high * 2^l) and step 3 (pack and store) in one pass:
+ * reads each INT-n weight once, writes the two pages.  Same results as nq_decompose
+ * followed by nq_pack. */
+nq_status nq_decompose_pack(const int8_t *d_w_int, int64_t N, int64_t K, const nq_cfg *cfg,
+                            void *d_packed_high, void *d_packed_low, void *stream);
+
+/* Inverse of nq_pack: pages -> int8[N][K] parts (w_high sign-extended from h bits, w_low
+ * in [0, 2^l - 1]).  Either pair may be NULL. */
+nq_status nq_unpack(const void *d_packed_high, const void *d_packed_low, int64_t N, int64_t K,
+                    const nq_cfg *cfg, int8_t *d_high, int8_t *d_low, void *stream);
+
+/* ---- switching (Sec. 3.2.3, Sec. 3.3) ---------------------------------------------- */
+/* Checks the descriptor, creates the internal event, sets low_resident = 0. */
+nq_status nq_weight_init(nq_weight *w);
+/* Destroys the internal event.  The caller frees its own buffers. */
+nq_status nq_weight_destroy(nq_weight *w);
+
+/* Downgrade full-bit -> part-bit: the lower-bit page is paged out.  The host copy is the
+ * master, so nothing is moved: the page is marked non-resident, full-bit calls on `w`
+ * now fail with NQ_ERR_NOT_RESIDENT, and the owner may reuse or free d_low once the work
+ * already enqueued on `stream` has finished. */
+nq_status nq_page_out_low(nq_weight *w, void *stream);
+
+/* Upgrade part-bit -> full-bit: copies low_bytes from h_low to d_low on `copy_stream`
+ * (asynchronous with respect to the host when h_low is pinned, so it can overlap part-bit
+ * work running on another stream), records the internal event and marks the page
+ * resident.  Later full-bit calls make their stream wait for that event. */
+nq_status nq_page_in_low(nq_weight *w, void *copy_stream);
+
+/* ---- inference (Sec. 3.3, Eq. 2, Eq. 4, Eq. 8) -------------------------------------- */
+/* Y[M][N] = epilogue( sum_k X[m][k] * (w_high[n][k] * 2^l + w_low[n][k]) ).
+ * d_x: device int8[M][K], K = w->K, row major.  d_y: device fp32[M][N] or int8[M][N]
+ * (epi->out_int8).  Requires w->low_resident, else NQ_ERR_NOT_RESIDENT (never falls back
+ * to part-bit: the caller chooses the mode).  Only NQ_LAYOUT_DENSE pages. M == 0 is a no-op. */
+nq_status nq_gemm_full(const int8_t *d_x, int64_t M, const nq_weight *w, const nq_epilogue *epi,
+                       void *d_y, void *stream);
+
+/* Y[M][N] = epilogue( sum_k X[m][k] * w_high[n][k] ) with the scale s * 2^l (Eq. 8).
+ * Never reads w->d_low. */
+nq_status nq_gemm_part(const int8_t *d_x, int64_t M, const nq_weight *w, const nq_epilogue *epi,
+                       void *d_y, void *stream);
+
+/* The same two modes as an implicit-GEMM convolution: d_x is int8[B][H][W][Cin], the
+ * output is [B][Ho][Wo][Cout]; w->N == Cout and w->K == KH*KW*Cin; the epilogue's
+ * residual and accumulator dump are indexed like the output. */
+nq_status nq_conv_full(const int8_t *d_x, const nq_conv_shape *shape, const nq_weight *w,
+                       const nq_epilogue *epi, void *d_y, void *stream);
+nq_status nq_conv_part(const int8_t *d_x, const nq_conv_shape *shape, const nq_weight *w,
+                       const nq_epilogue *epi, void *d_y, void *stream);
+
+/* ---- glue of a residual CNN on int8 NHWC activations (the paper is silent on these;
+ * they only make a whole quantised network runnable between the nested convolutions) --- */
+/* Max pooling over the int8 codes; padding never wins.  Out: int8[B][Ho][Wo][C]. */
+nq_status nq_maxpool_i8(const int8_t *d_x, int64_t B, int64_t H, int64_t W, int64_t C, int ksize,
+                        int stride, int pad, int8_t *d_y, void *stream);
+/* Global average pooling: int32 sum over the H*W positions, y = (float)sum * (in_scale /
+ * (float)(H*W)), q = clamp(round_half_even(y * inv_out_scale), -128, 127).  Out: int8[B][C]. */
+nq_status nq_avgpool_i8(const int8_t *d_x, int64_t B, int64_t HW, int64_t C, float in_scale,
+                        float inv_out_scale, int8_t *d_y, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NQ_H */

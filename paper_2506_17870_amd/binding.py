@@ -1,0 +1,244 @@
+"""ctypes binding of libnq.so -- argument marshalling only.
+
+Every function has the name and the argument order of its C entry point in
+include/nq.h; tensors are PyTorch tensors used purely as owners of device (or pinned
+host) memory, streams are `torch.cuda.Stream` objects or raw handles.  No step of the
+path is computed here.  Importing this module fails if the library has not been built:
+there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnq.so")
+
+NQ_OK, NQ_ERR_INVALID_ARG, NQ_ERR_UNSUPPORTED, NQ_ERR_SHAPE, NQ_ERR_ALIGN, NQ_ERR_NOT_RESIDENT, \
+    NQ_ERR_RANGE, NQ_ERR_HIP = range(8)
+NQ_LOW_UNSIGNED_L, NQ_LOW_SIGNED_L1 = 0, 1
+NQ_LAYOUT_DENSE, NQ_LAYOUT_PAPER_U64 = 0, 1
+NQ_MAX_K = 65536
+
+EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_decompose", "nq_pack", "nq_decompose_pack",
+           "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
+           "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_maxpool_i8", "nq_avgpool_i8"]
+
+
+class nq_cfg(ctypes.Structure):
+    _fields_ = [("n_bits", ctypes.c_int32), ("l_bits", ctypes.c_int32), ("low_format", ctypes.c_int32),
+                ("layout", ctypes.c_int32)]
+
+
+class nq_weight(ctypes.Structure):
+    _fields_ = [("cfg", nq_cfg), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("d_high", ctypes.c_void_p), ("high_bytes", ctypes.c_uint64),
+                ("d_low", ctypes.c_void_p), ("low_bytes", ctypes.c_uint64),
+                ("h_low", ctypes.c_void_p), ("d_scale", ctypes.c_void_p),
+                ("low_resident", ctypes.c_int32), ("low_event_armed", ctypes.c_int32),
+                ("low_event", ctypes.c_void_p)]
+
+
+class nq_epilogue(ctypes.Structure):
+    _fields_ = [("act_scale", ctypes.c_float), ("d_bias", ctypes.c_void_p), ("d_residual", ctypes.c_void_p),
+                ("residual_scale", ctypes.c_float), ("relu", ctypes.c_int32), ("out_int8", ctypes.c_int32),
+                ("inv_out_scale", ctypes.c_float), ("d_acc_dump", ctypes.c_void_p)]
+
+
+class nq_conv_shape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int64), ("H", ctypes.c_int64), ("W", ctypes.c_int64), ("Cin", ctypes.c_int64),
+                ("Cout", ctypes.c_int64), ("KH", ctypes.c_int32), ("KW", ctypes.c_int32),
+                ("stride", ctypes.c_int32), ("pad", ctypes.c_int32)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2506_17870_amd.build` "
+                      "(there is no CPU or PyTorch fallback for the HIP path)")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _i64, _int, _f = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+_cfgp, _wp, _ep, _sp = ctypes.POINTER(nq_cfg), ctypes.POINTER(nq_weight), ctypes.POINTER(nq_epilogue), \
+    ctypes.POINTER(nq_conv_shape)
+_SIGS = {
+    "nq_version": (ctypes.c_int, []),
+    "nq_status_string": (ctypes.c_char_p, [_int]),
+    "nq_packed_bytes": (ctypes.c_size_t, [_i64, _i64, _int, _int]),
+    "nq_decompose": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
+    "nq_pack": (_int, [_vp, _vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
+    "nq_decompose_pack": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
+    "nq_unpack": (_int, [_vp, _vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
+    "nq_weight_init": (_int, [_wp]),
+    "nq_weight_destroy": (_int, [_wp]),
+    "nq_page_out_low": (_int, [_wp, _vp]),
+    "nq_page_in_low": (_int, [_wp, _vp]),
+    "nq_gemm_full": (_int, [_vp, _i64, _wp, _ep, _vp, _vp]),
+    "nq_gemm_part": (_int, [_vp, _i64, _wp, _ep, _vp, _vp]),
+    "nq_conv_full": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
+    "nq_conv_part": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
+    "nq_maxpool_i8": (_int, [_vp, _i64, _i64, _i64, _i64, _int, _int, _int, _vp, _vp]),
+    "nq_avgpool_i8": (_int, [_vp, _i64, _i64, _i64, _f, _f, _vp, _vp]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(_lib, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+
+
+class NQError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {_lib.nq_status_string(status).decode()} (status {status})")
+
+
+def _check(status: int, where: str):
+    if status != NQ_OK:
+        raise NQError(status, where)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    assert t.is_contiguous(), "tensors handed to libnq must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(s):
+    if s is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream
+
+
+def make_cfg(n_bits=8, l_bits=2, low_format=NQ_LOW_UNSIGNED_L, layout=NQ_LAYOUT_DENSE) -> nq_cfg:
+    return nq_cfg(n_bits, l_bits, low_format, layout)
+
+
+def nq_version() -> int:
+    return _lib.nq_version()
+
+
+def nq_status_string(status: int) -> str:
+    return _lib.nq_status_string(status).decode()
+
+
+def nq_packed_bytes(N, K, field_bits, layout=NQ_LAYOUT_DENSE) -> int:
+    return int(_lib.nq_packed_bytes(N, K, field_bits, layout))
+
+
+def nq_decompose(d_w_int, N, K, cfg, d_high, d_low, stream=None):
+    _check(_lib.nq_decompose(_ptr(d_w_int), N, K, ctypes.byref(cfg), _ptr(d_high), _ptr(d_low), _stream(stream)),
+           "nq_decompose")
+
+
+def nq_pack(d_high, d_low, N, K, cfg, d_packed_high, d_packed_low, stream=None):
+    _check(_lib.nq_pack(_ptr(d_high), _ptr(d_low), N, K, ctypes.byref(cfg), _ptr(d_packed_high),
+                        _ptr(d_packed_low), _stream(stream)), "nq_pack")
+
+
+def nq_decompose_pack(d_w_int, N, K, cfg, d_packed_high, d_packed_low, stream=None):
+    _check(_lib.nq_decompose_pack(_ptr(d_w_int), N, K, ctypes.byref(cfg), _ptr(d_packed_high),
+                                  _ptr(d_packed_low), _stream(stream)), "nq_decompose_pack")
+
+
+def nq_unpack(d_packed_high, d_packed_low, N, K, cfg, d_high, d_low, stream=None):
+    _check(_lib.nq_unpack(_ptr(d_packed_high), _ptr(d_packed_low), N, K, ctypes.byref(cfg), _ptr(d_high),
+                          _ptr(d_low), _stream(stream)), "nq_unpack")
+
+
+def nq_weight_init(w: nq_weight):
+    _check(_lib.nq_weight_init(ctypes.byref(w)), "nq_weight_init")
+
+
+def nq_weight_destroy(w: nq_weight):
+    _check(_lib.nq_weight_destroy(ctypes.byref(w)), "nq_weight_destroy")
+
+
+def nq_page_out_low(w: nq_weight, stream=None):
+    _check(_lib.nq_page_out_low(ctypes.byref(w), _stream(stream)), "nq_page_out_low")
+
+
+def nq_page_in_low(w: nq_weight, copy_stream=None):
+    _check(_lib.nq_page_in_low(ctypes.byref(w), _stream(copy_stream)), "nq_page_in_low")
+
+
+def make_epilogue(act_scale=1.0, d_bias=None, d_residual=None, residual_scale=0.0, relu=False, out_int8=False,
+                  inv_out_scale=1.0, d_acc_dump=None) -> nq_epilogue:
+    return nq_epilogue(act_scale, _ptr(d_bias), _ptr(d_residual), residual_scale, int(relu), int(out_int8),
+                       inv_out_scale, _ptr(d_acc_dump))
+
+
+def nq_gemm_full(d_x, M, w: nq_weight, epi: nq_epilogue, d_y, stream=None):
+    _check(_lib.nq_gemm_full(_ptr(d_x), M, ctypes.byref(w), ctypes.byref(epi), _ptr(d_y), _stream(stream)),
+           "nq_gemm_full")
+
+
+def nq_gemm_part(d_x, M, w: nq_weight, epi: nq_epilogue, d_y, stream=None):
+    _check(_lib.nq_gemm_part(_ptr(d_x), M, ctypes.byref(w), ctypes.byref(epi), _ptr(d_y), _stream(stream)),
+           "nq_gemm_part")
+
+
+def nq_conv_full(d_x, shape: nq_conv_shape, w: nq_weight, epi: nq_epilogue, d_y, stream=None):
+    _check(_lib.nq_conv_full(_ptr(d_x), ctypes.byref(shape), ctypes.byref(w), ctypes.byref(epi), _ptr(d_y),
+                             _stream(stream)), "nq_conv_full")
+
+
+def nq_conv_part(d_x, shape: nq_conv_shape, w: nq_weight, epi: nq_epilogue, d_y, stream=None):
+    _check(_lib.nq_conv_part(_ptr(d_x), ctypes.byref(shape), ctypes.byref(w), ctypes.byref(epi), _ptr(d_y),
+                             _stream(stream)), "nq_conv_part")
+
+
+def nq_maxpool_i8(d_x, B, H, W, C, ksize, stride, pad, d_y, stream=None):
+    _check(_lib.nq_maxpool_i8(_ptr(d_x), B, H, W, C, ksize, stride, pad, _ptr(d_y), _stream(stream)),
+           "nq_maxpool_i8")
+
+
+def nq_avgpool_i8(d_x, B, HW, C, in_scale, inv_out_scale, d_y, stream=None):
+    _check(_lib.nq_avgpool_i8(_ptr(d_x), B, HW, C, in_scale, inv_out_scale, _ptr(d_y), _stream(stream)),
+           "nq_avgpool_i8")
+
+
+class NestedWeight:
+    """Owner of the buffers one nq_weight descriptor points to (memory plumbing only).
+
+    Holds the packed higher-bit page and the device slot of the lower-bit page as torch
+    tensors, the pinned host master copy of the lower-bit page and the per-channel scales,
+    and fills the descriptor.  `from_int8` runs nq_decompose_pack on the device and copies
+    the lower-bit page once to the pinned host buffer (the "storage" it is paged in from).
+    """
+
+    def __init__(self, N, K, cfg: nq_cfg, device="cuda"):
+        h = cfg.n_bits - cfg.l_bits
+        self.cfg, self.N, self.K = cfg, N, K
+        self.high = torch.empty(max(nq_packed_bytes(N, K, h, cfg.layout), 16), dtype=torch.uint8, device=device)
+        self.low = torch.empty(max(nq_packed_bytes(N, K, cfg.l_bits, cfg.layout), 16), dtype=torch.uint8,
+                               device=device)
+        self.low_host = torch.empty(self.low.numel(), dtype=torch.uint8, pin_memory=True)
+        self.scale = torch.ones(max(N, 1), dtype=torch.float32, device=device)
+        self.desc = nq_weight(cfg, N, K, self.high.data_ptr(), self.high.numel(), self.low.data_ptr(),
+                              self.low.numel(), self.low_host.data_ptr(), self.scale.data_ptr(), 0, 0, None)
+        nq_weight_init(self.desc)
+
+    @classmethod
+    def from_int8(cls, d_w_int, d_scale, cfg: nq_cfg, stream=None):
+        N, K = d_w_int.shape
+        self = cls(N, K, cfg, device=d_w_int.device)
+        nq_decompose_pack(d_w_int, N, K, cfg, self.high, self.low, stream)
+        self.scale.copy_(d_scale)
+        self.low_host.copy_(self.low)          # device -> pinned host, the master copy
+        torch.cuda.synchronize()
+        self.desc.low_resident = 1             # the page was written on the device
+        return self
+
+    def close(self):
+        if self.desc.low_event:
+            nq_weight_destroy(self.desc)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,69 @@
+"""Builds libnq.so (hand-written HIP for gfx950) in-tree with hipcc.
+
+    python -m paper_2506_17870_amd.build [--force]
+
+Objects go to _build/ next to this file, the library to paper_2506_17870_amd/libnq.so.
+One translation unit per nesting (h, l) holds the GEMM/convolution kernels, so the
+units compile in parallel.
+"""
+from __future__ import annotations
+
+import concurrent.futures
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
+LIB = os.path.join(HERE, "libnq.so")
+
+# (h, l): INT(8|h) for l = 1..6 and INT(6|h) for l = 1..4
+NESTINGS = [(7, 1), (6, 2), (5, 3), (4, 4), (3, 5), (2, 6), (5, 1), (4, 2), (3, 3), (2, 4)]
+
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+
+
+def _units():
+    units = [(os.path.join(CSRC, f + ".hip"), os.path.join(OBJ, f + ".o"), [])
+             for f in ("nq_pack", "nq_page", "nq_glue", "nq_gemm")]
+    for h, l in NESTINGS:
+        units.append((os.path.join(CSRC, "nq_gemm_inst.hip"), os.path.join(OBJ, f"nq_gemm_inst_{h}{l}.o"),
+                      [f"-DNQ_INST_H={h}", f"-DNQ_INST_L={l}"]))
+    return units
+
+
+def _newest_source():
+    paths = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
+    paths.append(os.path.join(os.path.dirname(HERE), "include", "nq.h"))
+    return max(os.path.getmtime(p) for p in paths)
+
+
+def _compile(unit):
+    src, obj, defs = unit
+    cmd = ["hipcc", *FLAGS, *defs, "-c", src, "-o", obj]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed for {os.path.basename(obj)}:\n{r.stderr[-4000:]}")
+    return obj
+
+
+def build(force: bool = False, jobs: int | None = None) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    newest = _newest_source()
+    units = _units()
+    todo = [u for u in units if force or not os.path.exists(u[1]) or os.path.getmtime(u[1]) < newest]
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
+        list(pool.map(_compile, todo))
+    if todo or not os.path.exists(LIB):
+        cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *[u[1] for u in units]]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("link failed:\n" + r.stderr[-4000:])
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force="--force" in sys.argv))

@@ -1,0 +1,349 @@
+// Integer weight decomposition and packing kernels (paper Sec. 3.2.1 Eq. 4-5, Alg. 1
+// steps 2-3, Sec. 3.3.4).  All kernels are elementwise streams bound by HBM bandwidth:
+// one byte read and (h + l)/8 bytes written per weight for the fused decompose-and-pack.
+#include "nq_codec.h"
+#include "nq_common.h"
+
+namespace nq {
+
+// ---------------------------------------------------------------------------------------
+// Eq. 5 (BitShift) and Alg. 1 step 2, unpacked: high = w >> l, low = w - high * 2^l.
+// 16 weights per thread, four per dword.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t sar_bytes(uint32_t x, int l)
+{
+    // arithmetic right shift of four int8 lanes: logical shift, then sign fill
+    const uint32_t keep = rep4(0xFFu >> l);
+    const uint32_t sign = x & 0x80808080u;
+    const uint32_t fill = (sign >> 7) * (0xFFu & ~(0xFFu >> l));
+    return ((x >> l) & keep) | fill;
+}
+
+__global__ void __launch_bounds__(256) k_decompose(const int8_t *__restrict__ w, int64_t count, int n_bits,
+                                                    int l, int8_t *__restrict__ high,
+                                                    int8_t *__restrict__ low, int vec_ok)
+{
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t base = tid * 16;
+    if (base >= count) return;
+    const uint32_t lowmask = rep4((1u << l) - 1u);
+    const int up = 8 - n_bits;  // an INT6 value is first moved to the top of its byte
+    if (vec_ok && base + 16 <= count) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(w + base);
+        uint32_t x[4] = {v.x, v.y, v.z, v.w}, hi[4], lo[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t top = (x[i] << up) & rep4(0xFFu << up);
+            hi[i] = sar_bytes(top, l + up);
+            lo[i] = x[i] & lowmask;
+        }
+        *reinterpret_cast<uint4 *>(high + base) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        *reinterpret_cast<uint4 *>(low + base) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    } else {
+        for (int64_t i = base; i < count && i < base + 16; ++i) {
+            const int v = (int8_t)((uint8_t)w[i] << up);
+            high[i] = (int8_t)(v >> (l + up));
+            low[i] = (int8_t)(w[i] & ((1 << l) - 1));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Dense-tile pack.  One wave per tile of 32 rows x 64 columns, one lane per slot: the lane
+// reads the 32 consecutive weights of its slot and writes H dwords of the higher-bit page
+// and L dwords of the lower-bit page; a wave's stores are 256 contiguous bytes each.
+// SRC 0: from w_int (fused decomposition); SRC 1: from separate high / low tensors.
+// ---------------------------------------------------------------------------------------
+template <int H, int L, int SRC>
+__global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a, const int8_t *__restrict__ b,
+                                                     int64_t N, int64_t K, int64_t KB, int64_t tiles,
+                                                     uint32_t *__restrict__ ph, uint32_t *__restrict__ pl,
+                                                     int vec_ok)
+{
+    constexpr int S = 8 - H;        // spare bits of a carrier byte
+    constexpr int UP = 8 - H - L;   // 0 for INT8 nesting, 2 for INT6 nesting
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= tiles) return;
+    const int64_t nb = tile / KB, kb = tile % KB;
+    const int r = lane & 31, g = lane >> 5;
+    const int64_t n = nb * 32 + r;
+    const int64_t c0 = kb * 64 + 32 * g;
+
+    uint32_t X[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) X[j] = 0;
+    if (n < N) {
+        uint32_t A[8], B[8];
+        if (vec_ok && c0 + 32 <= K) {
+            const uint4 *pa = a ? reinterpret_cast<const uint4 *>(a + n * K + c0) : nullptr;
+            const uint4 *pb = (SRC == 1 && b) ? reinterpret_cast<const uint4 *>(b + n * K + c0) : nullptr;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                uint4 va = pa ? pa[q] : make_uint4(0, 0, 0, 0);
+                A[4 * q + 0] = va.x; A[4 * q + 1] = va.y; A[4 * q + 2] = va.z; A[4 * q + 3] = va.w;
+                uint4 vb = pb ? pb[q] : make_uint4(0, 0, 0, 0);
+                B[4 * q + 0] = vb.x; B[4 * q + 1] = vb.y; B[4 * q + 2] = vb.z; B[4 * q + 3] = vb.w;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                uint32_t wa = 0, wb = 0;
+                for (int bb = 0; bb < 4; ++bb) {
+                    const int64_t c = c0 + 4 * j + bb;
+                    if (c < K) {
+                        if (a) wa |= (uint32_t)(uint8_t)a[n * K + c] << (8 * bb);
+                        if (SRC == 1 && b) wb |= (uint32_t)(uint8_t)b[n * K + c] << (8 * bb);
+                    }
+                }
+                A[j] = wa; B[j] = wb;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (SRC == 0) {
+                X[j] = (A[j] << UP) & rep4(0xFFu << UP);
+            } else {
+                X[j] = ((A[j] << S) & HighCodec<H>::HM) | ((B[j] << (S - L)) & LowCodec<L, S>::LM);
+            }
+        }
+    }
+    if (ph) {
+        uint32_t P[H];
+        HighCodec<H>::encode(X, P);
+        uint32_t *dst = ph + tile * (H * 64) + lane;
+#pragma unroll
+        for (int i = 0; i < H; ++i) dst[i * 64] = P[i];
+    }
+    if (pl) {
+        uint32_t Q[L];
+        LowCodec<L, S>::encode(X, Q);
+        uint32_t *dst = pl + tile * (L * 64) + lane;
+#pragma unroll
+        for (int i = 0; i < L; ++i) dst[i * 64] = Q[i];
+    }
+}
+
+// Dense-tile unpack: pages -> int8 parts.
+template <int H, int L>
+__global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict__ ph,
+                                                       const uint32_t *__restrict__ pl, int64_t N, int64_t K,
+                                                       int64_t KB, int64_t tiles, int8_t *__restrict__ high,
+                                                       int8_t *__restrict__ low)
+{
+    constexpr int S = 8 - H;
+    const int lane = threadIdx.x & 63;
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= tiles) return;
+    const int64_t nb = tile / KB, kb = tile % KB;
+    const int r = lane & 31, g = lane >> 5;
+    const int64_t n = nb * 32 + r;
+    const int64_t c0 = kb * 64 + 32 * g;
+    if (n >= N) return;
+    if (ph && high) {
+        uint32_t P[H], D[8];
+#pragma unroll
+        for (int i = 0; i < H; ++i) P[i] = ph[tile * (H * 64) + i * 64 + lane];
+        HighCodec<H>::decode(P, D);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            for (int bb = 0; bb < 4; ++bb) {
+                const int64_t c = c0 + 4 * j + bb;
+                if (c < K) high[n * K + c] = (int8_t)((int8_t)(D[j] >> (8 * bb)) >> S);
+            }
+    }
+    if (pl && low) {
+        uint32_t Q[L], D[8];
+#pragma unroll
+        for (int i = 0; i < L; ++i) Q[i] = pl[tile * (L * 64) + i * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) D[j] = 0;
+        LowCodec<L, S>::decode_or(Q, D);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            for (int bb = 0; bb < 4; ++bb) {
+                const int64_t c = c0 + 4 * j + bb;
+                if (c < K) low[n * K + c] = (int8_t)(((D[j] >> (8 * bb)) & 0xFFu) >> (S - L));
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// The paper's packed-bit tensor (Sec. 3.3.4): 64/k fields per unsigned 64-bit word.
+// One thread per word.  part 0: fields are (w >> l) from w_int; 1: the low l bits of w_int;
+// 2: the given values as they are.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_pack_paper(const int8_t *__restrict__ v, int64_t N, int64_t K, int k,
+                                                     int part, int l, int up, int64_t wpr,
+                                                     uint64_t *__restrict__ out)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= N * wpr) return;
+    const int64_t n = idx / wpr, wd = idx % wpr;
+    const int per = 64 / k;
+    const uint64_t mask = (1ull << k) - 1ull;
+    uint64_t word = 0;
+    for (int j = 0; j < per; ++j) {
+        const int64_t c = wd * per + j;
+        if (c >= K) break;
+        int val = v[n * K + c];
+        if (part == 0) val = ((int8_t)((uint8_t)val << up)) >> (l + up);
+        else if (part == 1) val = val & ((1 << l) - 1);
+        word |= ((uint64_t)(int64_t)val & mask) << (j * k);
+    }
+    out[idx] = word;
+}
+
+__global__ void __launch_bounds__(256) k_unpack_paper(const uint64_t *__restrict__ in, int64_t N, int64_t K,
+                                                       int k, int is_signed, int64_t wpr,
+                                                       int8_t *__restrict__ v)
+{
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= N * K) return;
+    const int64_t n = idx / K, c = idx % K;
+    const int per = 64 / k;
+    const uint64_t word = in[n * wpr + c / per];
+    int field = (int)((word >> ((c % per) * k)) & ((1ull << k) - 1ull));
+    if (is_signed && (field >> (k - 1))) field -= (1 << k);
+    v[idx] = (int8_t)field;
+}
+
+template <int H, int L>
+static void launch_pack_dense(int src, const int8_t *a, const int8_t *b, int64_t N, int64_t K, void *ph,
+                              void *pl, hipStream_t st)
+{
+    const int64_t NB = ceil_div(N, 32), KB = ceil_div(K, 64), tiles = NB * KB;
+    if (tiles == 0) return;
+    const int vec_ok = (K % 16 == 0) && aligned16(a) && (b == nullptr || aligned16(b));
+    const dim3 grid((unsigned)ceil_div(tiles, 4)), block(256);
+    if (src == 0)
+        hipLaunchKernelGGL((k_pack_dense<H, L, 0>), grid, block, 0, st, a, b, N, K, KB, tiles,
+                           (uint32_t *)ph, (uint32_t *)pl, vec_ok);
+    else
+        hipLaunchKernelGGL((k_pack_dense<H, L, 1>), grid, block, 0, st, a, b, N, K, KB, tiles,
+                           (uint32_t *)ph, (uint32_t *)pl, vec_ok);
+}
+
+template <int H, int L>
+static void launch_unpack_dense(const void *ph, const void *pl, int64_t N, int64_t K, int8_t *high,
+                                int8_t *low, hipStream_t st)
+{
+    const int64_t NB = ceil_div(N, 32), KB = ceil_div(K, 64), tiles = NB * KB;
+    if (tiles == 0) return;
+    hipLaunchKernelGGL((k_unpack_dense<H, L>), dim3((unsigned)ceil_div(tiles, 4)), dim3(256), 0, st,
+                       (const uint32_t *)ph, (const uint32_t *)pl, N, K, KB, tiles, high, low);
+}
+
+static nq_status check_pages(const nq_cfg *cfg, const void *ph, const void *pl)
+{
+    if ((ph && !aligned16(ph)) || (pl && !aligned16(pl))) return NQ_ERR_ALIGN;
+    (void)cfg;
+    return NQ_OK;
+}
+
+}  // namespace nq
+
+using namespace nq;
+
+extern "C" size_t nq_packed_bytes(int64_t N, int64_t K, int field_bits, int layout)
+{
+    if (N < 0 || K < 0) return 0;
+    if (layout == NQ_LAYOUT_DENSE) {
+        if (field_bits < 1 || field_bits > 7) return 0;
+        return (size_t)(round_up(N, 32) * round_up(K, 64) * field_bits / 8);
+    }
+    if (layout == NQ_LAYOUT_PAPER_U64) {
+        if (field_bits < 1 || field_bits > 8) return 0;
+        return (size_t)(N * ceil_div(K, 64 / field_bits) * 8);
+    }
+    return 0;
+}
+
+extern "C" nq_status nq_decompose(const int8_t *d_w_int, int64_t N, int64_t K, const nq_cfg *cfg,
+                                  int8_t *d_high, int8_t *d_low, void *stream)
+{
+    nq_status st = check_cfg(cfg);
+    if (st != NQ_OK) return st;
+    if ((st = check_shape(N, K)) != NQ_OK) return st;
+    const int64_t count = N * K;
+    if (count == 0) return NQ_OK;
+    if (!d_w_int || !d_high || !d_low) return NQ_ERR_INVALID_ARG;
+    const int vec_ok = aligned16(d_w_int) && aligned16(d_high) && aligned16(d_low);
+    const int64_t threads = ceil_div(count, 16);
+    hipLaunchKernelGGL(k_decompose, dim3((unsigned)ceil_div(threads, 256)), dim3(256), 0, (hipStream_t)stream,
+                       d_w_int, count, cfg->n_bits, cfg->l_bits, d_high, d_low, vec_ok);
+    return launch_status();
+}
+
+static nq_status pack_any(int src, const int8_t *a, const int8_t *b, int64_t N, int64_t K, const nq_cfg *cfg,
+                          void *ph, void *pl, void *stream)
+{
+    nq_status st = check_cfg(cfg);
+    if (st != NQ_OK) return st;
+    if ((st = check_shape(N, K)) != NQ_OK) return st;
+    if ((st = check_pages(cfg, ph, pl)) != NQ_OK) return st;
+    if (N * K == 0) return NQ_OK;
+    const int h = cfg->n_bits - cfg->l_bits, l = cfg->l_bits;
+    hipStream_t s = (hipStream_t)stream;
+    if (cfg->layout == NQ_LAYOUT_DENSE) {
+        NQ_DISPATCH_HL(h, l, launch_pack_dense, src, a, b, N, K, ph, pl, s);
+    } else {
+        const int up = 8 - cfg->n_bits;
+        if (ph) {
+            const int64_t wpr = ceil_div(K, 64 / h);
+            hipLaunchKernelGGL(k_pack_paper, dim3((unsigned)ceil_div(N * wpr, 256)), dim3(256), 0, s, a, N, K, h,
+                               src == 0 ? 0 : 2, l, up, wpr, (uint64_t *)ph);
+        }
+        if (pl) {
+            const int64_t wpr = ceil_div(K, 64 / l);
+            hipLaunchKernelGGL(k_pack_paper, dim3((unsigned)ceil_div(N * wpr, 256)), dim3(256), 0, s,
+                               src == 0 ? a : b, N, K, l, src == 0 ? 1 : 2, l, up, wpr, (uint64_t *)pl);
+        }
+    }
+    return launch_status();
+}
+
+extern "C" nq_status nq_pack(const int8_t *d_high, const int8_t *d_low, int64_t N, int64_t K, const nq_cfg *cfg,
+                             void *d_packed_high, void *d_packed_low, void *stream)
+{
+    // a page is packed only when both its input and its output are given
+    if ((d_high == nullptr) != (d_packed_high == nullptr)) return NQ_ERR_INVALID_ARG;
+    if ((d_low == nullptr) != (d_packed_low == nullptr)) return NQ_ERR_INVALID_ARG;
+    if (!d_high && !d_low) return NQ_ERR_INVALID_ARG;
+    return pack_any(1, d_high, d_low, N, K, cfg, d_packed_high, d_packed_low, stream);
+}
+
+extern "C" nq_status nq_decompose_pack(const int8_t *d_w_int, int64_t N, int64_t K, const nq_cfg *cfg,
+                                       void *d_packed_high, void *d_packed_low, void *stream)
+{
+    if (!d_w_int && N * K != 0) return NQ_ERR_INVALID_ARG;
+    if (!d_packed_high && !d_packed_low) return NQ_ERR_INVALID_ARG;
+    return pack_any(0, d_w_int, nullptr, N, K, cfg, d_packed_high, d_packed_low, stream);
+}
+
+extern "C" nq_status nq_unpack(const void *d_packed_high, const void *d_packed_low, int64_t N, int64_t K,
+                               const nq_cfg *cfg, int8_t *d_high, int8_t *d_low, void *stream)
+{
+    nq_status st = check_cfg(cfg);
+    if (st != NQ_OK) return st;
+    if ((st = check_shape(N, K)) != NQ_OK) return st;
+    if ((d_high == nullptr) != (d_packed_high == nullptr)) return NQ_ERR_INVALID_ARG;
+    if ((d_low == nullptr) != (d_packed_low == nullptr)) return NQ_ERR_INVALID_ARG;
+    if (!d_high && !d_low) return NQ_ERR_INVALID_ARG;
+    if ((st = check_pages(cfg, d_packed_high, d_packed_low)) != NQ_OK) return st;
+    if (N * K == 0) return NQ_OK;
+    const int h = cfg->n_bits - cfg->l_bits, l = cfg->l_bits;
+    hipStream_t s = (hipStream_t)stream;
+    if (cfg->layout == NQ_LAYOUT_DENSE) {
+        NQ_DISPATCH_HL(h, l, launch_unpack_dense, d_packed_high, d_packed_low, N, K, d_high, d_low, s);
+    } else {
+        const dim3 grid((unsigned)ceil_div(N * K, 256)), block(256);
+        if (d_high)
+            hipLaunchKernelGGL(k_unpack_paper, grid, block, 0, s, (const uint64_t *)d_packed_high, N, K, h, 1,
+                               ceil_div(K, 64 / h), d_high);
+        if (d_low)
+            hipLaunchKernelGGL(k_unpack_paper, grid, block, 0, s, (const uint64_t *)d_packed_low, N, K, l, 0,
+                               ceil_div(K, 64 / l), d_low);
+    }
+    return launch_status();
+}

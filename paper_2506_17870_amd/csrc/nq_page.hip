@@ -1,0 +1,95 @@
+// Switching between the full-bit and the part-bit model (paper Sec. 3.2.3 and Sec. 3.3):
+// downgrading pages the lower-bit weights out, upgrading pages them in from storage.  On
+// a GPU with a host master copy the page-out moves nothing; the page-in is one
+// host-to-device copy that can overlap part-bit inference on another stream.
+#include "nq_common.h"
+
+using namespace nq;
+
+extern "C" int nq_version(void) { return 1; }
+
+extern "C" const char *nq_status_string(int status)
+{
+    switch (status) {
+    case NQ_OK: return "ok";
+    case NQ_ERR_INVALID_ARG: return "invalid argument";
+    case NQ_ERR_UNSUPPORTED: return "unsupported nesting, format or layout";
+    case NQ_ERR_SHAPE: return "inconsistent or too large shape";
+    case NQ_ERR_ALIGN: return "page not 16-byte aligned";
+    case NQ_ERR_NOT_RESIDENT: return "lower-bit page is paged out";
+    case NQ_ERR_RANGE: return "buffer too small";
+    case NQ_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+extern "C" nq_status nq_weight_init(nq_weight *w)
+{
+    if (!w) return NQ_ERR_INVALID_ARG;
+    nq_status st = check_cfg(&w->cfg);
+    if (st != NQ_OK) return st;
+    if ((st = check_shape(w->N, w->K)) != NQ_OK) return st;
+    const int h = w->cfg.n_bits - w->cfg.l_bits, l = w->cfg.l_bits;
+    if (w->high_bytes < nq_packed_bytes(w->N, w->K, h, w->cfg.layout)) return NQ_ERR_RANGE;
+    if (w->low_bytes < nq_packed_bytes(w->N, w->K, l, w->cfg.layout)) return NQ_ERR_RANGE;
+    if ((w->d_high && !aligned16(w->d_high)) || (w->d_low && !aligned16(w->d_low))) return NQ_ERR_ALIGN;
+    hipEvent_t ev = nullptr;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) {
+        (void)hipGetLastError();
+        return NQ_ERR_HIP;
+    }
+    w->low_event = ev;
+    w->low_event_armed = 0;
+    w->low_resident = 0;
+    return NQ_OK;
+}
+
+extern "C" nq_status nq_weight_destroy(nq_weight *w)
+{
+    if (!w) return NQ_ERR_INVALID_ARG;
+    if (w->low_event) {
+        if (hipEventDestroy((hipEvent_t)w->low_event) != hipSuccess) {
+            (void)hipGetLastError();
+            return NQ_ERR_HIP;
+        }
+    }
+    w->low_event = nullptr;
+    w->low_event_armed = 0;
+    w->low_resident = 0;
+    return NQ_OK;
+}
+
+extern "C" nq_status nq_page_out_low(nq_weight *w, void *stream)
+{
+    (void)stream;  // nothing is enqueued: the host copy is the master
+    if (!w) return NQ_ERR_INVALID_ARG;
+    w->low_resident = 0;
+    w->low_event_armed = 0;
+    return NQ_OK;
+}
+
+extern "C" nq_status nq_page_in_low(nq_weight *w, void *copy_stream)
+{
+    if (!w) return NQ_ERR_INVALID_ARG;
+    nq_status st = check_cfg(&w->cfg);
+    if (st != NQ_OK) return st;
+    if (!w->low_event) return NQ_ERR_INVALID_ARG;  // nq_weight_init was not called
+    const size_t need = nq_packed_bytes(w->N, w->K, w->cfg.l_bits, w->cfg.layout);
+    if (w->low_bytes < need) return NQ_ERR_RANGE;
+    hipStream_t s = (hipStream_t)copy_stream;
+    if (need > 0) {
+        if (!w->d_low || !w->h_low) return NQ_ERR_INVALID_ARG;
+        if (!aligned16(w->d_low)) return NQ_ERR_ALIGN;
+        if (hipMemcpyAsync(w->d_low, w->h_low, need, hipMemcpyHostToDevice, s) != hipSuccess) {
+            (void)hipGetLastError();
+            return NQ_ERR_HIP;
+        }
+    }
+    if (hipEventRecord((hipEvent_t)w->low_event, s) != hipSuccess) {
+        (void)hipGetLastError();
+        return NQ_ERR_HIP;
+    }
+    w->low_event_armed = 1;
+    w->low_resident = 1;
+    return NQ_OK;
+}

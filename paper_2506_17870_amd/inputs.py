@@ -1,0 +1,69 @@
+"""Seeded synthetic inputs with the shapes and value distributions of the paper's
+workloads (ImageNet CNN layers and ViT MLPs, Sec. 4.1): NumPy only, no method arithmetic.
+
+The hot path starts from per-channel INT-n weights and int8 activations, so these
+generators hand out integers: Gaussian draws rounded to the nearest code on a per-channel
+(weights) or per-tensor (activations) grid.  Decomposition, packing, GEMM and dequantisation
+are not done here.  Both the HIP tests/benchmark and the CPU oracle's tests are fed from
+this one module so that they see identical bytes.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def int_grid(values: np.ndarray, n_bits: int, axis=None):
+    """Round `values` to signed n-bit codes on an absmax grid; returns (codes int8, step fp32)."""
+    v = np.asarray(values, np.float32)
+    qmax = np.float32((1 << (n_bits - 1)) - 1)
+    amax = np.max(np.abs(v), axis=axis, keepdims=axis is not None).astype(np.float32)
+    step = np.where(amax > 0, amax / qmax, np.float32(1.0)).astype(np.float32)
+    codes = np.clip(np.rint(v / step), -(1 << (n_bits - 1)), (1 << (n_bits - 1)) - 1).astype(np.int8)
+    return codes, (step.reshape(-1) if axis is not None else np.float32(step))
+
+
+def weights(N: int, K: int, sigma: float, n_bits: int = 8, seed: int = 0):
+    """INT-n codes [N,K] of N(0, sigma) weights and their per-output-channel steps fp32[N]."""
+    rng = np.random.default_rng(seed)
+    w = rng.normal(0.0, sigma, size=(N, K)).astype(np.float32)
+    return int_grid(w, n_bits, axis=1)
+
+
+def he_sigma(fan_in: int) -> float:
+    return float(np.sqrt(2.0 / fan_in))
+
+
+def uniform_activations(shape, seed: int = 0) -> np.ndarray:
+    """int8 codes uniform over [-128, 127]."""
+    rng = np.random.default_rng(seed + 1000003)
+    return rng.integers(-128, 128, size=shape, dtype=np.int64).astype(np.int8)
+
+
+def relu_activations(shape, seed: int = 0):
+    """int8 codes of ReLU-clipped N(0,1) data on a per-tensor absmax grid; returns (codes, step)."""
+    rng = np.random.default_rng(seed + 2000003)
+    a = np.maximum(rng.normal(0.0, 1.0, size=shape), 0.0).astype(np.float32)
+    return int_grid(a, 8)
+
+
+def gaussian_activations(shape, seed: int = 0):
+    """int8 codes of N(0,1) data on a per-tensor absmax grid; returns (codes, step)."""
+    rng = np.random.default_rng(seed + 3000003)
+    return int_grid(rng.normal(0.0, 1.0, size=shape).astype(np.float32), 8)
+
+
+def small_floats(n: int, scale: float, seed: int = 0) -> np.ndarray:
+    rng = np.random.default_rng(seed + 4000003)
+    return rng.normal(0.0, scale, size=n).astype(np.float32)
+
+
+# The benchmark configurations (shapes of ResNet / ViT layers; values as above).
+LINEAR_SMALL = dict(M=64, K=512, N=512, sigma=0.02, n_bits=8, l_bits=2)
+CONV_RESNET18 = dict(B=32, H=56, W=56, Cin=64, Cout=64, KH=3, KW=3, stride=1, pad=1, n_bits=8, l_bits=2)
+BOTTLENECK_RESNET101 = [
+    dict(B=64, H=14, W=14, Cin=1024, Cout=256, KH=1, KW=1, stride=1, pad=0),
+    dict(B=64, H=14, W=14, Cin=256, Cout=256, KH=3, KW=3, stride=1, pad=1),
+    dict(B=64, H=14, W=14, Cin=256, Cout=1024, KH=1, KW=1, stride=1, pad=0),
+]
+VIT_MLP = [dict(M=12608, K=768, N=3072, sigma=0.02, n_bits=8, l_bits=3),
+           dict(M=12608, K=3072, N=768, sigma=0.02, n_bits=8, l_bits=3)]

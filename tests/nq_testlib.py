@@ -1,0 +1,88 @@
+"""Shared plumbing of the GPU parity tests: run the same seeded inputs through the HIP path
+(via the C ABI binding) and through the CPU oracle.  No arithmetic of the method lives here."""
+import numpy as np
+import torch
+
+from oracle import nq_oracle as oracle
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+class Case:
+    """One nested layer: int8 weights [N,K] + scales, prepared on both sides."""
+
+    def __init__(self, nq, w_int, scale, n_bits, l_bits):
+        self.nq, self.n, self.l = nq, n_bits, l_bits
+        self.w_int, self.scale = w_int, scale
+        self.N, self.K = w_int.shape
+        self.cfg = nq.make_cfg(n_bits, l_bits)
+        self.W = nq.NestedWeight.from_int8(dev(w_int), dev(scale), self.cfg)
+        # oracle side, from its own pages
+        self.o_high, self.o_low = oracle.decompose_pack(w_int, n_bits, l_bits)
+        self.ow_full = oracle.weights_from_pages(self.o_high, self.o_low, self.N, self.K, n_bits, l_bits)
+        self.ow_part = oracle.weights_from_pages(self.o_high, None, self.N, self.K, n_bits, l_bits)
+
+    def pages_match(self):
+        return (np.array_equal(host(self.W.high)[:self.o_high.size], self.o_high) and
+                np.array_equal(host(self.W.low)[:self.o_low.size], self.o_low))
+
+
+def epi_pair(nq, case, full, M_shape, s_a=1.0, bias=None, residual=None, s_r=0.0, relu=False, out_int8=False,
+             inv_s_out=1.0):
+    """Builds the device epilogue descriptor + holders, and the oracle kwargs."""
+    N = case.N
+    keep = {}
+    keep["acc"] = torch.empty(tuple(M_shape) + (N,), dtype=torch.int32, device="cuda")
+    keep["bias"] = dev(bias) if bias is not None else None
+    keep["res"] = dev(residual) if residual is not None else None
+    epi = nq.make_epilogue(s_a, keep["bias"], keep["res"], s_r, relu, out_int8, inv_s_out, keep["acc"])
+    okw = dict(s_a=s_a, s_w=case.scale, part_l_bits=0 if full else case.l, bias=bias, residual=residual,
+               s_r=s_r, relu=relu, out_int8=out_int8, inv_s_out=inv_s_out)
+    return epi, keep, okw
+
+
+def check_outputs(y_gpu, acc_gpu, y_ref, acc_ref, out_int8):
+    assert np.array_equal(acc_gpu, acc_ref), "int32 accumulators differ"
+    if out_int8:
+        assert np.array_equal(y_gpu, y_ref), "requantised int8 outputs differ"
+    else:
+        # tolerance of the fp32 outputs: 1e-5 relative (they are in fact expected to be identical)
+        denom = np.maximum(np.abs(y_ref), 1e-30)
+        assert np.all(np.abs(y_gpu - y_ref) <= 1e-5 * denom), "fp32 outputs differ by more than 1e-5 relative"
+        assert np.array_equal(y_gpu, y_ref), "fp32 outputs are within tolerance but not identical"
+
+
+def run_gemm_both(nq, case, x, full, **epi_kw):
+    M = x.shape[0]
+    epi, keep, okw = epi_pair(nq, case, full, (M,), **epi_kw)
+    out_int8 = epi_kw.get("out_int8", False)
+    y = torch.empty((M, case.N), dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+    fn = nq.nq_gemm_full if full else nq.nq_gemm_part
+    fn(dev(x), M, case.W.desc, epi, y)
+    torch.cuda.synchronize()
+    acc_ref = oracle.gemm_acc(x, case.ow_full if full else case.ow_part)
+    y_ref = oracle.epilogue(acc_ref, **okw)
+    check_outputs(host(y), host(keep["acc"]), y_ref, acc_ref, out_int8)
+
+
+def run_conv_both(nq, case, x, shape, full, **epi_kw):
+    B, H, W, Cin = x.shape
+    KH, KW, stride, pad = shape
+    Ho, Wo = oracle.conv_out_hw(H, W, KH, KW, stride, pad)
+    epi, keep, okw = epi_pair(nq, case, full, (B, Ho, Wo), **epi_kw)
+    out_int8 = epi_kw.get("out_int8", False)
+    y = torch.empty((B, Ho, Wo, case.N), dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+    cs = nq.nq_conv_shape(B, H, W, Cin, case.N, KH, KW, stride, pad)
+    fn = nq.nq_conv_full if full else nq.nq_conv_part
+    fn(dev(x), cs, case.W.desc, epi, y)
+    torch.cuda.synchronize()
+    w4 = (case.ow_full if full else case.ow_part).reshape(case.N, KH, KW, Cin)
+    acc_ref = oracle.conv_acc(x, w4, stride, pad)
+    y_ref = oracle.epilogue(acc_ref, **okw)
+    check_outputs(host(y), host(keep["acc"]), y_ref, acc_ref, out_int8)

@@ -1,0 +1,119 @@
+"""CPU-only checks of the boundary: the library loads, exports every declared symbol, and
+rejects bad arguments on the host before anything touches a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def nq():
+    lib = os.path.join(ROOT, "paper_2506_17870_amd", "libnq.so")
+    if not os.path.exists(lib):
+        from paper_2506_17870_amd import build
+        build.build()
+    import paper_2506_17870_amd as nq
+    return nq
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "nq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(nq):
+    names = declared_functions()
+    assert len(names) >= 17
+    lib = ctypes.CDLL(nq.LIB_PATH)
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(nq.EXPORTS) == names
+    for name in names:
+        assert callable(getattr(nq, name)), f"binding lacks {name}"
+
+
+def test_version_and_status_strings(nq):
+    assert nq.nq_version() >= 1
+    assert nq.nq_status_string(nq.NQ_OK) == "ok"
+    assert "paged out" in nq.nq_status_string(nq.NQ_ERR_NOT_RESIDENT)
+
+
+def test_packed_bytes(nq):
+    # dense: exactly k bits per element on the padded shape
+    assert nq.nq_packed_bytes(512, 512, 6) == 512 * 512 * 6 // 8 == 196608
+    assert nq.nq_packed_bytes(512, 512, 2) == 65536
+    assert nq.nq_packed_bytes(1, 1, 3) == 32 * 64 * 3 // 8
+    assert nq.nq_packed_bytes(33, 65, 5) == 64 * 128 * 5 // 8
+    assert nq.nq_packed_bytes(0, 64, 5) == 0
+    # the paper's words: 21 three-bit or 12 five-bit fields per 64-bit word (Sec. 3.3.4)
+    assert nq.nq_packed_bytes(1, 21, 3, nq.NQ_LAYOUT_PAPER_U64) == 8
+    assert nq.nq_packed_bytes(1, 22, 3, nq.NQ_LAYOUT_PAPER_U64) == 16
+    assert nq.nq_packed_bytes(2, 12, 5, nq.NQ_LAYOUT_PAPER_U64) == 16
+    assert nq.nq_packed_bytes(4, 4, 0) == 0 and nq.nq_packed_bytes(4, 4, 8) == 0
+    assert nq.nq_packed_bytes(-1, 4, 3) == 0 and nq.nq_packed_bytes(4, 4, 3, 7) == 0
+
+
+def test_host_side_argument_checks(nq):
+    # all of these return before any HIP call: fake non-null addresses are never dereferenced
+    a = 0x1000
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_decompose(a, 4, 4, nq.make_cfg(7, 2), a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_UNSUPPORTED
+    for n, l in [(8, 0), (8, 7), (6, 5), (6, 0)]:
+        with pytest.raises(nq.NQError) as e:
+            nq.nq_decompose_pack(a, 4, 4, nq.make_cfg(n, l), a, a, stream=0)
+        assert e.value.status == nq.NQ_ERR_UNSUPPORTED
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_decompose_pack(a, 4, 4, nq.make_cfg(8, 2, nq.NQ_LOW_SIGNED_L1), a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_UNSUPPORTED
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_decompose_pack(a, 4, nq.NQ_MAX_K + 1, nq.make_cfg(8, 2), a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_SHAPE
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_decompose_pack(a, 4, 4, nq.make_cfg(8, 2), a + 4, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_ALIGN
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_decompose_pack(None, 4, 4, nq.make_cfg(8, 2), a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_pack(a, None, 4, 4, nq.make_cfg(8, 2), None, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    # empty tensors are a no-op
+    nq.nq_decompose(None, 0, 16, nq.make_cfg(8, 2), None, None, stream=0)
+    nq.nq_decompose_pack(a, 0, 16, nq.make_cfg(8, 2), a, a, stream=0)
+
+
+def test_gemm_argument_checks_without_gpu(nq):
+    a = 0x1000
+    cfg = nq.make_cfg(8, 2)
+    w = nq.nq_weight(cfg, 64, 64, a, 64 * 64 * 6 // 8, a, 64 * 64 * 2 // 8, a, a, 0, 0, None)
+    epi = nq.make_epilogue()
+    # full-bit while the lower-bit page is paged out: an error, never a silent downgrade
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gemm_full(a, 8, w, epi, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_NOT_RESIDENT
+    w.high_bytes = 16
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gemm_part(a, 8, w, epi, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_RANGE
+    w.high_bytes = 64 * 64 * 6 // 8
+    w.cfg.layout = nq.NQ_LAYOUT_PAPER_U64
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gemm_part(a, 8, w, epi, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_UNSUPPORTED
+    w.cfg.layout = nq.NQ_LAYOUT_DENSE
+    nq.nq_gemm_part(a, 0, w, epi, a, stream=0)          # M == 0: nothing to do
+    shape = nq.nq_conv_shape(1, 8, 8, 16, 64, 3, 3, 1, 1)  # K would be 144, the descriptor says 64
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_conv_part(a, shape, w, epi, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_SHAPE
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_page_in_low(w, 0)                        # nq_weight_init was never called
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_maxpool_i8(a, 1, 4, 4, 8, 3, 2, 3, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_SHAPE
