@@ -46,12 +46,16 @@ def cpu_baseline(inputs, cfg_conv, w_int, scale, x_all, s_a, bias, budget_s=12.0
             outs.append(oracle.epilogue(acc, s_a, scale, part_l_bits=part_l, bias=bias, relu=True))
         return time.perf_counter() - t0, outs
 
-    t1, _ = run(1)
-    nimg = int(max(1, min(x_all.shape[0], budget_s / max(t1, 1e-3))))
+    run(1)                                                    # first call pays the library load
+    nimg = x_all.shape[0]
     t, outs = run(nimg)
-    return dict(value=ops_img * nimg / t / 1e12, unit="TOPS", cores=oracle.threads(), kind="oracle",
-                sample=f"{nimg} of {x_all.shape[0]} images of the same convolution, part-bit then full-bit, "
-                       f"{t:.2f} s, C loops -O2 with OpenMP"), nimg, outs
+    total, reps = t, 1
+    while total < budget_s and reps < 200:                    # repeat the batch up to the time budget
+        dt, _ = run(nimg)
+        total, reps = total + dt, reps + 1
+    return dict(value=ops_img * nimg * reps / total / 1e12, unit="TOPS", cores=oracle.threads(), kind="oracle",
+                sample=f"{reps} x the {nimg}-image batch of the same convolution (decompose+pack, part-bit, "
+                       f"full-bit), {total:.1f} s, plain C loops -O2 with OpenMP"), nimg, outs
 
 
 def main():
@@ -121,10 +125,8 @@ def main():
         rc |= lib.nq_page_in_low(wref, ps)                                      # a4: upgrade, other stream
         rc |= lib.nq_conv_part(p_x[r], sref, wref, eref, p_yp[r], cs)           # a6 + a7, overlaps the copy
         if ev is not None:
-            ev[0].record(compute)
+            lib.nq_profile_next_launch(ev[0], ev[1])                            # time stamps of this dispatch
         rc |= lib.nq_conv_full(p_x[r], sref, wref, eref, p_yf[r], cs)           # a5 + a7, waits for the page
-        if ev is not None:
-            ev[1].record(compute)
         if rc:
             raise RuntimeError(f"libnq returned an error in step {i}")
 
@@ -137,7 +139,7 @@ def main():
         step(i)
     torch.cuda.synchronize()
 
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    events = [(ctypes.c_void_p(nq.nq_event_create()), ctypes.c_void_p(nq.nq_event_create()))
               for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -149,7 +151,10 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     value = 2 * ops_conv * args.steps / elapsed / 1e12
 
-    kern_ms = sorted(a.elapsed_time(b) for a, b in events)
+    kern_ms = sorted(nq.nq_event_elapsed_ms(a, b) for a, b in events)
+    for a, b in events:
+        nq.nq_event_destroy(a)
+        nq.nq_event_destroy(b)
     full_ms = sum(kern_ms) / len(kern_ms)
     # algorithmic bytes of one full-bit convolution launch: activations once, both packed pages once,
     # scales and bias once, fp32 outputs once
@@ -157,7 +162,7 @@ def main():
                        + 2 * 4 * Cout + 4 * M * Cout)
     achieved = bytes_conv_full / (full_ms * 1e-3) / 1e9
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=None, kernel="k_nested_gemm<6,2,full,256x64> (nq_conv_full)",
+                    traffic=None, kernel="k_nested_conv_window<6,2,full> (nq_conv_full)",
                     avg_kernel_us=1e3 * full_ms, median_kernel_us=1e3 * kern_ms[len(kern_ms) // 2],
                     algorithmic_bytes=bytes_conv_full,
                     mfma_tops=ops_conv / (full_ms * 1e-3) / 1e12,

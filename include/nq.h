@@ -213,6 +213,16 @@ nq_status nq_conv_full(const int8_t *d_x, const nq_conv_shape *shape, const nq_w
 nq_status nq_conv_part(const int8_t *d_x, const nq_conv_shape *shape, const nq_weight *w,
                        const nq_epilogue *epi, void *d_y, void *stream);
 
+/* Profiling aid: the next nq_gemm_* / nq_conv_* call made by this host thread attaches the two
+ * hipEvent_t (either may be NULL) to its kernel dispatch, so that hipEventElapsedTime(start,
+ * stop) is the execution time of that kernel alone.  One shot; events are the caller's. */
+nq_status nq_profile_next_launch(void *start_event, void *stop_event);
+/* Timing events for the call above: create / destroy a hipEvent_t, and the milliseconds
+ * between two completed events (blocks until stop_event has completed). */
+nq_status nq_event_create(void **event);
+nq_status nq_event_destroy(void *event);
+nq_status nq_event_elapsed_ms(void *start_event, void *stop_event, float *h_ms);
+
 /* ---- glue of a residual CNN on int8 NHWC activations (the paper is silent on these;
  * they only make a whole quantised network runnable between the nested convolutions) --- */
 /* Max pooling over the int8 codes; padding never wins.  Out: int8[B][Ho][Wo][C]. */

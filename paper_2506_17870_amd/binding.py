@@ -24,7 +24,8 @@ NQ_MAX_K = 65536
 
 EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_decompose", "nq_pack", "nq_decompose_pack",
            "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
-           "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_maxpool_i8", "nq_avgpool_i8"]
+           "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_profile_next_launch", "nq_event_create", "nq_event_destroy",
+           "nq_event_elapsed_ms", "nq_maxpool_i8", "nq_avgpool_i8"]
 
 
 class nq_cfg(ctypes.Structure):
@@ -77,6 +78,10 @@ _SIGS = {
     "nq_gemm_part": (_int, [_vp, _i64, _wp, _ep, _vp, _vp]),
     "nq_conv_full": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
     "nq_conv_part": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
+    "nq_profile_next_launch": (_int, [_vp, _vp]),
+    "nq_event_create": (_int, [ctypes.POINTER(ctypes.c_void_p)]),
+    "nq_event_destroy": (_int, [_vp]),
+    "nq_event_elapsed_ms": (_int, [_vp, _vp, ctypes.POINTER(ctypes.c_float)]),
     "nq_maxpool_i8": (_int, [_vp, _i64, _i64, _i64, _i64, _int, _int, _int, _vp, _vp]),
     "nq_avgpool_i8": (_int, [_vp, _i64, _i64, _i64, _f, _f, _vp, _vp]),
 }
@@ -189,6 +194,27 @@ def nq_conv_full(d_x, shape: nq_conv_shape, w: nq_weight, epi: nq_epilogue, d_y,
 def nq_conv_part(d_x, shape: nq_conv_shape, w: nq_weight, epi: nq_epilogue, d_y, stream=None):
     _check(_lib.nq_conv_part(_ptr(d_x), ctypes.byref(shape), ctypes.byref(w), ctypes.byref(epi), _ptr(d_y),
                              _stream(stream)), "nq_conv_part")
+
+
+def nq_profile_next_launch(start_event, stop_event):
+    """Raw hipEvent_t handles (integers) or None."""
+    _check(_lib.nq_profile_next_launch(start_event, stop_event), "nq_profile_next_launch")
+
+
+def nq_event_create() -> int:
+    ev = ctypes.c_void_p()
+    _check(_lib.nq_event_create(ctypes.byref(ev)), "nq_event_create")
+    return ev.value
+
+
+def nq_event_destroy(event):
+    _check(_lib.nq_event_destroy(event), "nq_event_destroy")
+
+
+def nq_event_elapsed_ms(start_event, stop_event) -> float:
+    ms = ctypes.c_float()
+    _check(_lib.nq_event_elapsed_ms(start_event, stop_event, ctypes.byref(ms)), "nq_event_elapsed_ms")
+    return ms.value
 
 
 def nq_maxpool_i8(d_x, B, H, W, C, ksize, stride, pad, d_y, stream=None):

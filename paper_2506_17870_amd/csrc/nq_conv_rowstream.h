@@ -1,0 +1,240 @@
+// Nested-integer convolution for layers with a short reduction (K = KH*KW*Cin of at most
+// 9 steps of 64), 32 output channels per block: weights stationary in registers,
+// activations streaming through LDS (paper Sec. 3.3 modes, Eq. 4 / Eq. 8; 8-bit
+// activations Sec. 4.2).
+//
+// Such layers (the wide, early layers of a CNN) move far more activation and output bytes
+// than weight bytes and run for only a few microseconds, so the kernel is organised around
+// the activation stream and around a short prologue.  A block is persistent: it loads and
+// decodes the packed weights of its 32 channels ONCE into matrix-core fragments that stay in
+// registers, then walks over its share of work units.  A unit is R whole output rows of one
+// image (at most 128 pixels, one 32-row tile per wave).  Units are handled in rounds of up to
+// RS_G: the input rows of all units of a round are requested together and copied into RS_G
+// LDS windows (pixels padded by 16 bytes against bank conflicts); after one barrier the units
+// are computed back to back, each one's output stores overlapping the next one's matrix-core
+// work.  The K loop has no barrier and no decoding: 16-byte LDS reads and MFMAs.
+//
+// Zero padding comes from the hardware range check of buffer loads: the buffer descriptor
+// covers exactly one image, rows above or below it fall outside the range and read as zero,
+// and halo columns get an offset that is out of range on purpose.  Index arithmetic that does
+// not depend on the data (tap offsets, division constants) is done once on the host.  The
+// kernel must not spill: a scratch reload would wait for every outstanding store.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nq_codec.h"
+#include "nq_gemm_kernel.h"
+
+namespace nq {
+
+typedef int r_v4i __attribute__((ext_vector_type(4)));
+typedef int r_v16i __attribute__((ext_vector_type(16)));
+typedef unsigned r_v4u __attribute__((ext_vector_type(4)));
+
+constexpr int RS_G = 4;                      // units per round = LDS windows per block
+constexpr int RS_HALO_OFFSET = 0x40000000;   // out of range for any image (host keeps images below 2^29 bytes)
+
+// RS_KCAP: the K steps of 64 of the layer (exact, so the K loop is straight-line code);
+// RS_LDMAX: 16-byte window pieces a thread stages per unit.
+template <int H, int L, bool FULL, bool GENERAL, int RS_KCAP, int RS_LDMAX>
+__global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmParams p, const StreamGeom g)
+{
+    constexpr int S = 8 - H;
+    constexpr int SHIFT = FULL ? (8 - H - L) : S;
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t win[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nb = blockIdx.y;               // 32-channel tile of this block (always a real one)
+    const int n0 = nb * 32;
+    const int CKP = p.Cin + 16;
+    const int c16 = p.Cin >> 4;
+
+    // ---- weights: every K step of the channel tile, requested first -----------------------------
+    uint32_t W8[RS_KCAP][8];   // packed dwords on arrival, decoded fragments afterwards
+    {
+        const uint32_t *ph = p.ph + (int64_t)nb * p.KB * (H * 64);
+        const uint32_t *pl = FULL ? p.pl + (int64_t)nb * p.KB * (L * 64) : nullptr;
+#pragma unroll
+        for (int s = 0; s < RS_KCAP; ++s) {
+#pragma unroll
+            for (int i = 0; i < H; ++i) W8[s][i] = ph[(unsigned)(s * (H * 64) + i * 64 + lane)];
+            if constexpr (FULL) {
+#pragma unroll
+                for (int i = 0; i < L; ++i) W8[s][H + i] = pl[(unsigned)(s * (L * 64) + i * 64 + lane)];
+            }
+        }
+    }
+
+    // ---- window staging plan of this thread (the same for every unit) --------------------------
+    int st_lds[RS_LDMAX], st_goff[RS_LDMAX];
+#pragma unroll
+    for (int j = 0; j < RS_LDMAX; ++j) {
+        const int q = tid + 256 * j;
+        const int pos = q >> g.c16_shift, c = q & (c16 - 1);
+        const int ir = (int)__umulhi((unsigned)pos, g.wc_magic);   // pos / WC
+        const int wc = pos - ir * g.WC;
+        const int iw = wc - p.pad;
+        const bool in_window = q < g.items;
+        const bool in_row = in_window && (unsigned)iw < (unsigned)p.W;
+        st_lds[j] = in_window ? pos * CKP + 16 * c : g.win_bytes;   // pieces past the window go to a spare slot
+        st_goff[j] = in_row ? (ir * p.W + iw) * p.Cin + 16 * c : RS_HALO_OFFSET;
+    }
+    r_v4u stage[RS_G][RS_LDMAX];
+    auto load_unit = [&](int b, int rb, r_v4u (&stg)[RS_LDMAX]) {
+        // the descriptor covers image b only: rows outside it and halo columns read as zero
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<int8_t *>(p.x) + (int64_t)b * g.img_bytes, 0, g.img_bytes, 0x00020000);
+        const int unit_off = (rb * g.R * p.stride - p.pad) * g.row_bytes;
+#pragma unroll
+        for (int j = 0; j < RS_LDMAX; ++j)
+            stg[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, unit_off + st_goff[j], 0, 0);
+    };
+    auto store_unit = [&](uint8_t *buf, const r_v4u (&stg)[RS_LDMAX]) {
+#pragma unroll
+        for (int j = 0; j < RS_LDMAX; ++j) *reinterpret_cast<r_v4u *>(buf + st_lds[j]) = stg[j];
+    };
+
+    // units of this block: blockIdx.x, blockIdx.x + gridDim.x, ...; (image, row block) of a unit
+    // advance by constants from one unit to the next
+    int ub[RS_G], urb[RS_G];
+    int nxt_u = blockIdx.x;
+    int nxt_b = nxt_u / g.RB, nxt_rb = nxt_u - nxt_b * g.RB;
+    auto request_round = [&]() {
+#pragma unroll
+        for (int j = 0; j < RS_G; ++j) {
+            ub[j] = nxt_b; urb[j] = nxt_rb;
+            if (nxt_u < g.units) load_unit(nxt_b, nxt_rb, stage[j]);
+            nxt_u += gridDim.x;
+            nxt_b += g.step_b; nxt_rb += g.step_rb;
+            if (nxt_rb >= g.RB) { nxt_rb -= g.RB; ++nxt_b; }
+        }
+    };
+    int u0 = blockIdx.x;
+    request_round();
+
+    // ---- per-lane constants ---------------------------------------------------------------------
+    int a_off;
+    {
+        int pl = wave * 32 + (lane & 31);
+        if (pl >= g.R * p.Wo) pl = 0;                 // phantom rows read a valid pixel, never stored
+        const int r = (int)__umulhi((unsigned)pl, g.wo_magic), ow = pl - r * p.Wo;
+        a_off = ((r * p.stride) * g.WC + ow * p.stride) * CKP + 32 * (lane >> 5);
+    }
+    const int col = lane & 31, rg = lane >> 5;
+    const EpiColumn ec = epi_column(p, n0 + col, FULL);
+
+    // ---- decode the weights in place into matrix-core fragments ---------------------------------
+#pragma unroll
+    for (int s = 0; s < RS_KCAP; ++s) {
+        uint32_t Pk[H], D[8];
+#pragma unroll
+        for (int i = 0; i < H; ++i) Pk[i] = W8[s][i];
+        HighCodec<H>::decode(Pk, D);
+        if constexpr (FULL) {
+            uint32_t Qk[L];
+#pragma unroll
+            for (int i = 0; i < L; ++i) Qk[i] = W8[s][H + i];
+            LowCodec<L, S>::decode_or(Qk, D);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) W8[s][i] = D[i];
+    }
+
+    for (; u0 < g.units; u0 += RS_G * (int)gridDim.x) {
+        int cur_b[RS_G], cur_rb[RS_G];
+#pragma unroll
+        for (int j = 0; j < RS_G; ++j) {
+            cur_b[j] = ub[j]; cur_rb[j] = urb[j];
+            if (u0 + j * (int)gridDim.x < g.units) store_unit(win + j * g.win_stride, stage[j]);
+        }
+        __syncthreads();
+        request_round();                              // the next round travels while this one is computed
+#pragma unroll
+        for (int j = 0; j < RS_G; ++j) {
+            const int u = u0 + j * (int)gridDim.x;
+            if (u < g.units) {
+                const uint8_t *buf = win + j * g.win_stride;
+                r_v16i acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = 0;
+                // Activation fragments are read RS_PF reads ahead of the MFMAs that consume them, so
+                // that the LDS latency is covered by matrix-core work; the fences keep that order.
+                constexpr int NFRAG = 2 * RS_KCAP;
+                constexpr int RS_PF = NFRAG < 4 ? NFRAG : 4;
+                r_v4i afrag[RS_PF];
+#pragma unroll
+                for (int f = 0; f < RS_PF; ++f)
+                    afrag[f] = *reinterpret_cast<const r_v4i *>(buf + a_off + g.tap_off[f >> 1] + 16 * (f & 1));
+#pragma unroll
+                for (int f = 0; f < NFRAG; ++f) {
+                    const int s = f >> 1, hf = f & 1;
+                    const r_v4i a = afrag[f % RS_PF];
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (f + RS_PF < NFRAG)
+                        afrag[f % RS_PF] = *reinterpret_cast<const r_v4i *>(
+                            buf + a_off + g.tap_off[(f + RS_PF) >> 1] + 16 * ((f + RS_PF) & 1));
+                    const r_v4i bfrag = r_v4i{(int)W8[s][4 * hf], (int)W8[s][4 * hf + 1], (int)W8[s][4 * hf + 2],
+                                              (int)W8[s][4 * hf + 3]};
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bfrag, acc, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+
+                // ---- epilogue (Eq. 2 / Eq. 8) ----------------------------------------------------------
+                const int oh0 = cur_rb[j] * g.R;
+                const int pix = min(g.R, p.Ho - oh0) * p.Wo;
+                const int64_t m_base = ((int64_t)cur_b[j] * p.Ho + oh0) * p.Wo;
+                if (n0 + col < p.N)
+                    epi_tile<GENERAL>(p, acc, SHIFT, ec, (m_base + wave * 32) * p.N + n0, (unsigned)(4 * rg * p.N + col),
+                                      rg, pix - wave * 32);
+            }
+        }
+        __syncthreads();   // all windows of the round are free again
+    }
+}
+
+template <typename K>
+inline void rs_grant_lds(K kernel, size_t lds)
+{
+    static size_t granted = 0;   // one per kernel instantiation
+    if (lds > granted) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds);
+        granted = lds;
+    }
+}
+
+#define NQ_RS_LAUNCH(FULLV, GENV, KCAP, LDMAX)                                \
+    do {                                                                      \
+        auto k = k_nested_conv_rowstream<H, L, FULLV, GENV, KCAP, LDMAX>;     \
+        rs_grant_lds(k, lds);                                                 \
+        launch_timed(k, grid, block, lds, st, ev_start, ev_stop, p, g);       \
+    } while (0)
+
+// Instantiated for the K-step counts of 3x3 convolutions with 64 input channels (9) and of 1x1
+// convolutions with 64, 128, 256 and 512 input channels (1, 2, 4, 8).
+template <int H, int L>
+void launch_nested_conv_rowstream(bool full, const GemmParams &p, const StreamGeom &g, int grid_x, hipStream_t st,
+                                  void *ev_start, void *ev_stop)
+{
+    const dim3 grid((unsigned)grid_x, (unsigned)((p.N + 31) / 32)), block(256);
+    const size_t lds = RS_G * (size_t)g.win_stride;
+    const bool general = p.acc_dump != nullptr || p.resid != nullptr;
+#define NQ_RS_CASE(FULLV, GENV)                              \
+    switch (g.ksteps) {                                      \
+    case 9: NQ_RS_LAUNCH(FULLV, GENV, 9, 4); break;          \
+    case 1: NQ_RS_LAUNCH(FULLV, GENV, 1, 4); break;          \
+    case 2: NQ_RS_LAUNCH(FULLV, GENV, 2, 8); break;          \
+    case 4: NQ_RS_LAUNCH(FULLV, GENV, 4, 8); break;          \
+    case 8: NQ_RS_LAUNCH(FULLV, GENV, 8, 8); break;          \
+    default: break;                                          \
+    }
+    if (full) {
+        if (general) { NQ_RS_CASE(true, true) } else { NQ_RS_CASE(true, false) }
+    } else {
+        if (general) { NQ_RS_CASE(false, true) } else { NQ_RS_CASE(false, false) }
+    }
+}
+
+}  // namespace nq

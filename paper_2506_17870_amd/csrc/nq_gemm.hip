@@ -13,6 +13,89 @@ struct Geometry {
     int H, W, Cin, Ho, Wo, KH, KW, stride, pad;
 };
 
+// One-shot profiling hook: events handed over by nq_profile_next_launch, consumed by the next launch.
+thread_local void *g_ev_start = nullptr;
+thread_local void *g_ev_stop = nullptr;
+
+// Decides whether the windowed convolution kernel applies and fills its geometry.
+bool plan_window(const Geometry &g, const int8_t *d_x, WindowGeom *wg, size_t *lds)
+{
+    if (g.KH * g.KW <= 1) return false;
+    if (g.Cin % 64 != 0 || !aligned16(d_x)) return false;
+    if (g.Wo > 256 || g.Wo < 1) return false;
+    const int WC = g.W + 2 * g.pad;
+    for (int CK : {256, 128, 64}) {
+        if (g.Cin % CK != 0) continue;
+        int R = 256 / g.Wo;                       // at most eight 32-row tiles per block
+        if (R > g.Ho) R = g.Ho;
+        for (; R >= 1; --R) {
+            const int IR = (R - 1) * g.stride + g.KH;
+            const size_t bytes = (size_t)IR * WC * (CK + 16);
+            if (bytes <= 72 * 1024) {
+                // do not shrink the block below half of its row budget just to widen the chunk
+                if (R * g.Wo < 128 && CK > 64 && 256 / g.Wo > R) break;
+                wg->R = R; wg->RB = (g.Ho + R - 1) / R; wg->IR = IR; wg->WC = WC; wg->CK = CK;
+                wg->NCH = g.Cin / CK;
+                wg->c16_shift = CK == 256 ? 4 : (CK == 128 ? 3 : 2);
+                *lds = bytes;
+                return true;
+            }
+        }
+    }
+    return false;
+}
+
+// Decides whether the register-stationary-weights kernel applies (short K, power-of-two Cin)
+// and works out its geometry.
+bool plan_rowstream(const Geometry &g, const int8_t *d_x, int64_t n_out, StreamGeom *sg, int *grid_x)
+{
+    const int Cin = g.Cin;
+    if (Cin < 64 || (Cin & (Cin - 1)) != 0 || !aligned16(d_x)) return false;
+    const int ksteps = g.KH * g.KW * (Cin / 64);
+    if (ksteps != 9 && ksteps != 1 && ksteps != 2 && ksteps != 4 && ksteps != 8) return false;
+    if (g.Wo > 128 || g.Wo < 1) return false;
+    const int64_t img_bytes = (int64_t)g.H * g.W * Cin;
+    if (img_bytes > (int64_t(1) << 29)) return false;
+    const int WC = g.W + 2 * g.pad;
+    const int ld_max = (ksteps == 9 || ksteps == 1) ? 4 : 8;   // window pieces per thread of that instantiation
+    int R = 128 / g.Wo;
+    if (R > g.Ho) R = g.Ho;
+    for (; R >= 1; --R) {
+        const int IR = (R - 1) * g.stride + g.KH;
+        const int64_t items = (int64_t)IR * WC * (Cin / 16);
+        const int64_t bytes = (int64_t)IR * WC * (Cin + 16);
+        if (items > ld_max * 256 || 4 * (bytes + 16) > 76 * 1024) continue;
+        if (R * g.Wo < 64 && 128 / g.Wo > R) return false;   // the window limit left too little work per unit
+        const int64_t images = g.M / ((int64_t)g.Ho * g.Wo);
+        const int RB = (g.Ho + R - 1) / R;
+        if (images * RB > 0x3fffffffLL) return false;
+        sg->R = R; sg->RB = RB; sg->WC = WC; sg->units = (int)(images * RB);
+        sg->ksteps = ksteps; sg->items = (int)items; sg->win_bytes = (int)bytes; sg->win_stride = (int)bytes + 16;
+        int sh = 0;
+        while ((16 << sh) < Cin) ++sh;
+        sg->c16_shift = sh;
+        sg->wc_magic = (unsigned)(((uint64_t(1) << 32) + WC - 1) / WC);
+        sg->wo_magic = (unsigned)(((uint64_t(1) << 32) + g.Wo - 1) / g.Wo);
+        if (WC == 1) sg->wc_magic = 0xFFFFFFFFu;   // not reached: WC >= KW >= 1 and a 1-wide window has Cin pieces only
+        sg->img_bytes = (int)img_bytes; sg->row_bytes = g.W * Cin;
+        const int cin64 = Cin / 64;
+        for (int s = 0; s < 9; ++s) {
+            const int tap = s / cin64, cb = s % cin64;
+            const int kh = tap / g.KW, kw = tap % g.KW;
+            sg->tap_off[s] = s < ksteps ? (kh * WC + kw) * (Cin + 16) + cb * 64 : 0;
+        }
+        // persistent blocks, two per compute unit (LDS windows), each with the same number of units
+        const int nblk = (int)ceil_div(n_out, 32);
+        int slots = 512 / nblk;
+        if (slots < 1) slots = 1;
+        const int per = (sg->units + slots - 1) / slots;
+        *grid_x = (sg->units + per - 1) / per;
+        sg->step_b = *grid_x / RB; sg->step_rb = *grid_x % RB;
+        return true;
+    }
+    return false;
+}
+
 int pick_tile(int64_t M, int64_t N)
 {
     if (N <= 64) return 0;
@@ -37,7 +120,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if (!aligned16(w->d_high) || (full && !aligned16(w->d_low))) return NQ_ERR_ALIGN;
     if (w->high_bytes < nq_packed_bytes(w->N, w->K, h, NQ_LAYOUT_DENSE)) return NQ_ERR_RANGE;
     if (full && w->low_bytes < nq_packed_bytes(w->N, w->K, l, NQ_LAYOUT_DENSE)) return NQ_ERR_RANGE;
-    if (g.M > (int64_t(1) << 40) / (w->N > 0 ? w->N : 1)) return NQ_ERR_SHAPE;
+    if (w->N > (1 << 24) || g.M > (int64_t(1) << 40) / (w->N > 0 ? w->N : 1)) return NQ_ERR_SHAPE;
 
     hipStream_t s = (hipStream_t)stream;
     if (full && w->low_event_armed && w->low_event) {
@@ -73,10 +156,27 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     // 16-byte activation loads need every chunk of 16 consecutive k inside one pixel
     p.fast_a = (g.Cin % 16 == 0) && aligned16(d_x);
 
+    void *ev0 = g_ev_start, *ev1 = g_ev_stop;
+    g_ev_start = g_ev_stop = nullptr;
+    StreamGeom sg;
+    int grid_x = 0;
+    if (plan_rowstream(g, d_x, w->N, &sg, &grid_x)) {
+        if (ceil_div(w->N, 32) > 65535) return NQ_ERR_SHAPE;
+        NQ_DISPATCH_HL(h, l, launch_nested_conv_rowstream, full, p, sg, grid_x, s, ev0, ev1);
+        return launch_status();
+    }
+    WindowGeom wg;
+    size_t lds = 0;
+    if (plan_window(g, d_x, &wg, &lds)) {
+        const int64_t blocks_x = (g.M / ((int64_t)g.Ho * g.Wo)) * wg.RB;
+        if (blocks_x > 0x7fffffffLL || ceil_div(w->N, 64) > 65535) return NQ_ERR_SHAPE;
+        NQ_DISPATCH_HL(h, l, launch_nested_conv_window, full, 0, p, wg, lds, s, ev0, ev1);
+        return launch_status();
+    }
     const int tile = pick_tile(g.M, w->N);
     if (ceil_div(g.M, NQ_TILE_BM[tile]) > 0x7fffffffLL || ceil_div(w->N, NQ_TILE_BN[tile]) > 65535)
         return NQ_ERR_SHAPE;
-    NQ_DISPATCH_HL(h, l, launch_nested_gemm, full, tile, p, s);
+    NQ_DISPATCH_HL(h, l, launch_nested_gemm, full, tile, p, s, ev0, ev1);
     return launch_status();
 }
 
@@ -114,6 +214,13 @@ nq_status conv(bool full, const int8_t *d_x, const nq_conv_shape *sh, const nq_w
 }
 
 }  // namespace
+
+extern "C" nq_status nq_profile_next_launch(void *start_event, void *stop_event)
+{
+    g_ev_start = start_event;
+    g_ev_stop = stop_event;
+    return NQ_OK;
+}
 
 extern "C" nq_status nq_gemm_full(const int8_t *d_x, int64_t M, const nq_weight *w, const nq_epilogue *epi,
                                   void *d_y, void *stream)

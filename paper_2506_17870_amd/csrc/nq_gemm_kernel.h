@@ -15,10 +15,12 @@
 // w_high * 2^(8-h) (part-bit, lower field cleared); the accumulator is an exact multiple
 // of that power of two and is shifted back before the epilogue.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "nq_codec.h"
+#include "nq_epilogue.h"
 #include "nq_gemm_params.h"
 
 namespace nq {
@@ -28,7 +30,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int A_STRIDE = 80;  // bytes per LDS row of the activation tile (64 + 16 padding)
 
-template <int H, int L, bool FULL, int BM, int BN, int WM, int WN>
+template <int H, int L, bool FULL, bool GENERAL, int BM, int BN, int WM, int WN>
 __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four waves per block");
@@ -194,59 +196,56 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
             }
     }
 
-    // ---- epilogue (Eq. 2 / Eq. 8), fp32, fixed order, no contraction -------------------------
+    // ---- epilogue (Eq. 2 / Eq. 8) -------------------------------------------------------------
     const int col = lane & 31, rg = lane >> 5;
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int n = n0 + (wn * TN + t) * 32 + col;
         if (n >= p.N) continue;
-        float c = p.act_scale * p.scale[n];
-        if (!FULL) c = c * p.part_mul;
-        const float bias = p.bias ? p.bias[n] : 0.0f;
+        const EpiColumn e = epi_column(p, n, FULL);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t m = m0 + wm * (BM / WM) + i * 32 + 8 * (r >> 2) + 4 * rg + (r & 3);
-                if (m >= p.M) continue;
-                const int a = acc[i][t][r] >> SHIFT;
-                const int64_t o = m * p.N + n;
-                if (p.acc_dump) p.acc_dump[o] = a;
-                float y = (float)a * c;
-                if (p.bias) y = y + bias;
-                if (p.resid) {
-                    const float rv = p.resid_scale * (float)p.resid[o];
-                    y = y + rv;
-                }
-                if (p.relu) y = fmaxf(y, 0.0f);
-                if (p.out_int8) {
-                    float q = rintf(y * p.inv_out_scale);
-                    q = fminf(fmaxf(q, -128.0f), 127.0f);
-                    reinterpret_cast<int8_t *>(p.y)[o] = (int8_t)(int)q;
-                } else {
-                    reinterpret_cast<float *>(p.y)[o] = y;
-                }
-            }
+            const int64_t row0 = m0 + wm * (BM / WM) + i * 32;
+            const int64_t left = p.M - row0;
+            const int rows_left = left > 32 ? 32 : (int)left;
+            const int nt0 = n0 + (wn * TN + t) * 32;
+            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left);
         }
     }
 }
 
-#define NQ_LAUNCH_TILE(FULLV, BM, BN, WM, WN)                                                            \
-    hipLaunchKernelGGL((k_nested_gemm<H, L, FULLV, BM, BN, WM, WN>),                                     \
-                       dim3((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN)), dim3(256), \
-                       0, st, p)
+// Launches `kernel`; with events the dispatch itself is time stamped (begin and end of the kernel).
+template <typename F, typename... Args>
+inline void launch_timed(F kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, void *ev_start, void *ev_stop,
+                         Args... args)
+{
+    if (ev_start || ev_stop)
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, (hipEvent_t)ev_start, (hipEvent_t)ev_stop, 0,
+                              args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, args...);
+}
+
+#define NQ_LAUNCH_TILE(FULLV, GENV, BM, BN, WM, WN)                                                       \
+    launch_timed(k_nested_gemm<H, L, FULLV, GENV, BM, BN, WM, WN>,                                        \
+                 dim3((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN)), dim3(256), 0, st, \
+                 ev_start, ev_stop, p)
+
+#define NQ_LAUNCH_TILES(FULLV, GENV)                                  \
+    do {                                                              \
+        if (tile == 0) NQ_LAUNCH_TILE(FULLV, GENV, 256, 64, 4, 1);    \
+        else if (tile == 1) NQ_LAUNCH_TILE(FULLV, GENV, 128, 256, 1, 4); \
+        else NQ_LAUNCH_TILE(FULLV, GENV, 64, 256, 1, 4);              \
+    } while (0)
 
 template <int H, int L>
-void launch_nested_gemm(bool full, int tile, const GemmParams &p, hipStream_t st)
+void launch_nested_gemm(bool full, int tile, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop)
 {
+    const bool general = p.acc_dump != nullptr || p.resid != nullptr;
     if (full) {
-        if (tile == 0) NQ_LAUNCH_TILE(true, 256, 64, 4, 1);
-        else if (tile == 1) NQ_LAUNCH_TILE(true, 128, 256, 1, 4);
-        else NQ_LAUNCH_TILE(true, 64, 256, 1, 4);
+        if (general) NQ_LAUNCH_TILES(true, true); else NQ_LAUNCH_TILES(true, false);
     } else {
-        if (tile == 0) NQ_LAUNCH_TILE(false, 256, 64, 4, 1);
-        else if (tile == 1) NQ_LAUNCH_TILE(false, 128, 256, 1, 4);
-        else NQ_LAUNCH_TILE(false, 64, 256, 1, 4);
+        if (general) NQ_LAUNCH_TILES(false, true); else NQ_LAUNCH_TILES(false, false);
     }
 }
 

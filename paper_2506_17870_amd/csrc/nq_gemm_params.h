@@ -23,12 +23,55 @@ struct GemmParams {
     int relu, out_int8, fast_a;
 };
 
+// Geometry of the LDS-resident input window of the windowed convolution kernel.
+struct WindowGeom {
+    int R;          // output rows per block
+    int RB;         // row blocks per image = ceil(Ho / R)
+    int IR;         // input rows in the window = (R-1)*stride + KH
+    int WC;         // window columns = W + 2*pad
+    int CK;         // input channels per chunk (64, 128 or 256)
+    int NCH;        // chunks = Cin / CK
+    int c16_shift;  // log2(CK / 16)
+};
+
+// Geometry of the register-stationary-weights convolution kernel (work unit = R output rows).
+// Everything that does not depend on the data is worked out on the host.
+struct StreamGeom {
+    int R;            // output rows per unit (R * Wo <= 128)
+    int RB;           // units per image = ceil(Ho / R)
+    int WC;           // window columns = W + 2*pad
+    int units;        // B * RB
+    int ksteps;       // KH*KW*Cin / 64: 1, 2, 4, 8 or 9
+    int items;        // 16-byte pieces of one window = IR * WC * Cin / 16
+    int win_bytes;    // bytes of one LDS window = IR * WC * (Cin + 16)
+    int win_stride;   // win_bytes + 16: one spare slot for pieces past the window
+    int c16_shift;    // log2(Cin / 16)
+    unsigned wc_magic;  // ceil(2^32 / WC): n / WC == umulhi(n, wc_magic) for n < 2^16
+    unsigned wo_magic;  // ceil(2^32 / Wo)
+    int step_b, step_rb;  // gridDim.x = step_b * RB + step_rb: how (image, row block) advance per unit
+    int img_bytes;    // H * W * Cin
+    int row_bytes;    // W * Cin
+    int tap_off[9];   // LDS byte offset of K step s: (kh*WC + kw)*(Cin+16) + 64*cb
+};
+
 // Tile shapes: 0 = 256x64 (narrow outputs), 1 = 128x256 (large), 2 = 64x256 (few rows).
 constexpr int NQ_TILE_BM[3] = {256, 128, 64};
 constexpr int NQ_TILE_BN[3] = {64, 256, 256};
 
 // Defined in nq_gemm_kernel.h, instantiated once per (h, l) by nq_gemm_inst.hip.
+// ev_start / ev_stop, if not null, are hipEvent_t that receive the begin and end time stamps
+// of the kernel itself.
 template <int H, int L>
-void launch_nested_gemm(bool full, int tile, const GemmParams &p, hipStream_t st);
+void launch_nested_gemm(bool full, int tile, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop);
+
+// Windowed convolution, shape 0: 2x2 waves, 8 row tiles x 64 channels per block.
+template <int H, int L>
+void launch_nested_conv_window(bool full, int shape, const GemmParams &p, const WindowGeom &g, size_t lds_bytes,
+                               hipStream_t st, void *ev_start, void *ev_stop);
+
+// Register-stationary weights, persistent blocks over row units; 64 output channels per block.
+template <int H, int L>
+void launch_nested_conv_rowstream(bool full, const GemmParams &p, const StreamGeom &g, int grid_x, hipStream_t st,
+                                  void *ev_start, void *ev_stop);
 
 }  // namespace nq

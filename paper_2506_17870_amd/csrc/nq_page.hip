@@ -93,3 +93,37 @@ extern "C" nq_status nq_page_in_low(nq_weight *w, void *copy_stream)
     w->low_resident = 1;
     return NQ_OK;
 }
+
+// ---- timing events for nq_profile_next_launch ------------------------------------------------
+extern "C" nq_status nq_event_create(void **event)
+{
+    if (!event) return NQ_ERR_INVALID_ARG;
+    hipEvent_t ev = nullptr;
+    if (hipEventCreate(&ev) != hipSuccess) {
+        (void)hipGetLastError();
+        return NQ_ERR_HIP;
+    }
+    *event = ev;
+    return NQ_OK;
+}
+
+extern "C" nq_status nq_event_destroy(void *event)
+{
+    if (!event) return NQ_ERR_INVALID_ARG;
+    if (hipEventDestroy((hipEvent_t)event) != hipSuccess) {
+        (void)hipGetLastError();
+        return NQ_ERR_HIP;
+    }
+    return NQ_OK;
+}
+
+extern "C" nq_status nq_event_elapsed_ms(void *start_event, void *stop_event, float *h_ms)
+{
+    if (!start_event || !stop_event || !h_ms) return NQ_ERR_INVALID_ARG;
+    if (hipEventSynchronize((hipEvent_t)stop_event) != hipSuccess ||
+        hipEventElapsedTime(h_ms, (hipEvent_t)start_event, (hipEvent_t)stop_event) != hipSuccess) {
+        (void)hipGetLastError();
+        return NQ_ERR_HIP;
+    }
+    return NQ_OK;
+}
