@@ -108,7 +108,11 @@ typedef struct {
     int32_t low_resident;   /* set by nq_page_in_low, cleared by nq_page_out_low; a       */
                             /* caller that wrote d_low on the device may set it itself    */
     int32_t low_event_armed;/* internal: low_event has been recorded                      */
-    void *low_event;        /* internal: hipEvent_t made by nq_weight_init                */
+    void *low_event;        /* internal: hipEvent_t made by nq_weight_init; "page is in"  */
+    void *free_event;       /* internal: hipEvent_t made by nq_weight_init; "readers of   */
+                            /* the page enqueued before nq_page_out_low are done"         */
+    int32_t free_event_armed;
+    int32_t reserved;
 } nq_weight;
 
 /* Fused epilogue of the GEMM / convolution (Eq. 2 and Eq. 8), fp32, in this order with
@@ -183,7 +187,9 @@ nq_status nq_weight_destroy(nq_weight *w);
 /* Downgrade full-bit -> part-bit: the lower-bit page is paged out.  The host copy is the
  * master, so nothing is moved: the page is marked non-resident, full-bit calls on `w`
  * now fail with NQ_ERR_NOT_RESIDENT, and the owner may reuse or free d_low once the work
- * already enqueued on `stream` has finished. */
+ * already enqueued on `stream` has finished.  An internal event is recorded on `stream` at
+ * this point; a later nq_page_in_low waits for it, so the incoming copy never overwrites
+ * a page that full-bit kernels enqueued earlier on `stream` are still reading. */
 nq_status nq_page_out_low(nq_weight *w, void *stream);
 
 /* Upgrade part-bit -> full-bit: copies low_bytes from h_low to d_low on `copy_stream`

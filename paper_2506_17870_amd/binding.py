@@ -39,7 +39,8 @@ class nq_weight(ctypes.Structure):
                 ("d_low", ctypes.c_void_p), ("low_bytes", ctypes.c_uint64),
                 ("h_low", ctypes.c_void_p), ("d_scale", ctypes.c_void_p),
                 ("low_resident", ctypes.c_int32), ("low_event_armed", ctypes.c_int32),
-                ("low_event", ctypes.c_void_p)]
+                ("low_event", ctypes.c_void_p), ("free_event", ctypes.c_void_p),
+                ("free_event_armed", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class nq_epilogue(ctypes.Structure):
@@ -245,7 +246,7 @@ class NestedWeight:
         self.low_host = torch.empty(self.low.numel(), dtype=torch.uint8, pin_memory=True)
         self.scale = torch.ones(max(N, 1), dtype=torch.float32, device=device)
         self.desc = nq_weight(cfg, N, K, self.high.data_ptr(), self.high.numel(), self.low.data_ptr(),
-                              self.low.numel(), self.low_host.data_ptr(), self.scale.data_ptr(), 0, 0, None)
+                              self.low.numel(), self.low_host.data_ptr(), self.scale.data_ptr(), 0, 0, None, None, 0, 0)
         nq_weight_init(self.desc)
 
     @classmethod

@@ -38,8 +38,17 @@ extern "C" nq_status nq_weight_init(nq_weight *w)
         (void)hipGetLastError();
         return NQ_ERR_HIP;
     }
+    hipEvent_t ev2 = nullptr;
+    if (hipEventCreateWithFlags(&ev2, hipEventDisableTiming) != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipEventDestroy(ev);
+        return NQ_ERR_HIP;
+    }
     w->low_event = ev;
+    w->free_event = ev2;
     w->low_event_armed = 0;
+    w->free_event_armed = 0;
+    w->reserved = 0;
     w->low_resident = 0;
     return NQ_OK;
 }
@@ -53,16 +62,32 @@ extern "C" nq_status nq_weight_destroy(nq_weight *w)
             return NQ_ERR_HIP;
         }
     }
+    if (w->free_event) {
+        if (hipEventDestroy((hipEvent_t)w->free_event) != hipSuccess) {
+            (void)hipGetLastError();
+            return NQ_ERR_HIP;
+        }
+    }
     w->low_event = nullptr;
+    w->free_event = nullptr;
     w->low_event_armed = 0;
+    w->free_event_armed = 0;
     w->low_resident = 0;
     return NQ_OK;
 }
 
 extern "C" nq_status nq_page_out_low(nq_weight *w, void *stream)
 {
-    (void)stream;  // nothing is enqueued: the host copy is the master
+    // nothing is moved: the host copy is the master; only the point after which the device
+    // slot may be overwritten is marked on `stream`
     if (!w) return NQ_ERR_INVALID_ARG;
+    if (w->free_event) {
+        if (hipEventRecord((hipEvent_t)w->free_event, (hipStream_t)stream) != hipSuccess) {
+            (void)hipGetLastError();
+            return NQ_ERR_HIP;
+        }
+        w->free_event_armed = 1;
+    }
     w->low_resident = 0;
     w->low_event_armed = 0;
     return NQ_OK;
@@ -77,6 +102,14 @@ extern "C" nq_status nq_page_in_low(nq_weight *w, void *copy_stream)
     const size_t need = nq_packed_bytes(w->N, w->K, w->cfg.l_bits, w->cfg.layout);
     if (w->low_bytes < need) return NQ_ERR_RANGE;
     hipStream_t s = (hipStream_t)copy_stream;
+    if (w->free_event_armed && w->free_event) {
+        // earlier readers of the slot (full-bit kernels before the page-out) finish first
+        if (hipStreamWaitEvent(s, (hipEvent_t)w->free_event, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            return NQ_ERR_HIP;
+        }
+        w->free_event_armed = 0;
+    }
     if (need > 0) {
         if (!w->d_low || !w->h_low) return NQ_ERR_INVALID_ARG;
         if (!aligned16(w->d_low)) return NQ_ERR_ALIGN;

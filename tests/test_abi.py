@@ -90,7 +90,7 @@ def test_host_side_argument_checks(nq):
 def test_gemm_argument_checks_without_gpu(nq):
     a = 0x1000
     cfg = nq.make_cfg(8, 2)
-    w = nq.nq_weight(cfg, 64, 64, a, 64 * 64 * 6 // 8, a, 64 * 64 * 2 // 8, a, a, 0, 0, None)
+    w = nq.nq_weight(cfg, 64, 64, a, 64 * 64 * 6 // 8, a, 64 * 64 * 2 // 8, a, a, 0, 0, None, None, 0, 0)
     epi = nq.make_epilogue()
     # full-bit while the lower-bit page is paged out: an error, never a silent downgrade
     with pytest.raises(nq.NQError) as e:

@@ -1,0 +1,60 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times (same entry points, same epilogue options).  The C oracle with OpenMP finishes each of these in
+seconds, so every output element is compared, not a sample."""
+import numpy as np
+import pytest
+import torch
+
+from nq_testlib import Case, run_conv_both, run_gemm_both
+from paper_2506_17870_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nq():
+    import paper_2506_17870_amd as nq
+    assert torch.cuda.is_available()
+    return nq
+
+
+def test_resnet18_conv_full_batch(nq):
+    # batch 32, 56x56x64 -> 64, 3x3 stride 1 pad 1, INT8 nesting INT6; bias + ReLU, fp32 out (as bench.py)
+    c = inputs.CONV_RESNET18
+    K = 9 * c["Cin"]
+    w_int, scale = inputs.weights(c["Cout"], K, inputs.he_sigma(K), 8, seed=0)
+    case = Case(nq, w_int, scale, 8, 2)
+    x = inputs.uniform_activations((c["B"], c["H"], c["W"], c["Cin"]), seed=0)
+    bias = inputs.small_floats(c["Cout"], 0.1, seed=2)
+    for full in (False, True):
+        run_conv_both(nq, case, x, (3, 3, 1, 1), full, s_a=0.02, bias=bias, relu=True)
+    run_conv_both(nq, case, x, (3, 3, 1, 1), True, s_a=0.02, bias=bias, relu=True, out_int8=True, inv_s_out=2.5)
+
+
+@pytest.mark.parametrize("l", [2, 4])
+def test_resnet101_bottleneck_full_batch(nq, l):
+    # batch 64, 14x14: 1x1 1024->256, 3x3 256->256, 1x1 256->1024; ReLU-clipped N(0,1) activations
+    x0, s0 = inputs.relu_activations((64, 14, 14, 1024), seed=7)
+    for i, g in enumerate(inputs.BOTTLENECK_RESNET101):
+        K = g["KH"] * g["KW"] * g["Cin"]
+        w_int, scale = inputs.weights(g["Cout"], K, inputs.he_sigma(K), 8, seed=10 * l + i)
+        case = Case(nq, w_int, scale, 8, l)
+        x = x0 if g["Cin"] == 1024 else inputs.relu_activations((64, 14, 14, g["Cin"]), seed=i)[0]
+        for full in (True, False):
+            run_conv_both(nq, case, x, (g["KH"], g["KW"], g["stride"], g["pad"]), full, s_a=float(s0), relu=True,
+                          out_int8=True, inv_s_out=6.0)
+        if i == 2:   # block output: residual added, fp32 out
+            run_conv_both(nq, case, x, (1, 1, 1, 0), True, s_a=float(s0), residual=x0, s_r=float(s0), relu=True)
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_vit_mlp_full_size(nq, idx):
+    # M = 12608 (197 x 64), fc1 768 -> 3072 and fc2 3072 -> 768, INT8 nesting INT5 (l = 3)
+    g = inputs.VIT_MLP[idx]
+    w_int, scale = inputs.weights(g["N"], g["K"], g["sigma"], 8, seed=idx)
+    case = Case(nq, w_int, scale, 8, g["l_bits"])
+    x, s_a = inputs.gaussian_activations((g["M"], g["K"]), seed=idx)
+    bias = inputs.small_floats(g["N"], 0.05, seed=idx)
+    for full in (True, False):
+        run_gemm_both(nq, case, x, full, s_a=float(s_a), bias=bias)
+    run_gemm_both(nq, case, x, True, s_a=float(s_a), bias=bias, out_int8=True, inv_s_out=20.0)
