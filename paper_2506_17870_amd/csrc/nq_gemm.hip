@@ -1,6 +1,8 @@
 // Host side of the inference entry points: argument checks, residency of the lower-bit
 // page (paper Sec. 3.2.3 / 3.3: the caller picks full-bit or part-bit; a paged-out page is
 // an error, never a silent downgrade), tile choice and launch.
+#include <stdlib.h>
+
 #include "nq_common.h"
 #include "nq_gemm_params.h"
 
@@ -158,16 +160,27 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
 
     void *ev0 = g_ev_start, *ev1 = g_ev_stop;
     g_ev_start = g_ev_stop = nullptr;
+    // NQ_KERNEL (tuning and test aid): 1 generic, 2 windowed, 3 register-stationary, 4 large GEMM;
+    // a kernel that does not apply to the shape is never forced, the choice falls through.
+    const char *env = getenv("NQ_KERNEL");
+    const int force = env ? atoi(env) : 0;
+    const bool plain_gemm = g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && w->K % 256 == 0 && aligned16(d_x);
+    if (plain_gemm && (force == 4 || (force == 0 && g.M > 64 && w->N > 64 && w->K >= 256))) {
+        const int64_t blocks = ceil_div(g.M, 96) * ceil_div(w->N, 256);
+        if (blocks > 0x7fffffffLL) return NQ_ERR_SHAPE;
+        NQ_DISPATCH_HL(h, l, launch_nested_gemm_big, full, p, s, ev0, ev1);
+        return launch_status();
+    }
     StreamGeom sg;
     int grid_x = 0;
-    if (plan_rowstream(g, d_x, w->N, &sg, &grid_x)) {
+    if ((force == 0 || force == 3) && plan_rowstream(g, d_x, w->N, &sg, &grid_x)) {
         if (ceil_div(w->N, 32) > 65535) return NQ_ERR_SHAPE;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_rowstream, full, p, sg, grid_x, s, ev0, ev1);
         return launch_status();
     }
     WindowGeom wg;
     size_t lds = 0;
-    if (plan_window(g, d_x, &wg, &lds)) {
+    if ((force == 0 || force == 2) && plan_window(g, d_x, &wg, &lds)) {
         const int64_t blocks_x = (g.M / ((int64_t)g.Ho * g.Wo)) * wg.RB;
         if (blocks_x > 0x7fffffffLL || ceil_div(w->N, 64) > 65535) return NQ_ERR_SHAPE;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_window, full, 0, p, wg, lds, s, ev0, ev1);

@@ -1,0 +1,241 @@
+// Nested-integer GEMM main loop for large problems (paper Sec. 3.3: full-bit = w_high * 2^l +
+// w_low recomposed on the fly, Eq. 4; part-bit = w_high with the scale s * 2^l, Eq. 8).  Also
+// serves 1x1 stride-1 convolutions, which are GEMMs over the NHWC pixels.
+//
+// Block tile (32*TM) x 256, four waves side by side along N (wave tile 32*TM x 64: TM x 2 MFMA
+// tiles of 32 x 32).  The K loop advances 256 at a time: one barrier per four K steps of 64.
+// Activations travel global -> LDS directly (buffer loads with the LDS bit: no registers, no
+// store instructions; rows past M read as zero through the range check), one iteration ahead,
+// into one of two panels of 128 rows x 256 bytes.  A wave-wide LDS-direct load writes 1024
+// contiguous bytes, so rows cannot be padded; instead the 16-byte pieces of row r are stored
+// at position c ^ (r & 7), which lets eight neighbouring rows be read without bank conflicts.
+// Weights: the packed dwords of a lane's own slot, requested four K steps (one iteration) ahead
+// in a rolling register pipeline, decoded in registers and reused for the four row tiles.  All
+// weight loads consumed in an iteration are older than that iteration's activation request, so
+// waiting for them never waits for the slower activation loads.  LDS reads run four fragments
+// ahead of the MFMAs that use them.  With TM <= 4 the kernel stays within 256 registers so that
+// two blocks share a compute unit: one block's prologue, barrier waits and output stores hide
+// behind the other's matrix-core work.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nq_codec.h"
+#include "nq_epilogue.h"
+#include "nq_gemm_kernel.h"
+
+namespace nq {
+
+typedef int g_v4i __attribute__((ext_vector_type(4)));
+typedef int g_v16i __attribute__((ext_vector_type(16)));
+typedef unsigned g_v4u __attribute__((ext_vector_type(4)));
+
+constexpr int GB_BN = 256, GB_KI = 4;                    // K steps of 64 per iteration
+constexpr int GB_ROW = GB_KI * 64;                       // LDS bytes per panel row (swizzled, not padded)
+
+// TM: 32-row tiles per wave (block tile 32*TM x 256); the host picks TM so that the number of
+// blocks fits the 256 compute units with little left over.  TM <= 4 fits two blocks per unit.
+template <int H, int L, bool FULL, bool GENERAL, int TM>
+__global__ void __launch_bounds__(256, (TM <= 4 ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
+{
+    constexpr int GB_BM = 32 * TM;
+    constexpr int GB_PANEL = GB_BM * GB_ROW;             // bytes per LDS panel
+    constexpr int S = 8 - H;
+    constexpr int SHIFT = FULL ? (8 - H - L) : S;
+    constexpr int TN = 2, PD = GB_KI;                    // weights are requested PD K steps ahead
+    constexpr int APT = 2 * TM;                          // LDS-direct loads per wave and iteration (4 rows each)
+
+    extern __shared__ __attribute__((aligned(16))) uint8_t panel[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave index is the same for every lane of a wave: tell the compiler, so that everything
+    // derived from it (tile numbers, page addresses) lives in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // n tiles vary fastest so that blocks running together share their activation rows
+    const int nblocks = (p.N + GB_BN - 1) / GB_BN;
+    const int bm = blockIdx.x / nblocks, bn = blockIdx.x - bm * nblocks;
+    const int64_t m0 = (int64_t)bm * GB_BM;
+    const int n0 = bn * GB_BN;
+
+    const int iters = (p.KB + GB_KI - 1) / GB_KI;
+
+    // ---- activations: descriptor over the rows of this block; rows past M are out of range ----
+    const int64_t rows_here = (p.M - m0) < GB_BM ? (p.M - m0) : GB_BM;
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(p.x) + m0 * p.K, 0, (int)(rows_here * p.K), 0x00020000);
+    // LDS-direct load k of wave w fills panel slots [(APT*w + k)*64, +64) (16 bytes each): lane l
+    // writes row 4*(APT*w + k) + (l >> 4), position l & 15, and therefore fetches piece
+    // c = (l & 15) ^ (row & 7) of that row; APT is even, so row & 7 = (l >> 4) | 4*(k & 1).
+    typedef __attribute__((address_space(3))) void *lds_ptr;
+    int a_goff[2];
+#pragma unroll
+    for (int par = 0; par < 2; ++par)
+        a_goff[par] = (wave * (4 * APT) + (lane >> 4)) * p.K + 16 * ((lane & 15) ^ ((lane >> 4) | (4 * par)));
+    auto load_a = [&](int it, uint8_t *dst) {
+        // An iteration that does not exist is requested out of range, which moves no data.  No branch:
+        // the loop body is the same straight-line code every time, which lets the compiler count
+        // outstanding loads exactly instead of waiting conservatively.
+        const int koff = it < iters ? it * (GB_KI * 64) : 0x7fff0000;
+#pragma unroll
+        for (int k = 0; k < APT; ++k)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_ptr)(dst + (wave * APT + k) * 1024), 16,
+                                                     a_goff[k & 1] + k * 4 * p.K + koff, 0, 0, 0);
+    };
+
+    // ---- weights: rolling pipeline of packed dwords, PD K steps deep --------------------------
+    const int nb0 = n0 / 32 + wave * TN;
+    uint32_t P[PD][TN][H];
+    uint32_t Q[PD][TN][FULL ? L : 1];
+    // K is a multiple of 256 here (host check), so every K step exists.  Column tiles past N read the
+    // last real tile instead: their accumulators are never stored, so no masking is needed.
+    int64_t tile0[TN];
+#pragma unroll
+    for (int t = 0; t < TN; ++t) tile0[t] = (int64_t)min(nb0 + t, p.NB - 1) * p.KB;
+    auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][FULL ? L : 1], int kb) {
+        const int kbc = min(kb, p.KB - 1);               // the refills of the last iteration are never used
+#pragma unroll
+        for (int t = 0; t < TN; ++t) {
+            const uint32_t *src = p.ph + (tile0[t] + kbc) * (H * 64);
+#pragma unroll
+            for (int i = 0; i < H; ++i) Pd[t][i] = src[(unsigned)(i * 64 + lane)];
+            if constexpr (FULL) {
+                const uint32_t *srcl = p.pl + (tile0[t] + kbc) * (L * 64);
+#pragma unroll
+                for (int i = 0; i < L; ++i) Qd[t][i] = srcl[(unsigned)(i * 64 + lane)];
+            }
+        }
+    };
+
+    g_v16i acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][t][r] = 0;
+
+#pragma unroll
+    for (int d = 0; d < PD; ++d) load_b(P[d], Q[d], d);
+    load_a(0, panel);
+
+    // LDS address of the lane's fragment for K step d and half hf: piece c = 4*d + 2*g + hf of row
+    // r sits at position c ^ (r & 7); the row tiles are multiples of 32 rows, so r & 7 = lane & 7.
+    int a_read[2][2];
+    {
+        const int r7 = lane & 7, g = lane >> 5;
+#pragma unroll
+        for (int d0 = 0; d0 < 2; ++d0)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+                a_read[d0][hf] = (lane & 31) * GB_ROW + 16 * (((4 * d0 + 2 * g + hf) ^ r7) & 7);
+    }
+
+    for (int it = 0; it < iters; ++it) {
+        uint8_t *cur = panel + (it & 1) * GB_PANEL;
+        __syncthreads();                                  // panel `cur` has arrived, the other one is free
+        load_a(it + 1, panel + ((it + 1) & 1) * GB_PANEL);   // travels during this iteration
+
+#pragma unroll
+        for (int d = 0; d < GB_KI; ++d) {
+            const int kb = it * GB_KI + d;
+            {
+                g_v4i bfrag[TN][2];
+#pragma unroll
+                for (int t = 0; t < TN; ++t) {
+                    uint32_t D[8];
+                    HighCodec<H>::decode(P[d % PD][t], D);
+                    if constexpr (FULL) LowCodec<L, S>::decode_or(Q[d % PD][t], D);
+#pragma unroll
+                    for (int hf = 0; hf < 2; ++hf)
+                        bfrag[t][hf] = g_v4i{(int)D[4 * hf], (int)D[4 * hf + 1], (int)D[4 * hf + 2], (int)D[4 * hf + 3]};
+                }
+                load_b(P[d % PD], Q[d % PD], kb + PD);   // refill this pipeline slot
+
+                // fragment f = (hf, i): LDS reads four fragments ahead of their MFMAs
+                constexpr int NF = 2 * TM, PF = 4;
+                g_v4i af[PF];
+#pragma unroll
+                for (int f = 0; f < PF; ++f)
+                    af[f] = *reinterpret_cast<const g_v4i *>(cur + a_read[d & 1][f / TM] + (f % TM) * 32 * GB_ROW +
+                                                             128 * (d >> 1));
+#pragma unroll
+                for (int f = 0; f < NF; ++f) {
+                    const int i = f % TM, hf = f / TM;
+                    const g_v4i a = af[f % PF];
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (f + PF < NF)
+                        af[f % PF] = *reinterpret_cast<const g_v4i *>(cur + a_read[d & 1][(f + PF) / TM] +
+                                                                      ((f + PF) % TM) * 32 * GB_ROW + 128 * (d >> 1));
+#pragma unroll
+                    for (int t = 0; t < TN; ++t)
+                        acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bfrag[t][hf], acc[i][t], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue (Eq. 2 / Eq. 8) -----------------------------------------------------------------
+    const int col = lane & 31, rg = lane >> 5;
+#pragma unroll
+    for (int t = 0; t < TN; ++t) {
+        const int nt0 = n0 + (wave * TN + t) * 32;
+        const int n = nt0 + col;
+        if (n >= p.N) continue;
+        const EpiColumn e = epi_column(p, n, FULL);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t row0 = m0 + i * 32;
+            const int64_t left = p.M - row0;
+            const int rows_left = left > 32 ? 32 : (int)left;
+            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left);
+        }
+    }
+}
+
+// Picks the rows per block: cost ~ (rounds of blocks over the compute units) x TM, two blocks
+// sharing a unit counted as 0.85 of running one after the other.
+inline int gemm_big_pick_tm(int64_t M, int64_t N)
+{
+    const int64_t nblocks = (N + GB_BN - 1) / GB_BN;
+    int best = 4;
+    double best_cost = 1e30;
+    for (int tm = 3; tm <= 5; ++tm) {
+        const int64_t blocks = ((M + 32 * tm - 1) / (32 * tm)) * nblocks;
+        const double rounds = (double)((blocks + 255) / 256);
+        const double cost = rounds * tm * (tm <= 4 && blocks > 256 ? 0.85 : 1.0);
+        if (cost < best_cost) { best_cost = cost; best = tm; }
+    }
+    return best;
+}
+
+template <int H, int L>
+void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop)
+{
+    const int nblocks = (p.N + GB_BN - 1) / GB_BN;
+    const bool general = p.acc_dump != nullptr || p.resid != nullptr;
+    const int tm = general ? 4 : gemm_big_pick_tm(p.M, p.N);   // the general epilogue is built for TM = 4 only
+#define NQ_GB_LAUNCH(FULLV, GENV, TMV)                                                      \
+    do {                                                                                    \
+        auto k = k_nested_gemm_big<H, L, FULLV, GENV, TMV>;                                 \
+        const size_t lds = 2 * (size_t)(32 * TMV) * GB_ROW;                                 \
+        const int64_t mblocks = (p.M + 32 * TMV - 1) / (32 * TMV);                          \
+        static bool granted = false;                                                        \
+        if (!granted) {                                                                     \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k),                    \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+            granted = true;                                                                 \
+        }                                                                                   \
+        launch_timed(k, dim3((unsigned)(mblocks * nblocks)), dim3(256), lds, st, ev_start, ev_stop, p); \
+    } while (0)
+#define NQ_GB_TM(FULLV)                                          \
+    do {                                                         \
+        if (general) NQ_GB_LAUNCH(FULLV, true, 4);               \
+        else if (tm == 3) NQ_GB_LAUNCH(FULLV, false, 3);         \
+        else if (tm == 5) NQ_GB_LAUNCH(FULLV, false, 5);         \
+        else NQ_GB_LAUNCH(FULLV, false, 4);                      \
+    } while (0)
+    if (full) NQ_GB_TM(true); else NQ_GB_TM(false);
+}
+
+}  // namespace nq

@@ -74,4 +74,8 @@ template <int H, int L>
 void launch_nested_conv_rowstream(bool full, const GemmParams &p, const StreamGeom &g, int grid_x, hipStream_t st,
                                   void *ev_start, void *ev_stop);
 
+// Large GEMM / 1x1 stride-1 convolution: 128 x 256 tiles, K advanced 256 per barrier.
+template <int H, int L>
+void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop);
+
 }  // namespace nq
