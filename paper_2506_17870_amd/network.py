@@ -1,0 +1,153 @@
+"""A whole quantised CNN on the nested-integer path: ResNet-101 shaped (bottleneck blocks
+[3, 4, 23, 3], stride on the 3x3 convolution, batch norm folded into a bias), random He-normal
+weights, every layer INT-n nesting INT-h.  The paper evaluates such CNNs with 8-bit activations
+(Sec. 4.1, 4.2) and switches the whole model between full-bit and part-bit by paging every
+layer's lower-bit page (Sec. 3.3); it gives no layer code, so the graph below is this
+repository's reading.
+
+This module only describes the graph and walks it, handing each layer to the C ABI
+(`nq_conv_*`, `nq_gemm_*`, `nq_maxpool_i8`, `nq_avgpool_i8`).  Nothing is computed in Python:
+residual add, ReLU and requantisation are part of the fused epilogue.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as nq
+from . import inputs
+
+
+def resnet101_plan(num_classes: int = 1000):
+    """Layer table.  Tensors are numbered; every op names its input/output tensor ids."""
+    ops = []
+    t = 0  # tensor 0 = network input, NHWC int8, 3 channels
+
+    def conv(src, cin, cout, k, stride, pad, relu, residual=None):
+        nonlocal t
+        t += 1
+        ops.append(dict(op="conv", src=src, dst=t, cin=cin, cout=cout, k=k, stride=stride, pad=pad, relu=relu,
+                        residual=residual))
+        return t
+
+    x = conv(0, 3, 64, 7, 2, 3, True)
+    t += 1
+    ops.append(dict(op="maxpool", src=x, dst=t, k=3, stride=2, pad=1))
+    x = t
+    cin = 64
+    for width, blocks, stride in ((64, 3, 1), (128, 4, 2), (256, 23, 2), (512, 3, 2)):
+        for b in range(blocks):
+            s = stride if b == 0 else 1
+            skip = x
+            if b == 0:
+                skip = conv(x, cin, 4 * width, 1, s, 0, False)          # projection shortcut
+            a = conv(x, cin, width, 1, 1, 0, True)
+            m = conv(a, width, width, 3, s, 1, True)
+            x = conv(m, width, 4 * width, 1, 1, 0, True, residual=skip)  # add + ReLU in the epilogue
+            cin = 4 * width
+    t += 1
+    ops.append(dict(op="avgpool", src=x, dst=t))
+    x = t
+    t += 1
+    ops.append(dict(op="fc", src=x, dst=t, cin=cin, cout=num_classes))
+    return ops
+
+
+def plan_weights(ops, n_bits: int = 8, seed: int = 0):
+    """INT-n codes, per-channel steps and a small bias for every conv / fc of the plan (NumPy)."""
+    out = []
+    for i, op in enumerate(ops):
+        if op["op"] not in ("conv", "fc"):
+            out.append(None)
+            continue
+        k = op.get("k", 1)
+        K = k * k * op["cin"]
+        w_int, scale = inputs.weights(op["cout"], K, inputs.he_sigma(K), n_bits, seed=seed + i)
+        bias = inputs.small_floats(op["cout"], 0.02, seed=seed + 7 * i)
+        out.append((w_int, scale, bias))
+    return out
+
+
+def out_hw(h, w, k, stride, pad):
+    return (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1
+
+
+class NestedCNN:
+    """Device-side owner of the nested weights of a plan and walker of the graph."""
+
+    def __init__(self, ops, weights, n_bits=8, l_bits=2):
+        self.ops, self.n_bits, self.l_bits = ops, n_bits, l_bits
+        self.cfg = nq.make_cfg(n_bits, l_bits)
+        self.layers = []
+        for op, w in zip(ops, weights):
+            if w is None:
+                self.layers.append(None)
+                continue
+            w_int, scale, bias = w
+            W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), self.cfg)
+            self.layers.append((W, torch.from_numpy(bias).cuda()))
+        self.out_scale = [None] * (max(op["dst"] for op in ops) + 1)   # step of every int8 tensor
+
+    def low_page_bytes(self) -> int:
+        return sum(nq.nq_packed_bytes(L[0].N, L[0].K, self.l_bits) for L in self.layers if L is not None)
+
+    def page_out_low(self, stream=None):
+        for L in self.layers:
+            if L is not None:
+                nq.nq_page_out_low(L[0].desc, stream)
+
+    def page_in_low(self, copy_stream=None):
+        for L in self.layers:
+            if L is not None:
+                nq.nq_page_in_low(L[0].desc, copy_stream)
+
+    def forward(self, x, in_scale: float, full: bool, calibrate: bool = False, keep=None):
+        """x: int8 NHWC device tensor.  Returns the fp32 logits [B, classes].
+        calibrate=True first runs every layer with fp32 output to fix its int8 step (absmax / 127)."""
+        B, H, W, _ = x.shape
+        tensors = {0: (x, H, W)}
+        self.out_scale[0] = float(in_scale)
+        logits = None
+        for op, L in zip(self.ops, self.layers):
+            src, hs, ws = tensors[op["src"]]
+            s_in = self.out_scale[op["src"]]
+            if op["op"] == "maxpool":
+                ho, wo = out_hw(hs, ws, op["k"], op["stride"], op["pad"])
+                y = torch.empty((B, ho, wo, src.shape[3]), dtype=torch.int8, device="cuda")
+                nq.nq_maxpool_i8(src, B, hs, ws, src.shape[3], op["k"], op["stride"], op["pad"], y)
+                self.out_scale[op["dst"]] = s_in
+                tensors[op["dst"]] = (y, ho, wo)
+            elif op["op"] == "avgpool":
+                C = src.shape[3]
+                if calibrate:
+                    self.out_scale[op["dst"]] = s_in            # a mean never exceeds the maximum
+                y = torch.empty((B, 1, 1, C), dtype=torch.int8, device="cuda")
+                nq.nq_avgpool_i8(src, B, hs * ws, C, s_in, 1.0 / self.out_scale[op["dst"]], y)
+                tensors[op["dst"]] = (y, 1, 1)
+            elif op["op"] == "fc":
+                Wt, bias = L
+                y = torch.empty((B, op["cout"]), dtype=torch.float32, device="cuda")
+                epi = nq.make_epilogue(s_in, bias)
+                (nq.nq_gemm_full if full else nq.nq_gemm_part)(src.view(B, -1), B, Wt.desc, epi, y)
+                logits = y
+            else:
+                Wt, bias = L
+                ho, wo = out_hw(hs, ws, op["k"], op["stride"], op["pad"])
+                shape = nq.nq_conv_shape(B, hs, ws, op["cin"], op["cout"], op["k"], op["k"], op["stride"], op["pad"])
+                res, s_r = None, 0.0
+                if op["residual"] is not None:
+                    res, s_r = tensors[op["residual"]][0], self.out_scale[op["residual"]]
+                fn = nq.nq_conv_full if full else nq.nq_conv_part
+                if calibrate:
+                    yf = torch.empty((B, ho, wo, op["cout"]), dtype=torch.float32, device="cuda")
+                    fn(src, shape, Wt.desc, nq.make_epilogue(s_in, bias, res, s_r, op["relu"]), yf)
+                    amax = float(yf.abs().max())
+                    self.out_scale[op["dst"]] = (amax / 127.0) if amax > 0 else 1.0
+                    del yf
+                y = torch.empty((B, ho, wo, op["cout"]), dtype=torch.int8, device="cuda")
+                epi = nq.make_epilogue(s_in, bias, res, s_r, op["relu"], True, 1.0 / self.out_scale[op["dst"]])
+                fn(src, shape, Wt.desc, epi, y)
+                tensors[op["dst"]] = (y, ho, wo)
+            if keep is not None:
+                keep[op["dst"]] = tensors.get(op["dst"], (logits,))[0]
+        return logits
