@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Per-configuration measurements behind the tables of the design doc and profiles/ (bench.py stays the one-line
+benchmark).  Every kernel time is the begin/end time stamp of the dispatch itself; buffers are rotated so that
+activations and outputs come from HBM, not from the Infinity Cache.
+
+    python bench_configs.py [c1] [c2] [c3] [c4] [c5] [pack] [page]
+"""
+from __future__ import annotations
+
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2506_17870_amd as nq  # noqa: E402
+from paper_2506_17870_amd import inputs, network  # noqa: E402
+
+MFMA_PEAK, HBM_PEAK = 5000.0, 8000.0   # TOPS (int8 dense), GB/s
+
+
+def kernel_us(fn, n=30):
+    """Median and minimum dispatch duration of the GEMM/conv launch made by fn(events)."""
+    for _ in range(5):
+        fn(None)
+    torch.cuda.synchronize()
+    evs = [(nq.nq_event_create(), nq.nq_event_create()) for _ in range(n)]
+    for a, b in evs:
+        fn((a, b))
+    torch.cuda.synchronize()
+    ts = sorted(nq.nq_event_elapsed_ms(a, b) * 1e3 for a, b in evs)
+    for a, b in evs:
+        nq.nq_event_destroy(a)
+        nq.nq_event_destroy(b)
+    return ts[len(ts) // 2], ts[0]
+
+
+def wall_us(fn, n=50):
+    """Back-to-back launches between two stream events (for kernels without the time-stamp hook)."""
+    for _ in range(5):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / n
+
+
+def row(name, mode, us, ops, byts):
+    tops = ops / us / 1e6
+    gbs = byts / us / 1e3
+    print(f"| {name} | {mode} | {us:.2f} | {tops:.1f} | {100 * tops / MFMA_PEAK:.1f} | {gbs:.0f} | {100 * gbs / HBM_PEAK:.1f} |")
+
+
+def header(title):
+    print(f"\n### {title}\n")
+    print("| layer | mode | kernel us | TOPS | % int8 MFMA peak | algorithmic GB/s | % HBM peak |")
+    print("|---|---|---|---|---|---|---|")
+
+
+def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02):
+    w_int, scale = inputs.weights(N, K, sigma, 8, 0)
+    W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
+    xs = [torch.from_numpy(inputs.uniform_activations((M, K), i)).cuda() for i in range(sets)]
+    ys = [torch.empty((M, N), dtype=torch.int8 if out8 else torch.float32, device="cuda") for _ in range(sets)]
+    epi = nq.make_epilogue(0.02, out_int8=out8, inv_out_scale=3.0)
+    for full in (True, False):
+        cnt = [0]
+
+        def fn(ev):
+            i = cnt[0] % sets
+            cnt[0] += 1
+            if ev:
+                nq.nq_profile_next_launch(ev[0], ev[1])
+            (nq.nq_gemm_full if full else nq.nq_gemm_part)(xs[i], M, W.desc, epi, ys[i])
+        med, _ = kernel_us(fn)
+        wb = nq.nq_packed_bytes(N, K, 8 - l) + (nq.nq_packed_bytes(N, K, l) if full else 0)
+        row(name, ("full" if full else "part") + (" int8 out" if out8 else " fp32 out"), med, 2.0 * M * N * K,
+            M * K + wb + M * N * (1 if out8 else 4))
+
+
+def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4):
+    K = k * k * Cin
+    w_int, scale = inputs.weights(Cout, K, inputs.he_sigma(K), 8, 0)
+    W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
+    Ho, Wo = network.out_hw(H, W_, k, stride, pad)
+    xs = [torch.from_numpy(inputs.uniform_activations((B, H, W_, Cin), i)).cuda() for i in range(sets)]
+    ys = [torch.empty((B, Ho, Wo, Cout), dtype=torch.int8 if out8 else torch.float32, device="cuda")
+          for _ in range(sets)]
+    epi = nq.make_epilogue(0.02, relu=True, out_int8=out8, inv_out_scale=3.0)
+    cs = nq.nq_conv_shape(B, H, W_, Cin, Cout, k, k, stride, pad)
+    for full in (True, False):
+        cnt = [0]
+
+        def fn(ev):
+            i = cnt[0] % sets
+            cnt[0] += 1
+            if ev:
+                nq.nq_profile_next_launch(ev[0], ev[1])
+            (nq.nq_conv_full if full else nq.nq_conv_part)(xs[i], cs, W.desc, epi, ys[i])
+        med, _ = kernel_us(fn)
+        M = B * Ho * Wo
+        wb = nq.nq_packed_bytes(Cout, K, 8 - l) + (nq.nq_packed_bytes(Cout, K, l) if full else 0)
+        row(name, ("full" if full else "part") + (" int8 out" if out8 else " fp32 out"), med, 2.0 * M * Cout * K,
+            B * H * W_ * Cin + wb + M * Cout * (1 if out8 else 4))
+
+
+def c1():
+    header("config 1: linear 64x512 -> 512 (launch bound) and a weight-bound stand-in (M = 64, 8192 x 8192)")
+    gemm("64x512->512 l=2", 64, 512, 512, 2)
+    gemm("64x8192->8192 l=2", 64, 8192, 8192, 2, sets=3)
+
+
+def c2():
+    header("config 2: ResNet-18 3x3 conv, batch 32, 56x56x64 -> 64, l=2")
+    conv("3x3 64->64", 32, 56, 56, 64, 64, 3, 1, 1, 2, out8=False, sets=8)
+    conv("3x3 64->64", 32, 56, 56, 64, 64, 3, 1, 1, 2, out8=True, sets=8)
+
+
+def c3():
+    header("config 3: ResNet-101 stage-3 bottleneck, batch 64, 14x14")
+    for l in (2, 4):
+        conv(f"1x1 1024->256 l={l}", 64, 14, 14, 1024, 256, 1, 1, 0, l)
+        conv(f"3x3 256->256 l={l}", 64, 14, 14, 256, 256, 3, 1, 1, l)
+        conv(f"1x1 256->1024 l={l}", 64, 14, 14, 256, 1024, 1, 1, 0, l)
+    conv("1x1 256->1024 l=2", 64, 14, 14, 256, 1024, 1, 1, 0, 2, out8=False)
+
+
+def c5():
+    header("config 5: ViT-B/16 MLP at batch 64 (M = 12608), l=3")
+    gemm("fc1 768->3072", 12608, 768, 3072, 3)
+    gemm("fc1 768->3072", 12608, 768, 3072, 3, out8=True)
+    gemm("fc2 3072->768", 12608, 3072, 768, 3)
+    gemm("fc2 3072->768", 12608, 3072, 768, 3, out8=True)
+
+
+def c4():
+    print("\n### config 4: ResNet-101 conv/fc stack, batch 128, 224x224x3, all layers INT(8|6)\n")
+    ops = network.resnet101_plan()
+    weights = network.plan_weights(ops, 8, seed=0)
+    model = network.NestedCNN(ops, weights, 8, 2)
+    B = 128
+    x, s_x = inputs.gaussian_activations((B, 224, 224, 3), seed=0)
+    dx = torch.from_numpy(x).cuda()
+    model.forward(dx, s_x, full=True, calibrate=True)
+    torch.cuda.synchronize()
+    macs = 0
+    h = w = 224
+    hw = {0: (224, 224)}
+    for op in ops:
+        hs, ws = hw[op["src"]]
+        if op["op"] == "conv":
+            ho, wo = network.out_hw(hs, ws, op["k"], op["stride"], op["pad"])
+            macs += ho * wo * op["cout"] * op["k"] ** 2 * op["cin"]
+            hw[op["dst"]] = (ho, wo)
+        elif op["op"] == "maxpool":
+            hw[op["dst"]] = network.out_hw(hs, ws, op["k"], op["stride"], op["pad"])
+        elif op["op"] == "avgpool":
+            hw[op["dst"]] = (1, 1)
+        else:
+            macs += op["cin"] * op["cout"]
+    ops_fwd = 2.0 * macs * B
+
+    def fwd(full):
+        for _ in range(2):
+            model.forward(dx, s_x, full=full)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        n = 5
+        for _ in range(n):
+            model.forward(dx, s_x, full=full)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e3
+    ms_full = fwd(True)
+    print(f"* full-bit forward: {ms_full:.2f} ms per batch of {B} ({ops_fwd / ms_full / 1e9:.1f} TOPS, "
+          f"{macs / 1e9:.2f} GMAC per image)")
+    t0 = time.perf_counter()
+    model.page_out_low()
+    t_out = (time.perf_counter() - t0) * 1e6
+    ms_part = fwd(False)
+    print(f"* downgrade (nq_page_out_low on 105 layers): {t_out:.0f} us of host time, nothing moved")
+    print(f"* part-bit forward: {ms_part:.2f} ms ({ops_fwd / ms_part / 1e9:.1f} TOPS)")
+    side = torch.cuda.Stream()
+    low = model.low_page_bytes()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    model.page_in_low(side)
+    side.synchronize()
+    t_in = (time.perf_counter() - t0) * 1e6
+    print(f"* upgrade (nq_page_in_low, {low / 1e6:.2f} MB in 105 pinned copies on a second stream): {t_in:.0f} us "
+          f"= {low / t_in / 1e3:.1f} GB/s host to device")
+    model.page_out_low()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    model.page_in_low(side)
+    model.forward(dx, s_x, full=True)
+    torch.cuda.synchronize()
+    print(f"* upgrade + first full-bit forward: {(time.perf_counter() - t0) * 1e3:.2f} ms")
+
+
+def pack():
+    print("\n### decompose-and-pack (1 B read + 1 B written per weight)\n")
+    print("| tensor | us | GB/s (read+write) | % HBM peak |")
+    print("|---|---|---|---|")
+    cfg = nq.make_cfg(8, 2)
+    for name, N, K in (("ResNet-101 largest layer 512x4608", 512, 4608), ("4096 x 4096", 4096, 4096),
+                       ("1 GiB: 32768 x 32768", 32768, 32768)):
+        w = torch.randint(-128, 128, (N, K), dtype=torch.int8, device="cuda")
+        ph = torch.empty(nq.nq_packed_bytes(N, K, 6), dtype=torch.uint8, device="cuda")
+        pl = torch.empty(nq.nq_packed_bytes(N, K, 2), dtype=torch.uint8, device="cuda")
+        us = wall_us(lambda: nq.nq_decompose_pack(w, N, K, cfg, ph, pl), n=20)
+        gbs = 2.0 * N * K / us / 1e3
+        print(f"| {name} | {us:.1f} | {gbs:.0f} | {100 * gbs / HBM_PEAK:.1f} |")
+        del w, ph, pl
+
+
+def page():
+    print("\n### page-in of the lower-bit page (pinned host -> device, `nq_page_in_low`)\n")
+    print("| page | us | GB/s |")
+    print("|---|---|---|")
+    for name, N, K, l in (("ViT fc1 low page l=3 (0.88 MB)", 3072, 768, 3), ("64 MiB page", 16384, 16384, 2)):
+        cfg = nq.make_cfg(8, l)
+        W = nq.NestedWeight(N, K, cfg)
+        side = torch.cuda.Stream()
+        best = 1e30
+        for _ in range(10):
+            nq.nq_page_out_low(W.desc)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            nq.nq_page_in_low(W.desc, side)
+            side.synchronize()
+            best = min(best, (time.perf_counter() - t0) * 1e6)
+        b = nq.nq_packed_bytes(N, K, l)
+        print(f"| {name} | {best:.0f} | {b / best / 1e3:.1f} |")
+    # overlap: part-bit GEMMs on the compute stream while the page is copied on the other stream
+    M, K, N, l = 12608, 3072, 768, 3
+    w_int, scale = inputs.weights(N, K, 0.02, 8, 0)
+    W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
+    x = torch.from_numpy(inputs.uniform_activations((M, K), 0)).cuda()
+    y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    epi = nq.make_epilogue(0.02)
+    side = torch.cuda.Stream()
+    alone = wall_us(lambda: nq.nq_gemm_part(x, M, W.desc, epi, y), n=30)
+
+    def both():
+        nq.nq_page_out_low(W.desc)
+        nq.nq_page_in_low(W.desc, side)
+        nq.nq_gemm_part(x, M, W.desc, epi, y)
+    with_copy = wall_us(both, n=30)
+    print(f"\npart-bit fc2 GEMM alone {alone:.1f} us; with a concurrent page-in of its 0.88 MB page {with_copy:.1f} us")
+
+
+if __name__ == "__main__":
+    torch.cuda.set_device(0)
+    which = sys.argv[1:] or ["c1", "c2", "c3", "c4", "c5", "pack", "page"]
+    for name in which:
+        {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "pack": pack, "page": page}[name]()

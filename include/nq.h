@@ -112,7 +112,7 @@ typedef struct {
     void *free_event;       /* internal: hipEvent_t made by nq_weight_init; "readers of   */
                             /* the page enqueued before nq_page_out_low are done"         */
     int32_t free_event_armed;
-    int32_t reserved;
+    int32_t events_borrowed;/* internal: the events belong to the head of a group           */
 } nq_weight;
 
 /* Fused epilogue of the GEMM / convolution (Eq. 2 and Eq. 8), fp32, in this order with
@@ -197,6 +197,17 @@ nq_status nq_page_out_low(nq_weight *w, void *stream);
  * work running on another stream), records the internal event and marks the page
  * resident.  Later full-bit calls make their stream wait for that event. */
 nq_status nq_page_in_low(nq_weight *w, void *copy_stream);
+
+/* Switching a whole model (Sec. 3.3: the full-bit MODEL downgrades to the part-bit MODEL and
+ * back).  nq_weight_init_group initialises `count` descriptors that share one pair of internal
+ * events owned by ws[0] (destroy ws[0] last).  The batch calls do for all of them what the
+ * single calls do for one, with one event operation in all; nq_page_in_low_batch merges the
+ * copies of pages that follow each other without a gap in both host and device memory (pages
+ * carved in the same order out of one pinned arena and one device arena) into single transfers,
+ * so a model is paged in with a few large copies instead of one small copy per layer. */
+nq_status nq_weight_init_group(nq_weight *const *ws, int64_t count);
+nq_status nq_page_out_low_batch(nq_weight *const *ws, int64_t count, void *stream);
+nq_status nq_page_in_low_batch(nq_weight *const *ws, int64_t count, void *copy_stream);
 
 /* ---- inference (Sec. 3.3, Eq. 2, Eq. 4, Eq. 8) -------------------------------------- */
 /* Y[M][N] = epilogue( sum_k X[m][k] * (w_high[n][k] * 2^l + w_low[n][k]) ).

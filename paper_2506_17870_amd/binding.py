@@ -24,6 +24,7 @@ NQ_MAX_K = 65536
 
 EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_decompose", "nq_pack", "nq_decompose_pack",
            "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
+           "nq_weight_init_group", "nq_page_out_low_batch", "nq_page_in_low_batch",
            "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_profile_next_launch", "nq_event_create", "nq_event_destroy",
            "nq_event_elapsed_ms", "nq_maxpool_i8", "nq_avgpool_i8"]
 
@@ -40,7 +41,7 @@ class nq_weight(ctypes.Structure):
                 ("h_low", ctypes.c_void_p), ("d_scale", ctypes.c_void_p),
                 ("low_resident", ctypes.c_int32), ("low_event_armed", ctypes.c_int32),
                 ("low_event", ctypes.c_void_p), ("free_event", ctypes.c_void_p),
-                ("free_event_armed", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("free_event_armed", ctypes.c_int32), ("events_borrowed", ctypes.c_int32)]
 
 
 class nq_epilogue(ctypes.Structure):
@@ -75,6 +76,9 @@ _SIGS = {
     "nq_weight_destroy": (_int, [_wp]),
     "nq_page_out_low": (_int, [_wp, _vp]),
     "nq_page_in_low": (_int, [_wp, _vp]),
+    "nq_weight_init_group": (_int, [ctypes.POINTER(_wp), _i64]),
+    "nq_page_out_low_batch": (_int, [ctypes.POINTER(_wp), _i64, _vp]),
+    "nq_page_in_low_batch": (_int, [ctypes.POINTER(_wp), _i64, _vp]),
     "nq_gemm_full": (_int, [_vp, _i64, _wp, _ep, _vp, _vp]),
     "nq_gemm_part": (_int, [_vp, _i64, _wp, _ep, _vp, _vp]),
     "nq_conv_full": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
@@ -171,6 +175,23 @@ def nq_page_in_low(w: nq_weight, copy_stream=None):
     _check(_lib.nq_page_in_low(ctypes.byref(w), _stream(copy_stream)), "nq_page_in_low")
 
 
+def _wlist(ws):
+    arr = (_wp * len(ws))(*[ctypes.pointer(w) for w in ws])
+    return arr
+
+
+def nq_weight_init_group(ws):
+    _check(_lib.nq_weight_init_group(_wlist(ws), len(ws)), "nq_weight_init_group")
+
+
+def nq_page_out_low_batch(ws, stream=None):
+    _check(_lib.nq_page_out_low_batch(_wlist(ws), len(ws), _stream(stream)), "nq_page_out_low_batch")
+
+
+def nq_page_in_low_batch(ws, copy_stream=None):
+    _check(_lib.nq_page_in_low_batch(_wlist(ws), len(ws), _stream(copy_stream)), "nq_page_in_low_batch")
+
+
 def make_epilogue(act_scale=1.0, d_bias=None, d_residual=None, residual_scale=0.0, relu=False, out_int8=False,
                   inv_out_scale=1.0, d_acc_dump=None) -> nq_epilogue:
     return nq_epilogue(act_scale, _ptr(d_bias), _ptr(d_residual), residual_scale, int(relu), int(out_int8),
@@ -237,28 +258,36 @@ class NestedWeight:
     the lower-bit page once to the pinned host buffer (the "storage" it is paged in from).
     """
 
-    def __init__(self, N, K, cfg: nq_cfg, device="cuda"):
+    def __init__(self, N, K, cfg: nq_cfg, device="cuda", low=None, low_host=None, init=True):
+        """low / low_host: optional uint8 views (device / pinned host) to use for the lower-bit page, e.g.
+        slices of two arenas so that a whole model can be paged in with few copies."""
         h = cfg.n_bits - cfg.l_bits
         self.cfg, self.N, self.K = cfg, N, K
+        low_bytes = max(nq_packed_bytes(N, K, cfg.l_bits, cfg.layout), 16)
         self.high = torch.empty(max(nq_packed_bytes(N, K, h, cfg.layout), 16), dtype=torch.uint8, device=device)
-        self.low = torch.empty(max(nq_packed_bytes(N, K, cfg.l_bits, cfg.layout), 16), dtype=torch.uint8,
-                               device=device)
-        self.low_host = torch.empty(self.low.numel(), dtype=torch.uint8, pin_memory=True)
+        self.low = low if low is not None else torch.empty(low_bytes, dtype=torch.uint8, device=device)
+        self.low_host = low_host if low_host is not None else torch.empty(low_bytes, dtype=torch.uint8,
+                                                                          pin_memory=True)
+        assert self.low.numel() == low_bytes and self.low_host.numel() == low_bytes
         self.scale = torch.ones(max(N, 1), dtype=torch.float32, device=device)
         self.desc = nq_weight(cfg, N, K, self.high.data_ptr(), self.high.numel(), self.low.data_ptr(),
                               self.low.numel(), self.low_host.data_ptr(), self.scale.data_ptr(), 0, 0, None, None, 0, 0)
-        nq_weight_init(self.desc)
+        if init:
+            nq_weight_init(self.desc)
+
+    def fill_from_int8(self, d_w_int, d_scale, stream=None):
+        """nq_decompose_pack on the device, then the master copy of the lower-bit page to the host."""
+        nq_decompose_pack(d_w_int, self.N, self.K, self.cfg, self.high, self.low, stream)
+        self.scale.copy_(d_scale)
+        self.low_host.copy_(self.low)
+        torch.cuda.synchronize()
+        self.desc.low_resident = 1
+        return self
 
     @classmethod
     def from_int8(cls, d_w_int, d_scale, cfg: nq_cfg, stream=None):
         N, K = d_w_int.shape
-        self = cls(N, K, cfg, device=d_w_int.device)
-        nq_decompose_pack(d_w_int, N, K, cfg, self.high, self.low, stream)
-        self.scale.copy_(d_scale)
-        self.low_host.copy_(self.low)          # device -> pinned host, the master copy
-        torch.cuda.synchronize()
-        self.desc.low_resident = 1             # the page was written on the device
-        return self
+        return cls(N, K, cfg, device=d_w_int.device).fill_from_int8(d_w_int, d_scale, stream)
 
     def close(self):
         if self.desc.low_event:

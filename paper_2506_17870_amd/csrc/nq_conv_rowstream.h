@@ -156,6 +156,13 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
             const int u = u0 + j * (int)gridDim.x;
             if (u < g.units) {
                 const uint8_t *buf = win + j * g.win_stride;
+                // the unit's residual codes travel while its MFMAs run
+                const int oh0 = cur_rb[j] * g.R;
+                const int pix = min(g.R, p.Ho - oh0) * p.Wo;
+                const int64_t m_base = ((int64_t)cur_b[j] * p.Ho + oh0) * p.Wo;
+                int res[16];
+                epi_resid_load<GENERAL>(p, (m_base + wave * 32) * p.N + n0, (unsigned)(4 * rg * p.N + col), rg,
+                                        n0 + col < p.N ? pix - wave * 32 : 0, res);
                 r_v16i acc;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[r] = 0;
@@ -182,12 +189,9 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
                 }
 
                 // ---- epilogue (Eq. 2 / Eq. 8) ----------------------------------------------------------
-                const int oh0 = cur_rb[j] * g.R;
-                const int pix = min(g.R, p.Ho - oh0) * p.Wo;
-                const int64_t m_base = ((int64_t)cur_b[j] * p.Ho + oh0) * p.Wo;
                 if (n0 + col < p.N)
                     epi_tile<GENERAL>(p, acc, SHIFT, ec, (m_base + wave * 32) * p.N + n0, (unsigned)(4 * rg * p.N + col),
-                                      rg, pix - wave * 32);
+                                      rg, pix - wave * 32, res);
             }
         }
         __syncthreads();   // all windows of the round are free again

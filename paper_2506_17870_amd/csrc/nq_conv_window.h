@@ -179,9 +179,19 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
         }
     }
 
-    // ---- epilogue (Eq. 2 / Eq. 8) -------------------------------------------------------------
+    // ---- epilogue (Eq. 2 / Eq. 8): residual codes of all tiles first, then the arithmetic -------
     const int64_t m_base = (b * p.Ho + oh0) * (int64_t)p.Wo;   // whole rows: local pixel -> m is an offset
     const int col = lane & 31, rg = lane >> 5;
+    int res[GENERAL ? TM * TN : 1][16];
+#pragma unroll
+    for (int t = 0; t < TN; ++t)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int nt0 = n0 + (wn * TN + t) * 32;
+            const int pl0 = (wm * TM + i) * 32;
+            epi_resid_load<GENERAL>(p, (m_base + pl0) * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg,
+                                    nt0 + col < p.N ? pix - pl0 : 0, res[GENERAL ? t * TM + i : 0]);
+        }
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int n = n0 + (wn * TN + t) * 32 + col;
@@ -191,7 +201,8 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
         for (int i = 0; i < TM; ++i) {
             const int pl0 = (wm * TM + i) * 32;
             const int nt0 = n0 + (wn * TN + t) * 32;
-            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, (m_base + pl0) * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, pix - pl0);
+            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, (m_base + pl0) * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg,
+                              pix - pl0, res[GENERAL ? t * TM + i : 0]);
         }
     }
 }

@@ -36,8 +36,9 @@ __device__ __forceinline__ EpiColumn epi_column(const GemmParams &p, int n, bool
 // the address is a scalar base plus a 32-bit lane offset; o_lane = 4*rg*N + column; rows_left:
 // how many tile rows, counted from tile row 0, are real outputs.
 template <bool OUT8, bool RESID, bool DUMP, bool WHOLE>
-__device__ __forceinline__ void epi_tile_rows(const GemmParams &p, const e_v16i &acc, int shift, const EpiColumn &e,
-                                              int64_t o_tile, unsigned o_lane, int rg, int rows_left)
+__device__ __forceinline__ void epi_tile_rows(const GemmParams &p, const e_v16i acc, int shift, const EpiColumn &e,
+                                              int64_t o_tile, unsigned o_lane, int rg, int rows_left,
+                                              const int (&res)[16])
 {
     // Opaque to the optimiser: otherwise the sixteen row offsets of every specialisation are
     // hoisted out of the caller's loops and held in registers for the whole kernel.
@@ -45,7 +46,6 @@ __device__ __forceinline__ void epi_tile_rows(const GemmParams &p, const e_v16i 
     const float lo = p.relu ? 0.0f : -__builtin_inff();
     float *yf = reinterpret_cast<float *>(p.y) + o_tile;
     int8_t *yq = reinterpret_cast<int8_t *>(p.y) + o_tile;
-    const int8_t *rq = p.resid + o_tile;
     int32_t *dq = p.acc_dump + o_tile;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -57,7 +57,7 @@ __device__ __forceinline__ void epi_tile_rows(const GemmParams &p, const e_v16i 
             float y = (float)a * e.c;
             y = y + e.bias;
             if (RESID) {
-                const float rv = p.resid_scale * (float)rq[off];
+                const float rv = p.resid_scale * (float)res[r];
                 y = y + rv;
             }
             y = fmaxf(y, lo);
@@ -72,43 +72,72 @@ __device__ __forceinline__ void epi_tile_rows(const GemmParams &p, const e_v16i 
     }
 }
 
-// A tile whose 32 rows are all real outputs (the usual case) carries no per-element test.
-template <bool OUT8, bool RESID, bool DUMP>
-__device__ __forceinline__ void epi_tile_impl(const GemmParams &p, const e_v16i &acc, int shift, const EpiColumn &e,
-                                              int64_t o_tile, unsigned o_lane, int rg, int rows_left)
+// A tile whose 32 rows are all real outputs (the usual case) carries no per-element test.  The
+// general kernels use the tested form only: with both forms of all their bodies the unrolled
+// epilogue of a block would exceed what the compiler is willing to unroll, and accumulators
+// indexed by a loop variable would fall out of the registers.
+template <bool OUT8, bool RESID, bool DUMP, bool BOTH_FORMS>
+__device__ __forceinline__ void epi_tile_impl(const GemmParams &p, const e_v16i acc, int shift, const EpiColumn &e,
+                                              int64_t o_tile, unsigned o_lane, int rg, int rows_left,
+                                              const int (&res)[16])
 {
-    if (rows_left >= 32) epi_tile_rows<OUT8, RESID, DUMP, true>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-    else if (rows_left > 0) epi_tile_rows<OUT8, RESID, DUMP, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
+    if (BOTH_FORMS && rows_left >= 32)
+        epi_tile_rows<OUT8, RESID, DUMP, true>(p, acc, shift, e, o_tile, o_lane, rg, rows_left, res);
+    else if (rows_left > 0)
+        epi_tile_rows<OUT8, RESID, DUMP, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left, res);
+}
+
+// Requests the residual codes of one tile (general kernels only).  Kernels call this for all
+// their tiles before the first epi_tile, so that the loads of every tile are in flight together
+// instead of one memory latency being paid per tile.
+template <bool GENERAL>
+__device__ __forceinline__ void epi_resid_load(const GemmParams &p, int64_t o_tile, unsigned o_lane, int rg,
+                                               int rows_left, int (&res)[16])
+{
+    if constexpr (GENERAL) {
+        if (p.resid) {
+            const int8_t *rq = p.resid + o_tile;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 8 * (r >> 2) + (r & 3);
+                res[r] = 0;
+                if (row + 4 * rg < rows_left) res[r] = rq[o_lane + (unsigned)(row * p.N)];
+            }
+        }
+    }
+}
+
+// Test aid: the raw int32 accumulators of a tile (after the exact shift), predicated per row.
+__device__ __forceinline__ void epi_dump(const GemmParams &p, const e_v16i acc, int shift, int64_t o_tile,
+                                         unsigned o_lane, int rg, int rows_left)
+{
+    int32_t *dq = p.acc_dump + o_tile;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + (r & 3);
+        if (row + 4 * rg < rows_left) dq[o_lane + (unsigned)(row * p.N)] = acc[r] >> shift;
+    }
 }
 
 // Chooses the specialisation once per tile (uniform branches), not once per element.
 // GENERAL = false: the kernel was launched for a plain epilogue (fp32 or int8 output, no
 // residual, no accumulator dump) and carries only those two bodies, which keeps the hot kernels
-// short of registers pressure; GENERAL = true kernels handle every combination.
+// short of register pressure; GENERAL = true kernels add the residual bodies and the dump pass.
 template <bool GENERAL>
-__device__ __forceinline__ void epi_tile(const GemmParams &p, const e_v16i &acc, int shift, const EpiColumn &e,
-                                         int64_t o_tile, unsigned o_lane, int rg, int rows_left)
+__device__ __forceinline__ void epi_tile(const GemmParams &p, const e_v16i acc, int shift, const EpiColumn &e,
+                                         int64_t o_tile, unsigned o_lane, int rg, int rows_left,
+                                         const int (&res)[16])
 {
-    if constexpr (!GENERAL) {
-        if (p.out_int8) epi_tile_impl<true, false, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-        else epi_tile_impl<false, false, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-    } else if (p.acc_dump) {
-        if (p.out_int8) {
-            if (p.resid) epi_tile_impl<true, true, true>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-            else epi_tile_impl<true, false, true>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-        } else {
-            if (p.resid) epi_tile_impl<false, true, true>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-            else epi_tile_impl<false, false, true>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-        }
-    } else {
-        if (p.out_int8) {
-            if (p.resid) epi_tile_impl<true, true, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-            else epi_tile_impl<true, false, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-        } else {
-            if (p.resid) epi_tile_impl<false, true, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
-            else epi_tile_impl<false, false, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left);
+    if constexpr (GENERAL) {
+        if (p.acc_dump) epi_dump(p, acc, shift, o_tile, o_lane, rg, rows_left);
+        if (p.resid) {
+            if (p.out_int8) epi_tile_impl<true, true, false, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left, res);
+            else epi_tile_impl<false, true, false, false>(p, acc, shift, e, o_tile, o_lane, rg, rows_left, res);
+            return;
         }
     }
+    if (p.out_int8) epi_tile_impl<true, false, false, !GENERAL>(p, acc, shift, e, o_tile, o_lane, rg, rows_left, res);
+    else epi_tile_impl<false, false, false, !GENERAL>(p, acc, shift, e, o_tile, o_lane, rg, rows_left, res);
 }
 
 }  // namespace nq

@@ -34,9 +34,10 @@ constexpr int GB_BN = 256, GB_KI = 4;                    // K steps of 64 per it
 constexpr int GB_ROW = GB_KI * 64;                       // LDS bytes per panel row (swizzled, not padded)
 
 // TM: 32-row tiles per wave (block tile 32*TM x 256); the host picks TM so that the number of
-// blocks fits the 256 compute units with little left over.  TM <= 4 fits two blocks per unit.
+// blocks fits the 256 compute units with little left over.  TM <= 4 fits two blocks per unit
+// (the general epilogue needs more registers and runs one block per unit rather than spill).
 template <int H, int L, bool FULL, bool GENERAL, int TM>
-__global__ void __launch_bounds__(256, (TM <= 4 ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
+__global__ void __launch_bounds__(256, (TM <= 4 && !GENERAL ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
 {
     constexpr int GB_BM = 32 * TM;
     constexpr int GB_PANEL = GB_BM * GB_ROW;             // bytes per LDS panel
@@ -175,8 +176,20 @@ __global__ void __launch_bounds__(256, (TM <= 4 ? 2 : 1)) k_nested_gemm_big(cons
         }
     }
 
-    // ---- epilogue (Eq. 2 / Eq. 8) -----------------------------------------------------------------
+    // ---- epilogue (Eq. 2 / Eq. 8): residual codes of all tiles first, then the arithmetic -------
     const int col = lane & 31, rg = lane >> 5;
+    int res[GENERAL ? TM * TN : 1][16];
+#pragma unroll
+    for (int t = 0; t < TN; ++t)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int nt0 = n0 + (wave * TN + t) * 32;
+            const int64_t row0 = m0 + i * 32;
+            const int64_t left = p.M - row0;
+            const int rows_left = nt0 + col < p.N ? (left > 32 ? 32 : (int)left) : 0;
+            epi_resid_load<GENERAL>(p, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left,
+                                    res[GENERAL ? t * TM + i : 0]);
+        }
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int nt0 = n0 + (wave * TN + t) * 32;
@@ -188,7 +201,8 @@ __global__ void __launch_bounds__(256, (TM <= 4 ? 2 : 1)) k_nested_gemm_big(cons
             const int64_t row0 = m0 + i * 32;
             const int64_t left = p.M - row0;
             const int rows_left = left > 32 ? 32 : (int)left;
-            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left);
+            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left,
+                              res[GENERAL ? t * TM + i : 0]);
         }
     }
 }

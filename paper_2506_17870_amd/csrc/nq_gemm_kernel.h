@@ -196,8 +196,20 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
             }
     }
 
-    // ---- epilogue (Eq. 2 / Eq. 8) -------------------------------------------------------------
+    // ---- epilogue (Eq. 2 / Eq. 8): residual codes of all tiles first, then the arithmetic -------
     const int col = lane & 31, rg = lane >> 5;
+    int res[GENERAL ? TM * TN : 1][16];
+#pragma unroll
+    for (int t = 0; t < TN; ++t)
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int nt0 = n0 + (wn * TN + t) * 32;
+            const int64_t row0 = m0 + wm * (BM / WM) + i * 32;
+            const int64_t left = p.M - row0;
+            const int rows_left = nt0 + col < p.N ? (left > 32 ? 32 : (int)left) : 0;
+            epi_resid_load<GENERAL>(p, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left,
+                                    res[GENERAL ? t * TM + i : 0]);
+        }
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int n = n0 + (wn * TN + t) * 32 + col;
@@ -209,7 +221,8 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
             const int64_t left = p.M - row0;
             const int rows_left = left > 32 ? 32 : (int)left;
             const int nt0 = n0 + (wn * TN + t) * 32;
-            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left);
+            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left,
+                              res[GENERAL ? t * TM + i : 0]);
         }
     }
 }

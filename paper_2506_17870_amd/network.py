@@ -78,28 +78,43 @@ class NestedCNN:
     def __init__(self, ops, weights, n_bits=8, l_bits=2):
         self.ops, self.n_bits, self.l_bits = ops, n_bits, l_bits
         self.cfg = nq.make_cfg(n_bits, l_bits)
+        # every layer's lower-bit page is a slice of one device arena and one pinned host arena, in the
+        # same order, so that the model is paged in with a single copy (nq_page_in_low_batch)
+        sizes = [0 if w is None else max(nq.nq_packed_bytes(w[0].shape[0], w[0].shape[1], l_bits), 16)
+                 for w in weights]
+        sizes = [(s + 255) // 256 * 256 if s else 0 for s in sizes]
+        total = sum(sizes)
+        self.low_arena = torch.zeros(total, dtype=torch.uint8, device="cuda")
+        self.low_arena_host = torch.zeros(total, dtype=torch.uint8, pin_memory=True)
         self.layers = []
-        for op, w in zip(ops, weights):
+        off = 0
+        for op, w, size in zip(ops, weights, sizes):
             if w is None:
                 self.layers.append(None)
                 continue
             w_int, scale, bias = w
-            W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), self.cfg)
+            N, K = w_int.shape
+            need = max(nq.nq_packed_bytes(N, K, l_bits), 16)
+            W = nq.NestedWeight(N, K, self.cfg, low=self.low_arena[off:off + need],
+                                low_host=self.low_arena_host[off:off + need], init=False)
+            W.desc.low_bytes = size            # the slot reaches up to the next page: contiguous runs
+            off += size
             self.layers.append((W, torch.from_numpy(bias).cuda()))
+        self.descs = [L[0].desc for L in self.layers if L is not None]
+        nq.nq_weight_init_group(self.descs)
+        for L, w in zip(self.layers, weights):
+            if L is not None:
+                L[0].fill_from_int8(torch.from_numpy(w[0]).cuda(), torch.from_numpy(w[1]).cuda())
         self.out_scale = [None] * (max(op["dst"] for op in ops) + 1)   # step of every int8 tensor
 
     def low_page_bytes(self) -> int:
         return sum(nq.nq_packed_bytes(L[0].N, L[0].K, self.l_bits) for L in self.layers if L is not None)
 
     def page_out_low(self, stream=None):
-        for L in self.layers:
-            if L is not None:
-                nq.nq_page_out_low(L[0].desc, stream)
+        nq.nq_page_out_low_batch(self.descs, stream)
 
     def page_in_low(self, copy_stream=None):
-        for L in self.layers:
-            if L is not None:
-                nq.nq_page_in_low(L[0].desc, copy_stream)
+        nq.nq_page_in_low_batch(self.descs, copy_stream)
 
     def forward(self, x, in_scale: float, full: bool, calibrate: bool = False, keep=None):
         """x: int8 NHWC device tensor.  Returns the fp32 logits [B, classes].

@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(nq):
     names = declared_functions()
-    assert len(names) >= 17
+    assert len(names) >= 24
     lib = ctypes.CDLL(nq.LIB_PATH)
     for name in names:
         assert hasattr(lib, name), name
