@@ -37,7 +37,7 @@ constexpr int RS_HALO_OFFSET = 0x40000000;   // out of range for any image (host
 
 // RS_KCAP: the K steps of 64 of the layer (exact, so the K loop is straight-line code);
 // RS_LDMAX: 16-byte window pieces a thread stages per unit.
-template <int H, int L, bool FULL, bool GENERAL, int RS_KCAP, int RS_LDMAX>
+template <int H, int L, bool FULL, int EPI, int RS_KCAP, int RS_LDMAX>
 __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmParams p, const StreamGeom g)
 {
     constexpr int S = 8 - H;
@@ -54,15 +54,16 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
     // ---- weights: every K step of the channel tile, requested first -----------------------------
     uint32_t W8[RS_KCAP][8];   // packed dwords on arrival, decoded fragments afterwards
     {
+        const int wslot = epi_weight_slot<EPI>(lane);   // channel order that suits the epilogue
         const uint32_t *ph = p.ph + (int64_t)nb * p.KB * (H * 64);
         const uint32_t *pl = FULL ? p.pl + (int64_t)nb * p.KB * (L * 64) : nullptr;
 #pragma unroll
         for (int s = 0; s < RS_KCAP; ++s) {
 #pragma unroll
-            for (int i = 0; i < H; ++i) W8[s][i] = ph[(unsigned)(s * (H * 64) + i * 64 + lane)];
+            for (int i = 0; i < H; ++i) W8[s][i] = ph[(unsigned)(s * (H * 64) + i * 64 + wslot)];
             if constexpr (FULL) {
 #pragma unroll
-                for (int i = 0; i < L; ++i) W8[s][H + i] = pl[(unsigned)(s * (L * 64) + i * 64 + lane)];
+                for (int i = 0; i < L; ++i) W8[s][H + i] = pl[(unsigned)(s * (L * 64) + i * 64 + wslot)];
             }
         }
     }
@@ -122,8 +123,23 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
         const int r = (int)__umulhi((unsigned)pl, g.wo_magic), ow = pl - r * p.Wo;
         a_off = ((r * p.stride) * g.WC + ow * p.stride) * CKP + 32 * (lane >> 5);
     }
-    const int col = lane & 31, rg = lane >> 5;
-    const EpiColumn ec = epi_column(p, n0 + col, FULL);
+    const int rg = lane >> 5;
+    // EPI_F32 keeps the lane's single channel constant in registers.  The sixteen per lane of the
+    // other layouts wait in LDS behind the windows and are read back for every unit: held in
+    // registers for the whole kernel they would push it into scratch.  The first barrier of the unit
+    // loop orders the write before the reads.
+    float *cols_lds = reinterpret_cast<float *>(win + RS_G * g.win_stride);
+    EpiCols<EPI> ec;
+    epi_cols<EPI>(p, n0, lane, FULL, ec);
+    if constexpr (EPI != EPI_F32) {
+        if (wave == 0 && (lane & 31) == 0) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                cols_lds[32 * rg + r] = ec.c[r];
+                cols_lds[32 * rg + 16 + r] = ec.bias[r];
+            }
+        }
+    }
 
     // ---- decode the weights in place into matrix-core fragments ---------------------------------
 #pragma unroll
@@ -160,9 +176,9 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
                 const int oh0 = cur_rb[j] * g.R;
                 const int pix = min(g.R, p.Ho - oh0) * p.Wo;
                 const int64_t m_base = ((int64_t)cur_b[j] * p.Ho + oh0) * p.Wo;
-                int res[16];
-                epi_resid_load<GENERAL>(p, (m_base + wave * 32) * p.N + n0, (unsigned)(4 * rg * p.N + col), rg,
-                                        n0 + col < p.N ? pix - wave * 32 : 0, res);
+                const int rows = min(max(pix - wave * 32, 0), 32);
+                e_v4i res;
+                epi_resid_load<EPI>(p, m_base + wave * 32, rows, n0, lane, res);
                 r_v16i acc;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[r] = 0;
@@ -184,14 +200,22 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
                             buf + a_off + g.tap_off[(f + RS_PF) >> 1] + 16 * ((f + RS_PF) & 1));
                     const r_v4i bfrag = r_v4i{(int)W8[s][4 * hf], (int)W8[s][4 * hf + 1], (int)W8[s][4 * hf + 2],
                                               (int)W8[s][4 * hf + 3]};
-                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bfrag, acc, 0, 0, 0);
+                    acc = epi_mfma<EPI>(bfrag, a, acc);
                     __builtin_amdgcn_sched_barrier(0);
                 }
 
                 // ---- epilogue (Eq. 2 / Eq. 8) ----------------------------------------------------------
-                if (n0 + col < p.N)
-                    epi_tile<GENERAL>(p, acc, SHIFT, ec, (m_base + wave * 32) * p.N + n0, (unsigned)(4 * rg * p.N + col),
-                                      rg, pix - wave * 32, res);
+                EpiCols<EPI> eu = ec;
+                if constexpr (EPI != EPI_F32) {
+                    const e_v4f *cl = reinterpret_cast<const e_v4f *>(cols_lds + 32 * rg);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const e_v4f c = cl[j], b = cl[4 + j];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) { eu.c[4 * j + i] = c[i]; eu.bias[4 * j + i] = b[i]; }
+                    }
+                }
+                epi_tile<EPI>(p, acc, SHIFT, eu, m_base + wave * 32, rows, n0, lane, res);
             }
         }
         __syncthreads();   // all windows of the round are free again
@@ -209,9 +233,9 @@ inline void rs_grant_lds(K kernel, size_t lds)
     }
 }
 
-#define NQ_RS_LAUNCH(FULLV, GENV, KCAP, LDMAX)                                \
+#define NQ_RS_LAUNCH(FULLV, EPIV, KCAP, LDMAX)                                \
     do {                                                                      \
-        auto k = k_nested_conv_rowstream<H, L, FULLV, GENV, KCAP, LDMAX>;     \
+        auto k = k_nested_conv_rowstream<H, L, FULLV, EPIV, KCAP, LDMAX>;     \
         rs_grant_lds(k, lds);                                                 \
         launch_timed(k, grid, block, lds, st, ev_start, ev_stop, p, g);       \
     } while (0)
@@ -223,22 +247,22 @@ void launch_nested_conv_rowstream(bool full, const GemmParams &p, const StreamGe
                                   void *ev_start, void *ev_stop)
 {
     const dim3 grid((unsigned)grid_x, (unsigned)((p.N + 31) / 32)), block(256);
-    const size_t lds = RS_G * (size_t)g.win_stride;
-    const bool general = p.acc_dump != nullptr || p.resid != nullptr;
-#define NQ_RS_CASE(FULLV, GENV)                              \
+    const size_t lds = RS_G * (size_t)g.win_stride + 256;   // windows + per-channel constants
+    const int mode = epi_mode(p);
+#define NQ_RS_CASE(FULLV, EPIV)                              \
     switch (g.ksteps) {                                      \
-    case 9: NQ_RS_LAUNCH(FULLV, GENV, 9, 4); break;          \
-    case 1: NQ_RS_LAUNCH(FULLV, GENV, 1, 4); break;          \
-    case 2: NQ_RS_LAUNCH(FULLV, GENV, 2, 8); break;          \
-    case 4: NQ_RS_LAUNCH(FULLV, GENV, 4, 8); break;          \
-    case 8: NQ_RS_LAUNCH(FULLV, GENV, 8, 8); break;          \
+    case 9: NQ_RS_LAUNCH(FULLV, EPIV, 9, 4); break;          \
+    case 1: NQ_RS_LAUNCH(FULLV, EPIV, 1, 4); break;          \
+    case 2: NQ_RS_LAUNCH(FULLV, EPIV, 2, 8); break;          \
+    case 4: NQ_RS_LAUNCH(FULLV, EPIV, 4, 8); break;          \
+    case 8: NQ_RS_LAUNCH(FULLV, EPIV, 8, 8); break;          \
     default: break;                                          \
     }
-    if (full) {
-        if (general) { NQ_RS_CASE(true, true) } else { NQ_RS_CASE(true, false) }
-    } else {
-        if (general) { NQ_RS_CASE(false, true) } else { NQ_RS_CASE(false, false) }
-    }
+#define NQ_RS_MODES(FULLV)                                            \
+    if (mode == EPI_ANY) { NQ_RS_CASE(FULLV, EPI_ANY) }               \
+    else if (mode == EPI_I8) { NQ_RS_CASE(FULLV, EPI_I8) }            \
+    else { NQ_RS_CASE(FULLV, EPI_F32) }
+    if (full) { NQ_RS_MODES(true) } else { NQ_RS_MODES(false) }
 }
 
 }  // namespace nq

@@ -21,7 +21,7 @@ namespace nq {
 typedef int w_v4i __attribute__((ext_vector_type(4)));
 typedef int w_v16i __attribute__((ext_vector_type(16)));
 
-template <int H, int L, bool FULL, bool GENERAL, int WMG, int WNG, int TM, int TN>
+template <int H, int L, bool FULL, int EPI, int WMG, int WNG, int TM, int TN>
 __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, const WindowGeom g)
 {
     static_assert(WMG * WNG == 4, "four waves per block");
@@ -57,6 +57,7 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
     // has the latency of the cache hierarchy hidden behind PD steps of matrix-core work.
     constexpr int PD = 4;
     const int nb0 = n0 / 32 + wn * TN;
+    const int wslot = epi_weight_slot<EPI>(lane);     // channel order that suits the epilogue
     uint32_t P[PD][TN][H];
     uint32_t Q[PD][TN][FULL ? L : 1];
     auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][FULL ? L : 1], int kb) {
@@ -65,11 +66,11 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
             const int nb = nb0 + t;
             if (nb < p.NB) {
                 const int64_t tile = (int64_t)nb * p.KB + kb;
-                const uint32_t *src = p.ph + tile * (H * 64) + lane;
+                const uint32_t *src = p.ph + tile * (H * 64) + wslot;
 #pragma unroll
                 for (int i = 0; i < H; ++i) Pd[t][i] = src[i * 64];
                 if constexpr (FULL) {
-                    const uint32_t *srcl = p.pl + tile * (L * 64) + lane;
+                    const uint32_t *srcl = p.pl + tile * (L * 64) + wslot;
 #pragma unroll
                     for (int i = 0; i < L; ++i) Qd[t][i] = srcl[i * 64];
                 }
@@ -171,8 +172,7 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
                                 *reinterpret_cast<const w_v4i *>(win + a_off[i] + tap_off + 16 * hf);
 #pragma unroll
                             for (int t = 0; t < TN; ++t)
-                                acc[i][t] =
-                                    __builtin_amdgcn_mfma_i32_32x32x32_i8(afrag, bfrag[t][hf], acc[i][t], 0, 0, 0);
+                                acc[i][t] = epi_mfma<EPI>(bfrag[t][hf], afrag, acc[i][t]);
                         }
                 }
             }
@@ -181,29 +181,25 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
 
     // ---- epilogue (Eq. 2 / Eq. 8): residual codes of all tiles first, then the arithmetic -------
     const int64_t m_base = (b * p.Ho + oh0) * (int64_t)p.Wo;   // whole rows: local pixel -> m is an offset
-    const int col = lane & 31, rg = lane >> 5;
-    int res[GENERAL ? TM * TN : 1][16];
+    auto rows_of = [&](int i) {
+        const int left = pix - (wm * TM + i) * 32;
+        return left > 32 ? 32 : (left < 0 ? 0 : left);
+    };
+    e_v4i res[TM * TN];
 #pragma unroll
     for (int t = 0; t < TN; ++t)
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int nt0 = n0 + (wn * TN + t) * 32;
-            const int pl0 = (wm * TM + i) * 32;
-            epi_resid_load<GENERAL>(p, (m_base + pl0) * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg,
-                                    nt0 + col < p.N ? pix - pl0 : 0, res[GENERAL ? t * TM + i : 0]);
-        }
+        for (int i = 0; i < TM; ++i)
+            epi_resid_load<EPI>(p, m_base + (wm * TM + i) * 32, rows_of(i), n0 + (wn * TN + t) * 32, lane,
+                                res[t * TM + i]);
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
-        const int n = n0 + (wn * TN + t) * 32 + col;
-        if (n >= p.N) continue;
-        const EpiColumn e = epi_column(p, n, FULL);
+        const int nt0 = n0 + (wn * TN + t) * 32;
+        EpiCols<EPI> e;
+        epi_cols<EPI>(p, nt0, lane, FULL, e);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int pl0 = (wm * TM + i) * 32;
-            const int nt0 = n0 + (wn * TN + t) * 32;
-            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, (m_base + pl0) * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg,
-                              pix - pl0, res[GENERAL ? t * TM + i : 0]);
-        }
+        for (int i = 0; i < TM; ++i)
+            epi_tile<EPI>(p, acc[i][t], SHIFT, e, m_base + (wm * TM + i) * 32, rows_of(i), nt0, lane, res[t * TM + i]);
     }
 }
 
@@ -226,18 +222,20 @@ void launch_nested_conv_window(bool full, int shape, const GemmParams &p, const 
     (void)shape;  // one shape so far: 2x2 waves, 8 row tiles x 64 channels
     const int64_t images = p.M / ((int64_t)p.Ho * p.Wo);
     const dim3 grid((unsigned)(images * g.RB), (unsigned)((p.N + 63) / 64)), block(256);
-    const bool general = p.acc_dump != nullptr || p.resid != nullptr;
-#define NQ_WIN_LAUNCH(FULLV, GENV)                                              \
+    const int mode = epi_mode(p);
+#define NQ_WIN_LAUNCH(FULLV, EPIV)                                              \
     do {                                                                        \
-        auto k = k_nested_conv_window<H, L, FULLV, GENV, 2, 2, 4, 1>;           \
+        auto k = k_nested_conv_window<H, L, FULLV, EPIV, 2, 2, 4, 1>;           \
         allow_large_lds(k, lds_bytes);                                          \
         launch_timed(k, grid, block, lds_bytes, st, ev_start, ev_stop, p, g);   \
     } while (0)
-    if (full) {
-        if (general) NQ_WIN_LAUNCH(true, true); else NQ_WIN_LAUNCH(true, false);
-    } else {
-        if (general) NQ_WIN_LAUNCH(false, true); else NQ_WIN_LAUNCH(false, false);
-    }
+#define NQ_WIN_MODES(FULLV)                                      \
+    do {                                                         \
+        if (mode == EPI_ANY) NQ_WIN_LAUNCH(FULLV, EPI_ANY);      \
+        else if (mode == EPI_I8) NQ_WIN_LAUNCH(FULLV, EPI_I8);   \
+        else NQ_WIN_LAUNCH(FULLV, EPI_F32);                      \
+    } while (0)
+    if (full) NQ_WIN_MODES(true); else NQ_WIN_MODES(false);
 }
 
 }  // namespace nq

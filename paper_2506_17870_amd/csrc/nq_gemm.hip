@@ -157,6 +157,13 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     p.out_int8 = epi->out_int8 != 0;
     // 16-byte activation loads need every chunk of 16 consecutive k inside one pixel
     p.fast_a = (g.Cin % 16 == 0) && aligned16(d_x);
+    // the vector epilogue of int8 outputs moves 16 channels at a time; fp32 outputs with a residual
+    // (a calibration pass) and the accumulator dump take the element-wise one as well
+    if (p.out_int8)
+        p.general = p.acc_dump != nullptr || p.N % 16 != 0 || !aligned16(d_y) || !aligned16(p.resid) ||
+                    !aligned16(p.scale) || !aligned16(p.bias);
+    else
+        p.general = p.acc_dump != nullptr || p.resid != nullptr;
 
     void *ev0 = g_ev_start, *ev1 = g_ev_stop;
     g_ev_start = g_ev_stop = nullptr;

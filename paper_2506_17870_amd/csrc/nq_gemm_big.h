@@ -35,9 +35,9 @@ constexpr int GB_ROW = GB_KI * 64;                       // LDS bytes per panel 
 
 // TM: 32-row tiles per wave (block tile 32*TM x 256); the host picks TM so that the number of
 // blocks fits the 256 compute units with little left over.  TM <= 4 fits two blocks per unit
-// (the general epilogue needs more registers and runs one block per unit rather than spill).
-template <int H, int L, bool FULL, bool GENERAL, int TM>
-__global__ void __launch_bounds__(256, (TM <= 4 && !GENERAL ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
+// (the element-wise epilogue needs more registers and runs one block per unit rather than spill).
+template <int H, int L, bool FULL, int EPI, int TM>
+__global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
 {
     constexpr int GB_BM = 32 * TM;
     constexpr int GB_PANEL = GB_BM * GB_ROW;             // bytes per LDS panel
@@ -85,6 +85,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && !GENERAL ? 2 : 1)) k_nested_g
 
     // ---- weights: rolling pipeline of packed dwords, PD K steps deep --------------------------
     const int nb0 = n0 / 32 + wave * TN;
+    const int wslot = epi_weight_slot<EPI>(lane);             // channel order that suits the epilogue
     uint32_t P[PD][TN][H];
     uint32_t Q[PD][TN][FULL ? L : 1];
     // K is a multiple of 256 here (host check), so every K step exists.  Column tiles past N read the
@@ -98,11 +99,11 @@ __global__ void __launch_bounds__(256, (TM <= 4 && !GENERAL ? 2 : 1)) k_nested_g
         for (int t = 0; t < TN; ++t) {
             const uint32_t *src = p.ph + (tile0[t] + kbc) * (H * 64);
 #pragma unroll
-            for (int i = 0; i < H; ++i) Pd[t][i] = src[(unsigned)(i * 64 + lane)];
+            for (int i = 0; i < H; ++i) Pd[t][i] = src[(unsigned)(i * 64 + wslot)];
             if constexpr (FULL) {
                 const uint32_t *srcl = p.pl + (tile0[t] + kbc) * (L * 64);
 #pragma unroll
-                for (int i = 0; i < L; ++i) Qd[t][i] = srcl[(unsigned)(i * 64 + lane)];
+                for (int i = 0; i < L; ++i) Qd[t][i] = srcl[(unsigned)(i * 64 + wslot)];
             }
         }
     };
@@ -169,7 +170,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && !GENERAL ? 2 : 1)) k_nested_g
                                                                       ((f + PF) % TM) * 32 * GB_ROW + 128 * (d >> 1));
 #pragma unroll
                     for (int t = 0; t < TN; ++t)
-                        acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bfrag[t][hf], acc[i][t], 0, 0, 0);
+                        acc[i][t] = epi_mfma<EPI>(bfrag[t][hf], a, acc[i][t]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -177,33 +178,24 @@ __global__ void __launch_bounds__(256, (TM <= 4 && !GENERAL ? 2 : 1)) k_nested_g
     }
 
     // ---- epilogue (Eq. 2 / Eq. 8): residual codes of all tiles first, then the arithmetic -------
-    const int col = lane & 31, rg = lane >> 5;
-    int res[GENERAL ? TM * TN : 1][16];
+    auto rows_of = [&](int i) {
+        const int64_t left = p.M - (m0 + i * 32);
+        return left > 32 ? 32 : (left < 0 ? 0 : (int)left);
+    };
+    e_v4i res[TM * TN];
 #pragma unroll
     for (int t = 0; t < TN; ++t)
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int nt0 = n0 + (wave * TN + t) * 32;
-            const int64_t row0 = m0 + i * 32;
-            const int64_t left = p.M - row0;
-            const int rows_left = nt0 + col < p.N ? (left > 32 ? 32 : (int)left) : 0;
-            epi_resid_load<GENERAL>(p, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left,
-                                    res[GENERAL ? t * TM + i : 0]);
-        }
+        for (int i = 0; i < TM; ++i)
+            epi_resid_load<EPI>(p, m0 + i * 32, rows_of(i), n0 + (wave * TN + t) * 32, lane, res[t * TM + i]);
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int nt0 = n0 + (wave * TN + t) * 32;
-        const int n = nt0 + col;
-        if (n >= p.N) continue;
-        const EpiColumn e = epi_column(p, n, FULL);
+        EpiCols<EPI> e;
+        epi_cols<EPI>(p, nt0, lane, FULL, e);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int64_t row0 = m0 + i * 32;
-            const int64_t left = p.M - row0;
-            const int rows_left = left > 32 ? 32 : (int)left;
-            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left,
-                              res[GENERAL ? t * TM + i : 0]);
-        }
+        for (int i = 0; i < TM; ++i)
+            epi_tile<EPI>(p, acc[i][t], SHIFT, e, m0 + i * 32, rows_of(i), nt0, lane, res[t * TM + i]);
     }
 }
 
@@ -227,11 +219,11 @@ template <int H, int L>
 void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop)
 {
     const int nblocks = (p.N + GB_BN - 1) / GB_BN;
-    const bool general = p.acc_dump != nullptr || p.resid != nullptr;
-    const int tm = general ? 4 : gemm_big_pick_tm(p.M, p.N);   // the general epilogue is built for TM = 4 only
-#define NQ_GB_LAUNCH(FULLV, GENV, TMV)                                                      \
+    const int mode = epi_mode(p);
+    const int tm = mode == EPI_ANY ? 4 : gemm_big_pick_tm(p.M, p.N);   // the element-wise epilogue is built for TM = 4 only
+#define NQ_GB_LAUNCH(FULLV, EPIV, TMV)                                                      \
     do {                                                                                    \
-        auto k = k_nested_gemm_big<H, L, FULLV, GENV, TMV>;                                 \
+        auto k = k_nested_gemm_big<H, L, FULLV, EPIV, TMV>;                                 \
         const size_t lds = 2 * (size_t)(32 * TMV) * GB_ROW;                                 \
         const int64_t mblocks = (p.M + 32 * TMV - 1) / (32 * TMV);                          \
         static bool granted = false;                                                        \
@@ -242,14 +234,19 @@ void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void
         }                                                                                   \
         launch_timed(k, dim3((unsigned)(mblocks * nblocks)), dim3(256), lds, st, ev_start, ev_stop, p); \
     } while (0)
-#define NQ_GB_TM(FULLV)                                          \
+#define NQ_GB_TM(FULLV, EPIV)                                    \
     do {                                                         \
-        if (general) NQ_GB_LAUNCH(FULLV, true, 4);               \
-        else if (tm == 3) NQ_GB_LAUNCH(FULLV, false, 3);         \
-        else if (tm == 5) NQ_GB_LAUNCH(FULLV, false, 5);         \
-        else NQ_GB_LAUNCH(FULLV, false, 4);                      \
+        if (tm == 3) NQ_GB_LAUNCH(FULLV, EPIV, 3);               \
+        else if (tm == 5) NQ_GB_LAUNCH(FULLV, EPIV, 5);          \
+        else NQ_GB_LAUNCH(FULLV, EPIV, 4);                       \
     } while (0)
-    if (full) NQ_GB_TM(true); else NQ_GB_TM(false);
+#define NQ_GB_MODE(FULLV)                                        \
+    do {                                                         \
+        if (mode == EPI_ANY) NQ_GB_LAUNCH(FULLV, EPI_ANY, 4);    \
+        else if (mode == EPI_I8) NQ_GB_TM(FULLV, EPI_I8);        \
+        else NQ_GB_TM(FULLV, EPI_F32);                           \
+    } while (0)
+    if (full) NQ_GB_MODE(true); else NQ_GB_MODE(false);
 }
 
 }  // namespace nq

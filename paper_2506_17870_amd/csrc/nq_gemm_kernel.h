@@ -9,7 +9,8 @@
 // touch LDS: a lane loads the packed dwords of its own slot of a dense tile (the page
 // layout is made for this: lane = slot, 256 contiguous bytes per wave load), decodes them
 // in registers into the two 16-byte fragments the matrix core wants and reuses them for
-// every row tile of the wave.  v_mfma_i32_32x32x32_i8 accumulates in int32; because
+// every row tile of the wave.  Which of the two is the matrix core's row operand depends on
+// the epilogue layout of the instantiation.  v_mfma_i32_32x32x32_i8 accumulates in int32; because
 // integer addition is associative any consistent assignment of k to fragment bytes gives
 // the exact sum.  The weight byte fed to the matrix core is w * 2^(8-n) (full-bit) or
 // w_high * 2^(8-h) (part-bit, lower field cleared); the accumulator is an exact multiple
@@ -30,7 +31,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int A_STRIDE = 80;  // bytes per LDS row of the activation tile (64 + 16 padding)
 
-template <int H, int L, bool FULL, bool GENERAL, int BM, int BN, int WM, int WN>
+template <int H, int L, bool FULL, int EPI, int BM, int BN, int WM, int WN>
 __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four waves per block");
@@ -119,6 +120,7 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
 
     // ---- weight staging: lane -> slot of a dense tile -------------------------------------
     const int nb0 = n0 / 32 + wn * TN;
+    const int wslot = epi_weight_slot<EPI>(lane);             // channel order that suits the epilogue
     uint32_t P[TN][H];
     uint32_t Q[TN][FULL ? L : 1];
     auto load_b = [&](int kb) {
@@ -127,11 +129,11 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
             const int nb = nb0 + t;
             if (nb < p.NB) {
                 const int64_t tile = (int64_t)nb * p.KB + kb;
-                const uint32_t *src = p.ph + tile * (H * 64) + lane;
+                const uint32_t *src = p.ph + tile * (H * 64) + wslot;
 #pragma unroll
                 for (int i = 0; i < H; ++i) P[t][i] = src[i * 64];
                 if constexpr (FULL) {
-                    const uint32_t *srcl = p.pl + tile * (L * 64) + lane;
+                    const uint32_t *srcl = p.pl + tile * (L * 64) + wslot;
 #pragma unroll
                     for (int i = 0; i < L; ++i) Q[t][i] = srcl[i * 64];
                 }
@@ -192,38 +194,30 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
                 const v4i afrag = *reinterpret_cast<const v4i *>(as + a_read + i * 32 * A_STRIDE + 16 * hf);
 #pragma unroll
                 for (int t = 0; t < TN; ++t)
-                    acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(afrag, bfrag[t][hf], acc[i][t], 0, 0, 0);
+                    acc[i][t] = epi_mfma<EPI>(bfrag[t][hf], afrag, acc[i][t]);
             }
     }
 
     // ---- epilogue (Eq. 2 / Eq. 8): residual codes of all tiles first, then the arithmetic -------
-    const int col = lane & 31, rg = lane >> 5;
-    int res[GENERAL ? TM * TN : 1][16];
+    const int64_t mw0 = m0 + wm * (BM / WM);
+    auto rows_of = [&](int i) {
+        const int64_t left = p.M - (mw0 + i * 32);
+        return left > 32 ? 32 : (left < 0 ? 0 : (int)left);
+    };
+    e_v4i res[TM * TN];
 #pragma unroll
     for (int t = 0; t < TN; ++t)
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int nt0 = n0 + (wn * TN + t) * 32;
-            const int64_t row0 = m0 + wm * (BM / WM) + i * 32;
-            const int64_t left = p.M - row0;
-            const int rows_left = nt0 + col < p.N ? (left > 32 ? 32 : (int)left) : 0;
-            epi_resid_load<GENERAL>(p, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left,
-                                    res[GENERAL ? t * TM + i : 0]);
-        }
+        for (int i = 0; i < TM; ++i)
+            epi_resid_load<EPI>(p, mw0 + i * 32, rows_of(i), n0 + (wn * TN + t) * 32, lane, res[t * TM + i]);
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
-        const int n = n0 + (wn * TN + t) * 32 + col;
-        if (n >= p.N) continue;
-        const EpiColumn e = epi_column(p, n, FULL);
+        const int nt0 = n0 + (wn * TN + t) * 32;
+        EpiCols<EPI> e;
+        epi_cols<EPI>(p, nt0, lane, FULL, e);
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int64_t row0 = m0 + wm * (BM / WM) + i * 32;
-            const int64_t left = p.M - row0;
-            const int rows_left = left > 32 ? 32 : (int)left;
-            const int nt0 = n0 + (wn * TN + t) * 32;
-            epi_tile<GENERAL>(p, acc[i][t], SHIFT, e, row0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows_left,
-                              res[GENERAL ? t * TM + i : 0]);
-        }
+        for (int i = 0; i < TM; ++i)
+            epi_tile<EPI>(p, acc[i][t], SHIFT, e, mw0 + i * 32, rows_of(i), nt0, lane, res[t * TM + i]);
     }
 }
 
@@ -239,27 +233,29 @@ inline void launch_timed(F kernel, dim3 grid, dim3 block, size_t lds, hipStream_
         hipLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, args...);
 }
 
-#define NQ_LAUNCH_TILE(FULLV, GENV, BM, BN, WM, WN)                                                       \
-    launch_timed(k_nested_gemm<H, L, FULLV, GENV, BM, BN, WM, WN>,                                        \
+#define NQ_LAUNCH_TILE(FULLV, EPIV, BM, BN, WM, WN)                                                       \
+    launch_timed(k_nested_gemm<H, L, FULLV, EPIV, BM, BN, WM, WN>,                                        \
                  dim3((unsigned)((p.M + BM - 1) / BM), (unsigned)((p.N + BN - 1) / BN)), dim3(256), 0, st, \
                  ev_start, ev_stop, p)
 
-#define NQ_LAUNCH_TILES(FULLV, GENV)                                  \
+#define NQ_LAUNCH_TILES(FULLV, EPIV)                                  \
     do {                                                              \
-        if (tile == 0) NQ_LAUNCH_TILE(FULLV, GENV, 256, 64, 4, 1);    \
-        else if (tile == 1) NQ_LAUNCH_TILE(FULLV, GENV, 128, 256, 1, 4); \
-        else NQ_LAUNCH_TILE(FULLV, GENV, 64, 256, 1, 4);              \
+        if (tile == 0) NQ_LAUNCH_TILE(FULLV, EPIV, 256, 64, 4, 1);    \
+        else if (tile == 1) NQ_LAUNCH_TILE(FULLV, EPIV, 128, 256, 1, 4); \
+        else NQ_LAUNCH_TILE(FULLV, EPIV, 64, 256, 1, 4);              \
     } while (0)
 
 template <int H, int L>
 void launch_nested_gemm(bool full, int tile, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop)
 {
-    const bool general = p.acc_dump != nullptr || p.resid != nullptr;
-    if (full) {
-        if (general) NQ_LAUNCH_TILES(true, true); else NQ_LAUNCH_TILES(true, false);
-    } else {
-        if (general) NQ_LAUNCH_TILES(false, true); else NQ_LAUNCH_TILES(false, false);
-    }
+    const int mode = epi_mode(p);
+#define NQ_LAUNCH_MODES(FULLV)                                     \
+    do {                                                           \
+        if (mode == EPI_ANY) NQ_LAUNCH_TILES(FULLV, EPI_ANY);      \
+        else if (mode == EPI_I8) NQ_LAUNCH_TILES(FULLV, EPI_I8);   \
+        else NQ_LAUNCH_TILES(FULLV, EPI_F32);                      \
+    } while (0)
+    if (full) NQ_LAUNCH_MODES(true); else NQ_LAUNCH_MODES(false);
 }
 
 }  // namespace nq

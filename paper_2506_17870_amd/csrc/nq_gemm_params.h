@@ -21,6 +21,7 @@ struct GemmParams {
     int H, W, Cin, Ho, Wo, KH, KW, stride, pad;
     float act_scale, resid_scale, inv_out_scale, part_mul;
     int relu, out_int8, fast_a;
+    int general;   // 1: the element-wise epilogue is needed (set by the host from the arguments)
 };
 
 // Geometry of the LDS-resident input window of the windowed convolution kernel.
