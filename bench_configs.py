@@ -190,13 +190,19 @@ def c4():
     print(f"* part-bit forward: {ms_part:.2f} ms ({ops_fwd / ms_part / 1e9:.1f} TOPS)")
     side = torch.cuda.Stream()
     low = model.low_page_bytes()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    model.page_in_low(side)
+    model.page_in_low(side)                       # first use of the stream and of the pinned arena: not timed
     side.synchronize()
-    t_in = (time.perf_counter() - t0) * 1e6
-    print(f"* upgrade (nq_page_in_low, {low / 1e6:.2f} MB in 105 pinned copies on a second stream): {t_in:.0f} us "
-          f"= {low / t_in / 1e3:.1f} GB/s host to device")
+    t_in = []
+    for _ in range(5):
+        model.page_out_low()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        model.page_in_low(side)
+        side.synchronize()
+        t_in.append((time.perf_counter() - t0) * 1e6)
+    t_in = sorted(t_in)[len(t_in) // 2]
+    print(f"* upgrade (nq_page_in_low_batch, {low / 1e6:.2f} MB of 105 pages as one pinned copy on a second stream): "
+          f"{t_in:.0f} us = {low / t_in / 1e3:.1f} GB/s host to device")
     model.page_out_low()
     torch.cuda.synchronize()
     t0 = time.perf_counter()

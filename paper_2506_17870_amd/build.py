@@ -3,7 +3,7 @@
     python -m paper_2506_17870_amd.build [--force]
 
 Objects go to _build/ next to this file, the library to paper_2506_17870_amd/libnq.so.
-One translation unit per nesting (h, l) holds the GEMM/convolution kernels, so the
+Two translation units per nesting (h, l) hold the GEMM/convolution kernels, so the
 units compile in parallel.
 """
 from __future__ import annotations
@@ -29,8 +29,9 @@ def _units():
     units = [(os.path.join(CSRC, f + ".hip"), os.path.join(OBJ, f + ".o"), [])
              for f in ("nq_pack", "nq_page", "nq_glue", "nq_gemm")]
     for h, l in NESTINGS:
-        units.append((os.path.join(CSRC, "nq_gemm_inst.hip"), os.path.join(OBJ, f"nq_gemm_inst_{h}{l}.o"),
-                      [f"-DNQ_INST_H={h}", f"-DNQ_INST_L={l}"]))
+        for part in (1, 0):
+            units.append((os.path.join(CSRC, "nq_gemm_inst.hip"), os.path.join(OBJ, f"nq_gemm_inst_{h}{l}_{part}.o"),
+                          [f"-DNQ_INST_H={h}", f"-DNQ_INST_L={l}", f"-DNQ_INST_PART={part}"]))
     return units
 
 

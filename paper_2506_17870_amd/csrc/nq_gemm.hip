@@ -172,8 +172,21 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     const char *env = getenv("NQ_KERNEL");
     const int force = env ? atoi(env) : 0;
     const bool plain_gemm = g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && w->K % 256 == 0 && aligned16(d_x);
-    if (plain_gemm && (force == 4 || (force == 0 && g.M > 64 && w->N > 64 && w->K >= 256))) {
-        const int64_t blocks = ceil_div(g.M, 96) * ceil_div(w->N, 256);
+    // implicit GEMM on the same kernel: any filter over a power-of-two number (>= 16) of input channels
+    const int64_t x_bytes = (g.M / ((int64_t)g.Ho * g.Wo)) * g.H * g.W * g.Cin;
+    const bool conv_gemm = !plain_gemm && g.Cin >= 16 && (g.Cin & (g.Cin - 1)) == 0 && aligned16(d_x) &&
+                           x_bytes < 0x7fff0000LL && g.M < (int64_t(1) << 31) && g.H <= 8192 && g.W <= 8192 &&
+                           g.KH * g.KW * g.KW < 65536;
+    p.conv_big = conv_gemm;
+    p.cin_shift = 0;
+    while ((1 << p.cin_shift) < g.Cin) ++p.cin_shift;
+    p.kw_magic = 65536 / g.KW + 1;
+    const bool big_ok = plain_gemm || conv_gemm;
+    bool big_wanted = g.M > 64 && w->N > 64 && w->K >= 256;
+    // short reductions with few output channels per block stay with the register-stationary kernel
+    if (conv_gemm && w->K <= 576) big_wanted = false;
+    if (big_ok && (force == 4 || (force == 0 && big_wanted))) {
+        const int64_t blocks = ceil_div(g.M, 64) * ceil_div(w->N, 256);
         if (blocks > 0x7fffffffLL) return NQ_ERR_SHAPE;
         NQ_DISPATCH_HL(h, l, launch_nested_gemm_big, full, p, s, ev0, ev1);
         return launch_status();

@@ -1,6 +1,9 @@
 // Nested-integer GEMM main loop for large problems (paper Sec. 3.3: full-bit = w_high * 2^l +
 // w_low recomposed on the fly, Eq. 4; part-bit = w_high with the scale s * 2^l, Eq. 8).  Also
-// serves 1x1 stride-1 convolutions, which are GEMMs over the NHWC pixels.
+// serves convolutions: 1x1 stride 1 is a GEMM over the NHWC pixels as it stands, and with CONV
+// any filter over a power-of-two number of input channels (>= 16) is an implicit GEMM in which
+// every 16-byte piece of an activation row is fetched from the input pixel its filter tap points
+// at (or from out of range, which reads as zero, for the padding and for the tail of K).
 //
 // Block tile (32*TM) x 256, four waves side by side along N (wave tile 32*TM x 64: TM x 2 MFMA
 // tiles of 32 x 32).  The K loop advances 256 at a time: one barrier per four K steps of 64.
@@ -36,7 +39,7 @@ constexpr int GB_ROW = GB_KI * 64;                       // LDS bytes per panel 
 // TM: 32-row tiles per wave (block tile 32*TM x 256); the host picks TM so that the number of
 // blocks fits the 256 compute units with little left over.  TM <= 4 fits two blocks per unit
 // (the element-wise epilogue needs more registers and runs one block per unit rather than spill).
-template <int H, int L, bool FULL, int EPI, int TM>
+template <int H, int L, bool FULL, int EPI, int TM, bool CONV>
 __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
 {
     constexpr int GB_BM = 32 * TM;
@@ -60,27 +63,76 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
 
     const int iters = (p.KB + GB_KI - 1) / GB_KI;
 
-    // ---- activations: descriptor over the rows of this block; rows past M are out of range ----
-    const int64_t rows_here = (p.M - m0) < GB_BM ? (p.M - m0) : GB_BM;
-    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<int8_t *>(p.x) + m0 * p.K, 0, (int)(rows_here * p.K), 0x00020000);
+    // ---- activations -------------------------------------------------------------------------
     // LDS-direct load k of wave w fills panel slots [(APT*w + k)*64, +64) (16 bytes each): lane l
     // writes row 4*(APT*w + k) + (l >> 4), position l & 15, and therefore fetches piece
     // c = (l & 15) ^ (row & 7) of that row; APT is even, so row & 7 = (l >> 4) | 4*(k & 1).
     typedef __attribute__((address_space(3))) void *lds_ptr;
-    int a_goff[2];
+    constexpr int OOR = 0x7fff0000;                      // beyond every descriptor range: moves no data
+    int piece[2];
 #pragma unroll
-    for (int par = 0; par < 2; ++par)
-        a_goff[par] = (wave * (4 * APT) + (lane >> 4)) * p.K + 16 * ((lane & 15) ^ ((lane >> 4) | (4 * par)));
+    for (int par = 0; par < 2; ++par) piece[par] = (lane & 15) ^ ((lane >> 4) | (4 * par));
+    // GEMM: descriptor over the rows of this block; rows past M are out of range.
+    // CONV: descriptor over the whole input tensor (the host keeps it below 2 GiB).
+    const int64_t rows_here = (p.M - m0) < GB_BM ? (p.M - m0) : GB_BM;
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(p.x) + (CONV ? 0 : m0 * p.K), 0,
+        CONV ? (int)((int64_t)(p.M / ((int64_t)p.Ho * p.Wo)) * p.H * p.W * p.Cin) : (int)(rows_here * p.K), 0x00020000);
+    int a_goff[2];                                       // GEMM: offset of the lane's piece in rows 0..3
+    // CONV: per row of the block, the byte offset of filter tap (0,0) and the packed (ih0, iw0) of the
+    // pixel, in a small LDS table behind the panels (worked out once, one row per thread)
+    int2 *rowtab = reinterpret_cast<int2 *>(panel + 2 * GB_PANEL);
+    if constexpr (CONV) {
+        if (tid < GB_BM) {
+            const int HoWo = p.Ho * p.Wo;
+            const int64_t m = m0 + tid;
+            const int mm = m < p.M ? (int)m : 0;
+            const int b = mm / HoWo, rem = mm - b * HoWo;
+            const int oh = rem / p.Wo, ow = rem - oh * p.Wo;
+            const int ih0 = oh * p.stride - p.pad, iw0 = ow * p.stride - p.pad;
+            // rows past M get a row index no tap can bring into the image
+            rowtab[tid] = make_int2(((b * p.H + ih0) * p.W + iw0) * p.Cin,
+                                    (m < p.M ? ih0 : -16384) * 65536 + (iw0 & 0xffff));
+        }
+        __syncthreads();
+    } else {
+#pragma unroll
+        for (int par = 0; par < 2; ++par)
+            a_goff[par] = (wave * (4 * APT) + (lane >> 4)) * p.K + 16 * piece[par];
+    }
     auto load_a = [&](int it, uint8_t *dst) {
         // An iteration that does not exist is requested out of range, which moves no data.  No branch:
         // the loop body is the same straight-line code every time, which lets the compiler count
         // outstanding loads exactly instead of waiting conservatively.
-        const int koff = it < iters ? it * (GB_KI * 64) : 0x7fff0000;
+        if constexpr (CONV) {
+            // k index of the lane's piece -> filter tap and channel (Cin is a power of two)
+            int tap_off[2], tap_hw[2];
 #pragma unroll
-        for (int k = 0; k < APT; ++k)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_ptr)(dst + (wave * APT + k) * 1024), 16,
-                                                     a_goff[k & 1] + k * 4 * p.K + koff, 0, 0, 0);
+            for (int par = 0; par < 2; ++par) {
+                const int kk = it * (GB_KI * 64) + 16 * piece[par];
+                const int tap = kk >> p.cin_shift, ci = kk & (p.Cin - 1);
+                const int kh = (tap * p.kw_magic) >> 16, kw = tap - kh * p.KW;
+                tap_off[par] = (kh * p.W + kw) * p.Cin + ci;
+                // a piece past the end of K gets a tap row that no pixel brings into the image
+                tap_hw[par] = kk < p.K ? (kh << 16) | kw : -16384 * 65536;
+            }
+#pragma unroll
+            for (int k = 0; k < APT; ++k) {
+                const int2 row = rowtab[4 * (wave * APT + k) + (lane >> 4)];
+                const int ih = (row.y >> 16) + (tap_hw[k & 1] >> 16);
+                const int iw = (int)(int16_t)(row.y & 0xffff) + (tap_hw[k & 1] & 0xffff);
+                const bool in = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                const int off = in ? row.x + tap_off[k & 1] : OOR;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_ptr)(dst + (wave * APT + k) * 1024), 16, off, 0, 0,
+                                                         0);
+            }
+        } else {
+            const int koff = it < iters ? it * (GB_KI * 64) : OOR;
+#pragma unroll
+            for (int k = 0; k < APT; ++k)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_ptr)(dst + (wave * APT + k) * 1024), 16,
+                                                         a_goff[k & 1] + k * 4 * p.K + koff, 0, 0, 0);
+        }
     };
 
     // ---- weights: rolling pipeline of packed dwords, PD K steps deep --------------------------
@@ -88,8 +140,9 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     const int wslot = epi_weight_slot<EPI>(lane);             // channel order that suits the epilogue
     uint32_t P[PD][TN][H];
     uint32_t Q[PD][TN][FULL ? L : 1];
-    // K is a multiple of 256 here (host check), so every K step exists.  Column tiles past N read the
-    // last real tile instead: their accumulators are never stored, so no masking is needed.
+    // K steps past the last one (K not a multiple of 256) read the last real tile: their activations
+    // are zero.  Column tiles past N read the last real tile as well: their accumulators are never
+    // stored.  So no masking is needed.
     int64_t tile0[TN];
 #pragma unroll
     for (int t = 0; t < TN; ++t) tile0[t] = (int64_t)min(nb0 + t, p.NB - 1) * p.KB;
@@ -199,17 +252,18 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     }
 }
 
-// Picks the rows per block: cost ~ (rounds of blocks over the compute units) x TM, two blocks
-// sharing a unit counted as 0.85 of running one after the other.
+// Picks the rows per block: cost ~ (rounds of blocks over the compute units) x (TM + the per-K-step
+// work that does not shrink with TM), two blocks sharing a unit counted as 0.85 of running one
+// after the other.
 inline int gemm_big_pick_tm(int64_t M, int64_t N)
 {
     const int64_t nblocks = (N + GB_BN - 1) / GB_BN;
     int best = 4;
     double best_cost = 1e30;
-    for (int tm = 3; tm <= 5; ++tm) {
+    for (int tm = 2; tm <= 5; ++tm) {
         const int64_t blocks = ((M + 32 * tm - 1) / (32 * tm)) * nblocks;
         const double rounds = (double)((blocks + 255) / 256);
-        const double cost = rounds * tm * (tm <= 4 && blocks > 256 ? 0.85 : 1.0);
+        const double cost = rounds * (tm + 1.5) * (tm <= 4 && blocks > 256 ? 0.85 : 1.0);
         if (cost < best_cost) { best_cost = cost; best = tm; }
     }
     return best;
@@ -221,10 +275,10 @@ void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void
     const int nblocks = (p.N + GB_BN - 1) / GB_BN;
     const int mode = epi_mode(p);
     const int tm = mode == EPI_ANY ? 4 : gemm_big_pick_tm(p.M, p.N);   // the element-wise epilogue is built for TM = 4 only
-#define NQ_GB_LAUNCH(FULLV, EPIV, TMV)                                                      \
+#define NQ_GB_LAUNCH(FULLV, EPIV, TMV, CONVV)                                               \
     do {                                                                                    \
-        auto k = k_nested_gemm_big<H, L, FULLV, EPIV, TMV>;                                 \
-        const size_t lds = 2 * (size_t)(32 * TMV) * GB_ROW;                                 \
+        auto k = k_nested_gemm_big<H, L, FULLV, EPIV, TMV, CONVV>;                          \
+        const size_t lds = 2 * (size_t)(32 * TMV) * GB_ROW + (CONVV ? 8 * 32 * TMV : 0);    \
         const int64_t mblocks = (p.M + 32 * TMV - 1) / (32 * TMV);                          \
         static bool granted = false;                                                        \
         if (!granted) {                                                                     \
@@ -234,19 +288,24 @@ void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void
         }                                                                                   \
         launch_timed(k, dim3((unsigned)(mblocks * nblocks)), dim3(256), lds, st, ev_start, ev_stop, p); \
     } while (0)
-#define NQ_GB_TM(FULLV, EPIV)                                    \
+#define NQ_GB_TM(FULLV, EPIV, CONVV)                             \
     do {                                                         \
-        if (tm == 3) NQ_GB_LAUNCH(FULLV, EPIV, 3);               \
-        else if (tm == 5) NQ_GB_LAUNCH(FULLV, EPIV, 5);          \
-        else NQ_GB_LAUNCH(FULLV, EPIV, 4);                       \
+        if (tm == 2) NQ_GB_LAUNCH(FULLV, EPIV, 2, CONVV);        \
+        else if (tm == 3) NQ_GB_LAUNCH(FULLV, EPIV, 3, CONVV);   \
+        else if (tm == 5) NQ_GB_LAUNCH(FULLV, EPIV, 5, CONVV);   \
+        else NQ_GB_LAUNCH(FULLV, EPIV, 4, CONVV);                \
     } while (0)
-#define NQ_GB_MODE(FULLV)                                        \
-    do {                                                         \
-        if (mode == EPI_ANY) NQ_GB_LAUNCH(FULLV, EPI_ANY, 4);    \
-        else if (mode == EPI_I8) NQ_GB_TM(FULLV, EPI_I8);        \
-        else NQ_GB_TM(FULLV, EPI_F32);                           \
+#define NQ_GB_MODE(FULLV, CONVV)                                         \
+    do {                                                                 \
+        if (mode == EPI_ANY) NQ_GB_LAUNCH(FULLV, EPI_ANY, 4, CONVV);     \
+        else if (mode == EPI_I8) NQ_GB_TM(FULLV, EPI_I8, CONVV);         \
+        else NQ_GB_TM(FULLV, EPI_F32, CONVV);                            \
     } while (0)
-    if (full) NQ_GB_MODE(true); else NQ_GB_MODE(false);
+    if (p.conv_big) {
+        if (full) NQ_GB_MODE(true, true); else NQ_GB_MODE(false, true);
+    } else {
+        if (full) NQ_GB_MODE(true, false); else NQ_GB_MODE(false, false);
+    }
 }
 
 }  // namespace nq

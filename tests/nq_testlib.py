@@ -1,5 +1,7 @@
 """Shared plumbing of the GPU parity tests: run the same seeded inputs through the HIP path
 (via the C ABI binding) and through the CPU oracle.  No arithmetic of the method lives here."""
+import os
+
 import numpy as np
 import torch
 
@@ -33,12 +35,31 @@ class Case:
                 np.array_equal(host(self.W.low)[:self.o_low.size], self.o_low))
 
 
+# Kernel choices every case is run with: the library's own, then each kernel forced through the
+# NQ_KERNEL environment variable (1 generic, 2 windowed, 3 register-stationary, 4 large GEMM; a kernel
+# that does not apply to a shape is not forced, the library's choice runs again).
+KERNEL_CHOICES = ("", "1", "2", "3", "4")
+
+
+def each_kernel():
+    for k in KERNEL_CHOICES:
+        if k:
+            os.environ["NQ_KERNEL"] = k
+        else:
+            os.environ.pop("NQ_KERNEL", None)
+        try:
+            yield k
+        finally:
+            os.environ.pop("NQ_KERNEL", None)
+
+
 def epi_pair(nq, case, full, M_shape, s_a=1.0, bias=None, residual=None, s_r=0.0, relu=False, out_int8=False,
-             inv_s_out=1.0):
-    """Builds the device epilogue descriptor + holders, and the oracle kwargs."""
+             inv_s_out=1.0, dump=True):
+    """Builds the device epilogue descriptor + holders, and the oracle kwargs.  dump=False leaves the
+    accumulator dump out, which is what lets the library pick its vector epilogues."""
     N = case.N
     keep = {}
-    keep["acc"] = torch.empty(tuple(M_shape) + (N,), dtype=torch.int32, device="cuda")
+    keep["acc"] = torch.empty(tuple(M_shape) + (N,), dtype=torch.int32, device="cuda") if dump else None
     keep["bias"] = dev(bias) if bias is not None else None
     keep["res"] = dev(residual) if residual is not None else None
     epi = nq.make_epilogue(s_a, keep["bias"], keep["res"], s_r, relu, out_int8, inv_s_out, keep["acc"])
@@ -48,7 +69,8 @@ def epi_pair(nq, case, full, M_shape, s_a=1.0, bias=None, residual=None, s_r=0.0
 
 
 def check_outputs(y_gpu, acc_gpu, y_ref, acc_ref, out_int8):
-    assert np.array_equal(acc_gpu, acc_ref), "int32 accumulators differ"
+    if acc_gpu is not None:
+        assert np.array_equal(acc_gpu, acc_ref), "int32 accumulators differ"
     if out_int8:
         assert np.array_equal(y_gpu, y_ref), "requantised int8 outputs differ"
     else:
@@ -60,32 +82,48 @@ def check_outputs(y_gpu, acc_gpu, y_ref, acc_ref, out_int8):
 
 def run_gemm_both(nq, case, x, full, **epi_kw):
     M = x.shape[0]
-    epi, keep, okw = epi_pair(nq, case, full, (M,), **epi_kw)
     out_int8 = epi_kw.get("out_int8", False)
-    y = torch.empty((M, case.N), dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
-    fn = nq.nq_gemm_full if full else nq.nq_gemm_part
-    fn(dev(x), M, case.W.desc, epi, y)
-    torch.cuda.synchronize()
     acc_ref = oracle.gemm_acc(x, case.ow_full if full else case.ow_part)
-    y_ref = oracle.epilogue(acc_ref, **okw)
-    check_outputs(host(y), host(keep["acc"]), y_ref, acc_ref, out_int8)
+    y_ref = None
+    dx = dev(x)
+    fn = nq.nq_gemm_full if full else nq.nq_gemm_part
+    for dump in (True, False):
+        for kernel in each_kernel():
+            epi, keep, okw = epi_pair(nq, case, full, (M,), dump=dump, **epi_kw)
+            if y_ref is None:
+                y_ref = oracle.epilogue(acc_ref, **okw)
+            y = torch.full((M, case.N), 77, dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+            fn(dx, M, case.W.desc, epi, y)
+            torch.cuda.synchronize()
+            try:
+                check_outputs(host(y), host(keep["acc"]) if dump else None, y_ref, acc_ref, out_int8)
+            except AssertionError as e:
+                raise AssertionError(f"{e} (NQ_KERNEL='{kernel}', accumulator dump {dump})") from None
 
 
 def run_conv_both(nq, case, x, shape, full, **epi_kw):
     B, H, W, Cin = x.shape
     KH, KW, stride, pad = shape
     Ho, Wo = oracle.conv_out_hw(H, W, KH, KW, stride, pad)
-    epi, keep, okw = epi_pair(nq, case, full, (B, Ho, Wo), **epi_kw)
     out_int8 = epi_kw.get("out_int8", False)
-    y = torch.empty((B, Ho, Wo, case.N), dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
     cs = nq.nq_conv_shape(B, H, W, Cin, case.N, KH, KW, stride, pad)
     fn = nq.nq_conv_full if full else nq.nq_conv_part
-    fn(dev(x), cs, case.W.desc, epi, y)
-    torch.cuda.synchronize()
     w4 = (case.ow_full if full else case.ow_part).reshape(case.N, KH, KW, Cin)
     acc_ref = oracle.conv_acc(x, w4, stride, pad)
-    y_ref = oracle.epilogue(acc_ref, **okw)
-    check_outputs(host(y), host(keep["acc"]), y_ref, acc_ref, out_int8)
+    y_ref = None
+    dx = dev(x)
+    for dump in (True, False):
+        for kernel in each_kernel():
+            epi, keep, okw = epi_pair(nq, case, full, (B, Ho, Wo), dump=dump, **epi_kw)
+            if y_ref is None:
+                y_ref = oracle.epilogue(acc_ref, **okw)
+            y = torch.full((B, Ho, Wo, case.N), 77, dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+            fn(dx, cs, case.W.desc, epi, y)
+            torch.cuda.synchronize()
+            try:
+                check_outputs(host(y), host(keep["acc"]) if dump else None, y_ref, acc_ref, out_int8)
+            except AssertionError as e:
+                raise AssertionError(f"{e} (NQ_KERNEL='{kernel}', accumulator dump {dump})") from None
 
 
 def oracle_cnn_forward(ops, weights, x, in_scale, n_bits, l_bits, full, scales=None):

@@ -83,6 +83,9 @@ def test_epilogue_options(nq):
     (2, 9, 8, 16, 24, 3, 3, 1, 1), (2, 9, 8, 16, 24, 3, 3, 2, 1), (1, 12, 12, 32, 40, 1, 1, 1, 0),
     (2, 11, 10, 64, 64, 3, 3, 1, 1), (1, 14, 14, 64, 96, 1, 1, 2, 0), (2, 20, 20, 3, 64, 7, 7, 2, 3),
     (1, 7, 7, 48, 33, 3, 3, 1, 0), (3, 6, 6, 5, 7, 3, 3, 1, 1), (1, 5, 5, 128, 300, 3, 3, 1, 1),
+    # implicit GEMM on the large-GEMM kernel: several row tiles, ragged rows, K not a multiple of 256 or 64
+    (2, 14, 14, 256, 256, 3, 3, 1, 1), (3, 15, 13, 32, 96, 3, 3, 2, 1), (1, 9, 9, 16, 130, 5, 5, 1, 2),
+    (2, 12, 12, 128, 272, 1, 1, 2, 0),
 ])
 def test_conv_geometries(nq, geom):
     B, H, W, Cin, Cout, KH, KW, stride, pad = geom
@@ -91,6 +94,11 @@ def test_conv_geometries(nq, geom):
     x = inputs.uniform_activations((B, H, W, Cin), seed=Cin)
     for full in (True, False):
         run_conv_both(nq, case, x, (KH, KW, stride, pad), full, s_a=0.02)
+    if Cout % 16 == 0:   # the 16-byte epilogue of int8 outputs, with a residual
+        res = inputs.uniform_activations((B, (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1, Cout),
+                                         seed=Cout)
+        run_conv_both(nq, case, x, (KH, KW, stride, pad), True, s_a=0.02, residual=res, s_r=0.05, relu=True,
+                      out_int8=True, inv_s_out=6.0)
 
 
 def test_conv_resnet18_layer_reduced_batch(nq):
