@@ -46,7 +46,12 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
     extern __shared__ __attribute__((aligned(16))) uint8_t win[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nb = blockIdx.y;               // 32-channel tile of this block (always a real one)
+    // Block id -> (unit slot, 32-channel tile).  Consecutive block ids go to different XCDs (id % 8),
+    // each with its own L2.  The blocks that work on the same units for different channel tiles get
+    // ids 8 apart: same XCD, dispatched back to back, so the second one finds the input rows in L2.
+    const int bid = blockIdx.x, xcd = bid & 7, bj = bid >> 3;
+    const int nb = bj % g.nblk;              // 32-channel tile of this block (always a real one)
+    const int slot = (bj / g.nblk) * 8 + xcd;   // first unit; slots at or past grid_x have no units
     const int n0 = nb * 32;
     const int CKP = p.Cin + 16;
     const int c16 = p.Cin >> 4;
@@ -97,22 +102,22 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
         for (int j = 0; j < RS_LDMAX; ++j) *reinterpret_cast<r_v4u *>(buf + st_lds[j]) = stg[j];
     };
 
-    // units of this block: blockIdx.x, blockIdx.x + gridDim.x, ...; (image, row block) of a unit
+    // units of this block: slot, slot + grid_x, ...; (image, row block) of a unit
     // advance by constants from one unit to the next
     int ub[RS_G], urb[RS_G];
-    int nxt_u = blockIdx.x;
+    int nxt_u = slot < g.grid_x ? slot : g.units;
     int nxt_b = nxt_u / g.RB, nxt_rb = nxt_u - nxt_b * g.RB;
     auto request_round = [&]() {
 #pragma unroll
         for (int j = 0; j < RS_G; ++j) {
             ub[j] = nxt_b; urb[j] = nxt_rb;
             if (nxt_u < g.units) load_unit(nxt_b, nxt_rb, stage[j]);
-            nxt_u += gridDim.x;
+            nxt_u += g.grid_x;
             nxt_b += g.step_b; nxt_rb += g.step_rb;
             if (nxt_rb >= g.RB) { nxt_rb -= g.RB; ++nxt_b; }
         }
     };
-    int u0 = blockIdx.x;
+    int u0 = nxt_u;
     request_round();
 
     // ---- per-lane constants ---------------------------------------------------------------------
@@ -158,18 +163,18 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
         for (int i = 0; i < 8; ++i) W8[s][i] = D[i];
     }
 
-    for (; u0 < g.units; u0 += RS_G * (int)gridDim.x) {
+    for (; u0 < g.units; u0 += RS_G * g.grid_x) {
         int cur_b[RS_G], cur_rb[RS_G];
 #pragma unroll
         for (int j = 0; j < RS_G; ++j) {
             cur_b[j] = ub[j]; cur_rb[j] = urb[j];
-            if (u0 + j * (int)gridDim.x < g.units) store_unit(win + j * g.win_stride, stage[j]);
+            if (u0 + j * g.grid_x < g.units) store_unit(win + j * g.win_stride, stage[j]);
         }
         __syncthreads();
         request_round();                              // the next round travels while this one is computed
 #pragma unroll
         for (int j = 0; j < RS_G; ++j) {
-            const int u = u0 + j * (int)gridDim.x;
+            const int u = u0 + j * g.grid_x;
             if (u < g.units) {
                 const uint8_t *buf = win + j * g.win_stride;
                 // the unit's residual codes travel while its MFMAs run
@@ -246,7 +251,7 @@ template <int H, int L>
 void launch_nested_conv_rowstream(bool full, const GemmParams &p, const StreamGeom &g, int grid_x, hipStream_t st,
                                   void *ev_start, void *ev_stop)
 {
-    const dim3 grid((unsigned)grid_x, (unsigned)((p.N + 31) / 32)), block(256);
+    const dim3 grid((unsigned)(((grid_x + 7) / 8) * 8 * g.nblk)), block(256);
     const size_t lds = RS_G * (size_t)g.win_stride + 256;   // windows + per-channel constants
     const int mode = epi_mode(p);
 #define NQ_RS_CASE(FULLV, EPIV)                              \

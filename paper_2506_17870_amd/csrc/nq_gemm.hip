@@ -93,6 +93,7 @@ bool plan_rowstream(const Geometry &g, const int8_t *d_x, int64_t n_out, StreamG
         const int per = (sg->units + slots - 1) / slots;
         *grid_x = (sg->units + per - 1) / per;
         sg->step_b = *grid_x / RB; sg->step_rb = *grid_x % RB;
+        sg->grid_x = *grid_x; sg->nblk = nblk;
         return true;
     }
     return false;
@@ -194,7 +195,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     StreamGeom sg;
     int grid_x = 0;
     if ((force == 0 || force == 3) && plan_rowstream(g, d_x, w->N, &sg, &grid_x)) {
-        if (ceil_div(w->N, 32) > 65535) return NQ_ERR_SHAPE;
+        if ((int64_t)(grid_x + 7) * ceil_div(w->N, 32) > 0x7fffffffLL) return NQ_ERR_SHAPE;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_rowstream, full, p, sg, grid_x, s, ev0, ev1);
         return launch_status();
     }

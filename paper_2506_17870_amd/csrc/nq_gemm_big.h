@@ -22,6 +22,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "nq_codec.h"
 #include "nq_epilogue.h"
@@ -46,7 +47,9 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     constexpr int GB_PANEL = GB_BM * GB_ROW;             // bytes per LDS panel
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
-    constexpr int TN = 2, PD = GB_KI;                    // weights are requested PD K steps ahead
+    // weights are requested PD K steps ahead (registers permitting: TM = 4 shares the compute unit with a
+    // second block and has 256 registers, TM >= 5 has 512)
+    constexpr int TN = 2, PD = (TM == 4 && FULL ? 2 : 4);
     constexpr int APT = 2 * TM;                          // LDS-direct loads per wave and iteration (4 rows each)
 
     extern __shared__ __attribute__((aligned(16))) uint8_t panel[];
@@ -100,7 +103,8 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
         for (int par = 0; par < 2; ++par)
             a_goff[par] = (wave * (4 * APT) + (lane >> 4)) * p.K + 16 * piece[par];
     }
-    auto load_a = [&](int it, uint8_t *dst) {
+    // requests the loads k0 <= k < k1 of iteration `it` (all of them: k0 = 0, k1 = APT)
+    auto load_a = [&](int it, uint8_t *dst, int k0, int k1) {
         // An iteration that does not exist is requested out of range, which moves no data.  No branch:
         // the loop body is the same straight-line code every time, which lets the compiler count
         // outstanding loads exactly instead of waiting conservatively.
@@ -118,6 +122,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
             }
 #pragma unroll
             for (int k = 0; k < APT; ++k) {
+                if (k < k0 || k >= k1) continue;
                 const int2 row = rowtab[4 * (wave * APT + k) + (lane >> 4)];
                 const int ih = (row.y >> 16) + (tap_hw[k & 1] >> 16);
                 const int iw = (int)(int16_t)(row.y & 0xffff) + (tap_hw[k & 1] & 0xffff);
@@ -129,9 +134,11 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
         } else {
             const int koff = it < iters ? it * (GB_KI * 64) : OOR;
 #pragma unroll
-            for (int k = 0; k < APT; ++k)
+            for (int k = 0; k < APT; ++k) {
+                if (k < k0 || k >= k1) continue;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_ptr)(dst + (wave * APT + k) * 1024), 16,
                                                          a_goff[k & 1] + k * 4 * p.K + koff, 0, 0, 0);
+            }
         }
     };
 
@@ -146,17 +153,22 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     int64_t tile0[TN];
 #pragma unroll
     for (int t = 0; t < TN; ++t) tile0[t] = (int64_t)min(nb0 + t, p.NB - 1) * p.KB;
-    auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][FULL ? L : 1], int kb) {
+    // dword j of a pipeline slot: j < TN*H is higher-bit dword (t = j / H, i = j % H), the rest are the
+    // lower-bit dwords; load_b requests the dwords j0 <= j < j1 of K step kb
+    constexpr int NBL = TN * (H + (FULL ? L : 0));
+    auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][FULL ? L : 1], int kb, int j0, int j1) {
         const int kbc = min(kb, p.KB - 1);               // the refills of the last iteration are never used
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
             const uint32_t *src = p.ph + (tile0[t] + kbc) * (H * 64);
 #pragma unroll
-            for (int i = 0; i < H; ++i) Pd[t][i] = src[(unsigned)(i * 64 + wslot)];
+            for (int i = 0; i < H; ++i)
+                if (t * H + i >= j0 && t * H + i < j1) Pd[t][i] = src[(unsigned)(i * 64 + wslot)];
             if constexpr (FULL) {
                 const uint32_t *srcl = p.pl + (tile0[t] + kbc) * (L * 64);
 #pragma unroll
-                for (int i = 0; i < L; ++i) Qd[t][i] = srcl[(unsigned)(i * 64 + wslot)];
+                for (int i = 0; i < L; ++i)
+                    if (TN * H + t * L + i >= j0 && TN * H + t * L + i < j1) Qd[t][i] = srcl[(unsigned)(i * 64 + wslot)];
             }
         }
     };
@@ -169,9 +181,15 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][t][r] = 0;
 
+    // in this order (the fences keep it): the loop's waits count on the panel being requested before
+    // the weights, and on the weights of K step d before those of d + 1
+    load_a(0, panel, 0, APT);
 #pragma unroll
-    for (int d = 0; d < PD; ++d) load_b(P[d], Q[d], d);
-    load_a(0, panel);
+    for (int d = 0; d < PD; ++d) {
+        __builtin_amdgcn_sched_barrier(0);
+        load_b(P[d], Q[d], d, 0, NBL);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 
     // LDS address of the lane's fragment for K step d and half hf: piece c = 4*d + 2*g + hf of row
     // r sits at position c ^ (r & 7); the row tiles are multiples of 32 rows, so r & 7 = lane & 7.
@@ -185,47 +203,60 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
                 a_read[d0][hf] = (lane & 31) * GB_ROW + 16 * (((4 * d0 + 2 * g + hf) ^ r7) & 7);
     }
 
+    // Memory instructions are spread through the matrix-core stream: a burst of them would hold the
+    // wave at the issue port (the address unit takes one at a time) while the matrix cores run dry.
+    // Per K step the wave issues its share of the next panel's LDS-direct loads (first three K steps of
+    // an iteration) and the refill of the weight slot it has just decoded, a few after every pair of
+    // MFMAs.
     for (int it = 0; it < iters; ++it) {
         uint8_t *cur = panel + (it & 1) * GB_PANEL;
+        uint8_t *nxt = panel + ((it + 1) & 1) * GB_PANEL;
+        // Every wave must have its own share of panel `cur` in LDS before anyone reads it.  Loads complete
+        // in order and at least NBL weight loads follow a wave's last panel load (the prologue and the
+        // last K step of an iteration request weights only), so "at most NBL loads outstanding" means
+        // that the panel loads are done; the newest weight loads stay in flight.
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt((NBL & 15) | (7 << 4) | (15 << 8) | ((NBL >> 4) << 14));
         __syncthreads();                                  // panel `cur` has arrived, the other one is free
-        load_a(it + 1, panel + ((it + 1) & 1) * GB_PANEL);   // travels during this iteration
+        __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
         for (int d = 0; d < GB_KI; ++d) {
             const int kb = it * GB_KI + d;
-            {
-                g_v4i bfrag[TN][2];
+            g_v4i bfrag[TN][2];
 #pragma unroll
-                for (int t = 0; t < TN; ++t) {
-                    uint32_t D[8];
-                    HighCodec<H>::decode(P[d % PD][t], D);
-                    if constexpr (FULL) LowCodec<L, S>::decode_or(Q[d % PD][t], D);
+            for (int t = 0; t < TN; ++t) {
+                uint32_t D[8];
+                HighCodec<H>::decode(P[d % PD][t], D);
+                if constexpr (FULL) LowCodec<L, S>::decode_or(Q[d % PD][t], D);
 #pragma unroll
-                    for (int hf = 0; hf < 2; ++hf)
-                        bfrag[t][hf] = g_v4i{(int)D[4 * hf], (int)D[4 * hf + 1], (int)D[4 * hf + 2], (int)D[4 * hf + 3]};
-                }
-                load_b(P[d % PD], Q[d % PD], kb + PD);   // refill this pipeline slot
+                for (int hf = 0; hf < 2; ++hf)
+                    bfrag[t][hf] = g_v4i{(int)D[4 * hf], (int)D[4 * hf + 1], (int)D[4 * hf + 2], (int)D[4 * hf + 3]};
+            }
 
-                // fragment f = (hf, i): LDS reads four fragments ahead of their MFMAs
-                constexpr int NF = 2 * TM, PF = 4;
-                g_v4i af[PF];
+            // fragment f = (hf, i): LDS reads four fragments ahead of their MFMAs
+            constexpr int NF = 2 * TM, PF = 4;
+            g_v4i af[PF];
 #pragma unroll
-                for (int f = 0; f < PF; ++f)
-                    af[f] = *reinterpret_cast<const g_v4i *>(cur + a_read[d & 1][f / TM] + (f % TM) * 32 * GB_ROW +
-                                                             128 * (d >> 1));
+            for (int f = 0; f < PF; ++f)
+                af[f] = *reinterpret_cast<const g_v4i *>(cur + a_read[d & 1][f / TM] + (f % TM) * 32 * GB_ROW +
+                                                         128 * (d >> 1));
 #pragma unroll
-                for (int f = 0; f < NF; ++f) {
-                    const int i = f % TM, hf = f / TM;
-                    const g_v4i a = af[f % PF];
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (f + PF < NF)
-                        af[f % PF] = *reinterpret_cast<const g_v4i *>(cur + a_read[d & 1][(f + PF) / TM] +
-                                                                      ((f + PF) % TM) * 32 * GB_ROW + 128 * (d >> 1));
+            for (int f = 0; f < NF; ++f) {
+                const int i = f % TM, hf = f / TM;
+                const g_v4i a = af[f % PF];
+                __builtin_amdgcn_sched_barrier(0);
+                if (f + PF < NF)
+                    af[f % PF] = *reinterpret_cast<const g_v4i *>(cur + a_read[d & 1][(f + PF) / TM] +
+                                                                  ((f + PF) % TM) * 32 * GB_ROW + 128 * (d >> 1));
 #pragma unroll
-                    for (int t = 0; t < TN; ++t)
-                        acc[i][t] = epi_mfma<EPI>(bfrag[t][hf], a, acc[i][t]);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+                for (int t = 0; t < TN; ++t) acc[i][t] = epi_mfma<EPI>(bfrag[t][hf], a, acc[i][t]);
+                // this step's share of the memory requests
+                if (d < GB_KI - 1)
+                    load_a(it + 1, nxt, (d * NF + f) * APT / ((GB_KI - 1) * NF),
+                           (d * NF + f + 1) * APT / ((GB_KI - 1) * NF));
+                load_b(P[d % PD], Q[d % PD], kb + PD, f * NBL / NF, (f + 1) * NBL / NF);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
@@ -274,7 +305,11 @@ void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void
 {
     const int nblocks = (p.N + GB_BN - 1) / GB_BN;
     const int mode = epi_mode(p);
-    const int tm = mode == EPI_ANY ? 4 : gemm_big_pick_tm(p.M, p.N);   // the element-wise epilogue is built for TM = 4 only
+    int tm = mode == EPI_ANY ? 4 : gemm_big_pick_tm(p.M, p.N);   // the element-wise epilogue is built for TM = 4 only
+    if (const char *env = getenv("NQ_BIG_TM")) {                 // tuning aid: force the tile height
+        const int v = atoi(env);
+        if (mode != EPI_ANY && v >= 2 && v <= 5) tm = v;
+    }
 #define NQ_GB_LAUNCH(FULLV, EPIV, TMV, CONVV)                                               \
     do {                                                                                    \
         auto k = k_nested_gemm_big<H, L, FULLV, EPIV, TMV, CONVV>;                          \

@@ -51,7 +51,8 @@ struct StreamGeom {
     int c16_shift;    // log2(Cin / 16)
     unsigned wc_magic;  // ceil(2^32 / WC): n / WC == umulhi(n, wc_magic) for n < 2^16
     unsigned wo_magic;  // ceil(2^32 / Wo)
-    int step_b, step_rb;  // gridDim.x = step_b * RB + step_rb: how (image, row block) advance per unit
+    int grid_x, nblk;     // unit slots (a block takes units slot, slot + grid_x, ...) and 32-channel tiles
+    int step_b, step_rb;  // grid_x = step_b * RB + step_rb: how (image, row block) advance per unit
     int img_bytes;    // H * W * Cin
     int row_bytes;    // W * Cin
     int tap_off[9];   // LDS byte offset of K step s: (kh*WC + kw)*(Cin+16) + 64*cb
