@@ -99,6 +99,43 @@ bool plan_rowstream(const Geometry &g, const int8_t *d_x, int64_t n_out, StreamG
     return false;
 }
 
+// Decides whether the few-input-channels kernel applies (a filter row is at most 32 bytes of the
+// NHWC input) and works out its geometry.
+bool plan_smallcin(const Geometry &g, const int8_t *d_x, int64_t n_out, SmallCinGeom *sg)
+{
+    const int seg = g.KW * g.Cin;
+    if (seg > 32 || g.Cin >= 16 || (g.KH != 7 && g.KH != 3)) return false;
+    const int row_bytes = g.W * g.Cin;
+    if (row_bytes % 4 != 0 || ((uintptr_t)d_x & 3) != 0) return false;
+    const int64_t img_bytes = (int64_t)g.H * row_bytes;
+    if (img_bytes > (int64_t(1) << 29)) return false;
+    const int64_t images = g.M / ((int64_t)g.Ho * g.Wo);
+    // pixels to the right of the image that the last output column still reaches
+    const int over = (g.Wo - 1) * g.stride - g.pad + g.KW - 1 - (g.W - 1);
+    const int halo = g.pad > over ? g.pad : over;
+    const int d0 = (halo * g.Cin + 3) / 4 * 4;
+    const int row_stride = (d0 + row_bytes + 3) / 4 * 4;
+    const int row_dwords = row_bytes / 4;
+    const int64_t kb = ceil_div((int64_t)g.KH * seg, 64);
+    for (int R = g.Ho; R >= 1; --R) {
+        const int IR = (R - 1) * g.stride + g.KH;
+        if ((int64_t)IR * row_dwords > 256 * 8) continue;          // dwords a block stages per window
+        const int64_t win = ((int64_t)IR * row_stride + 128 + 15) / 16 * 16;   // slack: fragments of the last row read past it
+        if (2 * win + 2 * 32 * kb * 64 + 512 > 72 * 1024) continue;   // two blocks per compute unit
+        if (images * ceil_div(g.Ho, R) > 0x3fffffffLL) return false;
+        sg->R = R; sg->RB = (int)ceil_div(g.Ho, R); sg->units = (int)(images * sg->RB);
+        sg->IR = IR; sg->seg = seg; sg->d0 = d0; sg->row_stride = row_stride; sg->row_dwords = row_dwords;
+        sg->row_bytes = row_bytes; sg->img_bytes = (int)img_bytes; sg->win_bytes = (int)win;
+        const int64_t groups = ceil_div(ceil_div(n_out, 32), 2);
+        if (groups > 65535) return false;
+        int64_t gx = 512 / groups;
+        if (gx < 1) gx = 1;
+        sg->grid_x = (int)(gx < sg->units ? gx : sg->units);
+        return sg->units > 0;
+    }
+    return false;
+}
+
 int pick_tile(int64_t M, int64_t N)
 {
     if (N <= 64) return 0;
@@ -168,7 +205,8 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
 
     void *ev0 = g_ev_start, *ev1 = g_ev_stop;
     g_ev_start = g_ev_stop = nullptr;
-    // NQ_KERNEL (tuning and test aid): 1 generic, 2 windowed, 3 register-stationary, 4 large GEMM;
+    // NQ_KERNEL (tuning and test aid): 1 generic, 2 windowed, 3 register-stationary, 4 large GEMM,
+    // 5 few input channels;
     // a kernel that does not apply to the shape is never forced, the choice falls through.
     const char *env = getenv("NQ_KERNEL");
     const int force = env ? atoi(env) : 0;
@@ -190,6 +228,11 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         const int64_t blocks = ceil_div(g.M, 64) * ceil_div(w->N, 256);
         if (blocks > 0x7fffffffLL) return NQ_ERR_SHAPE;
         NQ_DISPATCH_HL(h, l, launch_nested_gemm_big, full, p, s, ev0, ev1);
+        return launch_status();
+    }
+    SmallCinGeom cg;
+    if ((force == 0 || force == 5) && plan_smallcin(g, d_x, w->N, &cg)) {
+        NQ_DISPATCH_HL(h, l, launch_nested_conv_smallcin, full, p, cg, s, ev0, ev1);
         return launch_status();
     }
     StreamGeom sg;

@@ -1,8 +1,9 @@
 // Two translation units per nesting, compiled with -DNQ_INST_H=<h> -DNQ_INST_L=<l> and
-// -DNQ_INST_PART=0 (generic, windowed and register-stationary kernels) or 1 (large-GEMM kernels),
+// -DNQ_INST_PART=0 (generic, windowed, register-stationary and few-channel kernels) or 1 (large-GEMM kernels),
 // so that the units build in parallel.
 #if NQ_INST_PART == 0
 #include "nq_conv_rowstream.h"
+#include "nq_conv_smallcin.h"
 #include "nq_conv_window.h"
 #include "nq_gemm_kernel.h"
 
@@ -12,6 +13,8 @@ template void launch_nested_conv_window<NQ_INST_H, NQ_INST_L>(bool, int, const G
                                                               size_t, hipStream_t, void *, void *);
 template void launch_nested_conv_rowstream<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, const StreamGeom &, int,
                                                                  hipStream_t, void *, void *);
+template void launch_nested_conv_smallcin<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, const SmallCinGeom &,
+                                                                hipStream_t, void *, void *);
 }
 #else
 #include "nq_gemm_big.h"

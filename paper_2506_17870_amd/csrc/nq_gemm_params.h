@@ -58,6 +58,22 @@ struct StreamGeom {
     int tap_off[9];   // LDS byte offset of K step s: (kh*WC + kw)*(Cin+16) + 64*cb
 };
 
+// Geometry of the few-input-channels convolution kernel (work unit = R output rows of one image).
+struct SmallCinGeom {
+    int R;            // output rows per unit
+    int RB;           // units per image = ceil(Ho / R)
+    int units;        // B * RB
+    int IR;           // input rows of a unit = (R-1)*stride + KH
+    int seg;          // KW * Cin: bytes of one filter row (<= 32)
+    int d0;           // byte offset of input column 0 inside an LDS row (zero halo before it), multiple of 4
+    int row_stride;   // LDS bytes per input row, multiple of 4
+    int row_dwords;   // W * Cin / 4
+    int row_bytes;    // W * Cin
+    int img_bytes;    // H * W * Cin
+    int win_bytes;    // LDS bytes of one window incl. slack, multiple of 16
+    int grid_x;       // persistent blocks per channel group
+};
+
 // Tile shapes: 0 = 256x64 (narrow outputs), 1 = 128x256 (large), 2 = 64x256 (few rows).
 constexpr int NQ_TILE_BM[3] = {256, 128, 64};
 constexpr int NQ_TILE_BN[3] = {64, 256, 256};
@@ -77,6 +93,11 @@ void launch_nested_conv_window(bool full, int shape, const GemmParams &p, const 
 template <int H, int L>
 void launch_nested_conv_rowstream(bool full, const GemmParams &p, const StreamGeom &g, int grid_x, hipStream_t st,
                                   void *ev_start, void *ev_stop);
+
+// Few input channels (KW * Cin <= 32): one matrix-core step per filter row.
+template <int H, int L>
+void launch_nested_conv_smallcin(bool full, const GemmParams &p, const SmallCinGeom &g, hipStream_t st, void *ev_start,
+                                 void *ev_stop);
 
 // Large GEMM / 1x1 stride-1 convolution: 128 x 256 tiles, K advanced 256 per barrier.
 template <int H, int L>

@@ -36,9 +36,10 @@ class Case:
 
 
 # Kernel choices every case is run with: the library's own, then each kernel forced through the
-# NQ_KERNEL environment variable (1 generic, 2 windowed, 3 register-stationary, 4 large GEMM; a kernel
+# NQ_KERNEL environment variable (1 generic, 2 windowed, 3 register-stationary, 4 large GEMM, 5 few
+# input channels; a kernel
 # that does not apply to a shape is not forced, the library's choice runs again).
-KERNEL_CHOICES = ("", "1", "2", "3", "4")
+KERNEL_CHOICES = ("", "1", "2", "3", "4", "5")
 
 
 def each_kernel():
