@@ -9,7 +9,7 @@
 // decodes the packed weights of its 32 channels ONCE into matrix-core fragments that stay in
 // registers, then walks over its share of work units.  A unit is R whole output rows of one
 // image (at most 128 pixels, one 32-row tile per wave).  Units are handled in rounds of up to
-// RS_G: the input rows of all units of a round are requested together and copied into RS_G
+// rs_round(): the input rows of all units of a round are requested together and copied into RS_G
 // LDS windows (pixels padded by 16 bytes against bank conflicts); after one barrier the units
 // are computed back to back, each one's output stores overlapping the next one's matrix-core
 // work.  The K loop has no barrier and no decoding: 16-byte LDS reads and MFMAs.
@@ -32,16 +32,21 @@ typedef int r_v4i __attribute__((ext_vector_type(4)));
 typedef int r_v16i __attribute__((ext_vector_type(16)));
 typedef unsigned r_v4u __attribute__((ext_vector_type(4)));
 
-constexpr int RS_G = 4;                      // units per round = LDS windows per block
+constexpr int RS_GMAX = 4;                   // LDS windows a block has room for
+// units per round: four, or two where a thread stages eight pieces per unit (registers)
+constexpr int rs_round(int ldmax) { return ldmax > 4 ? 2 : 4; }
 constexpr int RS_HALO_OFFSET = 0x40000000;   // out of range for any image (host keeps images below 2^29 bytes)
 
 // RS_KCAP: the K steps of 64 of the layer (exact, so the K loop is straight-line code);
 // RS_LDMAX: 16-byte window pieces a thread stages per unit.
-template <int H, int L, bool FULL, int EPI, int RS_KCAP, int RS_LDMAX>
+// RS_CT: 32-channel tiles a block keeps weights for (short reductions leave registers for several:
+// the input rows of a unit are then fetched once for all of them).
+template <int H, int L, bool FULL, int EPI, int RS_KCAP, int RS_LDMAX, int RS_CT>
 __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmParams p, const StreamGeom g)
 {
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
+    constexpr int RS_G = rs_round(RS_LDMAX);
 
     extern __shared__ __attribute__((aligned(16))) uint8_t win[];
 
@@ -50,25 +55,28 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
     // each with its own L2.  The blocks that work on the same units for different channel tiles get
     // ids 8 apart: same XCD, dispatched back to back, so the second one finds the input rows in L2.
     const int bid = blockIdx.x, xcd = bid & 7, bj = bid >> 3;
-    const int nb = bj % g.nblk;              // 32-channel tile of this block (always a real one)
+    const int nb0 = (bj % g.nblk) * RS_CT;   // first 32-channel tile of this block (always a real one)
     const int slot = (bj / g.nblk) * 8 + xcd;   // first unit; slots at or past grid_x have no units
-    const int n0 = nb * 32;
     const int CKP = p.Cin + 16;
     const int c16 = p.Cin >> 4;
 
     // ---- weights: every K step of the channel tile, requested first -----------------------------
-    uint32_t W8[RS_KCAP][8];   // packed dwords on arrival, decoded fragments afterwards
+    uint32_t W8[RS_CT][RS_KCAP][8];   // packed dwords on arrival, decoded fragments afterwards
     {
         const int wslot = epi_weight_slot<EPI>(lane);   // channel order that suits the epilogue
-        const uint32_t *ph = p.ph + (int64_t)nb * p.KB * (H * 64);
-        const uint32_t *pl = FULL ? p.pl + (int64_t)nb * p.KB * (L * 64) : nullptr;
 #pragma unroll
-        for (int s = 0; s < RS_KCAP; ++s) {
+        for (int c = 0; c < RS_CT; ++c) {
+            const int nb = min(nb0 + c, p.NB - 1);      // a tile past N repeats the last one, never stored
+            const uint32_t *ph = p.ph + (int64_t)nb * p.KB * (H * 64);
+            const uint32_t *pl = FULL ? p.pl + (int64_t)nb * p.KB * (L * 64) : nullptr;
 #pragma unroll
-            for (int i = 0; i < H; ++i) W8[s][i] = ph[(unsigned)(s * (H * 64) + i * 64 + wslot)];
-            if constexpr (FULL) {
+            for (int s = 0; s < RS_KCAP; ++s) {
 #pragma unroll
-                for (int i = 0; i < L; ++i) W8[s][H + i] = pl[(unsigned)(s * (L * 64) + i * 64 + wslot)];
+                for (int i = 0; i < H; ++i) W8[c][s][i] = ph[(unsigned)(s * (H * 64) + i * 64 + wslot)];
+                if constexpr (FULL) {
+#pragma unroll
+                    for (int i = 0; i < L; ++i) W8[c][s][H + i] = pl[(unsigned)(s * (L * 64) + i * 64 + wslot)];
+                }
             }
         }
     }
@@ -129,39 +137,46 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
         a_off = ((r * p.stride) * g.WC + ow * p.stride) * CKP + 32 * (lane >> 5);
     }
     const int rg = lane >> 5;
-    // EPI_F32 keeps the lane's single channel constant in registers.  The sixteen per lane of the
-    // other layouts wait in LDS behind the windows and are read back for every unit: held in
-    // registers for the whole kernel they would push it into scratch.  The first barrier of the unit
-    // loop orders the write before the reads.
-    float *cols_lds = reinterpret_cast<float *>(win + RS_G * g.win_stride);
-    EpiCols<EPI> ec;
-    epi_cols<EPI>(p, n0, lane, FULL, ec);
-    if constexpr (EPI != EPI_F32) {
-        if (wave == 0 && (lane & 31) == 0) {
+    // The per-channel constants of the block's tiles wait in LDS behind the windows (64 floats per
+    // tile) and are read back for every unit: held in registers for the whole kernel they would push
+    // it into scratch.  The first barrier of the unit loop orders the write before the reads.
+    float *cols_lds = reinterpret_cast<float *>(win + RS_GMAX * g.win_stride);
+    if (wave == 0) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                cols_lds[32 * rg + r] = ec.c[r];
-                cols_lds[32 * rg + 16 + r] = ec.bias[r];
+        for (int c = 0; c < RS_CT; ++c) {
+            EpiCols<EPI> ec;
+            epi_cols<EPI>(p, (nb0 + c) * 32, lane, FULL, ec);
+            if constexpr (EPI == EPI_F32) {
+                cols_lds[64 * c + (lane & 31)] = ec.c[0];
+                cols_lds[64 * c + 32 + (lane & 31)] = ec.bias[0];
+            } else if ((lane & 31) == 0) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    cols_lds[64 * c + 32 * rg + r] = ec.c[r];
+                    cols_lds[64 * c + 32 * rg + 16 + r] = ec.bias[r];
+                }
             }
         }
     }
 
     // ---- decode the weights in place into matrix-core fragments ---------------------------------
 #pragma unroll
-    for (int s = 0; s < RS_KCAP; ++s) {
-        uint32_t Pk[H], D[8];
+    for (int c = 0; c < RS_CT; ++c)
 #pragma unroll
-        for (int i = 0; i < H; ++i) Pk[i] = W8[s][i];
-        HighCodec<H>::decode(Pk, D);
-        if constexpr (FULL) {
-            uint32_t Qk[L];
+        for (int s = 0; s < RS_KCAP; ++s) {
+            uint32_t Pk[H], D[8];
 #pragma unroll
-            for (int i = 0; i < L; ++i) Qk[i] = W8[s][H + i];
-            LowCodec<L, S>::decode_or(Qk, D);
+            for (int i = 0; i < H; ++i) Pk[i] = W8[c][s][i];
+            HighCodec<H>::decode(Pk, D);
+            if constexpr (FULL) {
+                uint32_t Qk[L];
+#pragma unroll
+                for (int i = 0; i < L; ++i) Qk[i] = W8[c][s][H + i];
+                LowCodec<L, S>::decode_or(Qk, D);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) W8[c][s][i] = D[i];
         }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) W8[s][i] = D[i];
-    }
 
     for (; u0 < g.units; u0 += RS_G * g.grid_x) {
         int cur_b[RS_G], cur_rb[RS_G];
@@ -182,45 +197,53 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
                 const int pix = min(g.R, p.Ho - oh0) * p.Wo;
                 const int64_t m_base = ((int64_t)cur_b[j] * p.Ho + oh0) * p.Wo;
                 const int rows = min(max(pix - wave * 32, 0), 32);
-                e_v4i res;
-                epi_resid_load<EPI>(p, m_base + wave * 32, rows, n0, lane, res);
-                r_v16i acc;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[r] = 0;
-                // Activation fragments are read RS_PF reads ahead of the MFMAs that consume them, so
-                // that the LDS latency is covered by matrix-core work; the fences keep that order.
-                constexpr int NFRAG = 2 * RS_KCAP;
-                constexpr int RS_PF = NFRAG < 4 ? NFRAG : 4;
-                r_v4i afrag[RS_PF];
+                for (int c = 0; c < RS_CT; ++c) {
+                    const int n0 = (nb0 + c) * 32;
+                    if (RS_CT > 1 && n0 >= p.N) continue;         // the block's last tiles may not exist
+                    e_v4i res;
+                    epi_resid_load<EPI>(p, m_base + wave * 32, rows, n0, lane, res);
+                    r_v16i acc;
 #pragma unroll
-                for (int f = 0; f < RS_PF; ++f)
-                    afrag[f] = *reinterpret_cast<const r_v4i *>(buf + a_off + g.tap_off[f >> 1] + 16 * (f & 1));
+                    for (int r = 0; r < 16; ++r) acc[r] = 0;
+                    // Activation fragments are read RS_PF reads ahead of the MFMAs that consume them, so
+                    // that the LDS latency is covered by matrix-core work; the fences keep that order.
+                    constexpr int NFRAG = 2 * RS_KCAP;
+                    constexpr int RS_PF = NFRAG < 4 ? NFRAG : 4;
+                    r_v4i afrag[RS_PF];
 #pragma unroll
-                for (int f = 0; f < NFRAG; ++f) {
-                    const int s = f >> 1, hf = f & 1;
-                    const r_v4i a = afrag[f % RS_PF];
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (f + RS_PF < NFRAG)
-                        afrag[f % RS_PF] = *reinterpret_cast<const r_v4i *>(
-                            buf + a_off + g.tap_off[(f + RS_PF) >> 1] + 16 * ((f + RS_PF) & 1));
-                    const r_v4i bfrag = r_v4i{(int)W8[s][4 * hf], (int)W8[s][4 * hf + 1], (int)W8[s][4 * hf + 2],
-                                              (int)W8[s][4 * hf + 3]};
-                    acc = epi_mfma<EPI>(bfrag, a, acc);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-
-                // ---- epilogue (Eq. 2 / Eq. 8) ----------------------------------------------------------
-                EpiCols<EPI> eu = ec;
-                if constexpr (EPI != EPI_F32) {
-                    const e_v4f *cl = reinterpret_cast<const e_v4f *>(cols_lds + 32 * rg);
+                    for (int f = 0; f < RS_PF; ++f)
+                        afrag[f] = *reinterpret_cast<const r_v4i *>(buf + a_off + g.tap_off[f >> 1] + 16 * (f & 1));
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const e_v4f c = cl[j], b = cl[4 + j];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) { eu.c[4 * j + i] = c[i]; eu.bias[4 * j + i] = b[i]; }
+                    for (int f = 0; f < NFRAG; ++f) {
+                        const int s = f >> 1, hf = f & 1;
+                        const r_v4i a = afrag[f % RS_PF];
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (f + RS_PF < NFRAG)
+                            afrag[f % RS_PF] = *reinterpret_cast<const r_v4i *>(
+                                buf + a_off + g.tap_off[(f + RS_PF) >> 1] + 16 * ((f + RS_PF) & 1));
+                        const r_v4i bfrag = r_v4i{(int)W8[c][s][4 * hf], (int)W8[c][s][4 * hf + 1],
+                                                  (int)W8[c][s][4 * hf + 2], (int)W8[c][s][4 * hf + 3]};
+                        acc = epi_mfma<EPI>(bfrag, a, acc);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
+
+                    // ---- epilogue (Eq. 2 / Eq. 8) ------------------------------------------------------
+                    EpiCols<EPI> eu;
+                    if constexpr (EPI == EPI_F32) {
+                        eu.c[0] = cols_lds[64 * c + (lane & 31)];
+                        eu.bias[0] = cols_lds[64 * c + 32 + (lane & 31)];
+                    } else {
+                        const e_v4f *cl = reinterpret_cast<const e_v4f *>(cols_lds + 64 * c + 32 * rg);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const e_v4f cc = cl[q], bb = cl[4 + q];
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) { eu.c[4 * q + i] = cc[i]; eu.bias[4 * q + i] = bb[i]; }
+                        }
+                    }
+                    epi_tile<EPI>(p, acc, SHIFT, eu, m_base + wave * 32, rows, n0, lane, res);
                 }
-                epi_tile<EPI>(p, acc, SHIFT, eu, m_base + wave * 32, rows, n0, lane, res);
             }
         }
         __syncthreads();   // all windows of the round are free again
@@ -238,29 +261,30 @@ inline void rs_grant_lds(K kernel, size_t lds)
     }
 }
 
-#define NQ_RS_LAUNCH(FULLV, EPIV, KCAP, LDMAX)                                \
+#define NQ_RS_LAUNCH(FULLV, EPIV, KCAP, LDMAX, CTV)                                \
     do {                                                                      \
-        auto k = k_nested_conv_rowstream<H, L, FULLV, EPIV, KCAP, LDMAX>;     \
+        auto k = k_nested_conv_rowstream<H, L, FULLV, EPIV, KCAP, LDMAX, CTV>;     \
         rs_grant_lds(k, lds);                                                 \
         launch_timed(k, grid, block, lds, st, ev_start, ev_stop, p, g);       \
     } while (0)
 
 // Instantiated for the K-step counts of 3x3 convolutions with 64 input channels (9) and of 1x1
-// convolutions with 64, 128, 256 and 512 input channels (1, 2, 4, 8).
+// convolutions with 64, 128, 256 and 512 input channels (1, 2, 4, 8); the shorter the reduction, the
+// more channel tiles a block takes (rs_channel_tiles).
 template <int H, int L>
 void launch_nested_conv_rowstream(bool full, const GemmParams &p, const StreamGeom &g, int grid_x, hipStream_t st,
                                   void *ev_start, void *ev_stop)
 {
     const dim3 grid((unsigned)(((grid_x + 7) / 8) * 8 * g.nblk)), block(256);
-    const size_t lds = RS_G * (size_t)g.win_stride + 256;   // windows + per-channel constants
+    const size_t lds = RS_GMAX * (size_t)g.win_stride + 1024;   // windows + per-channel constants of up to 4 tiles
     const int mode = epi_mode(p);
 #define NQ_RS_CASE(FULLV, EPIV)                              \
     switch (g.ksteps) {                                      \
-    case 9: NQ_RS_LAUNCH(FULLV, EPIV, 9, 4); break;          \
-    case 1: NQ_RS_LAUNCH(FULLV, EPIV, 1, 4); break;          \
-    case 2: NQ_RS_LAUNCH(FULLV, EPIV, 2, 8); break;          \
-    case 4: NQ_RS_LAUNCH(FULLV, EPIV, 4, 8); break;          \
-    case 8: NQ_RS_LAUNCH(FULLV, EPIV, 8, 8); break;          \
+    case 9: NQ_RS_LAUNCH(FULLV, EPIV, 9, 4, 1); break;       \
+    case 1: NQ_RS_LAUNCH(FULLV, EPIV, 1, 4, 4); break;       \
+    case 2: NQ_RS_LAUNCH(FULLV, EPIV, 2, 8, 4); break;       \
+    case 4: NQ_RS_LAUNCH(FULLV, EPIV, 4, 8, 2); break;       \
+    case 8: NQ_RS_LAUNCH(FULLV, EPIV, 8, 8, 1); break;       \
     default: break;                                          \
     }
 #define NQ_RS_MODES(FULLV)                                            \

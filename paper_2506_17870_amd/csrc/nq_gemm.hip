@@ -66,7 +66,7 @@ bool plan_rowstream(const Geometry &g, const int8_t *d_x, int64_t n_out, StreamG
         const int IR = (R - 1) * g.stride + g.KH;
         const int64_t items = (int64_t)IR * WC * (Cin / 16);
         const int64_t bytes = (int64_t)IR * WC * (Cin + 16);
-        if (items > ld_max * 256 || 4 * (bytes + 16) > 76 * 1024) continue;
+        if (items > ld_max * 256 || 4 * (bytes + 16) > 75 * 1024) continue;
         if (R * g.Wo < 64 && 128 / g.Wo > R) return false;   // the window limit left too little work per unit
         const int64_t images = g.M / ((int64_t)g.Ho * g.Wo);
         const int RB = (g.Ho + R - 1) / R;
@@ -87,7 +87,8 @@ bool plan_rowstream(const Geometry &g, const int8_t *d_x, int64_t n_out, StreamG
             sg->tap_off[s] = s < ksteps ? (kh * WC + kw) * (Cin + 16) + cb * 64 : 0;
         }
         // persistent blocks, two per compute unit (LDS windows), each with the same number of units
-        const int nblk = (int)ceil_div(n_out, 32);
+        // channel-tile groups: a block keeps the weights of rs_channel_tiles() tiles
+        const int nblk = (int)ceil_div(ceil_div(n_out, 32), rs_channel_tiles(ksteps));
         int slots = 512 / nblk;
         if (slots < 1) slots = 1;
         const int per = (sg->units + slots - 1) / slots;

@@ -51,12 +51,15 @@ struct StreamGeom {
     int c16_shift;    // log2(Cin / 16)
     unsigned wc_magic;  // ceil(2^32 / WC): n / WC == umulhi(n, wc_magic) for n < 2^16
     unsigned wo_magic;  // ceil(2^32 / Wo)
-    int grid_x, nblk;     // unit slots (a block takes units slot, slot + grid_x, ...) and 32-channel tiles
+    int grid_x, nblk;     // unit slots (a block takes units slot, slot + grid_x, ...) and channel-tile groups
     int step_b, step_rb;  // grid_x = step_b * RB + step_rb: how (image, row block) advance per unit
     int img_bytes;    // H * W * Cin
     int row_bytes;    // W * Cin
     int tap_off[9];   // LDS byte offset of K step s: (kh*WC + kw)*(Cin+16) + 64*cb
 };
+
+// 32-channel tiles per block of the register-stationary kernel, by K steps of the layer.
+inline int rs_channel_tiles(int ksteps) { return ksteps <= 2 ? 4 : (ksteps == 4 ? 2 : 1); }
 
 // Geometry of the few-input-channels convolution kernel (work unit = R output rows of one image).
 struct SmallCinGeom {
