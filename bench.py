@@ -5,10 +5,13 @@
 
 One step is one pass of the whole path over one batch of the ResNet-18-shaped 3x3
 convolution (batch 32, 56x56x64 -> 64, INT8 nesting INT6): decompose-and-pack the layer's
-INT8 weights, page the lower-bit page out, run the part-bit convolution while the page is
-copied back in from pinned host memory on a second stream, then run the full-bit
-convolution (which waits for the page).  Inputs are resident in HBM before the clock
-starts.  Prints one JSON line; see the design doc for how the roofline figures are derived.
+INT8 weights, page the lower-bit page out, copy it back in from pinned host memory, run the
+part-bit convolution, then the full-bit convolution (which waits for the page).  By default
+the page travels on the compute stream: it is 9 KiB, its copy takes 4 us, and handing work
+between two hardware queues costs more than that per hand-over; --side-stream copies it on
+a second stream concurrently with the part-bit convolution instead.  Inputs are resident in
+HBM before the clock starts.  Prints one JSON line; see the design doc for how the roofline
+figures are derived.
 """
 from __future__ import annotations
 
@@ -85,6 +88,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="issue every call of the timed steps from Python instead of "
                     "replaying a captured HIP graph of `sets` consecutive steps")
+    ap.add_argument("--side-stream", action="store_true", help="copy the lower-bit page in on a second stream, "
+                    "concurrently with the part-bit convolution (default: on the compute stream, see DESIGN.md)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs; "
@@ -127,7 +132,7 @@ def main():
     shape = nq.nq_conv_shape(B, H, W, Cin, Cout, KH, KW, c["stride"], c["pad"])
     epi = nq.make_epilogue(s_a, d_bias, None, 0.0, True, False, 1.0, None)
     compute = torch.cuda.current_stream()
-    copy = torch.cuda.Stream()
+    copy = torch.cuda.Stream() if args.side_stream else compute
     cs, ps = ctypes.c_void_p(compute.cuda_stream), ctypes.c_void_p(copy.cuda_stream)
     wref, eref, sref, cref = ctypes.byref(Wn.desc), ctypes.byref(epi), ctypes.byref(shape), ctypes.byref(cfg)
     p_w, p_hi, p_lo = ctypes.c_void_p(d_w_int.data_ptr()), ctypes.c_void_p(Wn.high.data_ptr()), \
@@ -140,9 +145,9 @@ def main():
         r = i % R
         rc = lib.nq_decompose_pack(p_w, Cout, K, cref, p_hi, p_lo, cs)          # a1 + a2
         rc |= lib.nq_page_out_low(wref, cs)                                     # a3: downgrade
-        rc |= lib.nq_page_in_low(wref, ps)                                      # a4: upgrade, other stream
-                                                                                # (waits for the page-out point)
-        rc |= lib.nq_conv_part(p_x[r], sref, wref, eref, p_yp[r], cs)           # a6 + a7, overlaps the copy
+        rc |= lib.nq_page_in_low(wref, ps)                                      # a4: upgrade (waits for the
+                                                                                # page-out point)
+        rc |= lib.nq_conv_part(p_x[r], sref, wref, eref, p_yp[r], cs)           # a6 + a7
         if ev is not None:
             lib.nq_profile_next_launch(ev[0], ev[1])                            # time stamps of this dispatch
         rc |= lib.nq_conv_full(p_x[r], sref, wref, eref, p_yf[r], cs)           # a5 + a7, waits for the page
@@ -168,11 +173,13 @@ def main():
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             cap = torch.cuda.current_stream()
-            cs_saved = cs
+            cs_saved, ps_saved = cs, ps
             cs = ctypes.c_void_p(cap.cuda_stream)
+            if not args.side_stream:
+                ps = cs
             for i in range(R):
                 step(i)
-            cs = cs_saved
+            cs, ps = cs_saved, ps_saved
         torch.cuda.synchronize()
     n_replay = args.steps // R if graph is not None else 0
     torch.cuda.synchronize()
@@ -221,7 +228,8 @@ def main():
                scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
                config=dict(workload="ResNet-18-shaped 3x3 conv, stride 1 pad 1, batch 32, 56x56x64 -> 64, NHWC int8 "
                                     "activations, per-channel INT8 nesting INT6 (l=2), fp32 outputs with bias+ReLU; "
-                                    "step = decompose_pack + page-out + part-bit conv || page-in + full-bit conv",
+                                    "step = decompose_pack + page-out + page-in + part-bit conv + full-bit conv"
+                                    + (" (page-in on a second stream)" if args.side_stream else ""),
                            buffer_sets=R, ops_per_step=2 * ops_conv,
                            host_issue_ms_per_step=1e3 * (t_issue - t0) / args.steps,
                            issue="hip graph of %d steps" % R if graph is not None else "eager"),
