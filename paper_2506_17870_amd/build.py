@@ -17,6 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnq.so")
+YARDSTICKS = os.path.join(HERE, "nq_yardsticks")   # standalone hardware yardsticks (csrc/nq_yardsticks.hip)
 
 # (h, l): INT(8|h) for l = 1..6 and INT(6|h) for l = 1..4
 NESTINGS = [(7, 1), (6, 2), (5, 3), (4, 4), (3, 5), (2, 6), (5, 1), (4, 2), (3, 3), (2, 4)]
@@ -27,7 +28,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 
 def _units():
     units = [(os.path.join(CSRC, f + ".hip"), os.path.join(OBJ, f + ".o"), [])
-             for f in ("nq_pack", "nq_page", "nq_glue", "nq_gemm")]
+             for f in ("nq_pack", "nq_page", "nq_glue", "nq_gemm")]   # nq_yardsticks.hip is a program of its own
     for h, l in NESTINGS:
         for part in (1, 0):
             units.append((os.path.join(CSRC, "nq_gemm_inst.hip"), os.path.join(OBJ, f"nq_gemm_inst_{h}{l}_{part}.o"),
@@ -63,6 +64,12 @@ def build(force: bool = False, jobs: int | None = None) -> str:
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("link failed:\n" + r.stderr[-4000:])
+    ysrc = os.path.join(CSRC, "nq_yardsticks.hip")
+    if force or not os.path.exists(YARDSTICKS) or os.path.getmtime(YARDSTICKS) < os.path.getmtime(ysrc):
+        r = subprocess.run(["hipcc", *[f for f in FLAGS if f != "-fPIC"], ysrc, "-o", YARDSTICKS],
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed for nq_yardsticks:\n" + r.stderr[-4000:])
     return LIB
 
 

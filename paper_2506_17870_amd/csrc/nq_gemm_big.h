@@ -49,7 +49,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
     // weights are requested PD K steps ahead (registers permitting: TM = 4 shares the compute unit with a
     // second block and has 256 registers, TM >= 5 has 512)
-    constexpr int TN = 2, PD = (TM == 4 && FULL ? 2 : 4);
+    constexpr int TN = 2, PD = (TM == 4 && (FULL || H == 7) ? 2 : 4);
     constexpr int APT = 2 * TM;                          // LDS-direct loads per wave and iteration (4 rows each)
 
     extern __shared__ __attribute__((aligned(16))) uint8_t panel[];
@@ -206,8 +206,23 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     // Memory instructions are spread through the matrix-core stream: a burst of them would hold the
     // wave at the issue port (the address unit takes one at a time) while the matrix cores run dry.
     // Per K step the wave issues its share of the next panel's LDS-direct loads (first three K steps of
-    // an iteration) and the refill of the weight slot it has just decoded, a few after every pair of
-    // MFMAs.
+    // an iteration) and the refill of the weight slot whose dwords it has already decoded, a few after
+    // every pair of MFMAs.  The decoding is spread the same way, one K step ahead: while the MFMAs of
+    // step d run, the wave decodes the weights of step d + 1 in four slices (higher-bit fields, then
+    // lower-bit fields, of each of its two column tiles), so that VALU and matrix cores work at the
+    // same time even when the wave has the SIMD to itself.
+    g_v4i bfrag[TN][2];                                   // decoded weights of the current K step
+    {
+#pragma unroll
+        for (int t = 0; t < TN; ++t) {
+            uint32_t D[8];
+            HighCodec<H>::decode(P[0][t], D);
+            if constexpr (FULL) LowCodec<L, S>::decode_or(Q[0][t], D);
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+                bfrag[t][hf] = g_v4i{(int)D[4 * hf], (int)D[4 * hf + 1], (int)D[4 * hf + 2], (int)D[4 * hf + 3]};
+        }
+    }
     for (int it = 0; it < iters; ++it) {
         uint8_t *cur = panel + (it & 1) * GB_PANEL;
         uint8_t *nxt = panel + ((it + 1) & 1) * GB_PANEL;
@@ -223,19 +238,11 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
 #pragma unroll
         for (int d = 0; d < GB_KI; ++d) {
             const int kb = it * GB_KI + d;
-            g_v4i bfrag[TN][2];
-#pragma unroll
-            for (int t = 0; t < TN; ++t) {
-                uint32_t D[8];
-                HighCodec<H>::decode(P[d % PD][t], D);
-                if constexpr (FULL) LowCodec<L, S>::decode_or(Q[d % PD][t], D);
-#pragma unroll
-                for (int hf = 0; hf < 2; ++hf)
-                    bfrag[t][hf] = g_v4i{(int)D[4 * hf], (int)D[4 * hf + 1], (int)D[4 * hf + 2], (int)D[4 * hf + 3]};
-            }
+            constexpr int NF = 2 * TM, PF = 4;
+            g_v4i bnext[TN][2];                           // the next K step's weights, decoded on the way
+            uint32_t Dn[8];
 
             // fragment f = (hf, i): LDS reads four fragments ahead of their MFMAs
-            constexpr int NF = 2 * TM, PF = 4;
             g_v4i af[PF];
 #pragma unroll
             for (int f = 0; f < PF; ++f)
@@ -251,13 +258,30 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
                                                                   ((f + PF) % TM) * 32 * GB_ROW + 128 * (d >> 1));
 #pragma unroll
                 for (int t = 0; t < TN; ++t) acc[i][t] = epi_mfma<EPI>(bfrag[t][hf], a, acc[i][t]);
-                // this step's share of the memory requests
+                // a slice of the next step's decoding
+#pragma unroll
+                for (int t = 0; t < TN; ++t) {
+                    if (f == t * NF / TN) HighCodec<H>::decode(P[(d + 1) % PD][t], Dn);
+                    if (f == t * NF / TN + 1) {
+                        if constexpr (FULL) LowCodec<L, S>::decode_or(Q[(d + 1) % PD][t], Dn);
+#pragma unroll
+                        for (int h2 = 0; h2 < 2; ++h2)
+                            bnext[t][h2] = g_v4i{(int)Dn[4 * h2], (int)Dn[4 * h2 + 1], (int)Dn[4 * h2 + 2],
+                                                 (int)Dn[4 * h2 + 3]};
+                    }
+                }
+                // this step's share of the memory requests; the slot refilled is the one decoded during the
+                // previous step
                 if (d < GB_KI - 1)
                     load_a(it + 1, nxt, (d * NF + f) * APT / ((GB_KI - 1) * NF),
                            (d * NF + f + 1) * APT / ((GB_KI - 1) * NF));
                 load_b(P[d % PD], Q[d % PD], kb + PD, f * NBL / NF, (f + 1) * NBL / NF);
                 __builtin_amdgcn_sched_barrier(0);
             }
+#pragma unroll
+            for (int t = 0; t < TN; ++t)
+#pragma unroll
+                for (int h2 = 0; h2 < 2; ++h2) bfrag[t][h2] = bnext[t][h2];
         }
     }
 
