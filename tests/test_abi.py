@@ -117,3 +117,32 @@ def test_gemm_argument_checks_without_gpu(nq):
     with pytest.raises(nq.NQError) as e:
         nq.nq_maxpool_i8(a, 1, 4, 4, 8, 3, 2, 3, a, stream=0)
     assert e.value.status == nq.NQ_ERR_SHAPE
+
+
+def test_batch_paging_argument_checks_without_gpu(nq):
+    # descriptors that never went through nq_weight_init_group have no events: rejected on the host
+    a = 0x1000
+    cfg = nq.make_cfg(8, 2)
+    ws = [nq.nq_weight(cfg, 64, 64, a, 64 * 64 * 6 // 8, a, 64 * 64 * 2 // 8, a, a, 0, 0, None, None, 0, 0)
+          for _ in range(3)]
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_page_out_low_batch(ws, 0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_page_in_low_batch(ws, 0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_page_in_low_batch([], 0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_weight_init_group([])
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    # the first descriptor of a group is checked like a single one: unsupported nesting, short page
+    bad = nq.nq_weight(nq.make_cfg(8, 7), 64, 64, a, 64 * 64, a, 64 * 64, a, a, 0, 0, None, None, 0, 0)
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_weight_init_group([bad])
+    assert e.value.status == nq.NQ_ERR_UNSUPPORTED
+    short = nq.nq_weight(cfg, 64, 64, a, 16, a, 64 * 64 * 2 // 8, a, a, 0, 0, None, None, 0, 0)
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_weight_init_group([short])
+    assert e.value.status == nq.NQ_ERR_RANGE
