@@ -58,3 +58,24 @@ def test_vit_mlp_full_size(nq, idx):
     for full in (True, False):
         run_gemm_both(nq, case, x, full, s_a=float(s_a), bias=bias)
     run_gemm_both(nq, case, x, True, s_a=float(s_a), bias=bias, out_int8=True, inv_s_out=20.0)
+
+
+def test_resnet101_early_layers_full_resolution(nq):
+    # the layers that depend on the image size, at 224 x 224 and a reduced batch: the 7x7 stride-2 stem on three
+    # input channels (few-channel kernel, several units per block) and the first bottleneck's 1x1 64 -> 256
+    # at 56 x 56 (register-stationary kernel with four channel tiles per block), with the residual epilogue
+    K = 7 * 7 * 3
+    w_int, scale = inputs.weights(64, K, inputs.he_sigma(K), 8, seed=41)
+    case = Case(nq, w_int, scale, 8, 2)
+    x, s_x = inputs.gaussian_activations((4, 224, 224, 3), seed=41)
+    bias = inputs.small_floats(64, 0.1, seed=42)
+    for full in (True, False):
+        run_conv_both(nq, case, x, (7, 7, 2, 3), full, s_a=float(s_x), bias=bias, relu=True, out_int8=True,
+                      inv_s_out=9.0)
+    w_int, scale = inputs.weights(256, 64, inputs.he_sigma(64), 8, seed=43)
+    case = Case(nq, w_int, scale, 8, 2)
+    x, s_x = inputs.relu_activations((4, 56, 56, 64), seed=43)
+    res = inputs.uniform_activations((4, 56, 56, 256), seed=44)
+    for full in (True, False):
+        run_conv_both(nq, case, x, (1, 1, 1, 0), full, s_a=float(s_x), residual=res, s_r=0.04, relu=True,
+                      out_int8=True, inv_s_out=5.0)
