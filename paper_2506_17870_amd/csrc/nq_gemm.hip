@@ -91,8 +91,9 @@ bool plan_rowstream(const Geometry &g, const int8_t *d_x, int64_t n_out, StreamG
         const int nblk = (int)ceil_div(ceil_div(n_out, 32), rs_channel_tiles(ksteps));
         int slots = 512 / nblk;
         if (slots < 1) slots = 1;
-        const int per = (sg->units + slots - 1) / slots;
-        *grid_x = (sg->units + per - 1) / per;
+        // every slot is used: with 3.5 units per slot the first half of the blocks (dispatched first, one
+        // per compute unit) gets four units and the second half three, instead of fewer blocks of four
+        *grid_x = sg->units < slots ? sg->units : slots;
         sg->step_b = *grid_x / RB; sg->step_rb = *grid_x % RB;
         sg->grid_x = *grid_x; sg->nblk = nblk;
         return true;

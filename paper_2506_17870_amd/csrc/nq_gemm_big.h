@@ -207,12 +207,15 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     // wave at the issue port (the address unit takes one at a time) while the matrix cores run dry.
     // Per K step the wave issues its share of the next panel's LDS-direct loads (first three K steps of
     // an iteration) and the refill of the weight slot whose dwords it has already decoded, a few after
-    // every pair of MFMAs.  The decoding is spread the same way, one K step ahead: while the MFMAs of
-    // step d run, the wave decodes the weights of step d + 1 in four slices (higher-bit fields, then
-    // lower-bit fields, of each of its two column tiles), so that VALU and matrix cores work at the
-    // same time even when the wave has the SIMD to itself.
+    // every pair of MFMAs.  Where the weight pipeline is four K steps deep (AHEAD) the decoding is
+    // spread the same way, one K step ahead: while the MFMAs of step d run, the wave decodes the weights
+    // of step d + 1 in four slices (higher-bit fields, then lower-bit fields, of each of its two column
+    // tiles), so that VALU and matrix cores work at the same time even when the wave has the SIMD to
+    // itself.  With the two-step pipeline that would leave the loads a single K step to arrive; there
+    // the weights of a step are decoded at its start.
+    constexpr bool AHEAD = PD >= 4;
     g_v4i bfrag[TN][2];                                   // decoded weights of the current K step
-    {
+    if constexpr (AHEAD) {
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
             uint32_t D[8];
@@ -241,6 +244,17 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
             constexpr int NF = 2 * TM, PF = 4;
             g_v4i bnext[TN][2];                           // the next K step's weights, decoded on the way
             uint32_t Dn[8];
+            if constexpr (!AHEAD) {
+#pragma unroll
+                for (int t = 0; t < TN; ++t) {
+                    HighCodec<H>::decode(P[d % PD][t], Dn);
+                    if constexpr (FULL) LowCodec<L, S>::decode_or(Q[d % PD][t], Dn);
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2)
+                        bfrag[t][h2] = g_v4i{(int)Dn[4 * h2], (int)Dn[4 * h2 + 1], (int)Dn[4 * h2 + 2],
+                                             (int)Dn[4 * h2 + 3]};
+                }
+            }
 
             // fragment f = (hf, i): LDS reads four fragments ahead of their MFMAs
             g_v4i af[PF];
@@ -260,7 +274,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
                 for (int t = 0; t < TN; ++t) acc[i][t] = epi_mfma<EPI>(bfrag[t][hf], a, acc[i][t]);
                 // a slice of the next step's decoding
 #pragma unroll
-                for (int t = 0; t < TN; ++t) {
+                for (int t = 0; t < TN && AHEAD; ++t) {
                     if (f == t * NF / TN) HighCodec<H>::decode(P[(d + 1) % PD][t], Dn);
                     if (f == t * NF / TN + 1) {
                         if constexpr (FULL) LowCodec<L, S>::decode_or(Q[(d + 1) % PD][t], Dn);
@@ -270,18 +284,20 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
                                                  (int)Dn[4 * h2 + 3]};
                     }
                 }
-                // this step's share of the memory requests; the slot refilled is the one decoded during the
-                // previous step
+                // this step's share of the memory requests; the slot refilled has been decoded (during the
+                // previous step, or at the start of this one)
                 if (d < GB_KI - 1)
                     load_a(it + 1, nxt, (d * NF + f) * APT / ((GB_KI - 1) * NF),
                            (d * NF + f + 1) * APT / ((GB_KI - 1) * NF));
                 load_b(P[d % PD], Q[d % PD], kb + PD, f * NBL / NF, (f + 1) * NBL / NF);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if constexpr (AHEAD) {
 #pragma unroll
-            for (int t = 0; t < TN; ++t)
+                for (int t = 0; t < TN; ++t)
 #pragma unroll
-                for (int h2 = 0; h2 < 2; ++h2) bfrag[t][h2] = bnext[t][h2];
+                    for (int h2 = 0; h2 < 2; ++h2) bfrag[t][h2] = bnext[t][h2];
+            }
         }
     }
 
