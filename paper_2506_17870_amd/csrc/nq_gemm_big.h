@@ -103,23 +103,26 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
         for (int par = 0; par < 2; ++par)
             a_goff[par] = (wave * (4 * APT) + (lane >> 4)) * p.K + 16 * piece[par];
     }
+    // CONV: where the lane's two pieces of iteration `it` come from: the k index of a piece -> filter tap
+    // and channel (Cin is a power of two).  Worked out once per iteration, used by all its requests.
+    int tap_off[2], tap_hw[2];
+    auto set_taps = [&](int it) {
+#pragma unroll
+        for (int par = 0; par < 2; ++par) {
+            const int kk = it * (GB_KI * 64) + 16 * piece[par];
+            const int tap = kk >> p.cin_shift, ci = kk & (p.Cin - 1);
+            const int kh = (tap * p.kw_magic) >> 16, kw = tap - kh * p.KW;
+            tap_off[par] = (kh * p.W + kw) * p.Cin + ci;
+            // a piece past the end of K gets a tap row that no pixel brings into the image
+            tap_hw[par] = kk < p.K ? (kh << 16) | kw : -16384 * 65536;
+        }
+    };
     // requests the loads k0 <= k < k1 of iteration `it` (all of them: k0 = 0, k1 = APT)
     auto load_a = [&](int it, uint8_t *dst, int k0, int k1) {
         // An iteration that does not exist is requested out of range, which moves no data.  No branch:
         // the loop body is the same straight-line code every time, which lets the compiler count
         // outstanding loads exactly instead of waiting conservatively.
         if constexpr (CONV) {
-            // k index of the lane's piece -> filter tap and channel (Cin is a power of two)
-            int tap_off[2], tap_hw[2];
-#pragma unroll
-            for (int par = 0; par < 2; ++par) {
-                const int kk = it * (GB_KI * 64) + 16 * piece[par];
-                const int tap = kk >> p.cin_shift, ci = kk & (p.Cin - 1);
-                const int kh = (tap * p.kw_magic) >> 16, kw = tap - kh * p.KW;
-                tap_off[par] = (kh * p.W + kw) * p.Cin + ci;
-                // a piece past the end of K gets a tap row that no pixel brings into the image
-                tap_hw[par] = kk < p.K ? (kh << 16) | kw : -16384 * 65536;
-            }
 #pragma unroll
             for (int k = 0; k < APT; ++k) {
                 if (k < k0 || k >= k1) continue;
@@ -183,6 +186,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
 
     // in this order (the fences keep it): the loop's waits count on the panel being requested before
     // the weights, and on the weights of K step d before those of d + 1
+    if constexpr (CONV) set_taps(0);
     load_a(0, panel, 0, APT);
 #pragma unroll
     for (int d = 0; d < PD; ++d) {
@@ -237,6 +241,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
         __builtin_amdgcn_s_waitcnt((NBL & 15) | (7 << 4) | (15 << 8) | ((NBL >> 4) << 14));
         __syncthreads();                                  // panel `cur` has arrived, the other one is free
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (CONV) set_taps(it + 1);
 
 #pragma unroll
         for (int d = 0; d < GB_KI; ++d) {
