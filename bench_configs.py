@@ -3,7 +3,7 @@
 benchmark).  Every kernel time is the begin/end time stamp of the dispatch itself; buffers are rotated so that
 activations and outputs come from HBM, not from the Infinity Cache.
 
-    python bench_configs.py [c1] [c2] [c3] [c4] [c5] [pack] [page]
+    python bench_configs.py [c1] [c2] [c3] [c4] [c5] [pack] [page] [sweep] [words]
 """
 from __future__ import annotations
 
@@ -66,10 +66,12 @@ def header(title):
     print("|---|---|---|---|---|---|---|")
 
 
-def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02):
-    w_int, scale = inputs.weights(N, K, sigma, 8, 0)
-    W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
-    xs = [torch.from_numpy(inputs.uniform_activations((M, K), i)).cuda() for i in range(sets)]
+def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8):
+    w_int, scale = inputs.weights(N, K, sigma, n_bits, 0)
+    W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(),
+                                  nq.make_cfg(n_bits, l))
+    # INT6 nesting runs with 6-bit activations (Sec. 4.2): int8 codes in [-32, 31]
+    xs = [torch.from_numpy(inputs.uniform_activations((M, K), i) >> (8 - n_bits)).cuda() for i in range(sets)]
     ys = [torch.empty((M, N), dtype=torch.int8 if out8 else torch.float32, device="cuda") for _ in range(sets)]
     epi = nq.make_epilogue(0.02, out_int8=out8, inv_out_scale=3.0)
     for full in (True, False):
@@ -82,7 +84,7 @@ def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02):
                 nq.nq_profile_next_launch(ev[0], ev[1])
             (nq.nq_gemm_full if full else nq.nq_gemm_part)(xs[i], M, W.desc, epi, ys[i])
         med, _ = kernel_us(fn)
-        wb = nq.nq_packed_bytes(N, K, 8 - l) + (nq.nq_packed_bytes(N, K, l) if full else 0)
+        wb = nq.nq_packed_bytes(N, K, n_bits - l) + (nq.nq_packed_bytes(N, K, l) if full else 0)
         row(name, ("full" if full else "part") + (" int8 out" if out8 else " fp32 out"), med, 2.0 * M * N * K,
             M * K + wb + M * N * (1 if out8 else 4))
 
@@ -114,9 +116,11 @@ def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4):
 
 
 def c1():
-    header("config 1: linear 64x512 -> 512 (launch bound) and a weight-bound stand-in (M = 64, 8192 x 8192)")
+    header("config 1: linear 64x512 -> 512 (launch bound) and weight-bound stand-ins (M = 64 and 16, 8192 x 8192)")
     gemm("64x512->512 l=2", 64, 512, 512, 2)
     gemm("64x8192->8192 l=2", 64, 8192, 8192, 2, sets=3)
+    gemm("16x8192->8192 l=2", 16, 8192, 8192, 2, sets=3)
+    gemm("16x8192->8192 l=4", 16, 8192, 8192, 4, sets=3)
 
 
 def c2():
@@ -264,8 +268,59 @@ def page():
     print(f"\npart-bit fc2 GEMM alone {alone:.1f} us; with a concurrent page-in of its 0.88 MB page {with_copy:.1f} us")
 
 
+def sweep():
+    """Throughput against the nesting (Sec. 4.2: INT8 nesting INT7..INT2, INT6 nesting INT5..INT2 with 6-bit
+    activations).  Part-bit weight bytes scale as h/n, which shows where the weight stream matters: a skinny
+    GEMM (16 rows against 8192 x 8192 weights); the ViT fc2 shape is matrix-core bound and barely moves."""
+    header("nesting sweep, skinny GEMM 16 x 8192 -> 8192 (weight-stream bound)")
+    for n, ls in ((8, (1, 2, 3, 4, 5, 6)), (6, (1, 2, 3, 4))):
+        for l in ls:
+            gemm(f"INT({n}|{n - l})", 16, 8192, 8192, l, sets=2, n_bits=n)
+    header("nesting sweep, ViT fc2 12608 x 3072 -> 768, int8 out (matrix-core bound)")
+    for n, ls in ((8, (1, 2, 3, 4, 5, 6)), (6, (1, 2, 3, 4))):
+        for l in ls:
+            gemm(f"INT({n}|{n - l})", 12608, 3072, 768, l, out8=True, sets=3, n_bits=n)
+
+
+def words():
+    """The paper's own page format (64 // k fields per unsigned 64-bit word, Sec. 3.3.4) against the dense
+    tile pages: bits per weight, and the cost of taking a model stored in words to the dense pages on the GPU
+    (nq_unpack of the word pages + nq_pack into tiles)."""
+    print("\n### word pages (64 // k fields per uint64) -> dense tile pages, 4096 x 4096 weights\n")
+    print("| nesting | word pages bit/weight | dense pages bit/weight | unpack + pack us | GB/s (all four streams) |")
+    print("|---|---|---|---|---|")
+    N = K = 4096
+    for l in (1, 2, 3, 4):
+        h = 8 - l
+        w_int, scale = inputs.weights(N, K, 0.02, 8, l)
+        cw = nq.make_cfg(8, l, layout=nq.NQ_LAYOUT_PAPER_U64)
+        cd = nq.make_cfg(8, l)
+        bw = nq.nq_packed_bytes(N, K, h, nq.NQ_LAYOUT_PAPER_U64) + nq.nq_packed_bytes(N, K, l, nq.NQ_LAYOUT_PAPER_U64)
+        bd = nq.nq_packed_bytes(N, K, h) + nq.nq_packed_bytes(N, K, l)
+        d_w = torch.from_numpy(w_int).cuda()
+        wh = torch.zeros(nq.nq_packed_bytes(N, K, h, nq.NQ_LAYOUT_PAPER_U64), dtype=torch.uint8, device="cuda")
+        wl = torch.zeros(nq.nq_packed_bytes(N, K, l, nq.NQ_LAYOUT_PAPER_U64), dtype=torch.uint8, device="cuda")
+        nq.nq_decompose_pack(d_w, N, K, cw, wh, wl)
+        hi = torch.empty((N, K), dtype=torch.int8, device="cuda")
+        lo = torch.empty((N, K), dtype=torch.int8, device="cuda")
+        dh = torch.zeros(nq.nq_packed_bytes(N, K, h), dtype=torch.uint8, device="cuda")
+        dl = torch.zeros(nq.nq_packed_bytes(N, K, l), dtype=torch.uint8, device="cuda")
+
+        def fn():
+            nq.nq_unpack(wh, wl, N, K, cw, hi, lo)
+            nq.nq_pack(hi, lo, N, K, cd, dh, dl)
+        us = wall_us(fn, 20)
+        # check: the dense pages made from the word pages equal the ones made from the weights directly
+        rh, rl = torch.zeros_like(dh), torch.zeros_like(dl)
+        nq.nq_decompose_pack(d_w, N, K, cd, rh, rl)
+        assert torch.equal(rh, dh) and torch.equal(rl, dl), "transcoded pages differ"
+        print(f"| INT(8\\|{h}) | {8.0 * bw / (N * K):.2f} | {8.0 * bd / (N * K):.2f} | {us:.1f} | "
+              f"{(bw + 4 * N * K + bd) / us / 1e3:.0f} |")
+
+
 if __name__ == "__main__":
     torch.cuda.set_device(0)
-    which = sys.argv[1:] or ["c1", "c2", "c3", "c4", "c5", "pack", "page"]
+    which = sys.argv[1:] or ["c1", "c2", "c3", "c4", "c5", "pack", "page", "sweep", "words"]
     for name in which:
-        {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "pack": pack, "page": page}[name]()
+        {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "pack": pack, "page": page, "sweep": sweep,
+         "words": words}[name]()

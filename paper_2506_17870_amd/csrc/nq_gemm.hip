@@ -208,7 +208,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     void *ev0 = g_ev_start, *ev1 = g_ev_stop;
     g_ev_start = g_ev_stop = nullptr;
     // NQ_KERNEL (tuning and test aid): 1 generic, 2 windowed, 3 register-stationary, 4 large GEMM,
-    // 5 few input channels;
+    // 5 few input channels, 6 few rows;
     // a kernel that does not apply to the shape is never forced, the choice falls through.
     const char *env = getenv("NQ_KERNEL");
     const int force = env ? atoi(env) : 0;
@@ -230,6 +230,13 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         const int64_t blocks = ceil_div(g.M, 64) * ceil_div(w->N, 256);
         if (blocks > 0x7fffffffLL) return NQ_ERR_SHAPE;
         NQ_DISPATCH_HL(h, l, launch_nested_gemm_big, full, p, s, ev0, ev1);
+        return launch_status();
+    }
+    // few rows: the packed weights are the traffic; one block per 32 columns, K split over the waves
+    const bool skinny_ok = g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && g.M <= 64 && w->K % 16 == 0 &&
+                           aligned16(d_x) && ceil_div(w->N, 32) <= 0x7fffffffLL;
+    if (skinny_ok && (force == 6 || (force == 0 && w->K >= 256))) {
+        NQ_DISPATCH_HL(h, l, launch_nested_gemm_skinny, full, p, s, ev0, ev1);
         return launch_status();
     }
     SmallCinGeom cg;

@@ -6,8 +6,10 @@
 #include "nq_conv_smallcin.h"
 #include "nq_conv_window.h"
 #include "nq_gemm_kernel.h"
+#include "nq_gemm_skinny.h"
 
 namespace nq {
+template void launch_nested_gemm_skinny<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, hipStream_t, void *, void *);
 template void launch_nested_gemm<NQ_INST_H, NQ_INST_L>(bool, int, const GemmParams &, hipStream_t, void *, void *);
 template void launch_nested_conv_window<NQ_INST_H, NQ_INST_L>(bool, int, const GemmParams &, const WindowGeom &,
                                                               size_t, hipStream_t, void *, void *);

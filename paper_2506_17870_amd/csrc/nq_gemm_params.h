@@ -102,6 +102,10 @@ template <int H, int L>
 void launch_nested_conv_smallcin(bool full, const GemmParams &p, const SmallCinGeom &g, hipStream_t st, void *ev_start,
                                  void *ev_stop);
 
+// Few rows (M <= 64): one block per 32-column tile, the waves split K.
+template <int H, int L>
+void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop);
+
 // Large GEMM / 1x1 stride-1 convolution: 128 x 256 tiles, K advanced 256 per barrier.
 template <int H, int L>
 void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop);

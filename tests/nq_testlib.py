@@ -37,9 +37,9 @@ class Case:
 
 # Kernel choices every case is run with: the library's own, then each kernel forced through the
 # NQ_KERNEL environment variable (1 generic, 2 windowed, 3 register-stationary, 4 large GEMM, 5 few
-# input channels; a kernel
+# input channels, 6 few rows; a kernel
 # that does not apply to a shape is not forced, the library's choice runs again).
-KERNEL_CHOICES = ("", "1", "2", "3", "4", "5")
+KERNEL_CHOICES = ("", "1", "2", "3", "4", "5", "6")
 
 
 def each_kernel():

@@ -45,7 +45,9 @@ def test_every_nesting(nq, n, l):
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (5, 33, 70), (3, 64, 16), (300, 100, 192), (130, 257, 320),
-                                   (257, 64, 1024), (64, 300, 64), (513, 40, 100), (200, 520, 48)])
+                                   (257, 64, 1024), (64, 300, 64), (513, 40, 100), (200, 520, 48),
+                                   # few rows: K split over the waves of a block (K steps 5, 17 and 36 + a tail)
+                                   (7, 96, 320), (33, 130, 1088), (64, 48, 2320), (1, 32, 4096)])
 def test_ragged_shapes(nq, M, N, K):
     # several tiles plus ragged tails in every dimension; K not a multiple of 16 takes the byte-gather path
     case = make_case(nq, N, K, 8, 2, seed=M + N + K)
