@@ -60,8 +60,14 @@ typedef enum {
  * NQ_LOW_UNSIGNED_L: the bit-wise split of Eq. 4: w_high = w_int >> l (arithmetic),
  *   w_low = the low l bits of the two's-complement code, in [0, 2^l - 1]; recomposition
  *   is exact for every INT-n value.
- * NQ_LOW_SIGNED_L1: the paper's extra-1-bit compensation, signed (l+1) bits, needed when
- *   w_high was rounded by something other than the shift. */
+ * NQ_LOW_SIGNED_L1: the paper's extra-1-bit compensation (Sec. 3.3.3): w_high comes from a rounding
+ *   other than the shift, w_low = w_int - w_high * 2^l lies in [-2^l + 1, 2^l - 1] and is stored as a
+ *   two's-complement field of l + 1 bits (the lower-bit page then has l + 1 bits per element; pass
+ *   l + 1 to nq_packed_bytes); recomposition is shift-ADD, w_high * 2^l + w_low (Eq. 4).
+ *   nq_decompose / nq_decompose_pack produce w_high = clip(round-half-to-even(w_int / 2^l)) to h bits;
+ *   any other w_high (adaptive rounding) goes through nq_pack with its own residual.  The part-bit
+ *   mode runs on every kernel as before; the full-bit mode of this format runs on the generic GEMM /
+ *   convolution kernel only. */
 typedef enum { NQ_LOW_UNSIGNED_L = 0, NQ_LOW_SIGNED_L1 = 1 } nq_low_format;
 
 /* Page layouts.

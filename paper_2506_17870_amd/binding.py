@@ -263,7 +263,8 @@ class NestedWeight:
         slices of two arenas so that a whole model can be paged in with few copies."""
         h = cfg.n_bits - cfg.l_bits
         self.cfg, self.N, self.K = cfg, N, K
-        low_bytes = max(nq_packed_bytes(N, K, cfg.l_bits, cfg.layout), 16)
+        low_field = cfg.l_bits + (1 if cfg.low_format == NQ_LOW_SIGNED_L1 else 0)   # compensated part: l + 1 bits
+        low_bytes = max(nq_packed_bytes(N, K, low_field, cfg.layout), 16)
         self.high = torch.empty(max(nq_packed_bytes(N, K, h, cfg.layout), 16), dtype=torch.uint8, device=device)
         self.low = low if low is not None else torch.empty(low_bytes, dtype=torch.uint8, device=device)
         self.low_host = low_host if low_host is not None else torch.empty(low_bytes, dtype=torch.uint8,
@@ -288,6 +289,16 @@ class NestedWeight:
     def from_int8(cls, d_w_int, d_scale, cfg: nq_cfg, stream=None):
         N, K = d_w_int.shape
         return cls(N, K, cfg, device=d_w_int.device).fill_from_int8(d_w_int, d_scale, stream)
+
+    def fill_from_parts(self, d_high, d_low, d_scale, stream=None):
+        """nq_pack of separately supplied w_high / w_low (e.g. a w_high rounded by the caller's own rule with
+        its signed residual, cfg.low_format = NQ_LOW_SIGNED_L1), then the master copy of the lower-bit page."""
+        nq_pack(d_high, d_low, self.N, self.K, self.cfg, self.high, self.low, stream)
+        self.scale.copy_(d_scale)
+        self.low_host.copy_(self.low)
+        torch.cuda.synchronize()
+        self.desc.low_resident = 1
+        return self
 
     def close(self):
         if self.desc.low_event:

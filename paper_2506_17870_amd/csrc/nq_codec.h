@@ -116,4 +116,34 @@ struct LowCodec {
     }
 };
 
+// The compensated lower-bit part of the paper (Sec. 3.3.3: one extra bit, signed): fields of L + 1
+// bits in two's complement, stored as the same kind of bit string as the unsigned part.  Full-bit
+// recomposition is shift-ADD, w = w_high * 2^l + w_low (Eq. 4), no longer a concatenation.  Per byte
+// lane: the top bit s of the field says w_low < 0, and then w = (w_high - 1) * 2^l + (w_low mod 2^l),
+// so the operand byte is the higher-bit byte minus s at bit S (a subtraction that must not borrow
+// from the neighbouring lane) with the low l bits of the field ORed in below.
+template <int L, int S>
+struct SignedLowCodec {
+    using Raw = LowCodec<L + 1, S + 1>;                       // field at bits [S-L, S]
+    static constexpr uint32_t TOP = rep4(1u << S);             // its sign bit
+    static constexpr uint32_t LOW = rep4(((1u << L) - 1u) << (S - L));
+
+    // D[0..7]: higher-bit bytes (lower S bits zero) -> full-bit operand bytes.
+    __device__ __forceinline__ static void decode_add(const uint32_t (&Q)[L + 1], uint32_t (&D)[8])
+    {
+        uint32_t T[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) T[j] = 0;
+        Raw::decode_or(Q, T);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            // byte-wise a - b for b < 128: force the top bit of a so that no lane borrows, then put
+            // the top bit right (it flips exactly where a's was clear)
+            const uint32_t a = D[j], b = T[j] & TOP;
+            const uint32_t r = ((a | 0x80808080u) - b) ^ (~a & 0x80808080u);
+            D[j] = r | (T[j] & LOW);
+        }
+    }
+};
+
 }  // namespace nq

@@ -19,9 +19,11 @@ inline nq_status check_cfg(const nq_cfg *cfg)
     if (cfg->l_bits < 1 || cfg->l_bits > cfg->n_bits - 2) return NQ_ERR_UNSUPPORTED;
     if (cfg->layout != NQ_LAYOUT_DENSE && cfg->layout != NQ_LAYOUT_PAPER_U64) return NQ_ERR_INVALID_ARG;
     if (cfg->low_format != NQ_LOW_UNSIGNED_L && cfg->low_format != NQ_LOW_SIGNED_L1) return NQ_ERR_INVALID_ARG;
-    if (cfg->low_format != NQ_LOW_UNSIGNED_L) return NQ_ERR_UNSUPPORTED;
     return NQ_OK;
 }
+
+// Field width of the lower-bit page: l, or l + 1 for the compensated signed part (Sec. 3.3.3).
+inline int low_field_bits(const nq_cfg *cfg) { return cfg->l_bits + (cfg->low_format == NQ_LOW_SIGNED_L1 ? 1 : 0); }
 
 inline nq_status check_shape(int64_t N, int64_t K)
 {

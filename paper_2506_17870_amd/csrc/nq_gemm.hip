@@ -161,7 +161,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if (!d_x || !d_y || !w->d_high || !w->d_scale || (full && !w->d_low)) return NQ_ERR_INVALID_ARG;
     if (!aligned16(w->d_high) || (full && !aligned16(w->d_low))) return NQ_ERR_ALIGN;
     if (w->high_bytes < nq_packed_bytes(w->N, w->K, h, NQ_LAYOUT_DENSE)) return NQ_ERR_RANGE;
-    if (full && w->low_bytes < nq_packed_bytes(w->N, w->K, l, NQ_LAYOUT_DENSE)) return NQ_ERR_RANGE;
+    if (full && w->low_bytes < nq_packed_bytes(w->N, w->K, low_field_bits(&w->cfg), NQ_LAYOUT_DENSE)) return NQ_ERR_RANGE;
     if (w->N > (1 << 24) || g.M > (int64_t(1) << 40) / (w->N > 0 ? w->N : 1)) return NQ_ERR_SHAPE;
 
     hipStream_t s = (hipStream_t)stream;
@@ -197,6 +197,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     p.out_int8 = epi->out_int8 != 0;
     // 16-byte activation loads need every chunk of 16 consecutive k inside one pixel
     p.fast_a = (g.Cin % 16 == 0) && aligned16(d_x);
+    p.low_signed = w->cfg.low_format == NQ_LOW_SIGNED_L1;
     // the vector epilogue of int8 outputs moves 16 channels at a time; fp32 outputs with a residual
     // (a calibration pass) and the accumulator dump take the element-wise one as well
     if (p.out_int8)
@@ -211,7 +212,10 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     // 5 few input channels, 6 few rows;
     // a kernel that does not apply to the shape is never forced, the choice falls through.
     const char *env = getenv("NQ_KERNEL");
-    const int force = env ? atoi(env) : 0;
+    int force = env ? atoi(env) : 0;
+    // The compensated lower-bit part (shift-add recomposition) is implemented in the generic kernel only;
+    // the part-bit mode never reads that page and keeps every kernel.
+    if (full && p.low_signed) force = 1;
     const bool plain_gemm = g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && w->K % 256 == 0 && aligned16(d_x);
     // implicit GEMM on the same kernel: any filter over a power-of-two number (>= 16) of input channels
     const int64_t x_bytes = (g.M / ((int64_t)g.Ho * g.Wo)) * g.H * g.W * g.Cin;

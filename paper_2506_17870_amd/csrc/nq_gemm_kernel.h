@@ -31,7 +31,9 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int A_STRIDE = 80;  // bytes per LDS row of the activation tile (64 + 16 padding)
 
-template <int H, int L, bool FULL, int EPI, int BM, int BN, int WM, int WN>
+// FULL: 0 part-bit, 1 full-bit with the unsigned l-bit lower part (concatenation), 2 full-bit with the
+// compensated signed (l+1)-bit lower part (shift-add, Sec. 3.3.3).
+template <int H, int L, int FULL, int EPI, int BM, int BN, int WM, int WN>
 __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
 {
     static_assert(WM * WN == 4, "four waves per block");
@@ -40,6 +42,7 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
     constexpr int TN = BN / WN / 32;   // 32-column tiles per wave
     constexpr int RPT = BM / 64;       // activation rows a thread stages per K step
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
+    constexpr int LD = FULL == 2 ? L + 1 : L;   // dwords of the lower-bit page per slot
 
     __shared__ __attribute__((aligned(16))) uint8_t As[2][BM * A_STRIDE];
 
@@ -122,7 +125,7 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
     const int nb0 = n0 / 32 + wn * TN;
     const int wslot = epi_weight_slot<EPI>(lane);             // channel order that suits the epilogue
     uint32_t P[TN][H];
-    uint32_t Q[TN][FULL ? L : 1];
+    uint32_t Q[TN][FULL ? LD : 1];
     auto load_b = [&](int kb) {
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
@@ -132,17 +135,17 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
                 const uint32_t *src = p.ph + tile * (H * 64) + wslot;
 #pragma unroll
                 for (int i = 0; i < H; ++i) P[t][i] = src[i * 64];
-                if constexpr (FULL) {
-                    const uint32_t *srcl = p.pl + tile * (L * 64) + wslot;
+                if constexpr (FULL != 0) {
+                    const uint32_t *srcl = p.pl + tile * (LD * 64) + wslot;
 #pragma unroll
-                    for (int i = 0; i < L; ++i) Q[t][i] = srcl[i * 64];
+                    for (int i = 0; i < LD; ++i) Q[t][i] = srcl[i * 64];
                 }
             } else {
 #pragma unroll
                 for (int i = 0; i < H; ++i) P[t][i] = 0;
-                if constexpr (FULL) {
+                if constexpr (FULL != 0) {
 #pragma unroll
-                    for (int i = 0; i < L; ++i) Q[t][i] = 0;
+                    for (int i = 0; i < LD; ++i) Q[t][i] = 0;
                 }
             }
         }
@@ -176,7 +179,8 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
         for (int t = 0; t < TN; ++t) {
             uint32_t D[8];
             HighCodec<H>::decode(P[t], D);
-            if constexpr (FULL) LowCodec<L, S>::decode_or(Q[t], D);
+            if constexpr (FULL == 1) LowCodec<L, S>::decode_or(Q[t], D);
+            if constexpr (FULL == 2) SignedLowCodec<L, S>::decode_add(Q[t], D);
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
                 bfrag[t][hf] = v4i{(int)D[4 * hf], (int)D[4 * hf + 1], (int)D[4 * hf + 2], (int)D[4 * hf + 3]};
@@ -255,7 +259,9 @@ void launch_nested_gemm(bool full, int tile, const GemmParams &p, hipStream_t st
         else if (mode == EPI_I8) NQ_LAUNCH_TILES(FULLV, EPI_I8);   \
         else NQ_LAUNCH_TILES(FULLV, EPI_F32);                      \
     } while (0)
-    if (full) NQ_LAUNCH_MODES(true); else NQ_LAUNCH_MODES(false);
+    if (full && p.low_signed) NQ_LAUNCH_MODES(2);
+    else if (full) NQ_LAUNCH_MODES(1);
+    else NQ_LAUNCH_MODES(0);
 }
 
 }  // namespace nq

@@ -21,6 +21,7 @@ struct GemmParams {
     int H, W, Cin, Ho, Wo, KH, KW, stride, pad;
     float act_scale, resid_scale, inv_out_scale, part_mul;
     int relu, out_int8, fast_a;
+    int low_signed;   // lower-bit page holds signed fields of l + 1 bits (compensated format)
     int general;   // 1: the element-wise epilogue is needed (set by the host from the arguments)
     // implicit GEMM of the large-GEMM kernel: Cin = 2^cin_shift, tap / KW = (tap * kw_magic) >> 16
     int conv_big, cin_shift, kw_magic;

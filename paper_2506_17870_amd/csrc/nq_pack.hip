@@ -19,13 +19,37 @@ __device__ __forceinline__ uint32_t sar_bytes(uint32_t x, int l)
     return ((x >> l) & keep) | fill;
 }
 
+// Compensated decomposition (Sec. 3.3.3, Alg. 1 step 2 with round-to-nearest instead of the shift):
+// w_high = clip(round_half_even(w / 2^l)) to h bits, w_low = w - w_high * 2^l, which lies in
+// [-2^l + 1, 2^l - 1] and needs l + 1 signed bits.  v is the INT-n value.
+__host__ __device__ __forceinline__ void split_rtn(int v, int l, int h, int *high, int *low)
+{
+    int q = v >> l;                                     // floor
+    const int r = v - (q << l), half = 1 << (l - 1);
+    if (r > half || (r == half && (q & 1))) ++q;
+    const int top = (1 << (h - 1)) - 1;
+    if (q > top) q = top;                               // (the bottom cannot be passed: floor >= -2^(h-1))
+    *high = q;
+    *low = v - (q << l);
+}
+
 __global__ void __launch_bounds__(256) k_decompose(const int8_t *__restrict__ w, int64_t count, int n_bits,
                                                     int l, int8_t *__restrict__ high,
-                                                    int8_t *__restrict__ low, int vec_ok)
+                                                    int8_t *__restrict__ low, int vec_ok, int sgn)
 {
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t base = tid * 16;
     if (base >= count) return;
+    if (sgn) {
+        for (int64_t i = base; i < count && i < base + 16; ++i) {
+            const int v = (int8_t)((uint8_t)w[i] << (8 - n_bits)) >> (8 - n_bits);   // INT-n value, sign extended
+            int hi, lo;
+            split_rtn(v, l, n_bits - l, &hi, &lo);
+            high[i] = (int8_t)hi;
+            low[i] = (int8_t)lo;
+        }
+        return;
+    }
     const uint32_t lowmask = rep4((1u << l) - 1u);
     const int up = 8 - n_bits;  // an INT6 value is first moved to the top of its byte
     if (vec_ok && base + 16 <= count) {
@@ -58,7 +82,7 @@ template <int H, int L, int SRC>
 __global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a, const int8_t *__restrict__ b,
                                                      int64_t N, int64_t K, int64_t KB, int64_t tiles,
                                                      uint32_t *__restrict__ ph, uint32_t *__restrict__ pl,
-                                                     int vec_ok)
+                                                     int vec_ok, int sgn)
 {
     constexpr int S = 8 - H;        // spare bits of a carrier byte
     constexpr int UP = 8 - H - L;   // 0 for INT8 nesting, 2 for INT6 nesting
@@ -73,6 +97,43 @@ __global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a
     uint32_t X[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) X[j] = 0;
+    if (sgn) {
+        // compensated format: fields of h and l + 1 bits from (w_high, signed w_low), which for SRC 0 are
+        // split off w_int with round-to-nearest first; byte by byte (this is not the measured path)
+        uint32_t XL[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) XL[j] = 0;
+        if (n < N) {
+            for (int j = 0; j < 8; ++j)
+                for (int bb = 0; bb < 4; ++bb) {
+                    const int64_t c = c0 + 4 * j + bb;
+                    if (c >= K) continue;
+                    int hi = 0, lo = 0;
+                    if (SRC == 0) {
+                        const int v = (int8_t)((uint8_t)a[n * K + c] << UP) >> UP;
+                        split_rtn(v, L, H, &hi, &lo);
+                    } else {
+                        if (a) hi = a[n * K + c];
+                        if (b) lo = b[n * K + c];
+                    }
+                    X[j] |= (((uint32_t)hi << S) & 0xFFu) << (8 * bb);
+                    XL[j] |= (((uint32_t)lo & ((2u << L) - 1u)) << (S - L)) << (8 * bb);
+                }
+        }
+        if (ph) {
+            uint32_t P[H];
+            HighCodec<H>::encode(X, P);
+#pragma unroll
+            for (int i = 0; i < H; ++i) ph[tile * (H * 64) + i * 64 + lane] = P[i];
+        }
+        if (pl) {
+            uint32_t Q[L + 1];
+            LowCodec<L + 1, S + 1>::encode(XL, Q);
+#pragma unroll
+            for (int i = 0; i < L + 1; ++i) pl[tile * ((L + 1) * 64) + i * 64 + lane] = Q[i];
+        }
+        return;
+    }
     if (n < N) {
         uint32_t A[8], B[8];
         if (vec_ok && c0 + 32 <= K) {
@@ -129,7 +190,7 @@ template <int H, int L>
 __global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict__ ph,
                                                        const uint32_t *__restrict__ pl, int64_t N, int64_t K,
                                                        int64_t KB, int64_t tiles, int8_t *__restrict__ high,
-                                                       int8_t *__restrict__ low)
+                                                       int8_t *__restrict__ low, int sgn)
 {
     constexpr int S = 8 - H;
     const int lane = threadIdx.x & 63;
@@ -152,7 +213,21 @@ __global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict
                 if (c < K) high[n * K + c] = (int8_t)((int8_t)(D[j] >> (8 * bb)) >> S);
             }
     }
-    if (pl && low) {
+    if (pl && low && sgn) {
+        uint32_t Q[L + 1], D[8];
+#pragma unroll
+        for (int i = 0; i < L + 1; ++i) Q[i] = pl[tile * ((L + 1) * 64) + i * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) D[j] = 0;
+        LowCodec<L + 1, S + 1>::decode_or(Q, D);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            for (int bb = 0; bb < 4; ++bb) {
+                const int64_t c = c0 + 4 * j + bb;
+                const int f = (int)(((D[j] >> (8 * bb)) & 0xFFu) >> (S - L)) & ((2 << L) - 1);
+                if (c < K) low[n * K + c] = (int8_t)((f >> L) ? f - (2 << L) : f);   // (l+1)-bit two's complement
+            }
+    } else if (pl && low) {
         uint32_t Q[L], D[8];
 #pragma unroll
         for (int i = 0; i < L; ++i) Q[i] = pl[tile * (L * 64) + i * 64 + lane];
@@ -171,7 +246,7 @@ __global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict
 // ---------------------------------------------------------------------------------------
 // The paper's packed-bit tensor (Sec. 3.3.4): 64/k fields per unsigned 64-bit word.
 // One thread per word.  part 0: fields are (w >> l) from w_int; 1: the low l bits of w_int;
-// 2: the given values as they are.
+// 2: the given values as they are; 3 / 4: the round-to-nearest w_high of w_int / its signed residual.
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) k_pack_paper(const int8_t *__restrict__ v, int64_t N, int64_t K, int k,
                                                      int part, int l, int up, int64_t wpr,
@@ -189,6 +264,11 @@ __global__ void __launch_bounds__(256) k_pack_paper(const int8_t *__restrict__ v
         int val = v[n * K + c];
         if (part == 0) val = ((int8_t)((uint8_t)val << up)) >> (l + up);
         else if (part == 1) val = val & ((1 << l) - 1);
+        else if (part == 3 || part == 4) {              // compensated split of w_int: its high / its low part
+            int hi, lo;
+            split_rtn(((int8_t)((uint8_t)val << up)) >> up, l, 8 - up - l, &hi, &lo);
+            val = part == 3 ? hi : lo;
+        }
         word |= ((uint64_t)(int64_t)val & mask) << (j * k);
     }
     out[idx] = word;
@@ -209,7 +289,7 @@ __global__ void __launch_bounds__(256) k_unpack_paper(const uint64_t *__restrict
 }
 
 template <int H, int L>
-static void launch_pack_dense(int src, const int8_t *a, const int8_t *b, int64_t N, int64_t K, void *ph,
+static void launch_pack_dense(int src, int sgn, const int8_t *a, const int8_t *b, int64_t N, int64_t K, void *ph,
                               void *pl, hipStream_t st)
 {
     const int64_t NB = ceil_div(N, 32), KB = ceil_div(K, 64), tiles = NB * KB;
@@ -218,20 +298,20 @@ static void launch_pack_dense(int src, const int8_t *a, const int8_t *b, int64_t
     const dim3 grid((unsigned)ceil_div(tiles, 4)), block(256);
     if (src == 0)
         hipLaunchKernelGGL((k_pack_dense<H, L, 0>), grid, block, 0, st, a, b, N, K, KB, tiles,
-                           (uint32_t *)ph, (uint32_t *)pl, vec_ok);
+                           (uint32_t *)ph, (uint32_t *)pl, vec_ok, sgn);
     else
         hipLaunchKernelGGL((k_pack_dense<H, L, 1>), grid, block, 0, st, a, b, N, K, KB, tiles,
-                           (uint32_t *)ph, (uint32_t *)pl, vec_ok);
+                           (uint32_t *)ph, (uint32_t *)pl, vec_ok, sgn);
 }
 
 template <int H, int L>
-static void launch_unpack_dense(const void *ph, const void *pl, int64_t N, int64_t K, int8_t *high,
+static void launch_unpack_dense(int sgn, const void *ph, const void *pl, int64_t N, int64_t K, int8_t *high,
                                 int8_t *low, hipStream_t st)
 {
     const int64_t NB = ceil_div(N, 32), KB = ceil_div(K, 64), tiles = NB * KB;
     if (tiles == 0) return;
     hipLaunchKernelGGL((k_unpack_dense<H, L>), dim3((unsigned)ceil_div(tiles, 4)), dim3(256), 0, st,
-                       (const uint32_t *)ph, (const uint32_t *)pl, N, K, KB, tiles, high, low);
+                       (const uint32_t *)ph, (const uint32_t *)pl, N, K, KB, tiles, high, low, sgn);
 }
 
 static nq_status check_pages(const nq_cfg *cfg, const void *ph, const void *pl)
@@ -271,7 +351,8 @@ extern "C" nq_status nq_decompose(const int8_t *d_w_int, int64_t N, int64_t K, c
     const int vec_ok = aligned16(d_w_int) && aligned16(d_high) && aligned16(d_low);
     const int64_t threads = ceil_div(count, 16);
     hipLaunchKernelGGL(k_decompose, dim3((unsigned)ceil_div(threads, 256)), dim3(256), 0, (hipStream_t)stream,
-                       d_w_int, count, cfg->n_bits, cfg->l_bits, d_high, d_low, vec_ok);
+                       d_w_int, count, cfg->n_bits, cfg->l_bits, d_high, d_low, vec_ok,
+                       cfg->low_format == NQ_LOW_SIGNED_L1);
     return launch_status();
 }
 
@@ -284,20 +365,21 @@ static nq_status pack_any(int src, const int8_t *a, const int8_t *b, int64_t N, 
     if ((st = check_pages(cfg, ph, pl)) != NQ_OK) return st;
     if (N * K == 0) return NQ_OK;
     const int h = cfg->n_bits - cfg->l_bits, l = cfg->l_bits;
+    const int sgn = cfg->low_format == NQ_LOW_SIGNED_L1, lf = low_field_bits(cfg);
     hipStream_t s = (hipStream_t)stream;
     if (cfg->layout == NQ_LAYOUT_DENSE) {
-        NQ_DISPATCH_HL(h, l, launch_pack_dense, src, a, b, N, K, ph, pl, s);
+        NQ_DISPATCH_HL(h, l, launch_pack_dense, src, sgn, a, b, N, K, ph, pl, s);
     } else {
         const int up = 8 - cfg->n_bits;
         if (ph) {
             const int64_t wpr = ceil_div(K, 64 / h);
             hipLaunchKernelGGL(k_pack_paper, dim3((unsigned)ceil_div(N * wpr, 256)), dim3(256), 0, s, a, N, K, h,
-                               src == 0 ? 0 : 2, l, up, wpr, (uint64_t *)ph);
+                               src == 0 ? (sgn ? 3 : 0) : 2, l, up, wpr, (uint64_t *)ph);
         }
         if (pl) {
-            const int64_t wpr = ceil_div(K, 64 / l);
+            const int64_t wpr = ceil_div(K, 64 / lf);
             hipLaunchKernelGGL(k_pack_paper, dim3((unsigned)ceil_div(N * wpr, 256)), dim3(256), 0, s,
-                               src == 0 ? a : b, N, K, l, src == 0 ? 1 : 2, l, up, wpr, (uint64_t *)pl);
+                               src == 0 ? a : b, N, K, lf, src == 0 ? (sgn ? 4 : 1) : 2, l, up, wpr, (uint64_t *)pl);
         }
     }
     return launch_status();
@@ -333,17 +415,18 @@ extern "C" nq_status nq_unpack(const void *d_packed_high, const void *d_packed_l
     if ((st = check_pages(cfg, d_packed_high, d_packed_low)) != NQ_OK) return st;
     if (N * K == 0) return NQ_OK;
     const int h = cfg->n_bits - cfg->l_bits, l = cfg->l_bits;
+    const int sgn = cfg->low_format == NQ_LOW_SIGNED_L1, lf = low_field_bits(cfg);
     hipStream_t s = (hipStream_t)stream;
     if (cfg->layout == NQ_LAYOUT_DENSE) {
-        NQ_DISPATCH_HL(h, l, launch_unpack_dense, d_packed_high, d_packed_low, N, K, d_high, d_low, s);
+        NQ_DISPATCH_HL(h, l, launch_unpack_dense, sgn, d_packed_high, d_packed_low, N, K, d_high, d_low, s);
     } else {
         const dim3 grid((unsigned)ceil_div(N * K, 256)), block(256);
         if (d_high)
             hipLaunchKernelGGL(k_unpack_paper, grid, block, 0, s, (const uint64_t *)d_packed_high, N, K, h, 1,
                                ceil_div(K, 64 / h), d_high);
         if (d_low)
-            hipLaunchKernelGGL(k_unpack_paper, grid, block, 0, s, (const uint64_t *)d_packed_low, N, K, l, 0,
-                               ceil_div(K, 64 / l), d_low);
+            hipLaunchKernelGGL(k_unpack_paper, grid, block, 0, s, (const uint64_t *)d_packed_low, N, K, lf, sgn,
+                               ceil_div(K, 64 / lf), d_low);
     }
     return launch_status();
 }

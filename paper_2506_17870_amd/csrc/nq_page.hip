@@ -29,7 +29,7 @@ extern "C" nq_status nq_weight_init(nq_weight *w)
     nq_status st = check_cfg(&w->cfg);
     if (st != NQ_OK) return st;
     if ((st = check_shape(w->N, w->K)) != NQ_OK) return st;
-    const int h = w->cfg.n_bits - w->cfg.l_bits, l = w->cfg.l_bits;
+    const int h = w->cfg.n_bits - w->cfg.l_bits, l = low_field_bits(&w->cfg);
     if (w->high_bytes < nq_packed_bytes(w->N, w->K, h, w->cfg.layout)) return NQ_ERR_RANGE;
     if (w->low_bytes < nq_packed_bytes(w->N, w->K, l, w->cfg.layout)) return NQ_ERR_RANGE;
     if ((w->d_high && !aligned16(w->d_high)) || (w->d_low && !aligned16(w->d_low))) return NQ_ERR_ALIGN;
@@ -103,7 +103,7 @@ extern "C" nq_status nq_page_in_low(nq_weight *w, void *copy_stream)
     nq_status st = check_cfg(&w->cfg);
     if (st != NQ_OK) return st;
     if (!w->low_event) return NQ_ERR_INVALID_ARG;  // nq_weight_init was not called
-    const size_t need = nq_packed_bytes(w->N, w->K, w->cfg.l_bits, w->cfg.layout);
+    const size_t need = nq_packed_bytes(w->N, w->K, low_field_bits(&w->cfg), w->cfg.layout);
     if (w->low_bytes < need) return NQ_ERR_RANGE;
     hipStream_t s = (hipStream_t)copy_stream;
     if (w->free_event_armed && w->free_event) {
@@ -142,7 +142,7 @@ extern "C" nq_status nq_weight_init_group(nq_weight *const *ws, int64_t count)
     for (int64_t i = 1; i < count; ++i) {
         nq_weight *w = ws[i];
         if ((st = check_cfg(&w->cfg)) != NQ_OK || (st = check_shape(w->N, w->K)) != NQ_OK) return st;
-        const int h = w->cfg.n_bits - w->cfg.l_bits, l = w->cfg.l_bits;
+        const int h = w->cfg.n_bits - w->cfg.l_bits, l = low_field_bits(&w->cfg);
         if (w->high_bytes < nq_packed_bytes(w->N, w->K, h, w->cfg.layout)) return NQ_ERR_RANGE;
         if (w->low_bytes < nq_packed_bytes(w->N, w->K, l, w->cfg.layout)) return NQ_ERR_RANGE;
         if ((w->d_high && !aligned16(w->d_high)) || (w->d_low && !aligned16(w->d_low))) return NQ_ERR_ALIGN;
@@ -188,7 +188,7 @@ extern "C" nq_status nq_page_in_low_batch(nq_weight *const *ws, int64_t count, v
     for (int64_t i = 0; i < count; ++i) {
         nq_status st = check_cfg(&ws[i]->cfg);
         if (st != NQ_OK) return st;
-        const size_t need = nq_packed_bytes(ws[i]->N, ws[i]->K, ws[i]->cfg.l_bits, ws[i]->cfg.layout);
+        const size_t need = nq_packed_bytes(ws[i]->N, ws[i]->K, low_field_bits(&ws[i]->cfg), ws[i]->cfg.layout);
         if (ws[i]->low_bytes < need) return NQ_ERR_RANGE;
         if (need > 0 && (!ws[i]->d_low || !ws[i]->h_low)) return NQ_ERR_INVALID_ARG;
         if (need > 0 && !aligned16(ws[i]->d_low)) return NQ_ERR_ALIGN;
@@ -211,7 +211,7 @@ extern "C" nq_status nq_page_in_low_batch(nq_weight *const *ws, int64_t count, v
             span += ws[j]->low_bytes;
             ++j;
         }
-        if (j == i + 1) span = nq_packed_bytes(ws[i]->N, ws[i]->K, ws[i]->cfg.l_bits, ws[i]->cfg.layout);
+        if (j == i + 1) span = nq_packed_bytes(ws[i]->N, ws[i]->K, low_field_bits(&ws[i]->cfg), ws[i]->cfg.layout);
         if (span > 0 && hipMemcpyAsync(d0, h0, span, hipMemcpyHostToDevice, s) != hipSuccess) {
             (void)hipGetLastError();
             return NQ_ERR_HIP;

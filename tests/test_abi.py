@@ -68,8 +68,11 @@ def test_host_side_argument_checks(nq):
             nq.nq_decompose_pack(a, 4, 4, nq.make_cfg(n, l), a, a, stream=0)
         assert e.value.status == nq.NQ_ERR_UNSUPPORTED
     with pytest.raises(nq.NQError) as e:
-        nq.nq_decompose_pack(a, 4, 4, nq.make_cfg(8, 2, nq.NQ_LOW_SIGNED_L1), a, a, stream=0)
-    assert e.value.status == nq.NQ_ERR_UNSUPPORTED
+        nq.nq_decompose_pack(a, 4, 4, nq.make_cfg(8, 2, 7), a, a, stream=0)     # no such lower-bit format
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    # the compensated format is accepted: an empty tensor is a no-op, its page has l + 1 bits per element
+    nq.nq_decompose_pack(a, 0, 16, nq.make_cfg(8, 2, nq.NQ_LOW_SIGNED_L1), a, a, stream=0)
+    assert nq.nq_packed_bytes(64, 128, 3) == 64 * 128 * 3 // 8
     with pytest.raises(nq.NQError) as e:
         nq.nq_decompose_pack(a, 4, nq.NQ_MAX_K + 1, nq.make_cfg(8, 2), a, a, stream=0)
     assert e.value.status == nq.NQ_ERR_SHAPE
