@@ -65,9 +65,8 @@ typedef enum {
  *   two's-complement field of l + 1 bits (the lower-bit page then has l + 1 bits per element; pass
  *   l + 1 to nq_packed_bytes); recomposition is shift-ADD, w_high * 2^l + w_low (Eq. 4).
  *   nq_decompose / nq_decompose_pack produce w_high = clip(round-half-to-even(w_int / 2^l)) to h bits;
- *   any other w_high (adaptive rounding) goes through nq_pack with its own residual.  The part-bit
- *   mode runs on every kernel as before; the full-bit mode of this format runs on the generic GEMM /
- *   convolution kernel only. */
+ *   any other w_high (adaptive rounding) goes through nq_pack with its own residual.  Both modes
+ *   run on every GEMM / convolution kernel; the full-bit mode decodes one more bit per weight. */
 typedef enum { NQ_LOW_UNSIGNED_L = 0, NQ_LOW_SIGNED_L1 = 1 } nq_low_format;
 
 /* Page layouts.

@@ -146,4 +146,18 @@ struct SignedLowCodec {
     }
 };
 
+// The lower-bit page as the GEMM / convolution kernels see it.  MODE 0: not read (part-bit model);
+// 1: unsigned l-bit part, concatenated below the higher-bit field; 2: compensated signed (l+1)-bit
+// part, added.  DW = packed dwords per slot of a tile.
+template <int L, int S, int MODE>
+struct LowPage {
+    static constexpr int DW = MODE == 2 ? L + 1 : (MODE == 1 ? L : 0);
+    static constexpr int ARR = DW ? DW : 1;                   // array extent (never zero)
+    __device__ __forceinline__ static void apply(const uint32_t (&Q)[ARR], uint32_t (&D)[8])
+    {
+        if constexpr (MODE == 1) LowCodec<L, S>::decode_or(Q, D);
+        if constexpr (MODE == 2) SignedLowCodec<L, S>::decode_add(Q, D);
+    }
+};
+
 }  // namespace nq

@@ -41,11 +41,13 @@ constexpr int RS_HALO_OFFSET = 0x40000000;   // out of range for any image (host
 // RS_LDMAX: 16-byte window pieces a thread stages per unit.
 // RS_CT: 32-channel tiles a block keeps weights for (short reductions leave registers for several:
 // the input rows of a unit are then fetched once for all of them).
-template <int H, int L, bool FULL, int EPI, int RS_KCAP, int RS_LDMAX, int RS_CT>
+template <int H, int L, int FULL, int EPI, int RS_KCAP, int RS_LDMAX, int RS_CT>
 __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmParams p, const StreamGeom g)
 {
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
+    using LP = LowPage<L, S, FULL>;
+    constexpr int WD = H + LP::DW > 8 ? H + LP::DW : 8;   // packed dwords of a K step on arrival (decoded: 8)
     constexpr int RS_G = rs_round(RS_LDMAX);
 
     extern __shared__ __attribute__((aligned(16))) uint8_t win[];
@@ -61,21 +63,22 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
     const int c16 = p.Cin >> 4;
 
     // ---- weights: every K step of the channel tile, requested first -----------------------------
-    uint32_t W8[RS_CT][RS_KCAP][8];   // packed dwords on arrival, decoded fragments afterwards
+    uint32_t W8[RS_CT][RS_KCAP][WD];   // packed dwords on arrival, decoded fragments afterwards
     {
         const int wslot = epi_weight_slot<EPI>(lane);   // channel order that suits the epilogue
 #pragma unroll
         for (int c = 0; c < RS_CT; ++c) {
             const int nb = min(nb0 + c, p.NB - 1);      // a tile past N repeats the last one, never stored
             const uint32_t *ph = p.ph + (int64_t)nb * p.KB * (H * 64);
-            const uint32_t *pl = FULL ? p.pl + (int64_t)nb * p.KB * (L * 64) : nullptr;
+            const uint32_t *pl = FULL ? p.pl + (int64_t)nb * p.KB * (LP::DW * 64) : nullptr;
 #pragma unroll
             for (int s = 0; s < RS_KCAP; ++s) {
 #pragma unroll
                 for (int i = 0; i < H; ++i) W8[c][s][i] = ph[(unsigned)(s * (H * 64) + i * 64 + wslot)];
-                if constexpr (FULL) {
+                if constexpr (FULL != 0) {
 #pragma unroll
-                    for (int i = 0; i < L; ++i) W8[c][s][H + i] = pl[(unsigned)(s * (L * 64) + i * 64 + wslot)];
+                    for (int i = 0; i < LP::DW; ++i)
+                        W8[c][s][H + i] = pl[(unsigned)(s * (LP::DW * 64) + i * 64 + wslot)];
                 }
             }
         }
@@ -168,11 +171,11 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
 #pragma unroll
             for (int i = 0; i < H; ++i) Pk[i] = W8[c][s][i];
             HighCodec<H>::decode(Pk, D);
-            if constexpr (FULL) {
-                uint32_t Qk[L];
+            if constexpr (FULL != 0) {
+                uint32_t Qk[LP::ARR];
 #pragma unroll
-                for (int i = 0; i < L; ++i) Qk[i] = W8[c][s][H + i];
-                LowCodec<L, S>::decode_or(Qk, D);
+                for (int i = 0; i < LP::DW; ++i) Qk[i] = W8[c][s][H + i];
+                LP::apply(Qk, D);
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) W8[c][s][i] = D[i];
@@ -291,7 +294,7 @@ void launch_nested_conv_rowstream(bool full, const GemmParams &p, const StreamGe
     if (mode == EPI_ANY) { NQ_RS_CASE(FULLV, EPI_ANY) }               \
     else if (mode == EPI_I8) { NQ_RS_CASE(FULLV, EPI_I8) }            \
     else { NQ_RS_CASE(FULLV, EPI_F32) }
-    if (full) { NQ_RS_MODES(true) } else { NQ_RS_MODES(false) }
+    if (full && p.low_signed) { NQ_RS_MODES(2) } else if (full) { NQ_RS_MODES(1) } else { NQ_RS_MODES(0) }
 }
 
 }  // namespace nq

@@ -31,11 +31,12 @@ constexpr int SC_NLD = 8;        // dwords of a window a thread stages (window d
 constexpr int SC_CT = 2;         // 32-channel tiles per block
 
 // KHC: filter rows (exact, so the K loop is straight-line code).
-template <int H, int L, bool FULL, int EPI, int KHC>
+template <int H, int L, int FULL, int EPI, int KHC>
 __global__ void __launch_bounds__(256, 2) k_nested_conv_smallcin(const GemmParams p, const SmallCinGeom g)
 {
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
+    using LP = LowPage<L, S, FULL>;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     uint8_t *win0 = lds;                                   // two windows of g.win_bytes
@@ -59,11 +60,11 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_smallcin(const GemmParam
 #pragma unroll
         for (int i = 0; i < H; ++i) P[i] = p.ph[tile * (H * 64) + i * 64 + lane];
         HighCodec<H>::decode(P, D);
-        if constexpr (FULL) {
-            uint32_t Q[L];
+        if constexpr (FULL != 0) {
+            uint32_t Q[LP::ARR];
 #pragma unroll
-            for (int i = 0; i < L; ++i) Q[i] = p.pl[tile * (L * 64) + i * 64 + lane];
-            LowCodec<L, S>::decode_or(Q, D);
+            for (int i = 0; i < LP::DW; ++i) Q[i] = p.pl[tile * (LP::DW * 64) + i * 64 + lane];
+            LP::apply(Q, D);
         }
         // slot = 32*g + row holds columns 32*g .. 32*g + 31 of the K step, four per dword
         uint8_t *dst = wmat + (t * 32 + (lane & 31)) * (p.KB * 64) + kb * 64 + 32 * (lane >> 5);
@@ -230,7 +231,7 @@ void launch_nested_conv_smallcin(bool full, const GemmParams &p, const SmallCinG
         else if (mode == EPI_I8) NQ_SC_KH(FULLV, EPI_I8);        \
         else NQ_SC_KH(FULLV, EPI_F32);                           \
     } while (0)
-    if (full) NQ_SC_MODES(true); else NQ_SC_MODES(false);
+    if (full && p.low_signed) NQ_SC_MODES(2); else if (full) NQ_SC_MODES(1); else NQ_SC_MODES(0);
 }
 
 }  // namespace nq

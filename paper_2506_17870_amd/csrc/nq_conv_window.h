@@ -21,12 +21,13 @@ namespace nq {
 typedef int w_v4i __attribute__((ext_vector_type(4)));
 typedef int w_v16i __attribute__((ext_vector_type(16)));
 
-template <int H, int L, bool FULL, int EPI, int WMG, int WNG, int TM, int TN>
+template <int H, int L, int FULL, int EPI, int WMG, int WNG, int TM, int TN>
 __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, const WindowGeom g)
 {
     static_assert(WMG * WNG == 4, "four waves per block");
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
+    using LP = LowPage<L, S, FULL>;
     constexpr int BN = WNG * TN * 32;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t win[];
@@ -59,8 +60,8 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
     const int nb0 = n0 / 32 + wn * TN;
     const int wslot = epi_weight_slot<EPI>(lane);     // channel order that suits the epilogue
     uint32_t P[PD][TN][H];
-    uint32_t Q[PD][TN][FULL ? L : 1];
-    auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][FULL ? L : 1], int kb) {
+    uint32_t Q[PD][TN][LP::ARR];
+    auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][LP::ARR], int kb) {
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
             const int nb = nb0 + t;
@@ -69,17 +70,17 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
                 const uint32_t *src = p.ph + tile * (H * 64) + wslot;
 #pragma unroll
                 for (int i = 0; i < H; ++i) Pd[t][i] = src[i * 64];
-                if constexpr (FULL) {
-                    const uint32_t *srcl = p.pl + tile * (L * 64) + wslot;
+                if constexpr (FULL != 0) {
+                    const uint32_t *srcl = p.pl + tile * (LP::DW * 64) + wslot;
 #pragma unroll
-                    for (int i = 0; i < L; ++i) Qd[t][i] = srcl[i * 64];
+                    for (int i = 0; i < LP::DW; ++i) Qd[t][i] = srcl[i * 64];
                 }
             } else {
 #pragma unroll
                 for (int i = 0; i < H; ++i) Pd[t][i] = 0;
-                if constexpr (FULL) {
+                if constexpr (FULL != 0) {
 #pragma unroll
-                    for (int i = 0; i < L; ++i) Qd[t][i] = 0;
+                    for (int i = 0; i < LP::DW; ++i) Qd[t][i] = 0;
                 }
             }
         }
@@ -153,7 +154,7 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
                     for (int t = 0; t < TN; ++t) {
                         uint32_t D[8];
                         HighCodec<H>::decode(P[d][t], D);
-                        if constexpr (FULL) LowCodec<L, S>::decode_or(Q[d][t], D);
+                        LP::apply(Q[d][t], D);
 #pragma unroll
                         for (int hf = 0; hf < 2; ++hf)
                             bfrag[t][hf] =
@@ -235,7 +236,7 @@ void launch_nested_conv_window(bool full, int shape, const GemmParams &p, const 
         else if (mode == EPI_I8) NQ_WIN_LAUNCH(FULLV, EPI_I8);   \
         else NQ_WIN_LAUNCH(FULLV, EPI_F32);                      \
     } while (0)
-    if (full) NQ_WIN_MODES(true); else NQ_WIN_MODES(false);
+    if (full && p.low_signed) NQ_WIN_MODES(2); else if (full) NQ_WIN_MODES(1); else NQ_WIN_MODES(0);
 }
 
 }  // namespace nq

@@ -212,10 +212,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     // 5 few input channels, 6 few rows;
     // a kernel that does not apply to the shape is never forced, the choice falls through.
     const char *env = getenv("NQ_KERNEL");
-    int force = env ? atoi(env) : 0;
-    // The compensated lower-bit part (shift-add recomposition) is implemented in the generic kernel only;
-    // the part-bit mode never reads that page and keeps every kernel.
-    if (full && p.low_signed) force = 1;
+    const int force = env ? atoi(env) : 0;
     const bool plain_gemm = g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && w->K % 256 == 0 && aligned16(d_x);
     // implicit GEMM on the same kernel: any filter over a power-of-two number (>= 16) of input channels
     const int64_t x_bytes = (g.M / ((int64_t)g.Ho * g.Wo)) * g.H * g.W * g.Cin;

@@ -40,13 +40,15 @@ constexpr int GB_ROW = GB_KI * 64;                       // LDS bytes per panel 
 // TM: 32-row tiles per wave (block tile 32*TM x 256); the host picks TM so that the number of
 // blocks fits the 256 compute units with little left over.  TM <= 4 fits two blocks per unit
 // (the element-wise epilogue needs more registers and runs one block per unit rather than spill).
-template <int H, int L, bool FULL, int EPI, int TM, bool CONV>
+// FULL: 0 part-bit, 1 full-bit (unsigned lower part), 2 full-bit (compensated signed lower part).
+template <int H, int L, int FULL, int EPI, int TM, bool CONV>
 __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
 {
     constexpr int GB_BM = 32 * TM;
     constexpr int GB_PANEL = GB_BM * GB_ROW;             // bytes per LDS panel
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
+    using LP = LowPage<L, S, FULL>;
     // weights are requested PD K steps ahead (registers permitting: TM = 4 shares the compute unit with a
     // second block and has 256 registers, TM >= 5 has 512)
     constexpr int TN = 2, PD = (TM == 4 && (FULL || H == 7) ? 2 : 4);
@@ -149,7 +151,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     const int nb0 = n0 / 32 + wave * TN;
     const int wslot = epi_weight_slot<EPI>(lane);             // channel order that suits the epilogue
     uint32_t P[PD][TN][H];
-    uint32_t Q[PD][TN][FULL ? L : 1];
+    uint32_t Q[PD][TN][LP::ARR];
     // K steps past the last one (K not a multiple of 256) read the last real tile: their activations
     // are zero.  Column tiles past N read the last real tile as well: their accumulators are never
     // stored.  So no masking is needed.
@@ -158,8 +160,8 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     for (int t = 0; t < TN; ++t) tile0[t] = (int64_t)min(nb0 + t, p.NB - 1) * p.KB;
     // dword j of a pipeline slot: j < TN*H is higher-bit dword (t = j / H, i = j % H), the rest are the
     // lower-bit dwords; load_b requests the dwords j0 <= j < j1 of K step kb
-    constexpr int NBL = TN * (H + (FULL ? L : 0));
-    auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][FULL ? L : 1], int kb, int j0, int j1) {
+    constexpr int NBL = TN * (H + LP::DW);
+    auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][LP::ARR], int kb, int j0, int j1) {
         const int kbc = min(kb, p.KB - 1);               // the refills of the last iteration are never used
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
@@ -167,11 +169,12 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
 #pragma unroll
             for (int i = 0; i < H; ++i)
                 if (t * H + i >= j0 && t * H + i < j1) Pd[t][i] = src[(unsigned)(i * 64 + wslot)];
-            if constexpr (FULL) {
-                const uint32_t *srcl = p.pl + (tile0[t] + kbc) * (L * 64);
+            if constexpr (FULL != 0) {
+                const uint32_t *srcl = p.pl + (tile0[t] + kbc) * (LP::DW * 64);
 #pragma unroll
-                for (int i = 0; i < L; ++i)
-                    if (TN * H + t * L + i >= j0 && TN * H + t * L + i < j1) Qd[t][i] = srcl[(unsigned)(i * 64 + wslot)];
+                for (int i = 0; i < LP::DW; ++i)
+                    if (TN * H + t * LP::DW + i >= j0 && TN * H + t * LP::DW + i < j1)
+                        Qd[t][i] = srcl[(unsigned)(i * 64 + wslot)];
             }
         }
     };
@@ -224,7 +227,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
         for (int t = 0; t < TN; ++t) {
             uint32_t D[8];
             HighCodec<H>::decode(P[0][t], D);
-            if constexpr (FULL) LowCodec<L, S>::decode_or(Q[0][t], D);
+            LP::apply(Q[0][t], D);
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
                 bfrag[t][hf] = g_v4i{(int)D[4 * hf], (int)D[4 * hf + 1], (int)D[4 * hf + 2], (int)D[4 * hf + 3]};
@@ -253,7 +256,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
 #pragma unroll
                 for (int t = 0; t < TN; ++t) {
                     HighCodec<H>::decode(P[d % PD][t], Dn);
-                    if constexpr (FULL) LowCodec<L, S>::decode_or(Q[d % PD][t], Dn);
+                    LP::apply(Q[d % PD][t], Dn);
 #pragma unroll
                     for (int h2 = 0; h2 < 2; ++h2)
                         bfrag[t][h2] = g_v4i{(int)Dn[4 * h2], (int)Dn[4 * h2 + 1], (int)Dn[4 * h2 + 2],
@@ -282,7 +285,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
                 for (int t = 0; t < TN && AHEAD; ++t) {
                     if (f == t * NF / TN) HighCodec<H>::decode(P[(d + 1) % PD][t], Dn);
                     if (f == t * NF / TN + 1) {
-                        if constexpr (FULL) LowCodec<L, S>::decode_or(Q[(d + 1) % PD][t], Dn);
+                        LP::apply(Q[(d + 1) % PD][t], Dn);
 #pragma unroll
                         for (int h2 = 0; h2 < 2; ++h2)
                             bnext[t][h2] = g_v4i{(int)Dn[4 * h2], (int)Dn[4 * h2 + 1], (int)Dn[4 * h2 + 2],
@@ -381,10 +384,11 @@ void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void
         else if (mode == EPI_I8) NQ_GB_TM(FULLV, EPI_I8, CONVV);         \
         else NQ_GB_TM(FULLV, EPI_F32, CONVV);                            \
     } while (0)
+    const int fmode = full ? (p.low_signed ? 2 : 1) : 0;
     if (p.conv_big) {
-        if (full) NQ_GB_MODE(true, true); else NQ_GB_MODE(false, true);
+        if (fmode == 2) NQ_GB_MODE(2, true); else if (fmode == 1) NQ_GB_MODE(1, true); else NQ_GB_MODE(0, true);
     } else {
-        if (full) NQ_GB_MODE(true, false); else NQ_GB_MODE(false, false);
+        if (fmode == 2) NQ_GB_MODE(2, false); else if (fmode == 1) NQ_GB_MODE(1, false); else NQ_GB_MODE(0, false);
     }
 }
 

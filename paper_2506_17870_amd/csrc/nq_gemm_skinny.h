@@ -22,14 +22,16 @@ namespace nq {
 typedef int k_v4i __attribute__((ext_vector_type(4)));
 typedef int k_v16i __attribute__((ext_vector_type(16)));
 
-constexpr int SK_PD = 4;   // K steps in flight per wave
 
 // TMS: 32-row tiles (1: M <= 32, 2: M <= 64).
-template <int H, int L, bool FULL, int EPI, int TMS>
+template <int H, int L, int FULL, int EPI, int TMS>
 __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams p)
 {
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
+    using LP = LowPage<L, S, FULL>;
+    // K steps in flight per wave; three where four would not fit the register file
+    constexpr int SK_PD = (TMS == 2 && H + LP::DW > 8) ? 3 : 4;
 
     __shared__ int red[3][TMS][16][64];
 
@@ -46,7 +48,7 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams 
     for (int i = 0; i < TMS; ++i) a_row[i] = (32 * i + (lane & 31)) * p.K + 32 * (lane >> 5);
 
     uint32_t P[SK_PD][H];
-    uint32_t Q[SK_PD][FULL ? L : 1];
+    uint32_t Q[SK_PD][LP::ARR];
     k_v4i A[SK_PD][TMS][2];
     const int64_t tile0 = (int64_t)nb * p.KB;
     // K steps past the end are requested like the last real one (weights) and out of range
@@ -56,10 +58,10 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams 
         const uint32_t *src = p.ph + (tile0 + kbc) * (H * 64);
 #pragma unroll
         for (int i = 0; i < H; ++i) P[slot][i] = src[(unsigned)(i * 64 + wslot)];
-        if constexpr (FULL) {
-            const uint32_t *srcl = p.pl + (tile0 + kbc) * (L * 64);
+        if constexpr (FULL != 0) {
+            const uint32_t *srcl = p.pl + (tile0 + kbc) * (LP::DW * 64);
 #pragma unroll
-            for (int i = 0; i < L; ++i) Q[slot][i] = srcl[(unsigned)(i * 64 + wslot)];
+            for (int i = 0; i < LP::DW; ++i) Q[slot][i] = srcl[(unsigned)(i * 64 + wslot)];
         }
         const int koff = kb < p.KB ? 64 * kb : 0x7fff0000;
 #pragma unroll
@@ -87,7 +89,7 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams 
         for (int d = 0; d < SK_PD; ++d) {
             uint32_t D[8];
             HighCodec<H>::decode(P[d], D);
-            if constexpr (FULL) LowCodec<L, S>::decode_or(Q[d], D);
+            LP::apply(Q[d], D);
             k_v4i a[TMS][2];
 #pragma unroll
             for (int i = 0; i < TMS; ++i)
@@ -150,7 +152,7 @@ void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, v
         else if (mode == EPI_I8) NQ_SK_LAUNCH(FULLV, EPI_I8);    \
         else NQ_SK_LAUNCH(FULLV, EPI_F32);                       \
     } while (0)
-    if (full) NQ_SK_MODES(true); else NQ_SK_MODES(false);
+    if (full && p.low_signed) NQ_SK_MODES(2); else if (full) NQ_SK_MODES(1); else NQ_SK_MODES(0);
 }
 
 }  // namespace nq

@@ -78,8 +78,9 @@ def test_decompose_and_pages(nq, n, l):
     assert np.array_equal(host(u_hi), hi_ref) and np.array_equal(host(u_lo), lo_ref)
 
 
-def run_both_modes(nq, W, x, hi, w_full, scale, l, conv=None):
+def run_both_modes(nq, W, x, hi, w_full, scale, l, conv=None, out_int8=False):
     """Full-bit (= the original INT-n weights) and part-bit (= the supplied w_high) against the oracle."""
+    inv_s_out = 9.0 if out_int8 else 1.0
     for full in (True, False):
         w_ref = (w_full if full else hi).astype(np.int16)
         if conv is None:
@@ -89,12 +90,13 @@ def run_both_modes(nq, W, x, hi, w_full, scale, l, conv=None):
             KH, KW, stride, pad = conv
             acc_ref = oracle.conv_acc(x, w_ref.reshape(W.N, KH, KW, x.shape[3]), stride, pad)
             shape = acc_ref.shape[:3]
-        y_ref = oracle.epilogue(acc_ref, 0.02, scale, part_l_bits=0 if full else l, relu=True)
+        y_ref = oracle.epilogue(acc_ref, 0.02, scale, part_l_bits=0 if full else l, relu=True,
+                                out_int8=out_int8, inv_s_out=inv_s_out)
         for dump in (True, False):
             for kernel in each_kernel():
                 acc = torch.empty(shape + (W.N,), dtype=torch.int32, device="cuda") if dump else None
-                y = torch.full(shape + (W.N,), 77, dtype=torch.float32, device="cuda")
-                epi = nq.make_epilogue(0.02, relu=True, d_acc_dump=acc)
+                y = torch.full(shape + (W.N,), 77, dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+                epi = nq.make_epilogue(0.02, relu=True, out_int8=out_int8, inv_out_scale=inv_s_out, d_acc_dump=acc)
                 if conv is None:
                     (nq.nq_gemm_full if full else nq.nq_gemm_part)(dev(x), x.shape[0], W.desc, epi, y)
                 else:
@@ -102,7 +104,7 @@ def run_both_modes(nq, W, x, hi, w_full, scale, l, conv=None):
                     (nq.nq_conv_full if full else nq.nq_conv_part)(dev(x), cs, W.desc, epi, y)
                 torch.cuda.synchronize()
                 try:
-                    check_outputs(host(y), host(acc) if dump else None, y_ref, acc_ref, False)
+                    check_outputs(host(y), host(acc) if dump else None, y_ref, acc_ref, out_int8)
                 except AssertionError as e:
                     raise AssertionError(f"{e} (full={full}, NQ_KERNEL='{kernel}', dump {dump})") from None
 
@@ -116,6 +118,39 @@ def test_gemm_with_round_to_nearest_high(nq, n, l):
     hi, _ = oracle.decompose(w, n, l, "rtn")
     x = inputs.uniform_activations((M, K), seed=l) >> (8 - n)
     run_both_modes(nq, W, x, hi, w, scale, l)
+
+
+# shapes that reach the specialised kernels: large GEMM (K a multiple of 256, several row tiles), few
+# rows (one and two 32-row tiles), each with fp32 and int8 outputs
+@pytest.mark.parametrize("n,l", [(8, 4), (8, 2), (8, 1), (6, 3), (6, 1)])
+@pytest.mark.parametrize("M,N,K", [(200, 160, 512), (330, 96, 768), (40, 96, 512), (16, 128, 1024)])
+def test_gemm_shapes_of_the_specialised_kernels(nq, n, l, M, N, K):
+    w, scale = inputs.weights(N, K, 0.02, n, seed=M + n + l)
+    cfg = nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1)
+    W = nq.NestedWeight.from_int8(dev(w), dev(scale), cfg)
+    hi, _ = oracle.decompose(w, n, l, "rtn")
+    x = inputs.uniform_activations((M, K), seed=K + l)
+    for out_int8 in (False, True):
+        run_both_modes(nq, W, x, hi, w, scale, l, out_int8=out_int8)
+
+
+# convolutions that reach the register-stationary kernel (1x1 and 3x3 over 64 channels, 1x1 over 256),
+# the large implicit GEMM (3x3 over 128 channels) and the few-channel kernel (7x7 and 3x3 over 3 channels)
+@pytest.mark.parametrize("n,l", [(8, 4), (8, 2), (6, 2)])
+@pytest.mark.parametrize("Cin,Cout,KH,stride,pad,HW", [(64, 64, 1, 1, 0, 20), (64, 96, 3, 1, 1, 14),
+                                                      (256, 64, 1, 1, 0, 12), (128, 128, 3, 1, 1, 12),
+                                                      (512, 128, 1, 1, 0, 9), (3, 64, 7, 2, 3, 40),
+                                                      (3, 32, 3, 2, 1, 33)])
+def test_convolution_shapes_of_the_specialised_kernels(nq, n, l, Cin, Cout, KH, stride, pad, HW):
+    B = 2
+    K = KH * KH * Cin
+    w, scale = inputs.weights(Cout, K, inputs.he_sigma(K), n, seed=Cin + KH + n + l)
+    cfg = nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1)
+    W = nq.NestedWeight.from_int8(dev(w), dev(scale), cfg)
+    hi, _ = oracle.decompose(w, n, l, "rtn")
+    x = inputs.uniform_activations((B, HW, HW - 1, Cin), seed=HW + l)
+    for out_int8 in (False, True):
+        run_both_modes(nq, W, x, hi, w, scale, l, conv=(KH, KH, stride, pad), out_int8=out_int8)
 
 
 @pytest.mark.parametrize("rounding", ["up", "down", "rtn"])
