@@ -230,6 +230,26 @@ def pack():
         gbs = 2.0 * N * K / us / 1e3
         print(f"| {name} | {us:.1f} | {gbs:.0f} | {100 * gbs / HBM_PEAK:.1f} |")
         del w, ph, pl
+    print("\n### quantise, decompose and pack from fp32 weights (Eq. 1 fused in front; 4 B read + 1 B written per "
+          "weight\ncounted, the second pass over the fp32 weights not counted)\n")
+    print("| tensor | us | GB/s (counted bytes) | % HBM peak | two calls: nq_quantize + nq_decompose_pack, us |")
+    print("|---|---|---|---|---|")
+    for name, N, K in (("ResNet-101 largest layer 512x4608", 512, 4608), ("4096 x 4096", 4096, 4096),
+                       ("16384 x 16384 (1 GiB of fp32)", 16384, 16384)):
+        w = torch.randn((N, K), dtype=torch.float32, device="cuda") * 0.02
+        wi = torch.empty((N, K), dtype=torch.int8, device="cuda")
+        sc = torch.empty(N, dtype=torch.float32, device="cuda")
+        ph = torch.empty(nq.nq_packed_bytes(N, K, 6), dtype=torch.uint8, device="cuda")
+        pl = torch.empty(nq.nq_packed_bytes(N, K, 2), dtype=torch.uint8, device="cuda")
+        us = wall_us(lambda: nq.nq_quantize_decompose_pack(w, N, K, cfg, sc, ph, pl), n=20)
+
+        def two_calls():
+            nq.nq_quantize(w, N, K, 8, wi, sc)
+            nq.nq_decompose_pack(wi, N, K, cfg, ph, pl)
+        us2 = wall_us(two_calls, n=20)
+        gbs = 5.0 * N * K / us / 1e3
+        print(f"| {name} | {us:.1f} | {gbs:.0f} | {100 * gbs / HBM_PEAK:.1f} | {us2:.1f} |")
+        del w, wi, ph, pl
 
 
 def page():

@@ -158,6 +158,24 @@ const char *nq_status_string(int status);
  * Returns 0 for invalid arguments (field_bits outside 1..8 for PAPER_U64, 1..7 for DENSE). */
 size_t nq_packed_bytes(int64_t N, int64_t K, int field_bits, int layout);
 
+/* ---- quantisation ---------------------------------------------------------------- */
+/* Eq. 1 (Sec. 3.1), per output channel (row n of the fp32 weights [N][K]): symmetric, no zero
+ * point; d_scale[n] = max_k |w[n][k]| / (2^(n_bits-1) - 1), 1.0 for an all-zero row;
+ * d_w_int[n][k] = Clip(round-half-to-even(w[n][k] / d_scale[n]), -2^(n_bits-1), 2^(n_bits-1) - 1).
+ * The quotient and the rounding are taken in fp32 (IEEE division, not a reciprocal), so the codes
+ * are a function of the fp32 inputs alone.  n_bits in 2..8.  Weights must be finite.
+ * In: device fp32[N*K].  Out: device int8[N*K], fp32[N]; all caller owned. */
+nq_status nq_quantize(const float *d_w, int64_t N, int64_t K, int n_bits, int8_t *d_w_int,
+                      float *d_scale, void *stream);
+
+/* Eq. 1 followed by the decomposition and packing of nq_decompose_pack (Alg. 1 steps 1-3) without the
+ * int8 tensor in between: one pass over the fp32 weights for the channel scales, one that quantises,
+ * splits and writes the pages.  Same pages as nq_quantize + nq_decompose_pack.  NQ_LAYOUT_DENSE only
+ * (NQ_ERR_UNSUPPORTED otherwise).  d_scale: out, fp32[N].  Either page may be NULL. */
+nq_status nq_quantize_decompose_pack(const float *d_w, int64_t N, int64_t K, const nq_cfg *cfg,
+                                     float *d_scale, void *d_packed_high, void *d_packed_low,
+                                     void *stream);
+
 /* ---- decomposition and packing ----------------------------------------------------- */
 /* Eq. 4 / Eq. 5 (BitShift): d_high[i] = d_w_int[i] >> l (arithmetic shift, i.e. floor),
  * d_low[i] = d_w_int[i] - d_high[i] * 2^l in [0, 2^l - 1].  Elementwise over N*K int8.

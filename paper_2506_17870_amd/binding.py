@@ -22,7 +22,8 @@ NQ_LOW_UNSIGNED_L, NQ_LOW_SIGNED_L1 = 0, 1
 NQ_LAYOUT_DENSE, NQ_LAYOUT_PAPER_U64 = 0, 1
 NQ_MAX_K = 65536
 
-EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_decompose", "nq_pack", "nq_decompose_pack",
+EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "nq_quantize_decompose_pack",
+           "nq_decompose", "nq_pack", "nq_decompose_pack",
            "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
            "nq_weight_init_group", "nq_page_out_low_batch", "nq_page_in_low_batch",
            "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_profile_next_launch", "nq_event_create", "nq_event_destroy",
@@ -68,6 +69,8 @@ _SIGS = {
     "nq_version": (ctypes.c_int, []),
     "nq_status_string": (ctypes.c_char_p, [_int]),
     "nq_packed_bytes": (ctypes.c_size_t, [_i64, _i64, _int, _int]),
+    "nq_quantize": (_int, [_vp, _i64, _i64, _int, _vp, _vp, _vp]),
+    "nq_quantize_decompose_pack": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp, _vp]),
     "nq_decompose": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
     "nq_pack": (_int, [_vp, _vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
     "nq_decompose_pack": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
@@ -147,6 +150,15 @@ def nq_decompose(d_w_int, N, K, cfg, d_high, d_low, stream=None):
 def nq_pack(d_high, d_low, N, K, cfg, d_packed_high, d_packed_low, stream=None):
     _check(_lib.nq_pack(_ptr(d_high), _ptr(d_low), N, K, ctypes.byref(cfg), _ptr(d_packed_high),
                         _ptr(d_packed_low), _stream(stream)), "nq_pack")
+
+
+def nq_quantize(d_w, N, K, n_bits, d_w_int, d_scale, stream=None):
+    _check(_lib.nq_quantize(_ptr(d_w), N, K, n_bits, _ptr(d_w_int), _ptr(d_scale), _stream(stream)), "nq_quantize")
+
+
+def nq_quantize_decompose_pack(d_w, N, K, cfg, d_scale, d_packed_high, d_packed_low, stream=None):
+    _check(_lib.nq_quantize_decompose_pack(_ptr(d_w), N, K, ctypes.byref(cfg), _ptr(d_scale), _ptr(d_packed_high),
+                                           _ptr(d_packed_low), _stream(stream)), "nq_quantize_decompose_pack")
 
 
 def nq_decompose_pack(d_w_int, N, K, cfg, d_packed_high, d_packed_low, stream=None):
@@ -289,6 +301,18 @@ class NestedWeight:
     def from_int8(cls, d_w_int, d_scale, cfg: nq_cfg, stream=None):
         N, K = d_w_int.shape
         return cls(N, K, cfg, device=d_w_int.device).fill_from_int8(d_w_int, d_scale, stream)
+
+    @classmethod
+    def from_float(cls, d_w, cfg: nq_cfg, stream=None):
+        """nq_quantize_decompose_pack of fp32 weights [N, K] on the device (dense layout), then the master
+        copy of the lower-bit page to the host."""
+        N, K = d_w.shape
+        self = cls(N, K, cfg, device=d_w.device)
+        nq_quantize_decompose_pack(d_w, N, K, cfg, self.scale, self.high, self.low, stream)
+        self.low_host.copy_(self.low)
+        torch.cuda.synchronize()
+        self.desc.low_resident = 1
+        return self
 
     def fill_from_parts(self, d_high, d_low, d_scale, stream=None):
         """nq_pack of separately supplied w_high / w_low (e.g. a w_high rounded by the caller's own rule with

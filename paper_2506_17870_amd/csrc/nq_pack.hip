@@ -76,7 +76,8 @@ __global__ void __launch_bounds__(256) k_decompose(const int8_t *__restrict__ w,
 // Dense-tile pack.  One wave per tile of 32 rows x 64 columns, one lane per slot: the lane
 // reads the 32 consecutive weights of its slot and writes H dwords of the higher-bit page
 // and L dwords of the lower-bit page; a wave's stores are 256 contiguous bytes each.
-// SRC 0: from w_int (fused decomposition); SRC 1: from separate high / low tensors.
+// SRC 0: from w_int (fused decomposition); SRC 1: from separate high / low tensors; SRC 2: from fp32
+// weights (a) and their channel scales (b), quantised on the way (Eq. 1).
 // ---------------------------------------------------------------------------------------
 template <int H, int L, int SRC>
 __global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a, const int8_t *__restrict__ b,
@@ -94,49 +95,37 @@ __global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a
     const int64_t n = nb * 32 + r;
     const int64_t c0 = kb * 64 + 32 * g;
 
-    uint32_t X[8];
+    // ---- the slot's 32 elements, four per dword; zero outside the matrix ------------------------
+    // A: the INT-n codes (SRC 0, 2) or w_high (SRC 1); B: w_low (SRC 1)
+    uint32_t A[8], B[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) X[j] = 0;
-    if (sgn) {
-        // compensated format: fields of h and l + 1 bits from (w_high, signed w_low), which for SRC 0 are
-        // split off w_int with round-to-nearest first; byte by byte (this is not the measured path)
-        uint32_t XL[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) XL[j] = 0;
-        if (n < N) {
-            for (int j = 0; j < 8; ++j)
-                for (int bb = 0; bb < 4; ++bb) {
-                    const int64_t c = c0 + 4 * j + bb;
-                    if (c >= K) continue;
-                    int hi = 0, lo = 0;
-                    if (SRC == 0) {
-                        const int v = (int8_t)((uint8_t)a[n * K + c] << UP) >> UP;
-                        split_rtn(v, L, H, &hi, &lo);
-                    } else {
-                        if (a) hi = a[n * K + c];
-                        if (b) lo = b[n * K + c];
-                    }
-                    X[j] |= (((uint32_t)hi << S) & 0xFFu) << (8 * bb);
-                    XL[j] |= (((uint32_t)lo & ((2u << L) - 1u)) << (S - L)) << (8 * bb);
-                }
-        }
-        if (ph) {
-            uint32_t P[H];
-            HighCodec<H>::encode(X, P);
-#pragma unroll
-            for (int i = 0; i < H; ++i) ph[tile * (H * 64) + i * 64 + lane] = P[i];
-        }
-        if (pl) {
-            uint32_t Q[L + 1];
-            LowCodec<L + 1, S + 1>::encode(XL, Q);
-#pragma unroll
-            for (int i = 0; i < L + 1; ++i) pl[tile * ((L + 1) * 64) + i * 64 + lane] = Q[i];
-        }
-        return;
-    }
+    for (int j = 0; j < 8; ++j) A[j] = B[j] = 0;
     if (n < N) {
-        uint32_t A[8], B[8];
-        if (vec_ok && c0 + 32 <= K) {
+        if constexpr (SRC == 2) {
+            // Eq. 1 with the channel's scale: IEEE fp32 quotient, round half to even, clip
+            const float *wf = reinterpret_cast<const float *>(a) + n * K;
+            const float sc = reinterpret_cast<const float *>(b)[n];
+            const int qmin = -(1 << (H + L - 1)), qmax = (1 << (H + L - 1)) - 1;
+            auto code = [&](float v) {
+                const int q = (int)__builtin_rintf(v / sc);
+                return (uint32_t)(min(max(q, qmin), qmax) & 0xFF);
+            };
+            if (vec_ok && c0 + 32 <= K) {
+                const float4 *pv = reinterpret_cast<const float4 *>(wf + c0);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float4 v = pv[j];
+                    A[j] = code(v.x) | (code(v.y) << 8) | (code(v.z) << 16) | (code(v.w) << 24);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    for (int bb = 0; bb < 4; ++bb) {
+                        const int64_t c = c0 + 4 * j + bb;
+                        if (c < K) A[j] |= code(wf[c]) << (8 * bb);
+                    }
+            }
+        } else if (vec_ok && c0 + 32 <= K) {
             const uint4 *pa = a ? reinterpret_cast<const uint4 *>(a + n * K + c0) : nullptr;
             const uint4 *pb = (SRC == 1 && b) ? reinterpret_cast<const uint4 *>(b + n * K + c0) : nullptr;
 #pragma unroll
@@ -160,13 +149,49 @@ __global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a
                 A[j] = wa; B[j] = wb;
             }
         }
+    }
+
+    if (sgn) {
+        // compensated format: fields of h and l + 1 bits from (w_high, signed w_low), which unless given
+        // (SRC 1) are split off the codes with round-to-nearest first; byte by byte (not the measured path)
+        uint32_t X[8], XL[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            if (SRC == 0) {
-                X[j] = (A[j] << UP) & rep4(0xFFu << UP);
-            } else {
-                X[j] = ((A[j] << S) & HighCodec<H>::HM) | ((B[j] << (S - L)) & LowCodec<L, S>::LM);
+            X[j] = XL[j] = 0;
+            for (int bb = 0; bb < 4; ++bb) {
+                int hi, lo;
+                if (SRC != 1) {
+                    const int v = (int8_t)((uint8_t)(A[j] >> (8 * bb)) << UP) >> UP;
+                    split_rtn(v, L, H, &hi, &lo);
+                } else {
+                    hi = (int8_t)(A[j] >> (8 * bb));
+                    lo = (int8_t)(B[j] >> (8 * bb));
+                }
+                X[j] |= (((uint32_t)hi << S) & 0xFFu) << (8 * bb);
+                XL[j] |= (((uint32_t)lo & ((2u << L) - 1u)) << (S - L)) << (8 * bb);
             }
+        }
+        if (ph) {
+            uint32_t P[H];
+            HighCodec<H>::encode(X, P);
+#pragma unroll
+            for (int i = 0; i < H; ++i) ph[tile * (H * 64) + i * 64 + lane] = P[i];
+        }
+        if (pl) {
+            uint32_t Q[L + 1];
+            LowCodec<L + 1, S + 1>::encode(XL, Q);
+#pragma unroll
+            for (int i = 0; i < L + 1; ++i) pl[tile * ((L + 1) * 64) + i * 64 + lane] = Q[i];
+        }
+        return;
+    }
+    uint32_t X[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (SRC != 1) {
+            X[j] = (A[j] << UP) & rep4(0xFFu << UP);
+        } else {
+            X[j] = ((A[j] << S) & HighCodec<H>::HM) | ((B[j] << (S - L)) & LowCodec<L, S>::LM);
         }
     }
     if (ph) {
@@ -182,6 +207,55 @@ __global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a
         uint32_t *dst = pl + tile * (L * 64) + lane;
 #pragma unroll
         for (int i = 0; i < L; ++i) dst[i * 64] = Q[i];
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Eq. 1: channel scales and codes.  k_row_absmax: one block per row, 16-byte loads where the
+// row allows; the scale is absmax / qmax (1 for an all-zero row).  k_quantize_codes: one
+// block per 1024 elements of a row.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_row_absmax(const float *__restrict__ w, int64_t K, float qmax,
+                                                     float *__restrict__ scale, int vec_ok)
+{
+    __shared__ float part[4];
+    const float *row = w + (int64_t)blockIdx.x * K;
+    float m = 0.0f;
+    if (vec_ok) {
+        const float4 *rv = reinterpret_cast<const float4 *>(row);
+        for (int64_t i = threadIdx.x; i < K / 4; i += 256) {
+            const float4 v = rv[i];
+            m = fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        }
+    } else {
+        for (int64_t i = threadIdx.x; i < K; i += 256) m = fmaxf(m, fabsf(row[i]));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+        scale[blockIdx.x] = m > 0.0f ? m / qmax : 1.0f;
+    }
+}
+
+__global__ void __launch_bounds__(256) k_quantize_codes(const float *__restrict__ w, int64_t K, int64_t chunks,
+                                                         int n_bits, const float *__restrict__ scale,
+                                                         int8_t *__restrict__ w_int, int vec_ok)
+{
+    const int64_t n = blockIdx.x / chunks, c0 = (blockIdx.x % chunks) * 1024 + threadIdx.x * 4;
+    if (c0 >= K) return;
+    const float sc = scale[n];
+    const int qmin = -(1 << (n_bits - 1)), qmax = (1 << (n_bits - 1)) - 1;
+    auto code = [&](float v) { return (uint32_t)(min(max((int)__builtin_rintf(v / sc), qmin), qmax) & 0xFF); };
+    const float *src = w + n * K + c0;
+    int8_t *dst = w_int + n * K + c0;
+    if (vec_ok) {        // K % 4 == 0: the four elements are inside the row
+        const float4 v = *reinterpret_cast<const float4 *>(src);
+        *reinterpret_cast<uint32_t *>(dst) = code(v.x) | (code(v.y) << 8) | (code(v.z) << 16) | (code(v.w) << 24);
+    } else {
+        for (int i = 0; i < 4 && c0 + i < K; ++i) dst[i] = (int8_t)code(src[i]);
     }
 }
 
@@ -294,9 +368,13 @@ static void launch_pack_dense(int src, int sgn, const int8_t *a, const int8_t *b
 {
     const int64_t NB = ceil_div(N, 32), KB = ceil_div(K, 64), tiles = NB * KB;
     if (tiles == 0) return;
-    const int vec_ok = (K % 16 == 0) && aligned16(a) && (b == nullptr || aligned16(b));
+    const int vec_ok = src == 2 ? (K % 4 == 0) && aligned16(a)
+                                : (K % 16 == 0) && aligned16(a) && (b == nullptr || aligned16(b));
     const dim3 grid((unsigned)ceil_div(tiles, 4)), block(256);
-    if (src == 0)
+    if (src == 2)
+        hipLaunchKernelGGL((k_pack_dense<H, L, 2>), grid, block, 0, st, a, b, N, K, KB, tiles,
+                           (uint32_t *)ph, (uint32_t *)pl, vec_ok, sgn);
+    else if (src == 0)
         hipLaunchKernelGGL((k_pack_dense<H, L, 0>), grid, block, 0, st, a, b, N, K, KB, tiles,
                            (uint32_t *)ph, (uint32_t *)pl, vec_ok, sgn);
     else
@@ -337,6 +415,52 @@ extern "C" size_t nq_packed_bytes(int64_t N, int64_t K, int field_bits, int layo
         return (size_t)(N * ceil_div(K, 64 / field_bits) * 8);
     }
     return 0;
+}
+
+static void launch_row_absmax(const float *d_w, int64_t N, int64_t K, int n_bits, float *d_scale, hipStream_t s)
+{
+    const int vec_ok = (K % 4 == 0) && aligned16(d_w);
+    hipLaunchKernelGGL(k_row_absmax, dim3((unsigned)N), dim3(256), 0, s, d_w, K,
+                       (float)((1 << (n_bits - 1)) - 1), d_scale, vec_ok);
+}
+
+extern "C" nq_status nq_quantize(const float *d_w, int64_t N, int64_t K, int n_bits, int8_t *d_w_int,
+                                 float *d_scale, void *stream)
+{
+    if (n_bits < 2 || n_bits > 8) return NQ_ERR_INVALID_ARG;
+    nq_status st = check_shape(N, K);
+    if (st != NQ_OK) return st;
+    if (N * K == 0) return NQ_OK;
+    if (!d_w || !d_w_int || !d_scale) return NQ_ERR_INVALID_ARG;
+    const int64_t chunks = ceil_div(K, 1024);
+    if (N * chunks > 0x7fffffff) return NQ_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    launch_row_absmax(d_w, N, K, n_bits, d_scale, s);
+    const int vec_ok = (K % 4 == 0) && aligned16(d_w) && ((uintptr_t)d_w_int % 4 == 0);
+    hipLaunchKernelGGL(k_quantize_codes, dim3((unsigned)(N * chunks)), dim3(256), 0, s, d_w, K, chunks, n_bits,
+                       d_scale, d_w_int, vec_ok);
+    return launch_status();
+}
+
+extern "C" nq_status nq_quantize_decompose_pack(const float *d_w, int64_t N, int64_t K, const nq_cfg *cfg,
+                                                float *d_scale, void *d_packed_high, void *d_packed_low,
+                                                void *stream)
+{
+    nq_status st = check_cfg(cfg);
+    if (st != NQ_OK) return st;
+    if (cfg->layout != NQ_LAYOUT_DENSE) return NQ_ERR_UNSUPPORTED;
+    if ((st = check_shape(N, K)) != NQ_OK) return st;
+    if ((st = check_pages(cfg, d_packed_high, d_packed_low)) != NQ_OK) return st;
+    if (N * K == 0) return NQ_OK;
+    if (!d_w || !d_scale) return NQ_ERR_INVALID_ARG;
+    if (N > 0x7fffffff) return NQ_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    launch_row_absmax(d_w, N, K, cfg->n_bits, d_scale, s);
+    const int h = cfg->n_bits - cfg->l_bits, l = cfg->l_bits;
+    const int sgn = cfg->low_format == NQ_LOW_SIGNED_L1;
+    NQ_DISPATCH_HL(h, l, launch_pack_dense, 2, sgn, reinterpret_cast<const int8_t *>(d_w),
+                   reinterpret_cast<const int8_t *>(d_scale), N, K, d_packed_high, d_packed_low, s);
+    return launch_status();
 }
 
 extern "C" nq_status nq_decompose(const int8_t *d_w_int, int64_t N, int64_t K, const nq_cfg *cfg,

@@ -22,11 +22,15 @@ def int_grid(values: np.ndarray, n_bits: int, axis=None):
     return codes, (step.reshape(-1) if axis is not None else np.float32(step))
 
 
+def float_weights(N: int, K: int, sigma: float, seed: int = 0) -> np.ndarray:
+    """fp32 N(0, sigma) weights [N,K] (the values a trained layer would hand to the quantiser)."""
+    rng = np.random.default_rng(seed)
+    return rng.normal(0.0, sigma, size=(N, K)).astype(np.float32)
+
+
 def weights(N: int, K: int, sigma: float, n_bits: int = 8, seed: int = 0):
     """INT-n codes [N,K] of N(0, sigma) weights and their per-output-channel steps fp32[N]."""
-    rng = np.random.default_rng(seed)
-    w = rng.normal(0.0, sigma, size=(N, K)).astype(np.float32)
-    return int_grid(w, n_bits, axis=1)
+    return int_grid(float_weights(N, K, sigma, seed), n_bits, axis=1)
 
 
 def he_sigma(fan_in: int) -> float:

@@ -85,6 +85,27 @@ def test_host_side_argument_checks(nq):
     with pytest.raises(nq.NQError) as e:
         nq.nq_pack(a, None, 4, 4, nq.make_cfg(8, 2), None, a, stream=0)
     assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    # the quantiser: width, pointers, layout, sizes
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize(a, 4, 4, 9, a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize(a, 4, 4, 8, None, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize(a, 4, nq.NQ_MAX_K + 1, 8, a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_SHAPE
+    nq.nq_quantize(a, 0, 16, 8, a, a, stream=0)
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize_decompose_pack(a, 4, 4, nq.make_cfg(8, 2, layout=nq.NQ_LAYOUT_PAPER_U64), a, a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_UNSUPPORTED
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize_decompose_pack(a, 4, 4, nq.make_cfg(8, 2), None, a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize_decompose_pack(a, 4, 4, nq.make_cfg(8, 2), a, a + 8, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_ALIGN
+    nq.nq_quantize_decompose_pack(a, 0, 16, nq.make_cfg(6, 2), a, a, a, stream=0)
     # empty tensors are a no-op
     nq.nq_decompose(None, 0, 16, nq.make_cfg(8, 2), None, None, stream=0)
     nq.nq_decompose_pack(a, 0, 16, nq.make_cfg(8, 2), a, a, stream=0)
