@@ -3,7 +3,7 @@
 benchmark).  Every kernel time is the begin/end time stamp of the dispatch itself; buffers are rotated so that
 activations and outputs come from HBM, not from the Infinity Cache.
 
-    python bench_configs.py [c1] [c2] [c3] [c4] [c5] [pack] [page] [sweep] [words]
+    python bench_configs.py [c1] [c2] [c3] [c4] [c5] [pack] [page] [sweep] [words] [dw]
 """
 from __future__ import annotations
 
@@ -113,6 +113,52 @@ def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4):
         wb = nq.nq_packed_bytes(Cout, K, 8 - l) + (nq.nq_packed_bytes(Cout, K, l) if full else 0)
         row(name, ("full" if full else "part") + (" int8 out" if out8 else " fp32 out"), med, 2.0 * M * Cout * K,
             B * H * W_ * Cin + wb + M * Cout * (1 if out8 else 4))
+
+
+def gconv(name, B, H, W_, C, groups, k, stride, l, sets=6):
+    """One depthwise / grouped layer, int8 in and out with bias and ReLU; full-bit and part-bit."""
+    gs = C // groups
+    K = k * k * gs
+    pad = k // 2
+    w_int, scale = inputs.weights(C, K, inputs.he_sigma(K), 8, 0)
+    W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
+    Ho, Wo = (H + 2 * pad - k) // stride + 1, (W_ + 2 * pad - k) // stride + 1
+    xs = [torch.from_numpy(inputs.uniform_activations((B, H, W_, C), i)).cuda() for i in range(sets)]
+    ys = [torch.empty((B, Ho, Wo, C), dtype=torch.int8, device="cuda") for _ in range(sets)]
+    bias = torch.from_numpy(inputs.small_floats(C, 0.1, 1)).cuda()
+    epi = nq.make_epilogue(0.02, d_bias=bias, relu=True, out_int8=True, inv_out_scale=3.0)
+    cs = nq.nq_conv_shape(B, H, W_, C, C, k, k, stride, pad)
+    for full in (True, False):
+        cnt = [0]
+
+        def fn(ev):
+            i = cnt[0] % sets
+            cnt[0] += 1
+            if ev:
+                nq.nq_profile_next_launch(ev[0], ev[1])
+            (nq.nq_gconv_full if full else nq.nq_gconv_part)(xs[i], cs, groups, W.desc, epi, ys[i])
+        med, _ = kernel_us(fn)
+        M = B * Ho * Wo
+        byts = B * H * W_ * C + M * C + nq.nq_packed_bytes(C, K, 8 - l) + (nq.nq_packed_bytes(C, K, l) if full else 0)
+        gbs = byts / med / 1e3
+        print(f"| {name} | {'full' if full else 'part'} | {med:.2f} | {byts / 1e6:.2f} | {gbs:.0f} | "
+              f"{100 * gbs / HBM_PEAK:.1f} | {2.0 * M * C * K / med / 1e6:.2f} |")
+
+
+def dw():
+    print("\n### depthwise / grouped layers of the lightweight CNNs, batch 32, int8 in and out, bias + ReLU, INT(8|5)\n")
+    print("| layer | mode | kernel us | algorithmic MB | GB/s | % HBM peak | useful TOPS |")
+    print("|---|---|---|---|---|---|---|")
+    # MobileNet (224 x 224 input): every distinct depthwise layer
+    for hw, c, s in ((112, 32, 1), (112, 64, 2), (56, 128, 1), (56, 128, 2), (28, 256, 1), (28, 256, 2), (14, 512, 1),
+                     (14, 512, 2), (7, 1024, 1)):
+        gconv(f"MobileNet dw 3x3 {hw}x{hw}x{c} s{s}", 32, hw, hw, c, c, 3, s, 3)
+    # MobileNetV2 / EfficientNet-B0 expanded widths, 5x5 filters, and a ResNeXt 32x4d grouped layer
+    gconv("MobileNetV2 dw 3x3 56x56x144 s1", 32, 56, 56, 144, 144, 3, 1, 3)
+    gconv("MobileNetV2 dw 3x3 14x14x576 s1", 32, 14, 14, 576, 576, 3, 1, 3)
+    gconv("EfficientNet-B0 dw 5x5 28x28x240 s1", 32, 28, 28, 240, 240, 5, 1, 3)
+    gconv("EfficientNet-B0 dw 5x5 14x14x672 s1", 32, 14, 14, 672, 672, 5, 1, 3)
+    gconv("ResNeXt 32x4d 3x3 56x56x128 g32", 32, 56, 56, 128, 32, 3, 1, 3)
 
 
 def c1():
@@ -340,7 +386,7 @@ def words():
 
 if __name__ == "__main__":
     torch.cuda.set_device(0)
-    which = sys.argv[1:] or ["c1", "c2", "c3", "c4", "c5", "pack", "page", "sweep", "words"]
+    which = sys.argv[1:] or ["c1", "c2", "c3", "c4", "c5", "pack", "page", "sweep", "words", "dw"]
     for name in which:
-        {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "pack": pack, "page": page, "sweep": sweep,
+        {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "pack": pack, "page": page, "sweep": sweep, "dw": dw,
          "words": words}[name]()

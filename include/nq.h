@@ -253,7 +253,19 @@ nq_status nq_conv_full(const int8_t *d_x, const nq_conv_shape *shape, const nq_w
 nq_status nq_conv_part(const int8_t *d_x, const nq_conv_shape *shape, const nq_weight *w,
                        const nq_epilogue *epi, void *d_y, void *stream);
 
-/* Profiling aid: the next nq_gemm_* / nq_conv_* call made by this host thread attaches the two
+/* Depthwise / grouped convolution in the same two modes (the layers of the lightweight CNNs of
+ * Sec. 4: as many output as input channels, C = Cin = Cout, split into `groups` groups of
+ * gs = C / groups channels; output channel c sums over the gs input channels of its own group).
+ * d_x int8[B][H][W][C], output [B][Ho][Wo][C]; w->N == C, w->K == KH*KW*gs with k = (kh*KW + kw)*gs + ci.
+ * Built for gs in {1, 2, 4}, C a multiple of 16, KH*KW <= 28, d_x 16-byte aligned and smaller than
+ * 2 GiB: NQ_ERR_UNSUPPORTED / NQ_ERR_ALIGN / NQ_ERR_SHAPE otherwise (a layer with wider groups is
+ * `groups` calls of nq_conv_* on channel slices copied out by the caller). */
+nq_status nq_gconv_full(const int8_t *d_x, const nq_conv_shape *shape, int groups, const nq_weight *w,
+                        const nq_epilogue *epi, void *d_y, void *stream);
+nq_status nq_gconv_part(const int8_t *d_x, const nq_conv_shape *shape, int groups, const nq_weight *w,
+                        const nq_epilogue *epi, void *d_y, void *stream);
+
+/* Profiling aid: the next nq_gemm_* / nq_conv_* / nq_gconv_* call made by this host thread attaches the two
  * hipEvent_t (either may be NULL) to its kernel dispatch, so that hipEventElapsedTime(start,
  * stop) is the execution time of that kernel alone.  One shot; events are the caller's. */
 nq_status nq_profile_next_launch(void *start_event, void *stop_event);

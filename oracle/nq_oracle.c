@@ -354,6 +354,44 @@ int oq_conv_i32(const int8_t *x, int64_t B, int64_t H, int64_t W, int64_t Cin,
 }
 
 /* ------------------------------------------------------------------ */
+/* Grouped convolution (depthwise when every group has one channel):  */
+/* output channel co belongs to group co / (Cout/groups) and sums     */
+/* over the Cin/groups input channels of that group only; weights     */
+/* [Cout][KH][KW][Cin/groups].  Same accumulator, zero padding.       */
+/* ------------------------------------------------------------------ */
+int oq_conv_grouped_i32(const int8_t *x, int64_t B, int64_t H, int64_t W, int64_t Cin,
+                        const int16_t *w, int64_t Cout, int64_t groups, int KH, int KW,
+                        int stride, int pad, int32_t *acc)
+{
+    if (stride < 1 || pad < 0 || KH < 1 || KW < 1 || groups < 1) return OQ_ERR_ARG;
+    if (Cin % groups != 0 || Cout % groups != 0) return OQ_ERR_ARG;
+    int64_t cig = Cin / groups, cog = Cout / groups;
+    int64_t Ho = (H + 2 * pad - KH) / stride + 1;
+    int64_t Wo = (W + 2 * pad - KW) / stride + 1;
+    if (Ho < 1 || Wo < 1) return OQ_ERR_ARG;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t oh = 0; oh < Ho; ++oh)
+            for (int64_t ow = 0; ow < Wo; ++ow)
+                for (int64_t co = 0; co < Cout; ++co) {
+                    int64_t first = (co / cog) * cig;      /* first input channel of the group */
+                    int32_t a = 0;
+                    for (int kh = 0; kh < KH; ++kh)
+                        for (int kw = 0; kw < KW; ++kw) {
+                            int64_t ih = oh * stride - pad + kh;
+                            int64_t iw = ow * stride - pad + kw;
+                            if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+                            const int8_t *xp = x + ((b * H + ih) * W + iw) * Cin + first;
+                            const int16_t *wp = w + ((co * KH + kh) * KW + kw) * cig;
+                            for (int64_t ci = 0; ci < cig; ++ci)
+                                a += (int32_t)xp[ci] * (int32_t)wp[ci];
+                        }
+                    acc[((b * Ho + oh) * Wo + ow) * Cout + co] = a;
+                }
+    return OQ_OK;
+}
+
+/* ------------------------------------------------------------------ */
 /* Dequantisation epilogue, fp32, fixed order, one rounding per step: */
 /*   c   = s_a * s_w[n]            (Eq. 2: w_hat = s * w_int)         */
 /*   c   = c * 2^l  in part-bit    (Eq. 8: s_high = s * 2^l, exact)   */

@@ -176,6 +176,21 @@ def conv_acc(x: np.ndarray, w: np.ndarray, stride: int, pad: int) -> np.ndarray:
     return acc
 
 
+def conv_grouped_acc(x: np.ndarray, w: np.ndarray, groups: int, stride: int, pad: int) -> np.ndarray:
+    """Grouped NHWC convolution (depthwise for groups == Cin); x [B,H,W,Cin] int8, w [Cout,KH,KW,Cin/groups];
+    int32 [B,Ho,Wo,Cout]."""
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    w = np.ascontiguousarray(w, dtype=np.int16)
+    B, H, W, Cin = x.shape
+    Cout, KH, KW, cig = w.shape
+    assert Cin == cig * groups
+    Ho, Wo = conv_out_hw(H, W, KH, KW, stride, pad)
+    acc = np.empty((B, Ho, Wo, Cout), np.int32)
+    _chk(lib().oq_conv_grouped_i32(_p(x), _i64(B), _i64(H), _i64(W), _i64(Cin), _p(w), _i64(Cout), _i64(groups),
+                                   int(KH), int(KW), int(stride), int(pad), _p(acc)), "grouped conv")
+    return acc
+
+
 def epilogue(acc: np.ndarray, s_a: float, s_w: np.ndarray, part_l_bits: int = 0, bias=None,
              residual=None, s_r: float = 0.0, relu: bool = False, out_int8: bool = False,
              inv_s_out: float = 1.0) -> np.ndarray:

@@ -26,7 +26,8 @@ EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "
            "nq_decompose", "nq_pack", "nq_decompose_pack",
            "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
            "nq_weight_init_group", "nq_page_out_low_batch", "nq_page_in_low_batch",
-           "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_profile_next_launch", "nq_event_create", "nq_event_destroy",
+           "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_gconv_full", "nq_gconv_part",
+           "nq_profile_next_launch", "nq_event_create", "nq_event_destroy",
            "nq_event_elapsed_ms", "nq_maxpool_i8", "nq_avgpool_i8"]
 
 
@@ -86,6 +87,8 @@ _SIGS = {
     "nq_gemm_part": (_int, [_vp, _i64, _wp, _ep, _vp, _vp]),
     "nq_conv_full": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
     "nq_conv_part": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
+    "nq_gconv_full": (_int, [_vp, _sp, _int, _wp, _ep, _vp, _vp]),
+    "nq_gconv_part": (_int, [_vp, _sp, _int, _wp, _ep, _vp, _vp]),
     "nq_profile_next_launch": (_int, [_vp, _vp]),
     "nq_event_create": (_int, [ctypes.POINTER(ctypes.c_void_p)]),
     "nq_event_destroy": (_int, [_vp]),
@@ -228,6 +231,16 @@ def nq_conv_full(d_x, shape: nq_conv_shape, w: nq_weight, epi: nq_epilogue, d_y,
 def nq_conv_part(d_x, shape: nq_conv_shape, w: nq_weight, epi: nq_epilogue, d_y, stream=None):
     _check(_lib.nq_conv_part(_ptr(d_x), ctypes.byref(shape), ctypes.byref(w), ctypes.byref(epi), _ptr(d_y),
                              _stream(stream)), "nq_conv_part")
+
+
+def nq_gconv_full(d_x, shape: nq_conv_shape, groups: int, w: nq_weight, epi: nq_epilogue, d_y, stream=None):
+    _check(_lib.nq_gconv_full(_ptr(d_x), ctypes.byref(shape), groups, ctypes.byref(w), ctypes.byref(epi), _ptr(d_y),
+                              _stream(stream)), "nq_gconv_full")
+
+
+def nq_gconv_part(d_x, shape: nq_conv_shape, groups: int, w: nq_weight, epi: nq_epilogue, d_y, stream=None):
+    _check(_lib.nq_gconv_part(_ptr(d_x), ctypes.byref(shape), groups, ctypes.byref(w), ctypes.byref(epi), _ptr(d_y),
+                              _stream(stream)), "nq_gconv_part")
 
 
 def nq_profile_next_launch(start_event, stop_event):

@@ -30,7 +30,7 @@ def _units():
     units = [(os.path.join(CSRC, f + ".hip"), os.path.join(OBJ, f + ".o"), [])
              for f in ("nq_pack", "nq_page", "nq_glue", "nq_gemm")]   # nq_yardsticks.hip is a program of its own
     for h, l in NESTINGS:
-        for part in (1, 0):
+        for part in (1, 0, 2):
             units.append((os.path.join(CSRC, "nq_gemm_inst.hip"), os.path.join(OBJ, f"nq_gemm_inst_{h}{l}_{part}.o"),
                           [f"-DNQ_INST_H={h}", f"-DNQ_INST_L={l}", f"-DNQ_INST_PART={part}"]))
     return units

@@ -67,11 +67,12 @@ struct EpiCols {
     float bias[NC];  // bias[n] or 0
 };
 
+// Constants of the sixteen channels nl0 .. nl0 + 15 (swapped layouts).
 template <int EPI>
-__device__ __forceinline__ void epi_cols(const GemmParams &p, int nt0, int lane, bool full, EpiCols<EPI> &e)
+__device__ __forceinline__ void epi_cols16(const GemmParams &p, int nl0, bool full, EpiCols<EPI> &e)
 {
+    static_assert(EPI != EPI_F32, "sixteen channels per lane: swapped layouts only");
     if constexpr (EPI == EPI_I8) {
-        const int nl0 = nt0 + 16 * (lane >> 5);
         const int n = nl0 < p.N ? nl0 : 0;
         const e_v4f *s4 = reinterpret_cast<const e_v4f *>(p.scale + n);
         const e_v4f *b4 = reinterpret_cast<const e_v4f *>(p.bias + n);
@@ -89,15 +90,29 @@ __device__ __forceinline__ void epi_cols(const GemmParams &p, int nt0, int lane,
             }
         }
     } else {
-        const int nl0 = EPI == EPI_F32 ? nt0 + (lane & 31) : nt0 + 16 * (lane >> 5);
 #pragma unroll
-        for (int r = 0; r < EpiCols<EPI>::NC; ++r) {
+        for (int r = 0; r < 16; ++r) {
             const bool ok = nl0 + r < p.N;
             float c = p.act_scale * (ok ? p.scale[nl0 + r] : 0.0f);
             if (!full) c = c * p.part_mul;
             e.c[r] = c;
             e.bias[r] = (ok && p.bias) ? p.bias[nl0 + r] : 0.0f;
         }
+    }
+}
+
+template <int EPI>
+__device__ __forceinline__ void epi_cols(const GemmParams &p, int nt0, int lane, bool full, EpiCols<EPI> &e)
+{
+    if constexpr (EPI == EPI_F32) {
+        const int n = nt0 + (lane & 31);
+        const bool ok = n < p.N;
+        float c = p.act_scale * (ok ? p.scale[n] : 0.0f);
+        if (!full) c = c * p.part_mul;
+        e.c[0] = c;
+        e.bias[0] = (ok && p.bias) ? p.bias[n] : 0.0f;
+    } else {
+        epi_cols16<EPI>(p, nt0 + 16 * (lane >> 5), full, e);
     }
 }
 
@@ -142,6 +157,68 @@ __device__ __forceinline__ void epi_tile_f32(const GemmParams &p, const e_v16i a
     }
 }
 
+// Swapped layouts: the lane's sixteen consecutive channels nl0 .. nl0 + 15 of output row o / N; o is the
+// element offset of channel nl0 in that row.  res: the residual codes from epi_resid_load (EPI_I8).
+template <int EPI>
+__device__ __forceinline__ void epi_row16(const GemmParams &p, const e_v16i acc, int shift, const EpiCols<EPI> &e,
+                                          int64_t o, int nl0, const e_v4i &res)
+{
+    static_assert(EPI != EPI_F32, "sixteen channels per lane: swapped layouts only");
+    const float lo = p.relu ? 0.0f : -__builtin_inff();
+    if constexpr (EPI == EPI_ANY) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            if (nl0 + r < p.N) {
+                const int a = acc[r] >> shift;
+                if (p.acc_dump) p.acc_dump[o + r] = a;
+                float y = (float)a * e.c[r];
+                y = y + e.bias[r];
+                if (p.resid) {
+                    const float rv = p.resid_scale * (float)p.resid[o + r];
+                    y = y + rv;
+                }
+                y = fmaxf(y, lo);
+                if (p.out_int8)
+                    reinterpret_cast<int8_t *>(p.y)[o + r] = (int8_t)(int)epi_quantise(y, p.inv_out_scale);
+                else
+                    reinterpret_cast<float *>(p.y)[o + r] = y;
+            }
+        }
+    } else {
+        if (nl0 >= p.N) return;
+        float y[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            y[r] = (float)(acc[r] >> shift) * e.c[r];
+            y[r] = y[r] + e.bias[r];
+        }
+        if (p.resid) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int code = (int)(int8_t)((unsigned)res[r >> 2] >> (8 * (r & 3)));
+                const float rv = p.resid_scale * (float)code;
+                y[r] = y[r] + rv;
+            }
+        }
+        // The rounded code plus 128 goes through the saturating float -> unsigned byte pack, which
+        // clamps it to [0, 255] (the clamp of the code to [-128, 127]); the offset is taken off
+        // again by flipping the top bit of every byte.  The sum is exact for every code that is
+        // not clamped anyway.
+        e_v4i q;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            unsigned d = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float v = rintf(fmaxf(y[4 * j + i], lo) * p.inv_out_scale) + 128.0f;
+                d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
+            }
+            q[j] = (int)(d ^ 0x80808080u);
+        }
+        *reinterpret_cast<e_v4i *>(reinterpret_cast<int8_t *>(p.y) + o) = q;
+    }
+}
+
 // One tile of the block's output.
 template <int EPI>
 __device__ __forceinline__ void epi_tile(const GemmParams &p, const e_v16i acc, int shift, const EpiCols<EPI> &e,
@@ -155,62 +232,9 @@ __device__ __forceinline__ void epi_tile(const GemmParams &p, const e_v16i acc, 
         if (rows >= 32) epi_tile_f32<true>(p, acc, shift, e, m0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows);
         else if (rows > 0) epi_tile_f32<false>(p, acc, shift, e, m0 * p.N + nt0, (unsigned)(4 * rg * p.N + col), rg, rows);
     } else {
-        const float lo = p.relu ? 0.0f : -__builtin_inff();
         const int nl0 = nt0 + 16 * rg;
         if ((lane & 31) >= rows) return;
-        const int64_t o = (m0 + (lane & 31)) * p.N + nl0;
-        if constexpr (EPI == EPI_ANY) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                if (nl0 + r < p.N) {
-                    const int a = acc[r] >> shift;
-                    if (p.acc_dump) p.acc_dump[o + r] = a;
-                    float y = (float)a * e.c[r];
-                    y = y + e.bias[r];
-                    if (p.resid) {
-                        const float rv = p.resid_scale * (float)p.resid[o + r];
-                        y = y + rv;
-                    }
-                    y = fmaxf(y, lo);
-                    if (p.out_int8)
-                        reinterpret_cast<int8_t *>(p.y)[o + r] = (int8_t)(int)epi_quantise(y, p.inv_out_scale);
-                    else
-                        reinterpret_cast<float *>(p.y)[o + r] = y;
-                }
-            }
-        } else {
-            if (nl0 >= p.N) return;
-            float y[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                y[r] = (float)(acc[r] >> shift) * e.c[r];
-                y[r] = y[r] + e.bias[r];
-            }
-            if (p.resid) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int code = (int)(int8_t)((unsigned)res[r >> 2] >> (8 * (r & 3)));
-                    const float rv = p.resid_scale * (float)code;
-                    y[r] = y[r] + rv;
-                }
-            }
-            // The rounded code plus 128 goes through the saturating float -> unsigned byte pack, which
-            // clamps it to [0, 255] (the clamp of the code to [-128, 127]); the offset is taken off
-            // again by flipping the top bit of every byte.  The sum is exact for every code that is
-            // not clamped anyway.
-            e_v4i q;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                unsigned d = 0;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float v = rintf(fmaxf(y[4 * j + i], lo) * p.inv_out_scale) + 128.0f;
-                    d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
-                }
-                q[j] = (int)(d ^ 0x80808080u);
-            }
-            *reinterpret_cast<e_v4i *>(reinterpret_cast<int8_t *>(p.y) + o) = q;
-        }
+        epi_row16<EPI>(p, acc, shift, e, (m0 + (lane & 31)) * p.N + nl0, nl0, res);
     }
 }
 

@@ -138,6 +138,65 @@ bool plan_smallcin(const Geometry &g, const int8_t *d_x, int64_t n_out, SmallCin
     return false;
 }
 
+// Patch shape of the depthwise / grouped kernel: the window of a patch must fit the registers that stage
+// it (640 pixels of 64 bytes); among the shapes that do, the one that fetches the fewest halo pixels per
+// output, fills its 16-pixel tiles and still leaves enough units for the whole GPU.
+bool plan_grouped(const Geometry &g, int gs, int64_t C, GroupGeom *gg)
+{
+    const int64_t images = g.M / ((int64_t)g.Ho * g.Wo);
+    const int CT = (int)ceil_div(C, 64);
+    double best = -1.0;
+    int bR = 0, bCW = 0;
+    const int cands[5] = {g.Wo, (g.Wo + 1) / 2, (g.Wo + 2) / 3, (g.Wo + 3) / 4, 16};
+    for (int CW : cands) {
+        if (CW > g.Wo) CW = g.Wo;
+        if (CW < 1 || CW > 255) continue;
+        const int ICp = (CW - 1) * g.stride + g.KW;
+        for (int R = g.Ho; R >= 1; --R) {
+            const int IRp = (R - 1) * g.stride + g.KH;
+            if ((int64_t)IRp * ICp > 640 || R * CW > 4000) continue;
+            const double halo = (double)R * CW * g.stride * g.stride / ((double)IRp * ICp);
+            const double fill = (double)R * CW / (16.0 * (double)ceil_div(R * CW, 16));
+            const double units = (double)images * (double)ceil_div(g.Ho, R) * (double)ceil_div(g.Wo, CW) * CT;
+            const int64_t pt = ceil_div(R * CW, 16);
+            const double balance = (double)pt / (4.0 * (double)ceil_div(pt, 4));   // tiles are dealt to four waves
+            // NQ_GC_UNITS (tuning aid): how many (unit, channel tile) pairs a launch should at least have;
+            // measured best at one per resident block, larger patches beating more of them
+            const char *te = getenv("NQ_GC_UNITS");
+            const double target = te ? atof(te) : 512.0;
+            const double score = halo * fill * balance * (units >= target ? 1.0 : units / target);
+            if (score > best) { best = score; bR = R; bCW = CW; }
+        }
+    }
+    if (best < 0.0) return false;
+    gg->gs = gs;
+    gg->taps = g.KH * g.KW;
+    gg->CT = CT;
+    gg->R = bR; gg->CW = bCW;
+    gg->RB = (int)ceil_div(g.Ho, bR); gg->CB = (int)ceil_div(g.Wo, bCW);
+    gg->IRp = (bR - 1) * g.stride + g.KH; gg->ICp = (bCW - 1) * g.stride + g.KW;
+    const int64_t units = images * gg->RB * gg->CB;
+    if (units > 0x3fffffffLL) return false;
+    gg->units = (int)units;
+    gg->ptiles = (int)ceil_div(bR * bCW, 16);
+    gg->np = (int)ceil_div((int64_t)gg->IRp * gg->ICp * 4, 256);
+    gg->cw_magic = (1 << 20) / bCW + 1;
+    gg->icp_magic = (1 << 20) / gg->ICp + 1;
+    gg->zero_off = gg->IRp * gg->ICp * 80;
+    // the decoded weights (8 KiB) and the fragment table (up to 28 KiB) pass through the same memory first
+    const int setup_bytes = 8192 + (gg->taps <= 12 ? 3 : 7) * 4096;
+    gg->lds_bytes = gg->zero_off + 64 < setup_bytes ? setup_bytes : gg->zero_off + 64;
+    gg->x_bytes = images * g.H * g.W * C;
+    // two resident blocks per compute unit, never more blocks than there are units
+    int64_t gx = ceil_div(512, CT);
+    if (gx > units) gx = units;
+    gg->grid_x = (int)(gx < 1 ? 1 : gx);
+    gg->step_cb = gg->grid_x % gg->CB;
+    gg->step_rb = (gg->grid_x / gg->CB) % gg->RB;
+    gg->step_b = gg->grid_x / (gg->CB * gg->RB);
+    return true;
+}
+
 int pick_tile(int64_t M, int64_t N)
 {
     if (N <= 64) return 0;
@@ -145,8 +204,10 @@ int pick_tile(int64_t M, int64_t N)
     return 1;
 }
 
+// gs: 0 for a GEMM or a dense convolution, else the channels per group of a grouped convolution
+// (the caller has checked that the shape is one the grouped kernel takes).
 nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *w, const nq_epilogue *epi,
-              void *d_y, void *stream)
+              void *d_y, void *stream, int gs = 0)
 {
     if (!w || !epi) return NQ_ERR_INVALID_ARG;
     nq_status st = check_cfg(&w->cfg);
@@ -208,6 +269,15 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
 
     void *ev0 = g_ev_start, *ev1 = g_ev_stop;
     g_ev_start = g_ev_stop = nullptr;
+    if (gs > 0) {
+        GroupGeom gg;
+        if (!plan_grouped(g, gs, w->N, &gg)) return NQ_ERR_UNSUPPORTED;
+        p.conv_big = 0;
+        p.cin_shift = 0;
+        p.kw_magic = 65536 / g.KW + 1;      // tap / KW == (tap * kw_magic) >> 16 for the few taps of a filter
+        NQ_DISPATCH_HL(h, l, launch_nested_conv_grouped, full, p, gg, s, ev0, ev1);
+        return launch_status();
+    }
     // NQ_KERNEL (tuning and test aid): 1 generic, 2 windowed, 3 register-stationary, 4 large GEMM,
     // 5 few input channels, 6 few rows;
     // a kernel that does not apply to the shape is never forced, the choice falls through.
@@ -300,7 +370,48 @@ nq_status conv(bool full, const int8_t *d_x, const nq_conv_shape *sh, const nq_w
     return run(full, d_x, g, w, epi, d_y, stream);
 }
 
+// Depthwise / grouped convolution: as many output as input channels, groups of 1, 2 or 4 channels.
+nq_status gconv(bool full, const int8_t *d_x, const nq_conv_shape *sh, int groups, const nq_weight *w,
+                const nq_epilogue *epi, void *d_y, void *stream)
+{
+    if (!sh || !w) return NQ_ERR_INVALID_ARG;
+    if (sh->B < 0 || sh->H < 1 || sh->W < 1 || sh->Cin < 1 || sh->Cout < 0 || sh->KH < 1 || sh->KW < 1 ||
+        sh->stride < 1 || sh->pad < 0 || groups < 1)
+        return NQ_ERR_INVALID_ARG;
+    if (sh->H > 32768 || sh->W > 32768 || sh->Cin > NQ_MAX_K || sh->KH > 64 || sh->KW > 64 || sh->pad > 64 ||
+        sh->stride > 64)
+        return NQ_ERR_SHAPE;
+    if (sh->Cin != sh->Cout || sh->Cin % groups != 0) return NQ_ERR_SHAPE;
+    const int64_t gs = sh->Cin / groups;
+    if (w->N != sh->Cout || w->K != (int64_t)sh->KH * sh->KW * gs) return NQ_ERR_SHAPE;
+    if (sh->H + 2 * sh->pad < sh->KH || sh->W + 2 * sh->pad < sh->KW) return NQ_ERR_SHAPE;
+    // what the kernel is built for: groups inside a run of 4 channels, 16-byte pieces of a pixel, up to 28 taps
+    if ((gs != 1 && gs != 2 && gs != 4) || sh->Cin % 16 != 0 || sh->KH * sh->KW > 28) return NQ_ERR_UNSUPPORTED;
+    if (!aligned16(d_x)) return NQ_ERR_ALIGN;
+    const int64_t Ho = (sh->H + 2 * sh->pad - sh->KH) / sh->stride + 1;
+    const int64_t Wo = (sh->W + 2 * sh->pad - sh->KW) / sh->stride + 1;
+    if (sh->B * sh->H * sh->W * sh->Cin >= 0x7fff0000LL || sh->B * Ho * Wo >= (int64_t(1) << 31) - 64)
+        return NQ_ERR_SHAPE;
+    Geometry g;
+    g.M = sh->B * Ho * Wo;
+    g.H = (int)sh->H; g.W = (int)sh->W; g.Cin = (int)sh->Cin; g.Ho = (int)Ho; g.Wo = (int)Wo;
+    g.KH = sh->KH; g.KW = sh->KW; g.stride = sh->stride; g.pad = sh->pad;
+    return run(full, d_x, g, w, epi, d_y, stream, (int)gs);
+}
+
 }  // namespace
+
+extern "C" nq_status nq_gconv_full(const int8_t *d_x, const nq_conv_shape *shape, int groups, const nq_weight *w,
+                                   const nq_epilogue *epi, void *d_y, void *stream)
+{
+    return gconv(true, d_x, shape, groups, w, epi, d_y, stream);
+}
+
+extern "C" nq_status nq_gconv_part(const int8_t *d_x, const nq_conv_shape *shape, int groups, const nq_weight *w,
+                                   const nq_epilogue *epi, void *d_y, void *stream)
+{
+    return gconv(false, d_x, shape, groups, w, epi, d_y, stream);
+}
 
 extern "C" nq_status nq_profile_next_launch(void *start_event, void *stop_event)
 {

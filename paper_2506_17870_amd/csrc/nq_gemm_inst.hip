@@ -1,6 +1,6 @@
-// Two translation units per nesting, compiled with -DNQ_INST_H=<h> -DNQ_INST_L=<l> and
-// -DNQ_INST_PART=0 (generic, windowed, register-stationary and few-channel kernels) or 1 (large-GEMM kernels),
-// so that the units build in parallel.
+// Three translation units per nesting, compiled with -DNQ_INST_H=<h> -DNQ_INST_L=<l> and
+// -DNQ_INST_PART=0 (generic, windowed, register-stationary and few-channel kernels), 1 (large-GEMM kernels)
+// or 2 (depthwise / grouped convolution), so that the units build in parallel.
 #if NQ_INST_PART == 0
 #include "nq_conv_rowstream.h"
 #include "nq_conv_smallcin.h"
@@ -17,6 +17,13 @@ template void launch_nested_conv_rowstream<NQ_INST_H, NQ_INST_L>(bool, const Gem
                                                                  hipStream_t, void *, void *);
 template void launch_nested_conv_smallcin<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, const SmallCinGeom &,
                                                                 hipStream_t, void *, void *);
+}
+#elif NQ_INST_PART == 2
+#include "nq_conv_grouped.h"
+
+namespace nq {
+template void launch_nested_conv_grouped<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, const GroupGeom &,
+                                                               hipStream_t, void *, void *);
 }
 #else
 #include "nq_gemm_big.h"

@@ -78,6 +78,27 @@ struct SmallCinGeom {
     int grid_x;       // persistent blocks per channel group
 };
 
+// Geometry of the depthwise / grouped convolution kernel (work unit = patch of R x CW output pixels of
+// one image).
+struct GroupGeom {
+    int gs;           // channels per group (1, 2 or 4), inputs and outputs alike
+    int taps;         // KH * KW (<= 28)
+    int CT;           // 64-channel tiles = ceil(C / 64)
+    int R, CW;        // output rows and columns of a patch
+    int RB, CB;       // patches per image: ceil(Ho / R) x ceil(Wo / CW)
+    int IRp, ICp;     // input rows and columns of a patch: (R-1)*stride + KH, (CW-1)*stride + KW
+    int units;        // B * RB * CB
+    int ptiles;       // 16-pixel tiles of a patch = ceil(R * CW / 16)
+    int np;           // 16-byte pieces a thread stages per window = ceil(IRp * ICp * 4 / 256) (<= 10)
+    int cw_magic;     // 2^20 / CW + 1: n / CW == (n * cw_magic) >> 20 for n < 4096
+    int icp_magic;    // 2^20 / ICp + 1, likewise for window pixels
+    int step_b, step_rb, step_cb;   // grid_x = (step_b * RB + step_rb) * CB + step_cb: how a unit advances
+    int zero_off;     // LDS offset of 64 zero bytes (behind the window of IRp * ICp pixels of 80 bytes)
+    int lds_bytes;    // dynamic LDS of the kernel
+    int grid_x;       // persistent blocks per channel tile
+    int64_t x_bytes;  // B * H * W * C (< 2^31)
+};
+
 // Tile shapes: 0 = 256x64 (narrow outputs), 1 = 128x256 (large), 2 = 64x256 (few rows).
 constexpr int NQ_TILE_BM[3] = {256, 128, 64};
 constexpr int NQ_TILE_BN[3] = {64, 256, 256};
@@ -102,6 +123,11 @@ void launch_nested_conv_rowstream(bool full, const GemmParams &p, const StreamGe
 template <int H, int L>
 void launch_nested_conv_smallcin(bool full, const GemmParams &p, const SmallCinGeom &g, hipStream_t st, void *ev_start,
                                  void *ev_stop);
+
+// Depthwise / grouped convolution with 1, 2 or 4 channels per group.
+template <int H, int L>
+void launch_nested_conv_grouped(bool full, const GemmParams &p, const GroupGeom &g, hipStream_t st, void *ev_start,
+                                void *ev_stop);
 
 // Few rows (M <= 64): one block per 32-column tile, the waves split K.
 template <int H, int L>

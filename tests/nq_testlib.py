@@ -127,6 +127,32 @@ def run_conv_both(nq, case, x, shape, full, **epi_kw):
                 raise AssertionError(f"{e} (NQ_KERNEL='{kernel}', accumulator dump {dump})") from None
 
 
+def run_gconv_both(nq, case, x, shape, groups, full, **epi_kw):
+    """Depthwise / grouped convolution: case holds [C, KH*KW*gs] weights, k = (kh*KW + kw)*gs + ci."""
+    B, H, W, C = x.shape
+    KH, KW, stride, pad = shape
+    gs = C // groups
+    Ho, Wo = oracle.conv_out_hw(H, W, KH, KW, stride, pad)
+    out_int8 = epi_kw.get("out_int8", False)
+    cs = nq.nq_conv_shape(B, H, W, C, C, KH, KW, stride, pad)
+    fn = nq.nq_gconv_full if full else nq.nq_gconv_part
+    w4 = (case.ow_full if full else case.ow_part).reshape(C, KH, KW, gs)
+    acc_ref = oracle.conv_grouped_acc(x, w4, groups, stride, pad)
+    y_ref = None
+    dx = dev(x)
+    for dump in (True, False):
+        epi, keep, okw = epi_pair(nq, case, full, (B, Ho, Wo), dump=dump, **epi_kw)
+        if y_ref is None:
+            y_ref = oracle.epilogue(acc_ref, **okw)
+        y = torch.full((B, Ho, Wo, C), 77, dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+        fn(dx, cs, groups, case.W.desc, epi, y)
+        torch.cuda.synchronize()
+        try:
+            check_outputs(host(y), host(keep["acc"]) if dump else None, y_ref, acc_ref, out_int8)
+        except AssertionError as e:
+            raise AssertionError(f"{e} (accumulator dump {dump})") from None
+
+
 def oracle_cnn_forward(ops, weights, x, in_scale, n_bits, l_bits, full, scales=None):
     """Walks a plan of paper_2506_17870_amd.network on the CPU oracle.  With scales=None every conv is first
     dequantised to fp32 to fix its int8 step (absmax / 127), which is returned for the other runs."""

@@ -135,6 +135,25 @@ def test_gemm_argument_checks_without_gpu(nq):
     with pytest.raises(nq.NQError) as e:
         nq.nq_conv_part(a, shape, w, epi, a, stream=0)
     assert e.value.status == nq.NQ_ERR_SHAPE
+    # grouped convolution: shape against the descriptor, group size, channel multiple, alignment
+    wd = nq.nq_weight(cfg, 64, 9, a, 64 * 64 * 6 // 8, a, 64 * 64 * 2 // 8, a, a, 0, 0, None, None, 0, 0)
+    dw = nq.nq_conv_shape(1, 8, 8, 64, 64, 3, 3, 1, 1)
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gconv_part(a, dw, 16, wd, epi, a, stream=0)        # groups of 4: K would be 36
+    assert e.value.status == nq.NQ_ERR_SHAPE
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gconv_part(a, dw, 7, wd, epi, a, stream=0)         # 7 does not divide 64
+    assert e.value.status == nq.NQ_ERR_SHAPE
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gconv_part(a + 4, dw, 64, wd, epi, a, stream=0)    # activations off a 16-byte boundary
+    assert e.value.status == nq.NQ_ERR_ALIGN
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gconv_full(a, dw, 64, wd, epi, a, stream=0)        # lower-bit page not resident
+    assert e.value.status == nq.NQ_ERR_NOT_RESIDENT
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gconv_part(a, nq.nq_conv_shape(1, 8, 8, 64, 32, 3, 3, 1, 1), 32, wd, epi, a, stream=0)   # Cin != Cout
+    assert e.value.status == nq.NQ_ERR_SHAPE
+    nq.nq_gconv_part(a, nq.nq_conv_shape(0, 8, 8, 64, 64, 3, 3, 1, 1), 64, wd, epi, a, stream=0)      # empty batch
     with pytest.raises(nq.NQError) as e:
         nq.nq_page_in_low(w, 0)                        # nq_weight_init was never called
     assert e.value.status == nq.NQ_ERR_INVALID_ARG

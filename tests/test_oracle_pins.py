@@ -314,6 +314,38 @@ def test_conv_1x1_is_a_gemm(oracle):
                           oracle.gemm_acc(x.reshape(-1, 16), w.reshape(8, 16)))
 
 
+# --- grouped / depthwise convolution --------------------------------------------------------------------
+@pytest.mark.parametrize("groups,cig,cog", [(6, 1, 1), (3, 2, 2), (2, 4, 4), (1, 5, 3), (4, 2, 3)])
+@pytest.mark.parametrize("KH,pad,stride", [(3, 1, 1), (3, 1, 2), (5, 2, 1), (1, 0, 1)])
+def test_grouped_conv_is_a_dense_conv_with_zeros_across_groups(oracle, groups, cig, cog, KH, pad, stride):
+    # the block-diagonal dense filter gives the same sums through the (separately pinned) dense convolution
+    rng = np.random.default_rng(groups * 10 + KH)
+    Cin, Cout = groups * cig, groups * cog
+    x = rng.integers(-128, 128, size=(2, 7, 6, Cin)).astype(np.int8)
+    w = rng.integers(-128, 128, size=(Cout, KH, KH, cig)).astype(np.int16)
+    dense = np.zeros((Cout, KH, KH, Cin), np.int16)
+    for co in range(Cout):
+        gi = co // cog
+        dense[co, :, :, gi * cig:(gi + 1) * cig] = w[co]
+    got = oracle.conv_grouped_acc(x, w, groups, stride, pad)
+    assert np.array_equal(got, oracle.conv_acc(x, dense, stride, pad))
+    assert np.array_equal(got, conv_loops(x, dense, stride, pad))
+
+
+def test_depthwise_conv_channel_by_channel(oracle):
+    # every channel of a depthwise convolution is a single-channel convolution of its own
+    rng = np.random.default_rng(12)
+    x = rng.integers(-128, 128, size=(2, 6, 5, 4)).astype(np.int8)
+    w = rng.integers(-128, 128, size=(4, 3, 3, 1)).astype(np.int16)
+    got = oracle.conv_grouped_acc(x, w, 4, 1, 1)
+    for c in range(4):
+        one = conv_loops(x[..., c:c + 1], w[c:c + 1], 1, 1)
+        assert np.array_equal(got[..., c:c + 1], one)
+    # groups == 1 is the dense convolution
+    wd = rng.integers(-128, 128, size=(3, 3, 3, 4)).astype(np.int16)
+    assert np.array_equal(oracle.conv_grouped_acc(x, wd, 1, 2, 1), oracle.conv_acc(x, wd, 2, 1))
+
+
 # --- epilogue: Eq. 2 and Eq. 8 ---------------------------------------------------------------------------
 def test_epilogue_against_exact_product(oracle):
     rng = np.random.default_rng(6)
