@@ -200,20 +200,36 @@ __device__ __forceinline__ void epi_row16(const GemmParams &p, const e_v16i acc,
                 y[r] = y[r] + rv;
             }
         }
-        // The rounded code plus 128 goes through the saturating float -> unsigned byte pack, which
-        // clamps it to [0, 255] (the clamp of the code to [-128, 127]); the offset is taken off
-        // again by flipping the top bit of every byte.  The sum is exact for every code that is
-        // not clamped anyway.
         e_v4i q;
+        if (p.relu && p.inv_out_scale > 0.0f) {
+            // With a ReLU and a positive output scale, clamp(rint(max(y, 0) * inv), -128, 127) is
+            // med3(rint(y * inv), 0, 127): rounding and a positive factor keep the order and map 0 to 0, so
+            // the ReLU can be taken after them, where it is the lower end of one three-operand clamp.
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            unsigned d = 0;
+            for (int j = 0; j < 4; ++j) {
+                unsigned d = 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float v = rintf(fmaxf(y[4 * j + i], lo) * p.inv_out_scale) + 128.0f;
-                d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
+                for (int i = 0; i < 4; ++i) {
+                    const float v = __builtin_amdgcn_fmed3f(rintf(y[4 * j + i] * p.inv_out_scale), 0.0f, 127.0f);
+                    d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
+                }
+                q[j] = (int)d;
             }
-            q[j] = (int)(d ^ 0x80808080u);
+        } else {
+            // The rounded code plus 128 goes through the saturating float -> unsigned byte pack, which
+            // clamps it to [0, 255] (the clamp of the code to [-128, 127]); the offset is taken off
+            // again by flipping the top bit of every byte.  The sum is exact for every code that is
+            // not clamped anyway.
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                unsigned d = 0;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float v = rintf(fmaxf(y[4 * j + i], lo) * p.inv_out_scale) + 128.0f;
+                    d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
+                }
+                q[j] = (int)(d ^ 0x80808080u);
+            }
         }
         *reinterpret_cast<e_v4i *>(reinterpret_cast<int8_t *>(p.y) + o) = q;
     }
