@@ -79,3 +79,36 @@ def test_resnet101_early_layers_full_resolution(nq):
     for full in (True, False):
         run_conv_both(nq, case, x, (1, 1, 1, 0), full, s_a=float(s_x), residual=res, s_r=0.04, relu=True,
                       out_int8=True, inv_s_out=5.0)
+
+
+@pytest.mark.parametrize("geom", [(112, 64, 64, 3, 2), (56, 128, 128, 3, 1), (28, 240, 240, 5, 1), (56, 128, 32, 3, 1)])
+def test_depthwise_layers_full_batch(nq, geom):
+    # batch 32, the sizes bench_configs.py times: MobileNet 112x112x64 stride 2 and 56x56x128, EfficientNet-B0
+    # 5x5 28x28x240, ResNeXt 32x4d 56x56x128 in 32 groups; int8 in and out, bias + ReLU, INT(8|5)
+    from nq_testlib import run_gconv_both
+    hw, C, groups, k, stride = geom
+    K = k * k * (C // groups)
+    w_int, scale = inputs.weights(C, K, inputs.he_sigma(K), 8, seed=hw + C)
+    case = Case(nq, w_int, scale, 8, 3)
+    x = inputs.uniform_activations((32, hw, hw, C), seed=hw)
+    bias = inputs.small_floats(C, 0.1, seed=1)
+    for full in (True, False):
+        run_gconv_both(nq, case, x, (k, k, stride, k // 2), groups, full, s_a=0.02, bias=bias, relu=True,
+                       out_int8=True, inv_s_out=3.0)
+
+
+def test_quantiser_full_size(nq):
+    # 4096 x 4096 fp32 weights (the size bench_configs.py times), INT(8|6): scales and pages bit exact
+    from nq_testlib import dev, host
+    from oracle import nq_oracle as oracle
+    N = K = 4096
+    w = inputs.float_weights(N, K, 0.02, seed=3)
+    wi_ref, s_ref = oracle.quantize(w, 8)
+    ph_ref, pl_ref = oracle.decompose_pack(wi_ref, 8, 2)
+    d_s = torch.empty(N, dtype=torch.float32, device="cuda")
+    ph = torch.zeros(ph_ref.size, dtype=torch.uint8, device="cuda")
+    pl = torch.zeros(pl_ref.size, dtype=torch.uint8, device="cuda")
+    nq.nq_quantize_decompose_pack(dev(w), N, K, nq.make_cfg(8, 2), d_s, ph, pl)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(d_s).view(np.uint32), s_ref.view(np.uint32))
+    assert np.array_equal(host(ph), ph_ref) and np.array_equal(host(pl), pl_ref)
