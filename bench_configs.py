@@ -3,7 +3,7 @@
 benchmark).  Every kernel time is the begin/end time stamp of the dispatch itself; buffers are rotated so that
 activations and outputs come from HBM, not from the Infinity Cache.
 
-    python bench_configs.py [c1] [c2] [c3] [c4] [c5] [pack] [page] [sweep] [words] [dw]
+    python bench_configs.py [c1] [c2] [c3] [c4] [c5] [pack] [page] [sweep] [words] [dw] [lib]
 """
 from __future__ import annotations
 
@@ -159,6 +159,41 @@ def dw():
     gconv("EfficientNet-B0 dw 5x5 28x28x240 s1", 32, 28, 28, 240, 240, 5, 1, 3)
     gconv("EfficientNet-B0 dw 5x5 14x14x672 s1", 32, 14, 14, 672, 672, 5, 1, 3)
     gconv("ResNeXt 32x4d 3x3 56x56x128 g32", 32, 56, 56, 128, 32, 3, 1, 3)
+
+
+def lib():
+    """Context, not a target: the vendor library's plain int8 GEMM (torch._int_mm -> hipBLASLt; int32 outputs, no
+    decode, no epilogue) on the GEMM shapes of the configurations, next to the nested kernels on the same shapes
+    (INT(8|5), int8 outputs with the fused epilogue; convolutions as the implicit GEMM they are)."""
+    print("\n### vendor library plain int8 GEMM (hipBLASLt through torch._int_mm) against the nested kernels\n")
+    print("| shape M x K x N | library us (back-to-back launches) | library TOPS | nested full-bit us | nested part-bit us |")
+    print("|---|---|---|---|---|")
+    for name, M, K, N in (("ViT fc1", 12608, 768, 3072), ("ViT fc2", 12608, 3072, 768),
+                          ("bottleneck 1x1 1024->256", 12544, 1024, 256), ("bottleneck 1x1 256->1024", 12544, 256, 1024),
+                          ("square", 8192, 4096, 4096)):
+        a = torch.randint(-128, 128, (M, K), dtype=torch.int8, device="cuda")
+        bt = torch.randint(-128, 128, (N, K), dtype=torch.int8, device="cuda")
+        try:
+            us_lib = wall_us(lambda: torch._int_mm(a, bt.t()), n=30)
+        except Exception as e:   # the library path is optional context
+            print(f"| {name} | not available ({type(e).__name__}) | | | |")
+            continue
+        w_int, scale = inputs.weights(N, K, 0.02, 8, 0)
+        W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, 3))
+        ys = [torch.empty((M, N), dtype=torch.int8, device="cuda") for _ in range(2)]
+        epi = nq.make_epilogue(0.02, out_int8=True, inv_out_scale=3.0)
+        ours = []
+        for full in (True, False):
+            cnt = [0]
+
+            def fn(ev):
+                cnt[0] += 1
+                if ev:
+                    nq.nq_profile_next_launch(ev[0], ev[1])
+                (nq.nq_gemm_full if full else nq.nq_gemm_part)(a, M, W.desc, epi, ys[cnt[0] % 2])
+            ours.append(kernel_us(fn)[0])
+        print(f"| {name} {M} x {K} x {N} | {us_lib:.1f} | {2.0 * M * K * N / us_lib / 1e6:.0f} | {ours[0]:.1f} | {ours[1]:.1f} |")
+        del a, bt, W, ys
 
 
 def c1():
@@ -386,7 +421,7 @@ def words():
 
 if __name__ == "__main__":
     torch.cuda.set_device(0)
-    which = sys.argv[1:] or ["c1", "c2", "c3", "c4", "c5", "pack", "page", "sweep", "words", "dw"]
+    which = sys.argv[1:] or ["c1", "c2", "c3", "c4", "c5", "pack", "page", "sweep", "words", "dw", "lib"]
     for name in which:
-        {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "pack": pack, "page": page, "sweep": sweep, "dw": dw,
+        {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "pack": pack, "page": page, "sweep": sweep, "dw": dw, "lib": lib,
          "words": words}[name]()
