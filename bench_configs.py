@@ -25,9 +25,15 @@ MFMA_PEAK, HBM_PEAK = 5000.0, 8000.0   # TOPS (int8 dense), GB/s
 
 
 def kernel_us(fn, n=30):
-    """Median and minimum dispatch duration of the GEMM/conv launch made by fn(events)."""
-    for _ in range(5):
+    """Median and minimum dispatch duration of the GEMM/conv launch made by fn(events).  The warm-up is long
+    enough for the clocks to settle (a handful of launches is not: the first figures then read 15 % high)."""
+    t0 = time.perf_counter()
+    for i in range(400):
         fn(None)
+        if i >= 24 and i % 8 == 0:
+            torch.cuda.synchronize()
+            if time.perf_counter() - t0 > 0.02:
+                break
     torch.cuda.synchronize()
     evs = [(nq.nq_event_create(), nq.nq_event_create()) for _ in range(n)]
     for a, b in evs:
