@@ -3,7 +3,7 @@
 benchmark).  Every kernel time is the begin/end time stamp of the dispatch itself; buffers are rotated so that
 activations and outputs come from HBM, not from the Infinity Cache.
 
-    python bench_configs.py [c1] [c2] [c3] [c4] [c5] [pack] [page] [sweep] [words] [dw] [lib]
+    python bench_configs.py [c1] [c2] [c3] [c4] [c5] [pack] [page] [sweep] [words] [dw] [lib] [cpu]
 """
 from __future__ import annotations
 
@@ -24,7 +24,7 @@ from paper_2506_17870_amd import inputs, network  # noqa: E402
 MFMA_PEAK, HBM_PEAK = 5000.0, 8000.0   # TOPS (int8 dense), GB/s
 
 
-def kernel_us(fn, n=30):
+def kernel_us(fn, n=50):
     """Median and minimum dispatch duration of the GEMM/conv launch made by fn(events).  The warm-up is long
     enough for the clocks to settle (a handful of launches is not: the first figures then read 15 % high)."""
     t0 = time.perf_counter()
@@ -202,12 +202,114 @@ def lib():
         del a, bt, W, ys
 
 
+def cpu():
+    """The CPU oracle (plain C loops, -O2, no intrinsics, no BLAS) on the host of the GPU machine: one thread and all
+    threads OpenMP gives it, integer accumulators only (the part the GPU's TOPS are quoted on)."""
+    import ctypes
+    import platform
+    from oracle import nq_oracle as oracle
+    model = platform.processor() or "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    omp = ctypes.CDLL("libgomp.so.1")
+    nthreads = oracle.threads()
+    print(f"\n### CPU oracle timing: {model}, os.cpu_count() = {os.cpu_count()}, OpenMP threads used = {nthreads}\n")
+    print("| configuration | GOP | 1 thread s | 1 thread GOPS | all threads s | all threads GOPS |")
+    print("|---|---|---|---|---|---|")
+
+    def timed(fn, threads):
+        omp.omp_set_num_threads(threads)
+        t0 = time.perf_counter()
+        fn()
+        return time.perf_counter() - t0
+
+    def row(name, gop, fn, single=True):
+        t_all = timed(fn, nthreads)
+        t_one = timed(fn, 1) if single else None
+        one = f"{t_one:.2f} | {gop / t_one:.1f}" if t_one else "not run | "
+        print(f"| {name} | {gop:.2f} | {one} | {t_all:.3f} | {gop / t_all:.1f} |", flush=True)
+    c = inputs.LINEAR_SMALL
+    w = inputs.weights(c["N"], c["K"], c["sigma"], 8, 0)[0].astype(np.int16)
+    x = inputs.uniform_activations((c["M"], c["K"]), 0)
+    row("c1 linear 64x512->512", 2e-9 * c["M"] * c["N"] * c["K"], lambda: oracle.gemm_acc(x, w))
+    c = inputs.CONV_RESNET18
+    K = 9 * c["Cin"]
+    w = inputs.weights(c["Cout"], K, inputs.he_sigma(K), 8, 0)[0].astype(np.int16).reshape(c["Cout"], 3, 3, c["Cin"])
+    x = inputs.uniform_activations((c["B"], c["H"], c["W"], c["Cin"]), 0)
+    row("c2 conv 3x3 56x56x64->64, batch 32", 2e-9 * c["B"] * c["H"] * c["W"] * c["Cout"] * K, lambda: oracle.conv_acc(x, w, 1, 1))
+    for g in inputs.BOTTLENECK_RESNET101:
+        K = g["KH"] * g["KW"] * g["Cin"]
+        w = inputs.weights(g["Cout"], K, inputs.he_sigma(K), 8, 0)[0].astype(np.int16).reshape(g["Cout"], g["KH"], g["KW"], g["Cin"])
+        x = inputs.uniform_activations((64, 14, 14, g["Cin"]), 0)
+        row(f"c3 {g['KH']}x{g['KW']} {g['Cin']}->{g['Cout']}, batch 64, 14x14", 2e-9 * 64 * 196 * g["Cout"] * K,
+            lambda: oracle.conv_acc(x, w, g["stride"], g["pad"]))
+    for g in inputs.VIT_MLP:
+        w = inputs.weights(g["N"], g["K"], g["sigma"], 8, 0)[0].astype(np.int16)
+        x = inputs.uniform_activations((g["M"], g["K"]), 0)
+        row(f"c5 ViT {g['K']}->{g['N']}, M = {g['M']}", 2e-9 * g["M"] * g["N"] * g["K"], lambda: oracle.gemm_acc(x, w))
+    omp.omp_set_num_threads(nthreads)
+    print("\n(c4, 2 TOP per forward, is timed by bench.py's cpu_baseline only through its c2-shaped layer; a whole forward "
+          "on the oracle is what tests/test_gpu_resnet101.py runs at a reduced batch.)")
+
+
 def c1():
     header("config 1: linear 64x512 -> 512 (launch bound) and weight-bound stand-ins (M = 64 and 16, 8192 x 8192)")
     gemm("64x512->512 l=2", 64, 512, 512, 2)
     gemm("64x8192->8192 l=2", 64, 8192, 8192, 2, sets=3)
     gemm("16x8192->8192 l=2", 16, 8192, 8192, 2, sets=3)
     gemm("16x8192->8192 l=4", 16, 8192, 8192, 4, sets=3)
+    c1_stack()
+
+
+def c1_stack():
+    """1024 distinct 512 x 512 layers (268 MB of packed pages: more than the Infinity Cache) as one sequence of
+    launches, replayed as a HIP graph so that the host is out of the picture."""
+    L, M, K, N = 1024, 64, 512, 512
+    cfg = nq.make_cfg(8, 2)
+    w_int, scale = inputs.weights(N, K, 0.02, 8, 0)
+    d_w, d_s = torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda()
+    low_bytes = nq.nq_packed_bytes(N, K, 2)
+    arena = torch.empty(L * low_bytes, dtype=torch.uint8, device="cuda")
+    host = torch.empty(L * low_bytes, dtype=torch.uint8, pin_memory=True)
+    layers = []
+    for i in range(L):
+        W = nq.NestedWeight(N, K, cfg, low=arena[i * low_bytes:(i + 1) * low_bytes],
+                            low_host=host[i * low_bytes:(i + 1) * low_bytes])
+        W.fill_from_int8(d_w, d_s)
+        layers.append(W)
+    x = torch.from_numpy(inputs.uniform_activations((M, K), 0)).cuda()
+    y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    epi = nq.make_epilogue(0.02)
+    print("\n* stack of 1024 distinct 64x512->512 layers (packed pages 268 MB full-bit, 201 MB part-bit), one HIP graph:")
+    for full in (True, False):
+        fn = nq.nq_gemm_full if full else nq.nq_gemm_part
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            for W in layers[:8]:
+                fn(x, M, W.desc, epi, y)
+            st.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=st):
+                for W in layers:
+                    fn(x, M, W.desc, epi, y)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 5
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / reps * 1e3
+        wb = L * (nq.nq_packed_bytes(N, K, 6) + (low_bytes if full else 0))
+        print(f"  {'full' if full else 'part'}-bit: {ms:.2f} ms = {ms * 1e3 / L:.2f} us per layer, {wb / ms / 1e6:.0f} GB/s of packed "
+              f"weights, {2.0 * M * N * K * L / ms / 1e9:.1f} TOPS (launch bound: a 64-row layer is one wave of 16 blocks)")
+        del graph
 
 
 def c2():
@@ -302,6 +404,53 @@ def c4():
     torch.cuda.synchronize()
     print(f"* upgrade + first full-bit forward: {(time.perf_counter() - t0) * 1e3:.2f} ms")
 
+    # per-layer: the time stamps of every GEMM / convolution dispatch of one full-bit forward, by layer shape
+    from paper_2506_17870_amd import binding
+    recs = []
+    originals = {name: getattr(binding, name) for name in ("nq_conv_full", "nq_gemm_full")}
+
+    def stamped(name):
+        orig = originals[name]
+
+        def call(*a, **k):
+            e0, e1 = binding.nq_event_create(), binding.nq_event_create()
+            binding.nq_profile_next_launch(e0, e1)
+            orig(*a, **k)
+            recs.append((e0, e1, a[1] if name == "nq_conv_full" else None, a[2]))
+        return call
+    for name in originals:
+        setattr(binding, name, stamped(name))
+    try:
+        model.forward(dx, s_x, full=True)
+        torch.cuda.synchronize()
+    finally:
+        for name, orig in originals.items():
+            setattr(binding, name, orig)
+    layers = {}
+    total = 0.0
+    for e0, e1, shape, wd in recs:
+        us = binding.nq_event_elapsed_ms(e0, e1) * 1e3
+        binding.nq_event_destroy(e0)
+        binding.nq_event_destroy(e1)
+        total += us
+        if shape is not None:
+            ho = (shape.H + 2 * shape.pad - shape.KH) // shape.stride + 1
+            wo = (shape.W + 2 * shape.pad - shape.KW) // shape.stride + 1
+            m, k = shape.B * ho * wo, shape.KH * shape.KW * shape.Cin
+            key = f"{shape.KH}x{shape.KW} s{shape.stride} {shape.H}x{shape.W} {shape.Cin}->{shape.Cout}"
+            lops, byts = 2.0 * m * shape.Cout * k, shape.B * shape.H * shape.W * shape.Cin + m * shape.Cout + shape.Cout * k
+        else:
+            key, lops, byts = f"fc {wd.K}->{wd.N}", 2.0 * B * wd.N * wd.K, B * wd.K + 4 * B * wd.N + wd.N * wd.K
+        a = layers.setdefault(key, [0, 0.0, 0.0, 0.0])
+        a[0] += 1; a[1] += us; a[2] += lops; a[3] += byts
+    print(f"\nper layer shape, full-bit (sum of the {len(recs)} kernel times {total / 1e3:.2f} ms; the rest of the forward is "
+          "pooling and launch gaps):\n")
+    print("| layer | launches | us each | TOPS | % int8 MFMA peak | algorithmic GB/s | % HBM peak |")
+    print("|---|---|---|---|---|---|---|")
+    for key, (cnt, us, lops, byts) in sorted(layers.items(), key=lambda kv: -kv[1][1]):
+        tops, gbs = lops / us / 1e6, byts / us / 1e3
+        print(f"| {key} | {cnt} | {us / cnt:.1f} | {tops:.0f} | {100 * tops / MFMA_PEAK:.1f} | {gbs:.0f} | {100 * gbs / HBM_PEAK:.1f} |")
+
 
 def pack():
     print("\n### decompose-and-pack (1 B read + 1 B written per weight)\n")
@@ -317,6 +466,28 @@ def pack():
         gbs = 2.0 * N * K / us / 1e3
         print(f"| {name} | {us:.1f} | {gbs:.0f} | {100 * gbs / HBM_PEAK:.1f} |")
         del w, ph, pl
+    # the whole ResNet-101 weight set (105 tensors, 44.4 M weights), one launch per layer, back to back
+    plan = network.resnet101_plan()
+    ws = network.plan_weights(plan, 8, seed=0)
+    tensors = []
+    for wgt in ws:
+        if wgt is None:
+            continue
+        w_int = wgt[0]
+        n_, k_ = w_int.shape[0], int(np.prod(w_int.shape[1:]))
+        tensors.append((torch.from_numpy(np.ascontiguousarray(w_int.reshape(n_, k_))).cuda(), n_, k_,
+                        torch.empty(nq.nq_packed_bytes(n_, k_, 6), dtype=torch.uint8, device="cuda"),
+                        torch.empty(nq.nq_packed_bytes(n_, k_, 2), dtype=torch.uint8, device="cuda")))
+    total = sum(n_ * k_ for _, n_, k_, _, _ in tensors)
+
+    def all_layers():
+        for w, n_, k_, ph, pl in tensors:
+            nq.nq_decompose_pack(w, n_, k_, cfg, ph, pl)
+    us = wall_us(all_layers, n=10)
+    gbs = 2.0 * total / us / 1e3
+    print(f"| ResNet-101, all {len(tensors)} tensors ({total / 1e6:.1f} M weights), one launch per tensor | {us:.1f} | {gbs:.0f} | "
+          f"{100 * gbs / HBM_PEAK:.1f} |")
+    del tensors
     print("\n### quantise, decompose and pack from fp32 weights (Eq. 1 fused in front; 4 B read + 1 B written per "
           "weight\ncounted, the second pass over the fp32 weights not counted)\n")
     print("| tensor | us | GB/s (counted bytes) | % HBM peak | two calls: nq_quantize + nq_decompose_pack, us |")
@@ -427,7 +598,7 @@ def words():
 
 if __name__ == "__main__":
     torch.cuda.set_device(0)
-    which = sys.argv[1:] or ["c1", "c2", "c3", "c4", "c5", "pack", "page", "sweep", "words", "dw", "lib"]
+    which = sys.argv[1:] or ["c1", "c2", "c3", "c4", "c5", "pack", "page", "sweep", "words", "dw", "lib", "cpu"]
     for name in which:
-        {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "pack": pack, "page": page, "sweep": sweep, "dw": dw, "lib": lib,
+        {"c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "pack": pack, "page": page, "sweep": sweep, "dw": dw, "lib": lib, "cpu": cpu,
          "words": words}[name]()
