@@ -22,7 +22,9 @@
 //    the accumulator dump.
 //
 // A tile is named by (m0, rows, nt0): the global output row of tile row 0, how many of the 32
-// tile rows are real outputs, and the first channel of the tile.
+// tile rows are real outputs, and the first channel of the tile.  The per-lane bodies of the swapped
+// layouts (epi_cols16, epi_row16: sixteen consecutive channels of one output row) are also what the
+// depthwise / grouped kernel calls, whose 16 x 16 accumulator tiles map lanes to pixels differently.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
