@@ -10,8 +10,10 @@
 // Activations travel global -> LDS directly (buffer loads with the LDS bit: no registers, no
 // store instructions; rows past M read as zero through the range check), one iteration ahead,
 // into one of two panels of 128 rows x 256 bytes.  A wave-wide LDS-direct load writes 1024
-// contiguous bytes, so rows cannot be padded; instead the 16-byte pieces of row r are stored
-// at position c ^ (r & 7), which lets eight neighbouring rows be read without bank conflicts.
+// contiguous bytes, so rows cannot be padded; instead the sixteen 16-byte pieces of row r are
+// stored at position c ^ (r & 15): a panel row is 256 bytes, once round the 64 banks, so without
+// the exchange the same piece of every row would sit in the same four banks, and with it sixteen
+// neighbouring rows are read without bank conflicts.
 // Weights: the packed dwords of a lane's own slot, requested four K steps (one iteration) ahead
 // in a rolling register pipeline, decoded in registers and reused for the four row tiles.  All
 // weight loads consumed in an iteration are older than that iteration's activation request, so
@@ -71,19 +73,20 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     // ---- activations -------------------------------------------------------------------------
     // LDS-direct load k of wave w fills panel slots [(APT*w + k)*64, +64) (16 bytes each): lane l
     // writes row 4*(APT*w + k) + (l >> 4), position l & 15, and therefore fetches piece
-    // c = (l & 15) ^ (row & 7) of that row; APT is even, so row & 7 = (l >> 4) | 4*(k & 1).
+    // c = (l & 15) ^ (row & 15) of that row, row & 15 = 4*((APT*w + k) & 3) + (l >> 4): four variants,
+    // kept in the order in which this wave's loads k = 0, 1, 2, 3 (mod 4) need them.
     typedef __attribute__((address_space(3))) void *lds_ptr;
     constexpr int OOR = 0x7fff0000;                      // beyond every descriptor range: moves no data
-    int piece[2];
+    int piece[4];
 #pragma unroll
-    for (int par = 0; par < 2; ++par) piece[par] = (lane & 15) ^ ((lane >> 4) | (4 * par));
+    for (int par = 0; par < 4; ++par) piece[par] = (lane & 15) ^ (4 * ((APT * wave + par) & 3) + (lane >> 4));
     // GEMM: descriptor over the rows of this block; rows past M are out of range.
     // CONV: descriptor over the whole input tensor (the host keeps it below 2 GiB).
     const int64_t rows_here = (p.M - m0) < GB_BM ? (p.M - m0) : GB_BM;
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<int8_t *>(p.x) + (CONV ? 0 : m0 * p.K), 0,
         CONV ? (int)((int64_t)(p.M / ((int64_t)p.Ho * p.Wo)) * p.H * p.W * p.Cin) : (int)(rows_here * p.K), 0x00020000);
-    int a_goff[2];                                       // GEMM: offset of the lane's piece in rows 0..3
+    int a_goff[4];                                       // GEMM: offset of the lane's piece in rows 0..3
     // CONV: per row of the block, the byte offset of filter tap (0,0) and the packed (ih0, iw0) of the
     // pixel, in a small LDS table behind the panels (worked out once, one row per thread)
     int2 *rowtab = reinterpret_cast<int2 *>(panel + 2 * GB_PANEL);
@@ -102,15 +105,15 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
         __syncthreads();
     } else {
 #pragma unroll
-        for (int par = 0; par < 2; ++par)
+        for (int par = 0; par < 4; ++par)
             a_goff[par] = (wave * (4 * APT) + (lane >> 4)) * p.K + 16 * piece[par];
     }
-    // CONV: where the lane's two pieces of iteration `it` come from: the k index of a piece -> filter tap
+    // CONV: where the lane's four pieces of iteration `it` come from: the k index of a piece -> filter tap
     // and channel (Cin is a power of two).  Worked out once per iteration, used by all its requests.
-    int tap_off[2], tap_hw[2];
+    int tap_off[4], tap_hw[4];
     auto set_taps = [&](int it) {
 #pragma unroll
-        for (int par = 0; par < 2; ++par) {
+        for (int par = 0; par < 4; ++par) {
             const int kk = it * (GB_KI * 64) + 16 * piece[par];
             const int tap = kk >> p.cin_shift, ci = kk & (p.Cin - 1);
             const int kh = (tap * p.kw_magic) >> 16, kw = tap - kh * p.KW;
@@ -129,10 +132,10 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
             for (int k = 0; k < APT; ++k) {
                 if (k < k0 || k >= k1) continue;
                 const int2 row = rowtab[4 * (wave * APT + k) + (lane >> 4)];
-                const int ih = (row.y >> 16) + (tap_hw[k & 1] >> 16);
-                const int iw = (int)(int16_t)(row.y & 0xffff) + (tap_hw[k & 1] & 0xffff);
+                const int ih = (row.y >> 16) + (tap_hw[k & 3] >> 16);
+                const int iw = (int)(int16_t)(row.y & 0xffff) + (tap_hw[k & 3] & 0xffff);
                 const bool in = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-                const int off = in ? row.x + tap_off[k & 1] : OOR;
+                const int off = in ? row.x + tap_off[k & 3] : OOR;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_ptr)(dst + (wave * APT + k) * 1024), 16, off, 0, 0,
                                                          0);
             }
@@ -142,7 +145,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
             for (int k = 0; k < APT; ++k) {
                 if (k < k0 || k >= k1) continue;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_ptr)(dst + (wave * APT + k) * 1024), 16,
-                                                         a_goff[k & 1] + k * 4 * p.K + koff, 0, 0, 0);
+                                                         a_goff[k & 3] + k * 4 * p.K + koff, 0, 0, 0);
             }
         }
     };
@@ -199,15 +202,15 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     __builtin_amdgcn_sched_barrier(0);
 
     // LDS address of the lane's fragment for K step d and half hf: piece c = 4*d + 2*g + hf of row
-    // r sits at position c ^ (r & 7); the row tiles are multiples of 32 rows, so r & 7 = lane & 7.
-    int a_read[2][2];
+    // r sits at position c ^ (r & 15); the row tiles are multiples of 32 rows, so r & 15 = lane & 15.
+    int a_read[4][2];
     {
-        const int r7 = lane & 7, g = lane >> 5;
+        const int r15 = lane & 15, g = lane >> 5;
 #pragma unroll
-        for (int d0 = 0; d0 < 2; ++d0)
+        for (int d0 = 0; d0 < 4; ++d0)
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf)
-                a_read[d0][hf] = (lane & 31) * GB_ROW + 16 * (((4 * d0 + 2 * g + hf) ^ r7) & 7);
+                a_read[d0][hf] = (lane & 31) * GB_ROW + 16 * ((4 * d0 + 2 * g + hf) ^ r15);
     }
 
     // Memory instructions are spread through the matrix-core stream: a burst of them would hold the
@@ -268,16 +271,15 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
             g_v4i af[PF];
 #pragma unroll
             for (int f = 0; f < PF; ++f)
-                af[f] = *reinterpret_cast<const g_v4i *>(cur + a_read[d & 1][f / TM] + (f % TM) * 32 * GB_ROW +
-                                                         128 * (d >> 1));
+                af[f] = *reinterpret_cast<const g_v4i *>(cur + a_read[d][f / TM] + (f % TM) * 32 * GB_ROW);
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
                 const int i = f % TM, hf = f / TM;
                 const g_v4i a = af[f % PF];
                 __builtin_amdgcn_sched_barrier(0);
                 if (f + PF < NF)
-                    af[f % PF] = *reinterpret_cast<const g_v4i *>(cur + a_read[d & 1][(f + PF) / TM] +
-                                                                  ((f + PF) % TM) * 32 * GB_ROW + 128 * (d >> 1));
+                    af[f % PF] = *reinterpret_cast<const g_v4i *>(cur + a_read[d][(f + PF) / TM] +
+                                                                  ((f + PF) % TM) * 32 * GB_ROW);
 #pragma unroll
                 for (int t = 0; t < TN; ++t) acc[i][t] = epi_mfma<EPI>(bfrag[t][hf], a, acc[i][t]);
                 // a slice of the next step's decoding
