@@ -487,6 +487,11 @@ def pack():
     gbs = 2.0 * total / us / 1e3
     print(f"| ResNet-101, all {len(tensors)} tensors ({total / 1e6:.1f} M weights), one launch per tensor | {us:.1f} | {gbs:.0f} | "
           f"{100 * gbs / HBM_PEAK:.1f} |")
+    jobs = [(w, n_, k_, ph, pl) for w, n_, k_, ph, pl in tensors]
+    us = wall_us(lambda: nq.nq_decompose_pack_batch(jobs, cfg), n=10)
+    gbs = 2.0 * total / us / 1e3
+    print(f"| the same as nq_decompose_pack_batch (two launches of up to 64 tensors) | {us:.1f} | {gbs:.0f} | "
+          f"{100 * gbs / HBM_PEAK:.1f} |")
     del tensors
     print("\n### quantise, decompose and pack from fp32 weights (Eq. 1 fused in front; 4 B read + 1 B written per "
           "weight\ncounted, the second pass over the fp32 weights not counted)\n")

@@ -196,6 +196,18 @@ nq_status nq_pack(const int8_t *d_high, const int8_t *d_low, int64_t N, int64_t 
 nq_status nq_decompose_pack(const int8_t *d_w_int, int64_t N, int64_t K, const nq_cfg *cfg,
                             void *d_packed_high, void *d_packed_low, void *stream);
 
+/* nq_decompose_pack for many tensors (the weights of a whole model) in as few launches as possible:
+ * a launch per tensor is launch bound for the small layers of a CNN.  `jobs` is a HOST array of `count`
+ * entries, read before the call returns; pointers inside are device memory as in nq_decompose_pack, both
+ * pages required.  NQ_LAYOUT_DENSE only.  Same pages as `count` calls of nq_decompose_pack. */
+typedef struct {
+    const int8_t *d_w_int;   /* device int8[N*K] */
+    int64_t N, K;
+    void *d_packed_high;     /* device, 16-byte aligned, nq_packed_bytes(N, K, h, DENSE) */
+    void *d_packed_low;      /* device, 16-byte aligned, nq_packed_bytes(N, K, l or l + 1, DENSE) */
+} nq_pack_job;
+nq_status nq_decompose_pack_batch(const nq_pack_job *jobs, int64_t count, const nq_cfg *cfg, void *stream);
+
 /* Inverse of nq_pack: pages -> int8[N][K] parts (w_high sign-extended from h bits, w_low
  * in [0, 2^l - 1]).  Either pair may be NULL. */
 nq_status nq_unpack(const void *d_packed_high, const void *d_packed_low, int64_t N, int64_t K,

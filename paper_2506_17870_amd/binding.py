@@ -23,7 +23,7 @@ NQ_LAYOUT_DENSE, NQ_LAYOUT_PAPER_U64 = 0, 1
 NQ_MAX_K = 65536
 
 EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "nq_quantize_decompose_pack",
-           "nq_decompose", "nq_pack", "nq_decompose_pack",
+           "nq_decompose", "nq_pack", "nq_decompose_pack", "nq_decompose_pack_batch",
            "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
            "nq_weight_init_group", "nq_page_out_low_batch", "nq_page_in_low_batch",
            "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_gconv_full", "nq_gconv_part",
@@ -44,6 +44,11 @@ class nq_weight(ctypes.Structure):
                 ("low_resident", ctypes.c_int32), ("low_event_armed", ctypes.c_int32),
                 ("low_event", ctypes.c_void_p), ("free_event", ctypes.c_void_p),
                 ("free_event_armed", ctypes.c_int32), ("events_borrowed", ctypes.c_int32)]
+
+
+class nq_pack_job(ctypes.Structure):
+    _fields_ = [("d_w_int", ctypes.c_void_p), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+                ("d_packed_high", ctypes.c_void_p), ("d_packed_low", ctypes.c_void_p)]
 
 
 class nq_epilogue(ctypes.Structure):
@@ -75,6 +80,7 @@ _SIGS = {
     "nq_decompose": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
     "nq_pack": (_int, [_vp, _vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
     "nq_decompose_pack": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
+    "nq_decompose_pack_batch": (_int, [ctypes.POINTER(nq_pack_job), _i64, _cfgp, _vp]),
     "nq_unpack": (_int, [_vp, _vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
     "nq_weight_init": (_int, [_wp]),
     "nq_weight_destroy": (_int, [_wp]),
@@ -167,6 +173,14 @@ def nq_quantize_decompose_pack(d_w, N, K, cfg, d_scale, d_packed_high, d_packed_
 def nq_decompose_pack(d_w_int, N, K, cfg, d_packed_high, d_packed_low, stream=None):
     _check(_lib.nq_decompose_pack(_ptr(d_w_int), N, K, ctypes.byref(cfg), _ptr(d_packed_high),
                                   _ptr(d_packed_low), _stream(stream)), "nq_decompose_pack")
+
+
+def nq_decompose_pack_batch(jobs, cfg, stream=None):
+    """jobs: sequence of (d_w_int, N, K, d_packed_high, d_packed_low)."""
+    arr = (nq_pack_job * max(len(jobs), 1))()
+    for i, (w, n, k, ph, pl) in enumerate(jobs):
+        arr[i] = nq_pack_job(_ptr(w), n, k, _ptr(ph), _ptr(pl))
+    _check(_lib.nq_decompose_pack_batch(arr, len(jobs), ctypes.byref(cfg), _stream(stream)), "nq_decompose_pack_batch")
 
 
 def nq_unpack(d_packed_high, d_packed_low, N, K, cfg, d_high, d_low, stream=None):

@@ -80,16 +80,14 @@ __global__ void __launch_bounds__(256) k_decompose(const int8_t *__restrict__ w,
 // weights (a) and their channel scales (b), quantised on the way (Eq. 1).
 // ---------------------------------------------------------------------------------------
 template <int H, int L, int SRC>
-__global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a, const int8_t *__restrict__ b,
-                                                     int64_t N, int64_t K, int64_t KB, int64_t tiles,
-                                                     uint32_t *__restrict__ ph, uint32_t *__restrict__ pl,
-                                                     int vec_ok, int sgn)
+__device__ __forceinline__ void pack_dense_tile(const int8_t *__restrict__ a, const int8_t *__restrict__ b,
+                                                int64_t N, int64_t K, int64_t KB, int64_t tile,
+                                                uint32_t *__restrict__ ph, uint32_t *__restrict__ pl,
+                                                int vec_ok, int sgn)
 {
     constexpr int S = 8 - H;        // spare bits of a carrier byte
     constexpr int UP = 8 - H - L;   // 0 for INT8 nesting, 2 for INT6 nesting
     const int lane = threadIdx.x & 63;
-    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (tile >= tiles) return;
     const int64_t nb = tile / KB, kb = tile % KB;
     const int r = lane & 31, g = lane >> 5;
     const int64_t n = nb * 32 + r;
@@ -208,6 +206,47 @@ __global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a
 #pragma unroll
         for (int i = 0; i < L; ++i) dst[i * 64] = Q[i];
     }
+}
+
+template <int H, int L, int SRC>
+__global__ void __launch_bounds__(256) k_pack_dense(const int8_t *__restrict__ a, const int8_t *__restrict__ b,
+                                                     int64_t N, int64_t K, int64_t KB, int64_t tiles,
+                                                     uint32_t *__restrict__ ph, uint32_t *__restrict__ pl,
+                                                     int vec_ok, int sgn)
+{
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= tiles) return;
+    pack_dense_tile<H, L, SRC>(a, b, N, K, KB, tile, ph, pl, vec_ok, sgn);
+}
+
+// Many tensors in one launch (the weights of a whole model): the jobs travel by value in the kernel
+// arguments, with the running count of their tiles; a wave finds its job by searching that count.
+constexpr int PACK_BATCH = 64;
+struct PackBatch {
+    const int8_t *w[PACK_BATCH];
+    uint32_t *ph[PACK_BATCH];
+    uint32_t *pl[PACK_BATCH];
+    int N[PACK_BATCH], K[PACK_BATCH];
+    int64_t first_tile[PACK_BATCH + 1];      // tiles of jobs 0 .. j-1; entries past `count` repeat the total
+    int count;
+};
+
+template <int H, int L>
+__global__ void __launch_bounds__(256) k_pack_dense_batch(const PackBatch jobs, int sgn)
+{
+    const int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (tile >= jobs.first_tile[jobs.count]) return;
+    int lo = 0, hi = jobs.count - 1;                      // last job whose first tile is <= tile
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (jobs.first_tile[mid] <= tile) lo = mid;
+        else hi = mid - 1;
+    }
+    const int64_t N = jobs.N[lo], K = jobs.K[lo];
+    const int8_t *w = jobs.w[lo];
+    const int vec_ok = (K % 16 == 0) && ((reinterpret_cast<uintptr_t>(w) & 15u) == 0);
+    pack_dense_tile<H, L, 0>(w, nullptr, N, K, (K + 63) / 64, tile - jobs.first_tile[lo], jobs.ph[lo], jobs.pl[lo],
+                             vec_ok, sgn);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -525,6 +564,53 @@ extern "C" nq_status nq_decompose_pack(const int8_t *d_w_int, int64_t N, int64_t
     if (!d_w_int && N * K != 0) return NQ_ERR_INVALID_ARG;
     if (!d_packed_high && !d_packed_low) return NQ_ERR_INVALID_ARG;
     return pack_any(0, d_w_int, nullptr, N, K, cfg, d_packed_high, d_packed_low, stream);
+}
+
+template <int H, int L>
+static void launch_pack_dense_batch(const PackBatch &jobs, int sgn, hipStream_t st)
+{
+    const int64_t tiles = jobs.first_tile[jobs.count];
+    hipLaunchKernelGGL((k_pack_dense_batch<H, L>), dim3((unsigned)ceil_div(tiles, 4)), dim3(256), 0, st, jobs, sgn);
+}
+
+extern "C" nq_status nq_decompose_pack_batch(const nq_pack_job *jobs, int64_t count, const nq_cfg *cfg, void *stream)
+{
+    nq_status st = check_cfg(cfg);
+    if (st != NQ_OK) return st;
+    if (cfg->layout != NQ_LAYOUT_DENSE) return NQ_ERR_UNSUPPORTED;
+    if (count < 0 || (count > 0 && !jobs)) return NQ_ERR_INVALID_ARG;
+    for (int64_t i = 0; i < count; ++i) {
+        if ((st = check_shape(jobs[i].N, jobs[i].K)) != NQ_OK) return st;
+        if (jobs[i].N > 0x7fffffff) return NQ_ERR_SHAPE;
+        if (jobs[i].N * jobs[i].K != 0 && (!jobs[i].d_w_int || !jobs[i].d_packed_high || !jobs[i].d_packed_low))
+            return NQ_ERR_INVALID_ARG;
+        if ((st = check_pages(cfg, jobs[i].d_packed_high, jobs[i].d_packed_low)) != NQ_OK) return st;
+    }
+    const int h = cfg->n_bits - cfg->l_bits, l = cfg->l_bits;
+    const int sgn = cfg->low_format == NQ_LOW_SIGNED_L1;
+    bool launched = false;
+    for (int64_t i0 = 0; i0 < count; i0 += PACK_BATCH) {
+        PackBatch b;
+        b.count = 0;
+        b.first_tile[0] = 0;
+        for (int64_t i = i0; i < count && i < i0 + PACK_BATCH; ++i) {
+            const int64_t tiles = ceil_div(jobs[i].N, 32) * ceil_div(jobs[i].K, 64);
+            if (tiles == 0) continue;
+            const int j = b.count++;
+            b.w[j] = jobs[i].d_w_int;
+            b.ph[j] = (uint32_t *)jobs[i].d_packed_high;
+            b.pl[j] = (uint32_t *)jobs[i].d_packed_low;
+            b.N[j] = (int)jobs[i].N;
+            b.K[j] = (int)jobs[i].K;
+            b.first_tile[j + 1] = b.first_tile[j] + tiles;
+        }
+        if (b.count == 0) continue;
+        if (ceil_div(b.first_tile[b.count], 4) > 0x7fffffffLL) return NQ_ERR_SHAPE;
+        for (int j = b.count + 1; j <= PACK_BATCH; ++j) b.first_tile[j] = b.first_tile[b.count];
+        NQ_DISPATCH_HL(h, l, launch_pack_dense_batch, b, sgn, (hipStream_t)stream);
+        launched = true;
+    }
+    return launched ? launch_status() : NQ_OK;          // nothing to do: no HIP call at all
 }
 
 extern "C" nq_status nq_unpack(const void *d_packed_high, const void *d_packed_low, int64_t N, int64_t K,

@@ -102,9 +102,21 @@ class NestedCNN:
             self.layers.append((W, torch.from_numpy(bias).cuda()))
         self.descs = [L[0].desc for L in self.layers if L is not None]
         nq.nq_weight_init_group(self.descs)
+        # all layers are decomposed and packed by one batched call, then the arena of lower-bit pages is
+        # copied once to its pinned master copy
+        jobs, keep = [], []
         for L, w in zip(self.layers, weights):
             if L is not None:
-                L[0].fill_from_int8(torch.from_numpy(w[0]).cuda(), torch.from_numpy(w[1]).cuda())
+                d_w = torch.from_numpy(w[0]).cuda()
+                keep.append(d_w)
+                jobs.append((d_w, L[0].N, L[0].K, L[0].high, L[0].low))
+                L[0].scale.copy_(torch.from_numpy(w[1]))
+        nq.nq_decompose_pack_batch(jobs, self.cfg)
+        self.low_arena_host.copy_(self.low_arena)
+        torch.cuda.synchronize()
+        for L in self.layers:
+            if L is not None:
+                L[0].desc.low_resident = 1
         self.out_scale = [None] * (max(op["dst"] for op in ops) + 1)   # step of every int8 tensor
 
     def low_page_bytes(self) -> int:

@@ -106,6 +106,18 @@ def test_host_side_argument_checks(nq):
         nq.nq_quantize_decompose_pack(a, 4, 4, nq.make_cfg(8, 2), a, a + 8, a, stream=0)
     assert e.value.status == nq.NQ_ERR_ALIGN
     nq.nq_quantize_decompose_pack(a, 0, 16, nq.make_cfg(6, 2), a, a, a, stream=0)
+    # the batched form: the same checks per job, dense layout only, an empty batch is a no-op
+    nq.nq_decompose_pack_batch([], nq.make_cfg(8, 2), stream=0)
+    nq.nq_decompose_pack_batch([(a, 0, 16, a, a)], nq.make_cfg(8, 2), stream=0)
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_decompose_pack_batch([(a, 4, 4, a, a), (a, 4, 4, a + 4, a)], nq.make_cfg(8, 2), stream=0)
+    assert e.value.status == nq.NQ_ERR_ALIGN
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_decompose_pack_batch([(a, 4, 4, a, None)], nq.make_cfg(8, 2), stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_decompose_pack_batch([(a, 4, 4, a, a)], nq.make_cfg(8, 2, layout=nq.NQ_LAYOUT_PAPER_U64), stream=0)
+    assert e.value.status == nq.NQ_ERR_UNSUPPORTED
     # empty tensors are a no-op
     nq.nq_decompose(None, 0, 16, nq.make_cfg(8, 2), None, None, stream=0)
     nq.nq_decompose_pack(a, 0, 16, nq.make_cfg(8, 2), a, a, stream=0)

@@ -101,3 +101,35 @@ def test_benchmark_sized_pages(nq, oracle):
         nq.nq_decompose_pack(dev(w), N, K, cfg, ph, pl)
         o_ph, o_pl = oracle.decompose_pack(w, n, l)
         assert np.array_equal(host(ph), o_ph) and np.array_equal(host(pl), o_pl)
+
+
+@pytest.mark.parametrize("n,l,fmt", [(8, 2, 0), (8, 5, 0), (6, 3, 0), (8, 3, 1)])
+def test_batched_decompose_pack(nq, oracle, n, l, fmt):
+    # 150 tensors of mixed shapes (more than one launch's worth of jobs, ragged tiles, an empty one, a large one)
+    rng = np.random.default_rng(n * 10 + l)
+    shapes = [(int(rng.integers(1, 130)), int(rng.integers(1, 300))) for _ in range(147)] + [(0, 16), (512, 4608), (64, 576)]
+    cfg = nq.make_cfg(n, l, fmt)
+    lf = l + fmt
+    jobs, refs = [], []
+    for i, (N, K) in enumerate(shapes):
+        w = rng.integers(-(1 << (n - 1)), 1 << (n - 1), size=(N, K)).astype(np.int8)
+        ph = torch.full((max(nq.nq_packed_bytes(N, K, n - l), 16),), 0x5A, dtype=torch.uint8, device="cuda")
+        pl = torch.full((max(nq.nq_packed_bytes(N, K, lf), 16),), 0x5A, dtype=torch.uint8, device="cuda")
+        jobs.append((torch.from_numpy(w).cuda() if N else torch.empty(16, dtype=torch.int8, device="cuda"), N, K, ph, pl))
+        refs.append(w)
+    nq.nq_decompose_pack_batch(jobs, cfg)
+    torch.cuda.synchronize()
+    for (d_w, N, K, ph, pl), w in zip(jobs, refs):
+        if N == 0:
+            continue
+        ph1, pl1 = torch.zeros_like(ph), torch.zeros_like(pl)
+        nq.nq_decompose_pack(d_w, N, K, cfg, ph1, pl1)      # itself checked against the oracle above
+        torch.cuda.synchronize()
+        hb, lb = nq.nq_packed_bytes(N, K, n - l), nq.nq_packed_bytes(N, K, lf)
+        assert torch.equal(ph[:hb], ph1[:hb]) and torch.equal(pl[:lb], pl1[:lb]), (N, K)
+    # and directly against the oracle for a few of them
+    if fmt == 0:
+        for idx in (0, 5, 148, 149):
+            d_w, N, K, ph, pl = jobs[idx]
+            oh, ol = oracle.decompose_pack(refs[idx], n, l)
+            assert np.array_equal(ph.cpu().numpy()[:oh.size], oh) and np.array_equal(pl.cpu().numpy()[:ol.size], ol)
