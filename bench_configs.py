@@ -72,10 +72,11 @@ def header(title):
     print("|---|---|---|---|---|---|---|")
 
 
-def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8):
+def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8, layout=None):
+    layout = nq.NQ_LAYOUT_DENSE if layout is None else layout
     w_int, scale = inputs.weights(N, K, sigma, n_bits, 0)
     W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(),
-                                  nq.make_cfg(n_bits, l))
+                                  nq.make_cfg(n_bits, l, layout=layout))
     # INT6 nesting runs with 6-bit activations (Sec. 4.2): int8 codes in [-32, 31]
     xs = [torch.from_numpy(inputs.uniform_activations((M, K), i) >> (8 - n_bits)).cuda() for i in range(sets)]
     ys = [torch.empty((M, N), dtype=torch.int8 if out8 else torch.float32, device="cuda") for _ in range(sets)]
@@ -90,7 +91,7 @@ def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8):
                 nq.nq_profile_next_launch(ev[0], ev[1])
             (nq.nq_gemm_full if full else nq.nq_gemm_part)(xs[i], M, W.desc, epi, ys[i])
         med, _ = kernel_us(fn)
-        wb = nq.nq_packed_bytes(N, K, n_bits - l) + (nq.nq_packed_bytes(N, K, l) if full else 0)
+        wb = nq.nq_packed_bytes(N, K, n_bits - l, layout) + (nq.nq_packed_bytes(N, K, l, layout) if full else 0)
         row(name, ("full" if full else "part") + (" int8 out" if out8 else " fp32 out"), med, 2.0 * M * N * K,
             M * K + wb + M * N * (1 if out8 else 4))
 
@@ -567,8 +568,8 @@ def sweep():
 
 def words():
     """The paper's own page format (64 // k fields per unsigned 64-bit word, Sec. 3.3.4) against the dense
-    tile pages: bits per weight, and the cost of taking a model stored in words to the dense pages on the GPU
-    (nq_unpack of the word pages + nq_pack into tiles)."""
+    tile pages: bits per weight, the cost of taking a model stored in words to the dense pages on the GPU
+    (nq_unpack of the word pages + nq_pack into tiles), and the GEMM that reads the word pages as they are."""
     print("\n### word pages (64 // k fields per uint64) -> dense tile pages, 4096 x 4096 weights\n")
     print("| nesting | word pages bit/weight | dense pages bit/weight | unpack + pack us | GB/s (all four streams) |")
     print("|---|---|---|---|---|")
@@ -599,6 +600,15 @@ def words():
         assert torch.equal(rh, dh) and torch.equal(rl, dl), "transcoded pages differ"
         print(f"| INT(8\\|{h}) | {8.0 * bw / (N * K):.2f} | {8.0 * bd / (N * K):.2f} | {us:.1f} | "
               f"{(bw + 4 * N * K + bd) / us / 1e3:.0f} |")
+
+
+    header("GEMM straight from the word pages against the dense pages, 16 x 8192 -> 8192 (the pages are the traffic)")
+    for l in (1, 2, 3, 4):
+        gemm(f"INT(8|{8 - l}) dense pages", 16, 8192, 8192, l, sets=2)
+        gemm(f"INT(8|{8 - l}) word pages", 16, 8192, 8192, l, sets=2, layout=nq.NQ_LAYOUT_PAPER_U64)
+    header("the same for a large batch: ViT fc1 12608 x 768 -> 3072, fp32 out (word pages are read once per 32 rows)")
+    gemm("INT(8|5) dense pages", 12608, 768, 3072, 3, sets=2)
+    gemm("INT(8|5) word pages", 12608, 768, 3072, 3, sets=2, layout=nq.NQ_LAYOUT_PAPER_U64)
 
 
 if __name__ == "__main__":

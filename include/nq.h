@@ -85,8 +85,12 @@ typedef enum { NQ_LOW_UNSIGNED_L = 0, NQ_LOW_SIGNED_L1 = 1 } nq_low_format;
  *   A field is the value modulo 2^k.
  * NQ_LAYOUT_PAPER_U64: the paper's packed-bit tensor (Sec. 3.3.4): 64/k (integer
  *   division) fields per unsigned 64-bit word, field j in bits [j*k, (j+1)*k), spare top
- *   bits zero, each row starts a new word, the last word of a row zero padded.  This
- *   layout can be packed and unpacked; the GEMM/convolution kernels read NQ_LAYOUT_DENSE. */
+ *   bits zero (readers ignore them), each row starts a new word, the last word of a row
+ *   zero padded.  This layout can be packed and unpacked, and nq_gemm_full / nq_gemm_part
+ *   read it directly (a model stored as the paper packs it needs no repacking; the
+ *   activations must then start on a 4-byte boundary and M * K stay below 2^31 - 2^16).
+ *   It is the slower way in: the dense pages are what the kernels are built around, and
+ *   the convolution entry points read nothing else (NQ_ERR_UNSUPPORTED). */
 typedef enum { NQ_LAYOUT_DENSE = 0, NQ_LAYOUT_PAPER_U64 = 1 } nq_layout;
 
 typedef struct {
@@ -248,7 +252,8 @@ nq_status nq_page_in_low_batch(nq_weight *const *ws, int64_t count, void *copy_s
 /* Y[M][N] = epilogue( sum_k X[m][k] * (w_high[n][k] * 2^l + w_low[n][k]) ).
  * d_x: device int8[M][K], K = w->K, row major.  d_y: device fp32[M][N] or int8[M][N]
  * (epi->out_int8).  Requires w->low_resident, else NQ_ERR_NOT_RESIDENT (never falls back
- * to part-bit: the caller chooses the mode).  Only NQ_LAYOUT_DENSE pages. M == 0 is a no-op. */
+ * to part-bit: the caller chooses the mode).  Pages in either layout (NQ_LAYOUT_PAPER_U64: see there
+ * for its two extra conditions, NQ_ERR_ALIGN / NQ_ERR_SHAPE).  M == 0 is a no-op. */
 nq_status nq_gemm_full(const int8_t *d_x, int64_t M, const nq_weight *w, const nq_epilogue *epi,
                        void *d_y, void *stream);
 

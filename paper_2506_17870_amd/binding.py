@@ -351,6 +351,20 @@ class NestedWeight:
         self.desc.low_resident = 1
         return self
 
+    def fill_from_pages(self, high_page, low_page, d_scale):
+        """Takes pages that are packed already in cfg.layout (uint8 tensors or arrays of nq_packed_bytes each),
+        e.g. a model file that stores w_high and w_low as the paper's 64-bit words (Sec. 3.3.4)."""
+        for dst, src in ((self.high, high_page), (self.low, low_page)):
+            src = torch.as_tensor(src).reshape(-1).view(torch.uint8)
+            assert src.numel() <= dst.numel()
+            dst.zero_()
+            dst[:src.numel()].copy_(src)
+        self.scale.copy_(torch.as_tensor(d_scale))
+        self.low_host.copy_(self.low)
+        torch.cuda.synchronize()
+        self.desc.low_resident = 1
+        return self
+
     def close(self):
         if self.desc.low_event:
             nq_weight_destroy(self.desc)

@@ -28,7 +28,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 
 def _units():
     units = [(os.path.join(CSRC, f + ".hip"), os.path.join(OBJ, f + ".o"), [])
-             for f in ("nq_pack", "nq_page", "nq_glue", "nq_gemm")]   # nq_yardsticks.hip is a program of its own
+             for f in ("nq_pack", "nq_page", "nq_glue", "nq_gemm", "nq_gemm_words")]   # nq_yardsticks.hip is a program of its own
     for h, l in NESTINGS:
         for part in (1, 0, 2):
             units.append((os.path.join(CSRC, "nq_gemm_inst.hip"), os.path.join(OBJ, f"nq_gemm_inst_{h}{l}_{part}.o"),

@@ -212,7 +212,9 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if (!w || !epi) return NQ_ERR_INVALID_ARG;
     nq_status st = check_cfg(&w->cfg);
     if (st != NQ_OK) return st;
-    if (w->cfg.layout != NQ_LAYOUT_DENSE) return NQ_ERR_UNSUPPORTED;
+    // the paper's word pages (Sec. 3.3.4) are read by the plain GEMM only
+    const bool words = w->cfg.layout == NQ_LAYOUT_PAPER_U64;
+    if (words && (gs > 0 || g.KH != 1 || g.KW != 1 || g.stride != 1 || g.pad != 0)) return NQ_ERR_UNSUPPORTED;
     if ((st = check_shape(w->N, w->K)) != NQ_OK) return st;
     if (g.M < 0) return NQ_ERR_INVALID_ARG;
     const int h = w->cfg.n_bits - w->cfg.l_bits, l = w->cfg.l_bits;
@@ -221,8 +223,8 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if (w->K == 0) return NQ_ERR_SHAPE;
     if (!d_x || !d_y || !w->d_high || !w->d_scale || (full && !w->d_low)) return NQ_ERR_INVALID_ARG;
     if (!aligned16(w->d_high) || (full && !aligned16(w->d_low))) return NQ_ERR_ALIGN;
-    if (w->high_bytes < nq_packed_bytes(w->N, w->K, h, NQ_LAYOUT_DENSE)) return NQ_ERR_RANGE;
-    if (full && w->low_bytes < nq_packed_bytes(w->N, w->K, low_field_bits(&w->cfg), NQ_LAYOUT_DENSE)) return NQ_ERR_RANGE;
+    if (w->high_bytes < nq_packed_bytes(w->N, w->K, h, w->cfg.layout)) return NQ_ERR_RANGE;
+    if (full && w->low_bytes < nq_packed_bytes(w->N, w->K, low_field_bits(&w->cfg), w->cfg.layout)) return NQ_ERR_RANGE;
     if (w->N > (1 << 24) || g.M > (int64_t(1) << 40) / (w->N > 0 ? w->N : 1)) return NQ_ERR_SHAPE;
 
     hipStream_t s = (hipStream_t)stream;
@@ -269,6 +271,19 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
 
     void *ev0 = g_ev_start, *ev1 = g_ev_stop;
     g_ev_start = g_ev_stop = nullptr;
+    if (words) {
+        // 32-bit byte offsets into the activations, dword loads relative to their first byte
+        if (g.M * w->K >= 0x7fff0000LL || ceil_div(g.M, 32) > 65535) return NQ_ERR_SHAPE;
+        if ((reinterpret_cast<uintptr_t>(d_x) & 3u) != 0) return NQ_ERR_ALIGN;
+        p.conv_big = 0;
+        p.cin_shift = 0;
+        p.kw_magic = 0;
+        const int WH = (int)ceil_div(w->K, 64 / h);
+        const int lf = low_field_bits(&w->cfg);
+        const int WL = (int)ceil_div(w->K, 64 / lf);
+        launch_nested_gemm_words(full, h, l, p, WH, WL, s, ev0, ev1);
+        return launch_status();
+    }
     if (gs > 0) {
         GroupGeom gg;
         if (!plan_grouped(g, gs, w->N, &gg)) return NQ_ERR_UNSUPPORTED;

@@ -137,4 +137,9 @@ void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, v
 template <int H, int L>
 void launch_nested_gemm_big(bool full, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop);
 
+// GEMM over the paper's word pages (64 / k fields per 64-bit word); WH, WL: words per row of the two pages.
+// Not a template: nq_gemm_words.hip holds every nesting.
+void launch_nested_gemm_words(bool full, int h, int l, const GemmParams &p, int WH, int WL, hipStream_t st,
+                              void *ev_start, void *ev_stop);
+
 }  // namespace nq

@@ -1,0 +1,233 @@
+// Nested-integer GEMM that reads the paper's own pages (Sec. 3.3.4: 64 / k fields of k bits per unsigned
+// 64-bit word, every row starting a new word), so that a model stored exactly as the paper packs it runs
+// without being repacked: full-bit w_high * 2^l + w_low (Eq. 4) or part-bit w_high with s * 2^l (Eq. 8).
+//
+// The two pages cut a row into words of different lengths (12 five-bit fields against 21 three-bit ones), so
+// the parts are not recomposed element by element.  The sum over k is split instead:
+//     sum_k x[k] * (high[k] * 2^l + low[k])  =  2^l * sum_k x[k] * high[k]  +  sum_k x[k] * low[k],
+// one pass of the matrix core over each page, each with its own order of k, joined in int32 at the end (exact:
+// integers).  Within a page a matrix-core step takes sixteen operand slots per half-wave; a lane fills them
+// with the fields of one word (k >= 4: one word per half-wave, slots past the 64 / k fields are zero) or with
+// one sixteen-field group of a word (k <= 3).  The activations of a step are the sixteen bytes of the lane's
+// row that start at the first field's k, whatever its alignment; what they hold past the word's last field
+// meets a zero weight.  Signed fields are decoded to the top of their byte (value * 2^(8-k), no sign extension
+// needed) and the page's sum is shifted back, unsigned ones to the bottom.
+//
+// One block per 32 rows x 32 columns; its four waves split the steps of a page (wave w takes steps w, w + 4,
+// ...) and keep PD of them requested ahead; the partial sums meet in LDS and wave 0 runs the epilogue.  Like the
+// kernel for few rows it is made for the regime in which the packed weights are the traffic; it takes any M,
+// reading the pages once per 32 rows.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nq_epilogue.h"
+#include "nq_gemm_kernel.h"
+
+namespace nq {
+
+// Fields of one word of k = KB bits, as bytes of the matrix core's operand.
+template <int KB, bool SGN>
+struct WordFields {
+    static constexpr int F = 64 / KB;               // fields per word
+    static constexpr int G = (F + 15) / 16;         // groups of sixteen fields per word: 1, 2 or 4
+    static constexpr int NF = F < 16 ? F : 16;      // fields of a group
+    static constexpr int UP = SGN ? 8 - KB : 0;     // a byte holds field << UP
+    static constexpr int SPW = G > 1 ? G / 2 : 1;   // matrix-core steps per word when both half-waves share it
+
+    // (lo, hi): the word, shifted down so that the group's first field is at bit 0, nothing but fields above
+    __device__ __forceinline__ static e_v4i bytes(uint32_t lo, uint32_t hi)
+    {
+        uint32_t D[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < NF; ++j) {
+            const int b = j * KB;                   // where the field is
+            const int tb = 8 * (j & 3) + UP;        // where it goes
+            const uint32_t mask = ((1u << KB) - 1u) << tb;
+            uint32_t src;
+            int sb;
+            if (b + KB <= 32) { src = lo; sb = b; }
+            else if (b >= 32) { src = hi; sb = b - 32; }
+            else { src = __builtin_amdgcn_alignbit(hi, lo, b); sb = 0; }
+            const uint32_t moved = sb >= tb ? src >> (sb - tb) : src << (tb - sb);
+            D[j >> 2] |= moved & mask;
+        }
+        return e_v4i{(int)D[0], (int)D[1], (int)D[2], (int)D[3]};
+    }
+
+    // Operand bytes of group `group` of the word (lo, hi).
+    __device__ __forceinline__ static e_v4i decode(uint32_t lo, uint32_t hi, int group)
+    {
+        if constexpr (G > 1) {
+            if constexpr (F * KB < 64) hi &= (1u << (F * KB - 32)) - 1u;     // spare top bits are no field
+            const uint64_t v = (((uint64_t)hi << 32) | lo) >> (16 * KB * group);
+            return bytes((uint32_t)v, (uint32_t)(v >> 32));
+        } else {
+            return bytes(lo, hi);
+        }
+    }
+};
+
+// acc += X[32 rows] * page[32 columns]^T over the whole row of one page.  wrs: the 32 weight rows of the block
+// (rows past N are out of its range and read as zero), row_off: byte offset of the lane's row in it, W: words
+// per row; xrs: the activations, x_off: byte offset of the lane's row (rows past M are out of range).  The
+// result holds the fields times 2^UP.
+//
+// Every load is a range-checked buffer load at a dword-aligned offset.  The sixteen activation bytes of a step
+// start at any byte: five dwords are fetched and shifted into place.  Bytes past the end of a row belong to
+// the next row (or read as zero past the last one) and meet zero weights: the row's last word is zero padded.
+// FIFTH: the sixteen bytes may start inside a dword and reach into a fifth one.
+template <int KB, bool SGN, int PD, bool FIFTH>
+__device__ __forceinline__ void words_page_steps(const __amdgpu_buffer_rsrc_t wrs, int row_off, int W,
+                                           const __amdgpu_buffer_rsrc_t xrs, uint32_t x_off, int wave, int nw, int g,
+                                           e_v16i &acc)
+{
+    using WF = WordFields<KB, SGN>;
+    constexpr int F = WF::F, G = WF::G, SPW = WF::SPW;
+    constexpr uint32_t NOWHERE = 0x7fff0000u;     // past every buffer: reads as zero
+    const int T = G == 1 ? (W + 1) / 2 : W * SPW;      // steps of the page
+    const int rounds = (T + nw - 1) / nw;              // per wave; steps past T read zero words
+    // Step t of the page (wave w takes t = w, w + nw, ...; nw is even).  Byte offsets of its word and of the
+    // first activation of its sixteen slots are linear in t:
+    //   one word per half-wave (k >= 4):   word 2t + g,  k = (2t + g) * F
+    //   one word per step (k = 2, 3):      word t,       k = t * F + 16 g          (group g)
+    //   two steps per word (k = 1):        word t >> 1,  k = 32 t + 16 g           (group 2 (t & 1) + g)
+    constexpr int WSTEP = G == 1 ? 16 : 8 / SPW;
+    constexpr int XSTEP = G == 1 ? 2 * F : F / SPW;
+    const int group = G == 1 ? 0 : 2 * (wave % SPW) + g;
+    const uint32_t w_end = (uint32_t)(row_off + 8 * W);
+    uint32_t w_at = (uint32_t)(row_off + WSTEP * wave + (G == 1 ? 8 * g : -(8 / SPW) * (wave % SPW)));
+    uint32_t x_at = x_off + (uint32_t)(XSTEP * wave + (G == 1 ? F * g : 16 * g));     // of the next request
+    uint32_t x_use = x_at;                                                            // of the next step computed
+
+    uint2 Wd[PD];
+    e_v4i Xd[PD];
+    int Xe[PD];
+    auto request = [&](int slot) {
+        const bool in = w_at < w_end;
+        const auto wv = __builtin_amdgcn_raw_buffer_load_b64(wrs, in ? w_at : NOWHERE, 0, 0);
+        Wd[slot] = uint2{(uint32_t)wv[0], (uint32_t)wv[1]};
+        const uint32_t xo = in ? x_at & ~3u : NOWHERE;
+        const auto xv = __builtin_amdgcn_raw_buffer_load_b128(xrs, xo, 0, 0);
+        Xd[slot] = e_v4i{(int)xv[0], (int)xv[1], (int)xv[2], (int)xv[3]};
+        if constexpr (FIFTH) Xe[slot] = (int)__builtin_amdgcn_raw_buffer_load_b32(xrs, xo + 16, 0, 0);
+        else Xe[slot] = 0;
+        w_at += (uint32_t)(WSTEP * nw);
+        x_at += (uint32_t)(XSTEP * nw);
+    };
+#pragma unroll
+    for (int d = 0; d < PD; ++d) {
+        request(d);
+        __builtin_amdgcn_sched_barrier(0);     // oldest first, as the loop expects them to arrive
+    }
+    for (int j0 = 0; j0 < rounds; j0 += PD) {
+#pragma unroll
+        for (int d = 0; d < PD; ++d) {
+            const uint32_t sh = x_use & 3u;        // the step's first activation byte inside its dword
+            x_use += (uint32_t)(XSTEP * nw);
+            const e_v4i xa = Xd[d];
+            const e_v4i a = e_v4i{(int)__builtin_amdgcn_alignbyte((uint32_t)xa[1], (uint32_t)xa[0], sh),
+                                  (int)__builtin_amdgcn_alignbyte((uint32_t)xa[2], (uint32_t)xa[1], sh),
+                                  (int)__builtin_amdgcn_alignbyte((uint32_t)xa[3], (uint32_t)xa[2], sh),
+                                  (int)__builtin_amdgcn_alignbyte((uint32_t)Xe[d], (uint32_t)xa[3], sh)};
+            const e_v4i b = WF::decode(Wd[d].x, Wd[d].y, group);
+            // the slot's registers are free again: the new request lands in them
+            __builtin_amdgcn_sched_barrier(0);
+            request(d);
+            acc = epi_mfma<EPI_ANY>(b, a, acc);
+            // keeps the steps in this order: request, wait for the oldest, compute
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+template <int KB, bool SGN, int PD>
+__device__ __forceinline__ void words_page(const __amdgpu_buffer_rsrc_t wrs, int row_off, int W,
+                                           const __amdgpu_buffer_rsrc_t xrs, uint32_t x_off, int K, int wave, int nw,
+                                           int g, e_v16i &acc)
+{
+    using WF = WordFields<KB, SGN>;
+    // No fifth dword where a step has at most thirteen fields (up to three bytes are lost to the alignment),
+    // nor where every step starts on a multiple of sixteen bytes of a row and the rows start on dwords.
+    constexpr bool on16 = KB == 1 || KB == 2 || KB == 4;
+    if constexpr (WF::NF <= 13) {
+        words_page_steps<KB, SGN, PD, false>(wrs, row_off, W, xrs, x_off, wave, nw, g, acc);
+    } else {
+        if (on16 && (K & 3) == 0) words_page_steps<KB, SGN, PD, false>(wrs, row_off, W, xrs, x_off, wave, nw, g, acc);
+        else words_page_steps<KB, SGN, PD, true>(wrs, row_off, W, xrs, x_off, wave, nw, g, acc);
+    }
+}
+
+// HB: bits of the higher-bit fields.  MODE 0: part-bit; 1: unsigned lower-bit fields of LB = l bits; 2: signed
+// lower-bit fields of LB = l + 1 bits (compensated format, Sec. 3.3.3).  WH, WL: words per row of the pages.
+template <int HB, int LB, int MODE>
+__global__ void __launch_bounds__(1024) k_nested_gemm_words(const GemmParams p, int WH, int WL)
+{
+    constexpr int EPI = EPI_ANY;
+    constexpr int PD = 6;
+    extern __shared__ int red[];          // [waves - 1][16][64]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nw = (int)(blockDim.x >> 6);          // 4 or 16 waves share the steps of a page
+    const int g = lane >> 5;
+    const int nb = blockIdx.x;
+    const int64_t m0 = (int64_t)blockIdx.y * 32;
+
+    // the block's 32 weight rows of either page and the activations as range-checked buffers: rows past N or
+    // M read as zero (and are not stored)
+    const int cols = p.N - nb * 32 < 32 ? p.N - nb * 32 : 32;
+    const int cn = epi_weight_slot<EPI>(lane) & 31;
+    // The range ends with the dword that holds the last activation (the host checks that they start on one):
+    // what that dword holds behind it stands at k >= K of the last row and meets zero weights.
+    const __amdgpu_buffer_rsrc_t xrs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.x), 0, (int)((p.M * p.K + 3) & ~int64_t(3)), 0x00020000);
+    const int64_t m = m0 + (lane & 31);
+    const uint32_t x_off = m < p.M ? (uint32_t)(m * p.K) : 0x7fff0000u;
+
+    e_v16i acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0;
+    {
+        const uint2 *rows_h = reinterpret_cast<const uint2 *>(p.ph) + (int64_t)nb * 32 * WH;
+        const __amdgpu_buffer_rsrc_t wrs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint2 *>(rows_h), 0, cols * WH * 8, 0x00020000);
+        words_page<HB, true, PD>(wrs, cn * WH * 8, WH, xrs, x_off, p.K, wave, nw, g, acc);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] >>= 8 - HB;
+    if constexpr (MODE != 0) {
+        constexpr int L = MODE == 2 ? LB - 1 : LB;
+        e_v16i acl;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acl[r] = 0;
+        const uint2 *rows_l = reinterpret_cast<const uint2 *>(p.pl) + (int64_t)nb * 32 * WL;
+        const __amdgpu_buffer_rsrc_t wrs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint2 *>(rows_l), 0, cols * WL * 8, 0x00020000);
+        words_page<LB, MODE == 2, PD>(wrs, cn * WL * 8, WL, xrs, x_off, p.K, wave, nw, g, acl);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = acc[r] * (1 << L) + (acl[r] >> (MODE == 2 ? 8 - LB : 0));
+    }
+
+    // ---- add the four partial sums ---------------------------------------------------------------
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) red[((wave - 1) * 16 + r) * 64 + lane] = acc[r];
+    }
+    __syncthreads();
+    if (wave > 0) return;
+    for (int w = 0; w < nw - 1; ++w)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] += red[(w * 16 + r) * 64 + lane];
+
+    // ---- epilogue (Eq. 2 / Eq. 8) ----------------------------------------------------------------
+    EpiCols<EPI> e;
+    epi_cols<EPI>(p, nb * 32, lane, MODE != 0, e);
+    const int64_t left = p.M - m0;
+    const int rows = left > 32 ? 32 : (int)left;
+    e_v4i res;
+    epi_resid_load<EPI>(p, m0, rows, nb * 32, lane, res);
+    epi_tile<EPI>(p, acc, 0, e, m0, rows, nb * 32, lane, res);
+}
+
+}  // namespace nq

@@ -138,9 +138,18 @@ def test_gemm_argument_checks_without_gpu(nq):
     assert e.value.status == nq.NQ_ERR_RANGE
     w.high_bytes = 64 * 64 * 6 // 8
     w.cfg.layout = nq.NQ_LAYOUT_PAPER_U64
+    # the paper's word pages: 7 words of ten 6-bit fields per row, more bytes than the dense page
     with pytest.raises(nq.NQError) as e:
         nq.nq_gemm_part(a, 8, w, epi, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_RANGE
+    w.high_bytes = 64 * 7 * 8
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gemm_part(a + 2, 8, w, epi, a, stream=0)      # activations off a dword boundary
+    assert e.value.status == nq.NQ_ERR_ALIGN
+    with pytest.raises(nq.NQError) as e:                    # convolutions read the dense pages only
+        nq.nq_conv_part(a, nq.nq_conv_shape(1, 8, 8, 16, 64, 2, 2, 1, 0), w, epi, a, stream=0)
     assert e.value.status == nq.NQ_ERR_UNSUPPORTED
+    w.high_bytes = 64 * 64 * 6 // 8
     w.cfg.layout = nq.NQ_LAYOUT_DENSE
     nq.nq_gemm_part(a, 0, w, epi, a, stream=0)          # M == 0: nothing to do
     shape = nq.nq_conv_shape(1, 8, 8, 16, 64, 3, 3, 1, 1)  # K would be 144, the descriptor says 64

@@ -1,0 +1,165 @@
+"""GPU parity of the GEMM that reads the paper's own pages (Sec. 3.3.4: 64 // k fields per unsigned 64-bit word)
+directly, full-bit (Eq. 4) and part-bit (Eq. 8), for every nesting and both lower-bit formats.  The pages the
+kernel reads are the ORACLE's (packed on the CPU), so the test is that of a model file written as the paper
+describes.  Bar: int32 accumulators bit exact, fp32 outputs identical, int8 outputs identical."""
+import numpy as np
+import pytest
+import torch
+
+from nq_testlib import check_outputs, dev, host
+from oracle import nq_oracle as oracle
+from paper_2506_17870_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+ALL_NL = [(8, l) for l in range(1, 7)] + [(6, l) for l in range(1, 5)]
+
+
+@pytest.fixture(scope="module")
+def nq():
+    import paper_2506_17870_amd as nq
+    assert torch.cuda.is_available()
+    return nq
+
+
+def oracle_side(w_int, n, l, signed):
+    """(word page of w_high, word page of w_low, full-bit weights, higher-bit part) from the CPU oracle."""
+    h = n - l
+    if signed:
+        hi, res = oracle.decompose(w_int, n, l, "rtn")
+        lo = oracle.low_encode(res, l, oracle.LOW_SIGNED_L1)
+        lf = l + 1
+    else:
+        hi, res = oracle.decompose(w_int, n, l, "bitshift")
+        lo = oracle.low_encode(res, l, oracle.LOW_UNSIGNED_L)
+        lf = l
+    ph = oracle.pack_paper(hi, h)
+    pl = oracle.pack_paper(lo, lf)
+    N, K = w_int.shape
+    # what the pages hold, read back by the oracle's own unpacker
+    hi_back = oracle.unpack_paper(ph, N, K, h, True)
+    lo_back = oracle.unpack_paper(pl, N, K, lf, signed)
+    full = oracle.compose(hi_back, lo_back, l)
+    assert np.array_equal(full, w_int.astype(np.int16))
+    return ph, pl, full, hi_back.astype(np.int16)
+
+
+def weight_from_pages(nq, ph, pl, scale, N, K, n, l, signed):
+    cfg = nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1 if signed else nq.NQ_LOW_UNSIGNED_L, nq.NQ_LAYOUT_PAPER_U64)
+    W = nq.NestedWeight(N, K, cfg)
+    assert ph.nbytes == nq.nq_packed_bytes(N, K, n - l, nq.NQ_LAYOUT_PAPER_U64)
+    assert pl.nbytes == nq.nq_packed_bytes(N, K, l + (1 if signed else 0), nq.NQ_LAYOUT_PAPER_U64)
+    W.fill_from_pages(ph.view(np.uint8).ravel(), pl.view(np.uint8).ravel(), scale)
+    return W
+
+
+def run_both(nq, W, x, w_ref, scale, l, full, out_int8=False, bias=None, residual=None, s_r=0.0, relu=False,
+             s_a=0.043, inv_s_out=1.0):
+    M, N = x.shape[0], w_ref.shape[0]
+    acc_ref = oracle.gemm_acc(x, w_ref)
+    y_ref = oracle.epilogue(acc_ref, s_a=s_a, s_w=scale, part_l_bits=0 if full else l, bias=bias, residual=residual,
+                            s_r=s_r, relu=relu, out_int8=out_int8, inv_s_out=inv_s_out)
+    fn = nq.nq_gemm_full if full else nq.nq_gemm_part
+    dx = dev(x)
+    for dump in (True, False):
+        acc = torch.empty((M, N), dtype=torch.int32, device="cuda") if dump else None
+        d_bias = dev(bias) if bias is not None else None
+        d_res = dev(residual) if residual is not None else None
+        epi = nq.make_epilogue(s_a, d_bias, d_res, s_r, relu, out_int8, inv_s_out, acc)
+        y = torch.full((M, N), 77, dtype=torch.int8 if out_int8 else torch.float32, device="cuda")
+        fn(dx, M, W.desc, epi, y)
+        torch.cuda.synchronize()
+        check_outputs(host(y), host(acc) if dump else None, y_ref, acc_ref, out_int8)
+
+
+# (M, N, K): ragged in every dimension; K below one word, K a whole number of words, several row tiles
+SHAPES = [(1, 1, 1), (16, 70, 333), (45, 33, 64), (3, 32, 7), (33, 96, 1000), (16, 40, 1024)]
+
+
+@pytest.mark.parametrize("signed", [False, True])
+@pytest.mark.parametrize("n,l", ALL_NL)
+def test_words_gemm_all_nestings(nq, n, l, signed):
+    for si, (M, N, K) in enumerate(SHAPES):
+        seed = 1000 * n + 100 * l + 10 * si + int(signed)
+        w_int, scale = inputs.weights(N, K, 0.05, n, seed=seed)
+        x = inputs.uniform_activations((M, K), seed=seed + 1)
+        ph, pl, w_full, w_high = oracle_side(w_int, n, l, signed)
+        W = weight_from_pages(nq, ph, pl, scale, N, K, n, l, signed)
+        run_both(nq, W, x, w_full, scale, l, True)
+        run_both(nq, W, x, w_high, scale, l, False)
+
+
+@pytest.mark.parametrize("n,l,signed", [(8, 3, False), (8, 3, True), (8, 4, False), (6, 2, True), (8, 1, False)])
+def test_words_gemm_epilogues(nq, n, l, signed):
+    M, N, K = 37, 80, 520
+    rng = np.random.default_rng(7 * n + l)
+    w_int, scale = inputs.weights(N, K, 0.05, n, seed=5 + l)
+    x = inputs.uniform_activations((M, K), seed=6 + l)
+    bias = rng.normal(0, 0.5, N).astype(np.float32)
+    residual = rng.integers(-128, 128, (M, N)).astype(np.int8)
+    ph, pl, w_full, w_high = oracle_side(w_int, n, l, signed)
+    W = weight_from_pages(nq, ph, pl, scale, N, K, n, l, signed)
+    for full, w_ref in ((True, w_full), (False, w_high)):
+        run_both(nq, W, x, w_ref, scale, l, full, bias=bias, relu=True)
+        run_both(nq, W, x, w_ref, scale, l, full, bias=bias, residual=residual, s_r=0.02, relu=True, out_int8=True,
+                 inv_s_out=1.0 / 0.05)
+        run_both(nq, W, x, w_ref, scale, l, full, out_int8=True, inv_s_out=1.0 / 0.11)
+
+
+def test_extreme_values_and_spare_bits(nq):
+    """All-minimum weights against all-minimum activations (the largest accumulator of a row), and words whose
+    spare top bits are set: the format leaves them undefined, the kernel must not read them as fields."""
+    for n, l in ((8, 3), (8, 1), (6, 3), (8, 5)):
+        h = n - l
+        M, N, K = 5, 34, 2000
+        w_int = np.full((N, K), -(1 << (n - 1)), dtype=np.int8)
+        w_int[1::2] = (1 << (n - 1)) - 1
+        scale = np.full(N, 0.01, dtype=np.float32)
+        x = np.full((M, K), -128, dtype=np.int8)
+        x[1::2] = 127
+        ph, pl, w_full, w_high = oracle_side(w_int, n, l, False)
+        for k, page in ((h, ph), (l, pl)):
+            spare = 64 - (64 // k) * k
+            if spare:
+                page |= np.uint64(((1 << spare) - 1) << (64 - spare))
+        W = weight_from_pages(nq, ph, pl, scale, N, K, n, l, False)
+        run_both(nq, W, x, w_full, scale, l, True)
+        run_both(nq, W, x, w_high, scale, l, False)
+
+
+def test_gpu_packed_word_pages_feed_the_gemm(nq):
+    """Pages packed by nq_decompose_pack in the word layout equal the oracle's and run through the same GEMM."""
+    n, l = 8, 3
+    M, N, K = 16, 64, 700
+    w_int, scale = inputs.weights(N, K, 0.05, n, seed=3)
+    x = inputs.uniform_activations((M, K), seed=4)
+    ph, pl, w_full, w_high = oracle_side(w_int, n, l, False)
+    cfg = nq.make_cfg(n, l, nq.NQ_LOW_UNSIGNED_L, nq.NQ_LAYOUT_PAPER_U64)
+    W = nq.NestedWeight.from_int8(dev(w_int), dev(scale), cfg)
+    assert np.array_equal(host(W.high)[:ph.nbytes], ph.view(np.uint8).ravel())
+    assert np.array_equal(host(W.low)[:pl.nbytes], pl.view(np.uint8).ravel())
+    run_both(nq, W, x, w_full, scale, l, True)
+    run_both(nq, W, x, w_high, scale, l, False)
+
+
+def test_word_pages_argument_checks(nq):
+    n, l = 8, 2
+    N, K, M = 32, 128, 4
+    w_int, scale = inputs.weights(N, K, 0.05, n, seed=1)
+    cfg = nq.make_cfg(n, l, nq.NQ_LOW_UNSIGNED_L, nq.NQ_LAYOUT_PAPER_U64)
+    W = nq.NestedWeight.from_int8(dev(w_int), dev(scale), cfg)
+    epi = nq.make_epilogue(1.0)
+    y = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    xb = torch.zeros(M * K + 4, dtype=torch.int8, device="cuda")
+    # activations that do not start on a dword
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gemm_full(xb[1:1 + M * K], M, W.desc, epi, y)
+    assert e.value.status == nq.NQ_ERR_ALIGN
+    # convolutions read the dense pages only
+    cs = nq.nq_conv_shape(1, 4, 4, 8, N, 4, 4, 1, 0)
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_conv_full(xb, cs, W.desc, epi, y)
+    assert e.value.status == nq.NQ_ERR_UNSUPPORTED
+    # nothing to do
+    nq.nq_gemm_full(xb, 0, W.desc, epi, y)
+    torch.cuda.synchronize()
