@@ -163,3 +163,15 @@ def test_word_pages_argument_checks(nq):
     # nothing to do
     nq.nq_gemm_full(xb, 0, W.desc, epi, y)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("l,signed", [(3, False), (2, True)])
+def test_words_gemm_at_the_measured_size(nq, l, signed):
+    """16 x 8192 -> 8192, the size the word-page tables are measured at; every output compared."""
+    n, M, N, K = 8, 16, 8192, 8192
+    w_int, scale = inputs.weights(N, K, 0.02, n, seed=40 + l)
+    x = inputs.uniform_activations((M, K), seed=41 + l)
+    ph, pl, w_full, w_high = oracle_side(w_int, n, l, signed)
+    W = weight_from_pages(nq, ph, pl, scale, N, K, n, l, signed)
+    run_both(nq, W, x, w_full, scale, l, True, s_a=0.02)
+    run_both(nq, W, x, w_high, scale, l, False, s_a=0.02)
