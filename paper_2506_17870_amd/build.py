@@ -3,8 +3,8 @@
     python -m paper_2506_17870_amd.build [--force]
 
 Objects go to _build/ next to this file, the library to paper_2506_17870_amd/libnq.so.
-Two translation units per nesting (h, l) hold the GEMM/convolution kernels, so the
-units compile in parallel.
+Three translation units per nesting (h, l) hold the GEMM/convolution kernels, so the
+units compile in parallel; the GEMM over the paper's word pages is one unit for all nestings.
 """
 from __future__ import annotations
 
