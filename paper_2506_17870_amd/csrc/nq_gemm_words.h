@@ -13,10 +13,11 @@
 // meets a zero weight.  Signed fields are decoded to the top of their byte (value * 2^(8-k), no sign extension
 // needed) and the page's sum is shifted back, unsigned ones to the bottom.
 //
-// One block per 32 rows x 32 columns; its four waves split the steps of a page (wave w takes steps w, w + 4,
-// ...) and keep PD of them requested ahead; the partial sums meet in LDS and wave 0 runs the epilogue.  Like the
-// kernel for few rows it is made for the regime in which the packed weights are the traffic; it takes any M,
-// reading the pages once per 32 rows.
+// One block per 32 rows x 32 columns; its four or eight waves split the steps of a page (wave w takes steps w,
+// w + NW, ...) and keep eight of them requested ahead; the partial sums meet in LDS and wave 0 runs the
+// epilogue.  Like the kernel for few rows it is made for the regime in which the packed weights are the
+// traffic; it takes any M, reading the pages once per 32 rows.  What bounds it is the vector ALU: about two
+// instructions per field to move it, four per weight with everything else of a step.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -68,68 +69,138 @@ struct WordFields {
     }
 };
 
-// acc += X[32 rows] * page[32 columns]^T over the whole row of one page.  wrs: the 32 weight rows of the block
-// (rows past N are out of its range and read as zero), row_off: byte offset of the lane's row in it, W: words
-// per row; xrs: the activations, x_off: byte offset of the lane's row (rows past M are out of range).  The
-// result holds the fields times 2^UP.
-//
-// Every load is a range-checked buffer load at a dword-aligned offset.  The sixteen activation bytes of a step
-// start at any byte: five dwords are fetched and shifted into place.  Bytes past the end of a row belong to
-// the next row (or read as zero past the last one) and meet zero weights: the row's last word is zero padded.
-// FIFTH: the sixteen bytes may start inside a dword and reach into a fifth one.
-template <int KB, bool SGN, int PD, bool FIFTH>
-__device__ __forceinline__ void words_page_steps(const __amdgpu_buffer_rsrc_t wrs, int row_off, int W,
-                                           const __amdgpu_buffer_rsrc_t xrs, uint32_t x_off, int wave, int nw, int g,
-                                           e_v16i &acc)
-{
-    using WF = WordFields<KB, SGN>;
-    constexpr int F = WF::F, G = WF::G, SPW = WF::SPW;
-    constexpr uint32_t NOWHERE = 0x7fff0000u;     // past every buffer: reads as zero
-    const int T = G == 1 ? (W + 1) / 2 : W * SPW;      // steps of the page
-    const int rounds = (T + nw - 1) / nw;              // per wave; steps past T read zero words
-    // Step t of the page (wave w takes t = w, w + nw, ...; nw is even).  Byte offsets of its word and of the
-    // first activation of its sixteen slots are linear in t:
+// Geometry of the activation chunks in LDS for pages of KB-bit fields and NW waves per block.  A chunk is what
+// 8 * NW consecutive steps of a page read: 8 steps per wave.
+template <int KB, int NW>
+struct WordChunk {
+    static constexpr int F = 64 / KB, G = (F + 15) / 16, SPW = G > 1 ? G / 2 : 1;
+    // Step t of the page (wave w takes t = w, w + NW, ...).  Byte offsets of its word and of the first
+    // activation of its sixteen slots are linear in t:
     //   one word per half-wave (k >= 4):   word 2t + g,  k = (2t + g) * F
     //   one word per step (k = 2, 3):      word t,       k = t * F + 16 g          (group g)
     //   two steps per word (k = 1):        word t >> 1,  k = 32 t + 16 g           (group 2 (t & 1) + g)
-    constexpr int WSTEP = G == 1 ? 16 : 8 / SPW;
-    constexpr int XSTEP = G == 1 ? 2 * F : F / SPW;
+    static constexpr int WSTEP = G == 1 ? 16 : 8 / SPW;
+    static constexpr int XSTEP = G == 1 ? 2 * F : F / SPW;
+    static constexpr int SC = 8 * NW;                    // steps of a chunk
+    static constexpr int SPAN = XSTEP * SC;              // activation bytes a chunk advances by
+    // bytes of a row in LDS: the span, the last step's reach past it (less than a step, plus up to 3 bytes
+    // of alignment and 20 bytes read), in 16-byte pieces, an odd number of them (rows fall on different banks)
+    static constexpr int PPR = ((SPAN + 32 + 15) / 16) | 1;
+    static constexpr int RS = 16 * PPR;
+    static constexpr int BUF = 32 * RS + 16;             // one buffer; the last 16 bytes take pieces of no row
+    static constexpr int NPT = (32 * PPR + 64 * NW - 1) / (64 * NW);   // pieces a thread stages per chunk
+};
+
+// LDS bytes of the kernel: two chunk buffers of the page with the longest rows, or the partial sums.
+template <int HB, int LB, int NW>
+constexpr int words_lds_bytes()
+{
+    int b = 2 * WordChunk<HB, NW>::BUF;
+    if (LB > 0 && 2 * WordChunk<(LB > 0 ? LB : 1), NW>::BUF > b) b = 2 * WordChunk<(LB > 0 ? LB : 1), NW>::BUF;
+    return b > (NW - 1) * 4096 ? b : (NW - 1) * 4096;
+}
+
+// Barrier of the block that orders LDS accesses only (a __syncthreads would also wait for every global load in
+// flight).
+__device__ __forceinline__ void words_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// acc += X[32 rows] * page[32 columns]^T over the whole row of one page.  wrs: the 32 weight rows of the block
+// (rows past N are out of its range and read as zero), row_off: byte offset of the lane's row in it, W: words
+// per row.  xrs: the activations; x_row0: byte offset of the block's first row, x_rows: how many of its 32 rows
+// exist.  lds: two chunk buffers.  The result holds the fields times 2^UP.
+//
+// Activations go through LDS.  Fetched straight from memory, the sixteen bytes of a step are one cache line per
+// lane for nine to sixteen weights.  Instead the block copies, chunk by chunk, a run of every row into LDS with
+// whole-line loads (each row from the dword its run starts in, so every load is dword aligned whatever K is),
+// and a step reads four or five dwords of its row there and shifts the sixteen bytes into place.  Bytes past
+// the end of a row belong to the next row (or read as zero past the last one) and meet zero weights: the
+// row's last word is zero padded.  The words themselves stream from memory, eight steps ahead per wave, across
+// the chunks.
+// FIFTH: the sixteen bytes may start inside a dword and reach into a fifth one.
+template <int KB, bool SGN, bool FIFTH, int NW>
+__device__ __forceinline__ void words_page_steps(const __amdgpu_buffer_rsrc_t wrs, int row_off, int W,
+                                                 const __amdgpu_buffer_rsrc_t xrs, uint32_t x_row0, int x_rows, int K,
+                                                 uint8_t *lds, int tid, int wave, int g, e_v16i &acc)
+{
+    using WF = WordFields<KB, SGN>;
+    using WC = WordChunk<KB, NW>;
+    constexpr int F = WF::F, G = WF::G, SPW = WF::SPW;
+    constexpr int WSTEP = WC::WSTEP, XSTEP = WC::XSTEP, RS = WC::RS, PPR = WC::PPR, NPT = WC::NPT;
+    constexpr uint32_t NOWHERE = 0x7fff0000u;     // past every buffer: reads as zero
+    const int lane = tid & 63;
+    const int T = G == 1 ? (W + 1) / 2 : W * SPW;      // steps of the page
+    const int chunks = (T + WC::SC - 1) / WC::SC;      // steps past T read zero words
     const int group = G == 1 ? 0 : 2 * (wave % SPW) + g;
     const uint32_t w_end = (uint32_t)(row_off + 8 * W);
     uint32_t w_at = (uint32_t)(row_off + WSTEP * wave + (G == 1 ? 8 * g : -(8 / SPW) * (wave % SPW)));
-    uint32_t x_at = x_off + (uint32_t)(XSTEP * wave + (G == 1 ? F * g : 16 * g));     // of the next request
-    uint32_t x_use = x_at;                                                            // of the next step computed
 
-    uint2 Wd[PD];
-    e_v4i Xd[PD];
-    int Xe[PD];
-    auto request = [&](int slot) {
-        const bool in = w_at < w_end;
-        const auto wv = __builtin_amdgcn_raw_buffer_load_b64(wrs, in ? w_at : NOWHERE, 0, 0);
-        Wd[slot] = uint2{(uint32_t)wv[0], (uint32_t)wv[1]};
-        const uint32_t xo = in ? x_at & ~3u : NOWHERE;
-        const auto xv = __builtin_amdgcn_raw_buffer_load_b128(xrs, xo, 0, 0);
-        Xd[slot] = e_v4i{(int)xv[0], (int)xv[1], (int)xv[2], (int)xv[3]};
-        if constexpr (FIFTH) Xe[slot] = (int)__builtin_amdgcn_raw_buffer_load_b32(xrs, xo + 16, 0, 0);
-        else Xe[slot] = 0;
-        w_at += (uint32_t)(WSTEP * nw);
-        x_at += (uint32_t)(XSTEP * nw);
-    };
+    // ---- staging plan of this thread: piece q of the chunk is piece q % PPR of row q / PPR ----------------
+    uint32_t st_x[NPT];     // byte offset of the piece's row in the activations (NOWHERE past M)
+    int st_lds[NPT];        // where the piece goes in a buffer
 #pragma unroll
-    for (int d = 0; d < PD; ++d) {
+    for (int i = 0; i < NPT; ++i) {
+        const int q = tid + 64 * NW * i;
+        const int r = q / PPR, pi = q - r * PPR;
+        const bool real = r < 32;
+        st_x[i] = real && r < x_rows ? x_row0 + (uint32_t)(r * K) : NOWHERE;
+        st_lds[i] = real ? r * RS + 16 * pi : 32 * RS;
+    }
+    e_v4i stage[NPT];
+    auto stage_load = [&](int c) {
+        const uint32_t k_lo = (uint32_t)(c * WC::SPAN);
+#pragma unroll
+        for (int i = 0; i < NPT; ++i) {
+            const int q = tid + 64 * NW * i;
+            const int pi = q % PPR;
+            // the row's run starts in the dword that holds its byte k_lo
+            const uint32_t at = st_x[i] == NOWHERE ? NOWHERE : ((st_x[i] + k_lo) & ~3u) + (uint32_t)(16 * pi);
+            const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrs, at, 0, 0);
+            stage[i] = e_v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+        }
+    };
+    // the lane's own row: where its bytes are in a buffer
+    const int xr = lane & 31;
+    const uint32_t x_mine = xr < x_rows ? x_row0 + (uint32_t)(xr * K) : 0u;
+    uint32_t x_use = x_mine + (uint32_t)(XSTEP * wave + (G == 1 ? F * g : 16 * g));   // first byte of the next step
+
+    uint2 Wd[8];
+    auto request = [&](int slot) {
+        const auto wv = __builtin_amdgcn_raw_buffer_load_b64(wrs, w_at < w_end ? w_at : NOWHERE, 0, 0);
+        Wd[slot] = uint2{(uint32_t)wv[0], (uint32_t)wv[1]};
+        w_at += (uint32_t)(WSTEP * NW);
+    };
+
+    stage_load(0);
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
         request(d);
         __builtin_amdgcn_sched_barrier(0);     // oldest first, as the loop expects them to arrive
     }
-    for (int j0 = 0; j0 < rounds; j0 += PD) {
+    for (int c = 0; c < chunks; ++c) {
+        uint8_t *buf = lds + (c & 1) * WC::BUF;
+        // The buffer was last read two chunks ago, and every wave has passed the barrier of the chunk in
+        // between since: one barrier per chunk is enough.
 #pragma unroll
-        for (int d = 0; d < PD; ++d) {
-            const uint32_t sh = x_use & 3u;        // the step's first activation byte inside its dword
-            x_use += (uint32_t)(XSTEP * nw);
-            const e_v4i xa = Xd[d];
-            const e_v4i a = e_v4i{(int)__builtin_amdgcn_alignbyte((uint32_t)xa[1], (uint32_t)xa[0], sh),
-                                  (int)__builtin_amdgcn_alignbyte((uint32_t)xa[2], (uint32_t)xa[1], sh),
-                                  (int)__builtin_amdgcn_alignbyte((uint32_t)xa[3], (uint32_t)xa[2], sh),
-                                  (int)__builtin_amdgcn_alignbyte((uint32_t)Xe[d], (uint32_t)xa[3], sh)};
+        for (int i = 0; i < NPT; ++i) *reinterpret_cast<e_v4i *>(buf + st_lds[i]) = stage[i];
+        if (c + 1 < chunks) stage_load(c + 1);         // travels while this chunk is computed
+        words_lds_barrier();
+        const uint8_t *mine = buf + xr * RS;
+        const uint32_t run0 = (x_mine + (uint32_t)(c * WC::SPAN)) & ~3u;      // first byte of the row's run
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            const uint32_t pos = x_use - run0;
+            x_use += (uint32_t)(XSTEP * NW);
+            const uint32_t sh = pos & 3u;
+            const uint32_t *src = reinterpret_cast<const uint32_t *>(mine + (pos & ~3u));
+            const uint32_t x0 = src[0], x1 = src[1], x2 = src[2], x3 = src[3];
+            const uint32_t x4 = FIFTH ? src[4] : 0u;
+            const e_v4i a = e_v4i{(int)__builtin_amdgcn_alignbyte(x1, x0, sh), (int)__builtin_amdgcn_alignbyte(x2, x1, sh),
+                                  (int)__builtin_amdgcn_alignbyte(x3, x2, sh), (int)__builtin_amdgcn_alignbyte(x4, x3, sh)};
             const e_v4i b = WF::decode(Wd[d].x, Wd[d].y, group);
             // the slot's registers are free again: the new request lands in them
             __builtin_amdgcn_sched_barrier(0);
@@ -139,37 +210,39 @@ __device__ __forceinline__ void words_page_steps(const __amdgpu_buffer_rsrc_t wr
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    words_lds_barrier();      // the buffers are free for the next page or for the partial sums
 }
 
-template <int KB, bool SGN, int PD>
+template <int KB, bool SGN, int NW>
 __device__ __forceinline__ void words_page(const __amdgpu_buffer_rsrc_t wrs, int row_off, int W,
-                                           const __amdgpu_buffer_rsrc_t xrs, uint32_t x_off, int K, int wave, int nw,
-                                           int g, e_v16i &acc)
+                                           const __amdgpu_buffer_rsrc_t xrs, uint32_t x_row0, int x_rows, int K,
+                                           uint8_t *lds, int tid, int wave, int g, e_v16i &acc)
 {
     using WF = WordFields<KB, SGN>;
     // No fifth dword where a step has at most thirteen fields (up to three bytes are lost to the alignment),
     // nor where every step starts on a multiple of sixteen bytes of a row and the rows start on dwords.
     constexpr bool on16 = KB == 1 || KB == 2 || KB == 4;
     if constexpr (WF::NF <= 13) {
-        words_page_steps<KB, SGN, PD, false>(wrs, row_off, W, xrs, x_off, wave, nw, g, acc);
+        words_page_steps<KB, SGN, false, NW>(wrs, row_off, W, xrs, x_row0, x_rows, K, lds, tid, wave, g, acc);
     } else {
-        if (on16 && (K & 3) == 0) words_page_steps<KB, SGN, PD, false>(wrs, row_off, W, xrs, x_off, wave, nw, g, acc);
-        else words_page_steps<KB, SGN, PD, true>(wrs, row_off, W, xrs, x_off, wave, nw, g, acc);
+        if (on16 && (K & 3) == 0)
+            words_page_steps<KB, SGN, false, NW>(wrs, row_off, W, xrs, x_row0, x_rows, K, lds, tid, wave, g, acc);
+        else
+            words_page_steps<KB, SGN, true, NW>(wrs, row_off, W, xrs, x_row0, x_rows, K, lds, tid, wave, g, acc);
     }
 }
 
 // HB: bits of the higher-bit fields.  MODE 0: part-bit; 1: unsigned lower-bit fields of LB = l bits; 2: signed
 // lower-bit fields of LB = l + 1 bits (compensated format, Sec. 3.3.3).  WH, WL: words per row of the pages.
-template <int HB, int LB, int MODE>
-__global__ void __launch_bounds__(1024) k_nested_gemm_words(const GemmParams p, int WH, int WL)
+// NW: waves per block (4, or 8 where a layer has few blocks).
+template <int HB, int LB, int MODE, int NW>
+__global__ void __launch_bounds__(64 * NW) k_nested_gemm_words(const GemmParams p, int WH, int WL)
 {
     constexpr int EPI = EPI_ANY;
-    constexpr int PD = 6;
-    extern __shared__ int red[];          // [waves - 1][16][64]
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];   // chunk buffers, then the partial sums
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nw = (int)(blockDim.x >> 6);          // 4 or 16 waves share the steps of a page
     const int g = lane >> 5;
     const int nb = blockIdx.x;
     const int64_t m0 = (int64_t)blockIdx.y * 32;
@@ -182,8 +255,8 @@ __global__ void __launch_bounds__(1024) k_nested_gemm_words(const GemmParams p, 
     // what that dword holds behind it stands at k >= K of the last row and meets zero weights.
     const __amdgpu_buffer_rsrc_t xrs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.x), 0, (int)((p.M * p.K + 3) & ~int64_t(3)), 0x00020000);
-    const int64_t m = m0 + (lane & 31);
-    const uint32_t x_off = m < p.M ? (uint32_t)(m * p.K) : 0x7fff0000u;
+    const uint32_t x_row0 = (uint32_t)(m0 * p.K);
+    const int x_rows = p.M - m0 < 32 ? (int)(p.M - m0) : 32;
 
     e_v16i acc;
 #pragma unroll
@@ -192,7 +265,7 @@ __global__ void __launch_bounds__(1024) k_nested_gemm_words(const GemmParams p, 
         const uint2 *rows_h = reinterpret_cast<const uint2 *>(p.ph) + (int64_t)nb * 32 * WH;
         const __amdgpu_buffer_rsrc_t wrs =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint2 *>(rows_h), 0, cols * WH * 8, 0x00020000);
-        words_page<HB, true, PD>(wrs, cn * WH * 8, WH, xrs, x_off, p.K, wave, nw, g, acc);
+        words_page<HB, true, NW>(wrs, cn * WH * 8, WH, xrs, x_row0, x_rows, p.K, lds, tid, wave, g, acc);
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] >>= 8 - HB;
@@ -204,19 +277,21 @@ __global__ void __launch_bounds__(1024) k_nested_gemm_words(const GemmParams p, 
         const uint2 *rows_l = reinterpret_cast<const uint2 *>(p.pl) + (int64_t)nb * 32 * WL;
         const __amdgpu_buffer_rsrc_t wrs =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint2 *>(rows_l), 0, cols * WL * 8, 0x00020000);
-        words_page<LB, MODE == 2, PD>(wrs, cn * WL * 8, WL, xrs, x_off, p.K, wave, nw, g, acl);
+        words_page<LB, MODE == 2, NW>(wrs, cn * WL * 8, WL, xrs, x_row0, x_rows, p.K, lds, tid, wave, g, acl);
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = acc[r] * (1 << L) + (acl[r] >> (MODE == 2 ? 8 - LB : 0));
     }
 
-    // ---- add the four partial sums ---------------------------------------------------------------
+    // ---- add the partial sums of the waves ----------------------------------------------------------
+    int *red = reinterpret_cast<int *>(lds);          // [NW - 1][16][64]
     if (wave > 0) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) red[((wave - 1) * 16 + r) * 64 + lane] = acc[r];
     }
     __syncthreads();
     if (wave > 0) return;
-    for (int w = 0; w < nw - 1; ++w)
+#pragma unroll
+    for (int w = 0; w < NW - 1; ++w)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] += red[(w * 16 + r) * 64 + lane];
 

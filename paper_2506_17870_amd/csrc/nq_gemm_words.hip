@@ -4,15 +4,35 @@
 
 namespace nq {
 
+template <typename K>
+static void words_grant_lds(K kernel, size_t lds)
+{
+    static bool granted = false;   // one per kernel instantiation
+    if (!granted && lds > 64 * 1024) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds);
+        granted = true;
+    }
+}
+
 template <int HB, int LB, int MODE>
 static void launch_words(const GemmParams &p, int WH, int WL, hipStream_t st, void *ev_start, void *ev_stop)
 {
-    // Four waves per block.  (Sixteen, to have more of the pages in flight when a layer has few blocks, measured
-    // slower: the activation fetches of a step, one cache line per lane, are what a compute unit runs out of.)
+    // Four waves per block, two or more blocks per compute unit; where a layer with long rows has fewer blocks
+    // than that, eight waves per block share a page's steps.
     const dim3 grid((unsigned)p.NB, (unsigned)((p.M + 31) / 32));
-    const int waves = 4;
-    launch_timed(k_nested_gemm_words<HB, LB, MODE>, grid, dim3(64 * waves), (size_t)(waves - 1) * 4096, st, ev_start,
-                 ev_stop, p, WH, WL);
+    const bool wide = (int64_t)grid.x * grid.y < 512 && WH >= 128;
+    if (wide) {
+        auto k = k_nested_gemm_words<HB, LB, MODE, 8>;
+        constexpr size_t lds = words_lds_bytes<HB, LB, 8>();
+        words_grant_lds(k, lds);
+        launch_timed(k, grid, dim3(512), lds, st, ev_start, ev_stop, p, WH, WL);
+    } else {
+        auto k = k_nested_gemm_words<HB, LB, MODE, 4>;
+        constexpr size_t lds = words_lds_bytes<HB, LB, 4>();
+        words_grant_lds(k, lds);
+        launch_timed(k, grid, dim3(256), lds, st, ev_start, ev_stop, p, WH, WL);
+    }
 }
 
 template <int H, int L>
