@@ -205,14 +205,16 @@ __device__ __forceinline__ void epi_row16(const GemmParams &p, const e_v16i acc,
         e_v4i q;
         if (p.relu && p.inv_out_scale > 0.0f) {
             // With a ReLU and a positive output scale, clamp(rint(max(y, 0) * inv), -128, 127) is
-            // med3(rint(y * inv), 0, 127): rounding and a positive factor keep the order and map 0 to 0, so
-            // the ReLU can be taken after them, where it is the lower end of one three-operand clamp.
+            // rint(med3(y * inv, 0, 127)): rounding and a positive factor keep the order and map 0 to 0, so
+            // the ReLU can be taken after the scaling, where it is the lower end of one three-operand clamp,
+            // and rounding commutes with a clamp to whole numbers.  The rounding itself (to nearest, ties to
+            // even) is done by the float -> unsigned byte pack.
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 unsigned d = 0;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float v = __builtin_amdgcn_fmed3f(rintf(y[4 * j + i] * p.inv_out_scale), 0.0f, 127.0f);
+                    const float v = __builtin_amdgcn_fmed3f(y[4 * j + i] * p.inv_out_scale, 0.0f, 127.0f);
                     d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
                 }
                 q[j] = (int)d;
