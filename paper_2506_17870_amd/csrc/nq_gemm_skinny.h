@@ -3,8 +3,10 @@
 // reads the higher-bit page only; Eq. 4 / Eq. 8 for the two modes).
 //
 // One block per 32-column tile of the weights, so that a layer with N columns spreads over N / 32
-// blocks however few rows there are.  The four waves of a block split the reduction: wave w takes
-// the K steps w, w + 4, ..., which together are one contiguous stream of the tile's packed dwords.
+// blocks however few rows there are.  The NWS waves of a block (four, or eight where a layer has no
+// more blocks than there are compute units: twice the packed bytes in flight per unit) split the
+// reduction: wave w takes the K steps w, w + NWS, ..., which together are one contiguous stream of
+// the tile's packed dwords.
 // Every wave keeps its own accumulators; at the end they are added up through LDS (integer sums, so
 // the order does not matter) and wave 0 runs the epilogue.  Activations are small and shared by all
 // blocks (they stay in L2): a lane loads its 16-byte fragments straight from memory, rows past M
@@ -23,9 +25,9 @@ typedef int k_v4i __attribute__((ext_vector_type(4)));
 typedef int k_v16i __attribute__((ext_vector_type(16)));
 
 
-// TMS: 32-row tiles (1: M <= 32, 2: M <= 64).
-template <int H, int L, int FULL, int EPI, int TMS>
-__global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams p)
+// TMS: 32-row tiles (1: M <= 32, 2: M <= 64).  NWS: waves per block (4 or 8).
+template <int H, int L, int FULL, int EPI, int TMS, int NWS>
+__global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skinny(const GemmParams p)
 {
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
@@ -33,7 +35,7 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams 
     // K steps in flight per wave; three where four would not fit the register file
     constexpr int SK_PD = (TMS == 2 && H + LP::DW > 8) ? 3 : 4;
 
-    __shared__ int red[3][TMS][16][64];
+    __shared__ int red[NWS - 1][TMS][16][64];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -80,10 +82,10 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams 
         for (int r = 0; r < 16; ++r) acc[i][r] = 0;
 
 #pragma unroll
-    for (int d = 0; d < SK_PD; ++d) request(d, wave + 4 * d);
+    for (int d = 0; d < SK_PD; ++d) request(d, wave + NWS * d);
 
-    // wave w: K steps w + 4*j; all waves run the same number of rounds (the extra ones add zeros)
-    const int rounds = (p.KB + 3) / 4;
+    // wave w: K steps w + NWS*j; all waves run the same number of rounds (the extra ones add zeros)
+    const int rounds = (p.KB + NWS - 1) / NWS;
     for (int j0 = 0; j0 < rounds; j0 += SK_PD) {
 #pragma unroll
         for (int d = 0; d < SK_PD; ++d) {
@@ -95,7 +97,7 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams 
             for (int i = 0; i < TMS; ++i)
 #pragma unroll
                 for (int hf = 0; hf < 2; ++hf) a[i][hf] = A[d][i][hf];
-            request(d, wave + 4 * (j0 + d + SK_PD));
+            request(d, wave + NWS * (j0 + d + SK_PD));
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const k_v4i b = k_v4i{(int)D[4 * hf], (int)D[4 * hf + 1], (int)D[4 * hf + 2], (int)D[4 * hf + 3]};
@@ -105,7 +107,7 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams 
         }
     }
 
-    // ---- add the four partial sums ---------------------------------------------------------------
+    // ---- add the partial sums of the waves ---------------------------------------------------------------
     if (wave > 0) {
 #pragma unroll
         for (int i = 0; i < TMS; ++i)
@@ -115,7 +117,7 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams 
     __syncthreads();
     if (wave > 0) return;
 #pragma unroll
-    for (int w = 0; w < 3; ++w)
+    for (int w = 0; w < NWS - 1; ++w)
 #pragma unroll
         for (int i = 0; i < TMS; ++i)
 #pragma unroll
@@ -137,14 +139,22 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny(const GemmParams 
 template <int H, int L>
 void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop)
 {
-    const dim3 grid((unsigned)p.NB), block(256);
+    const dim3 grid((unsigned)p.NB);
     const int mode = epi_mode(p);
-#define NQ_SK_LAUNCH(FULLV, EPIV)                                                                           \
-    do {                                                                                                    \
-        if (p.M <= 32)                                                                                      \
-            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, 1>, grid, block, 0, st, ev_start, ev_stop, p); \
-        else                                                                                                \
-            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, 2>, grid, block, 0, st, ev_start, ev_stop, p); \
+    // eight waves where every compute unit gets at most one block, the reduction is long enough to share and
+    // there is one row tile (with two, measured slower: 25.8 us against 23.1 us at 64 x 8192 -> 8192)
+    const bool wide = p.NB <= 256 && p.KB >= 32 && p.M <= 32;
+#define NQ_SK_LAUNCH_W(FULLV, EPIV, TMSV)                                                                          \
+    do {                                                                                                          \
+        if (wide)                                                                                                 \
+            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, TMSV, 8>, grid, dim3(512), 0, st, ev_start, ev_stop, p); \
+        else                                                                                                      \
+            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, TMSV, 4>, grid, dim3(256), 0, st, ev_start, ev_stop, p); \
+    } while (0)
+#define NQ_SK_LAUNCH(FULLV, EPIV)                                   \
+    do {                                                            \
+        if (p.M <= 32) NQ_SK_LAUNCH_W(FULLV, EPIV, 1);              \
+        else NQ_SK_LAUNCH_W(FULLV, EPIV, 2);                        \
     } while (0)
 #define NQ_SK_MODES(FULLV)                                       \
     do {                                                         \

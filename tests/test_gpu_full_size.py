@@ -112,3 +112,17 @@ def test_quantiser_full_size(nq):
     torch.cuda.synchronize()
     assert np.array_equal(host(d_s).view(np.uint32), s_ref.view(np.uint32))
     assert np.array_equal(host(ph), ph_ref) and np.array_equal(host(pl), pl_ref)
+
+
+@pytest.mark.parametrize("M,l", [(16, 2), (64, 4), (33, 3)])
+def test_weight_bound_linear_long_rows(nq, M, l):
+    # few rows against a long reduction (the weight-bound stand-in of the linear configuration: the packed
+    # pages are the traffic); N small enough that every block has a compute unit to itself
+    N, K = 2048, 8192
+    w_int, scale = inputs.weights(N, K, 0.02, 8, seed=50 + l)
+    case = Case(nq, w_int, scale, 8, l)
+    x = inputs.uniform_activations((M, K), seed=51 + l)
+    bias = inputs.small_floats(N, 0.05, seed=l)
+    for full in (True, False):
+        run_gemm_both(nq, case, x, full, s_a=0.02, bias=bias)
+    run_gemm_both(nq, case, x, True, s_a=0.02, bias=bias, relu=True, out_int8=True, inv_s_out=4.0)
