@@ -298,12 +298,40 @@ __global__ void __launch_bounds__(256) k_quantize_codes(const float *__restrict_
     }
 }
 
-// Dense-tile unpack: pages -> int8 parts.
+// Dense-tile unpack: pages -> int8 parts.  A lane holds 32 consecutive elements of one row as eight dwords;
+// the fields are moved to the bottom of their bytes and sign extended four bytes at a time, and leave as two
+// 16-byte stores where the row allows (vec_ok: K a multiple of 16, 16-byte aligned outputs), else byte by byte.
+__device__ __forceinline__ void unpack_store32(int8_t *__restrict__ dst, int64_t c0, int64_t K, const uint32_t (&V)[8],
+                                               int vec_ok)
+{
+    if (vec_ok && c0 + 32 <= K) {
+        uint4 *d4 = reinterpret_cast<uint4 *>(dst + c0);
+        d4[0] = make_uint4(V[0], V[1], V[2], V[3]);
+        d4[1] = make_uint4(V[4], V[5], V[6], V[7]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            for (int bb = 0; bb < 4; ++bb) {
+                const int64_t c = c0 + 4 * j + bb;
+                if (c < K) dst[c] = (int8_t)(V[j] >> (8 * bb));
+            }
+    }
+}
+
+// Bytes that hold a field of `bits` bits at their bottom (zeros above): the same bytes sign extended.
+template <int BITS>
+__device__ __forceinline__ uint32_t sext_bytes(uint32_t t)
+{
+    constexpr uint32_t above = (0xFFu << BITS) & 0xFFu;              // the bits of a byte above the field
+    const uint32_t sign = (t >> (BITS - 1)) & 0x01010101u;           // 1 in every byte whose field is negative
+    return t | sign * above;                                          // no carries: 1 * above < 256
+}
+
 template <int H, int L>
 __global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict__ ph,
                                                        const uint32_t *__restrict__ pl, int64_t N, int64_t K,
                                                        int64_t KB, int64_t tiles, int8_t *__restrict__ high,
-                                                       int8_t *__restrict__ low, int sgn)
+                                                       int8_t *__restrict__ low, int sgn, int vec_ok)
 {
     constexpr int S = 8 - H;
     const int lane = threadIdx.x & 63;
@@ -315,44 +343,36 @@ __global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict
     const int64_t c0 = kb * 64 + 32 * g;
     if (n >= N) return;
     if (ph && high) {
-        uint32_t P[H], D[8];
+        uint32_t P[H], D[8], V[8];
 #pragma unroll
         for (int i = 0; i < H; ++i) P[i] = ph[tile * (H * 64) + i * 64 + lane];
         HighCodec<H>::decode(P, D);
+        // a decoded byte is w_high * 2^S: down by S, the neighbour's bits masked off, sign extended from h bits
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            for (int bb = 0; bb < 4; ++bb) {
-                const int64_t c = c0 + 4 * j + bb;
-                if (c < K) high[n * K + c] = (int8_t)((int8_t)(D[j] >> (8 * bb)) >> S);
-            }
+        for (int j = 0; j < 8; ++j) V[j] = sext_bytes<H>((D[j] >> S) & rep4(0xFFu >> S));
+        unpack_store32(high + n * K, c0, K, V, vec_ok);
     }
     if (pl && low && sgn) {
-        uint32_t Q[L + 1], D[8];
+        uint32_t Q[L + 1], D[8], V[8];
 #pragma unroll
         for (int i = 0; i < L + 1; ++i) Q[i] = pl[tile * ((L + 1) * 64) + i * 64 + lane];
 #pragma unroll
         for (int j = 0; j < 8; ++j) D[j] = 0;
         LowCodec<L + 1, S + 1>::decode_or(Q, D);
+        // (l+1)-bit two's complement fields at bits [S-L, S+1) of their bytes
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            for (int bb = 0; bb < 4; ++bb) {
-                const int64_t c = c0 + 4 * j + bb;
-                const int f = (int)(((D[j] >> (8 * bb)) & 0xFFu) >> (S - L)) & ((2 << L) - 1);
-                if (c < K) low[n * K + c] = (int8_t)((f >> L) ? f - (2 << L) : f);   // (l+1)-bit two's complement
-            }
+        for (int j = 0; j < 8; ++j) V[j] = sext_bytes<L + 1>((D[j] >> (S - L)) & rep4((2u << L) - 1u));
+        unpack_store32(low + n * K, c0, K, V, vec_ok);
     } else if (pl && low) {
-        uint32_t Q[L], D[8];
+        uint32_t Q[L], D[8], V[8];
 #pragma unroll
         for (int i = 0; i < L; ++i) Q[i] = pl[tile * (L * 64) + i * 64 + lane];
 #pragma unroll
         for (int j = 0; j < 8; ++j) D[j] = 0;
         LowCodec<L, S>::decode_or(Q, D);
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            for (int bb = 0; bb < 4; ++bb) {
-                const int64_t c = c0 + 4 * j + bb;
-                if (c < K) low[n * K + c] = (int8_t)(((D[j] >> (8 * bb)) & 0xFFu) >> (S - L));
-            }
+        for (int j = 0; j < 8; ++j) V[j] = (D[j] >> (S - L)) & rep4((1u << L) - 1u);
+        unpack_store32(low + n * K, c0, K, V, vec_ok);
     }
 }
 
@@ -361,20 +381,45 @@ __global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict
 // One thread per word.  part 0: fields are (w >> l) from w_int; 1: the low l bits of w_int;
 // 2: the given values as they are; 3 / 4: the round-to-nearest w_high of w_int / its signed residual.
 // ---------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_pack_paper(const int8_t *__restrict__ v, int64_t N, int64_t K, int k,
-                                                     int part, int l, int up, int64_t wpr,
-                                                     uint64_t *__restrict__ out)
+template <int KF>     // bits of a field
+__global__ void __launch_bounds__(256) k_pack_paper(const int8_t *__restrict__ v, int64_t N, int64_t K,
+                                                     int part, int l, int up, int64_t wpr, int64_t bpr,
+                                                     uint64_t *__restrict__ out, int vec_ok)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= N * wpr) return;
-    const int64_t n = idx / wpr, wd = idx % wpr;
-    const int per = 64 / k;
+    constexpr int k = KF;
+    // A block packs 256 consecutive words of one row.  Their 256 * (64 / k) source bytes are brought into LDS
+    // with 16-byte loads (from the 16-byte boundary below the first one) and each thread then collects the
+    // bytes of its word there; reading them straight from memory, a wave's lanes are 64 / k bytes apart.
+    // Byte i of the segment is at i + 4 * (i / 64): a wave's lanes, 64 / k bytes apart, then fall on different
+    // banks whatever k is.
+    __shared__ __attribute__((aligned(16))) int8_t seg[(256 * 64 + 16) / 64 * 68 + 68];
+    auto at_seg = [](int64_t i) { return i + 4 * (i >> 6); };
+    const int64_t n = blockIdx.x / bpr;
+    const int64_t wd0 = (blockIdx.x - n * bpr) * 256;
+    constexpr int per = 64 / k;
+    const int64_t e0 = wd0 * per;                                     // first element of the block
+    const int64_t e1 = e0 + 256 * per < K ? e0 + 256 * per : K;       // one past its last
+    const int8_t *row = v + n * K;
+    const int64_t a0 = vec_ok ? (e0 & ~int64_t(15)) : e0;
+    if (vec_ok) {
+        for (int64_t at = a0 + 16 * threadIdx.x; at < e1; at += 16 * 256) {     // K % 16 == 0: whole pieces
+            const uint4 piece = *reinterpret_cast<const uint4 *>(row + at);
+            uint32_t *dst = reinterpret_cast<uint32_t *>(seg + at_seg(at - a0));   // a piece never straddles 64
+            dst[0] = piece.x; dst[1] = piece.y; dst[2] = piece.z; dst[3] = piece.w;
+        }
+    } else {
+        for (int64_t at = a0 + threadIdx.x; at < e1; at += 256) seg[at_seg(at - a0)] = row[at];
+    }
+    __syncthreads();
+    const int64_t wd = wd0 + threadIdx.x;
+    if (wd >= wpr) return;
     const uint64_t mask = (1ull << k) - 1ull;
     uint64_t word = 0;
+#pragma unroll
     for (int j = 0; j < per; ++j) {
         const int64_t c = wd * per + j;
-        if (c >= K) break;
-        int val = v[n * K + c];
+        if (c >= K) continue;
+        int val = seg[at_seg(c - a0)];
         if (part == 0) val = ((int8_t)((uint8_t)val << up)) >> (l + up);
         else if (part == 1) val = val & ((1 << l) - 1);
         else if (part == 3 || part == 4) {              // compensated split of w_int: its high / its low part
@@ -384,21 +429,40 @@ __global__ void __launch_bounds__(256) k_pack_paper(const int8_t *__restrict__ v
         }
         word |= ((uint64_t)(int64_t)val & mask) << (j * k);
     }
-    out[idx] = word;
+    out[n * wpr + wd] = word;
 }
 
+// One thread per 16 consecutive elements of a row: it walks through the words that hold them.
 __global__ void __launch_bounds__(256) k_unpack_paper(const uint64_t *__restrict__ in, int64_t N, int64_t K,
-                                                       int k, int is_signed, int64_t wpr,
-                                                       int8_t *__restrict__ v)
+                                                       int k, int is_signed, int64_t wpr, int64_t cpr,
+                                                       int8_t *__restrict__ v, int vec_ok)
 {
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= N * K) return;
-    const int64_t n = idx / K, c = idx % K;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= N * cpr) return;
+    const int64_t n = t / cpr;
+    const int c0 = (int)(t - n * cpr) * 16;
     const int per = 64 / k;
-    const uint64_t word = in[n * wpr + c / per];
-    int field = (int)((word >> ((c % per) * k)) & ((1ull << k) - 1ull));
-    if (is_signed && (field >> (k - 1))) field -= (1 << k);
-    v[idx] = (int8_t)field;
+    const uint32_t mask = (1u << k) - 1u, sign = 1u << (k - 1);
+    const uint64_t *row = in + n * wpr;
+    int wi = c0 / per, f = c0 - wi * per;
+    uint64_t word = row[wi] >> (f * k);
+    uint32_t V[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if (c0 + i < K) {
+            uint32_t field = (uint32_t)word & mask;
+            if (is_signed && (field & sign)) field |= ~mask;          // two's complement of k bits
+            V[i >> 2] |= (field & 0xFFu) << (8 * (i & 3));
+            word >>= k;
+            if (++f == per && c0 + i + 1 < K) { f = 0; word = row[++wi]; }
+        }
+    }
+    int8_t *dst = v + n * K + c0;
+    if (vec_ok && c0 + 16 <= K) {
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(V[0], V[1], V[2], V[3]);
+    } else {
+        for (int i = 0; i < 16 && c0 + i < K; ++i) dst[i] = (int8_t)(V[i >> 2] >> (8 * (i & 3)));
+    }
 }
 
 template <int H, int L>
@@ -427,8 +491,9 @@ static void launch_unpack_dense(int sgn, const void *ph, const void *pl, int64_t
 {
     const int64_t NB = ceil_div(N, 32), KB = ceil_div(K, 64), tiles = NB * KB;
     if (tiles == 0) return;
+    const int vec_ok = (K % 16 == 0) && (high == nullptr || aligned16(high)) && (low == nullptr || aligned16(low));
     hipLaunchKernelGGL((k_unpack_dense<H, L>), dim3((unsigned)ceil_div(tiles, 4)), dim3(256), 0, st,
-                       (const uint32_t *)ph, (const uint32_t *)pl, N, K, KB, tiles, high, low, sgn);
+                       (const uint32_t *)ph, (const uint32_t *)pl, N, K, KB, tiles, high, low, sgn, vec_ok);
 }
 
 static nq_status check_pages(const nq_cfg *cfg, const void *ph, const void *pl)
@@ -519,6 +584,20 @@ extern "C" nq_status nq_decompose(const int8_t *d_w_int, int64_t N, int64_t K, c
     return launch_status();
 }
 
+static void launch_pack_paper(int k, dim3 grid, hipStream_t s, const int8_t *v, int64_t N, int64_t K, int part, int l,
+                              int up, int64_t wpr, int64_t bpr, uint64_t *out, int vec_ok)
+{
+    switch (k) {
+#define NQ_PP_CASE(KV)                                                                                           \
+    case KV:                                                                                                     \
+        hipLaunchKernelGGL(k_pack_paper<KV>, grid, dim3(256), 0, s, v, N, K, part, l, up, wpr, bpr, out, vec_ok); \
+        break;
+        NQ_PP_CASE(1) NQ_PP_CASE(2) NQ_PP_CASE(3) NQ_PP_CASE(4) NQ_PP_CASE(5) NQ_PP_CASE(6) NQ_PP_CASE(7)
+#undef NQ_PP_CASE
+    default: break;
+    }
+}
+
 static nq_status pack_any(int src, const int8_t *a, const int8_t *b, int64_t N, int64_t K, const nq_cfg *cfg,
                           void *ph, void *pl, void *stream)
 {
@@ -534,15 +613,19 @@ static nq_status pack_any(int src, const int8_t *a, const int8_t *b, int64_t N, 
         NQ_DISPATCH_HL(h, l, launch_pack_dense, src, sgn, a, b, N, K, ph, pl, s);
     } else {
         const int up = 8 - cfg->n_bits;
+        if (N * ceil_div(ceil_div(K, 64 / (h < lf ? h : lf)), 256) > 0x7fffffffLL) return NQ_ERR_SHAPE;   // grid
         if (ph) {
             const int64_t wpr = ceil_div(K, 64 / h);
-            hipLaunchKernelGGL(k_pack_paper, dim3((unsigned)ceil_div(N * wpr, 256)), dim3(256), 0, s, a, N, K, h,
-                               src == 0 ? (sgn ? 3 : 0) : 2, l, up, wpr, (uint64_t *)ph);
+            const int64_t bpr = ceil_div(wpr, 256);
+            launch_pack_paper(h, dim3((unsigned)(N * bpr)), s, a, N, K, src == 0 ? (sgn ? 3 : 0) : 2, l, up, wpr, bpr,
+                              (uint64_t *)ph, (int)((K % 16 == 0) && aligned16(a)));
         }
         if (pl) {
             const int64_t wpr = ceil_div(K, 64 / lf);
-            hipLaunchKernelGGL(k_pack_paper, dim3((unsigned)ceil_div(N * wpr, 256)), dim3(256), 0, s,
-                               src == 0 ? a : b, N, K, lf, src == 0 ? (sgn ? 4 : 1) : 2, l, up, wpr, (uint64_t *)pl);
+            const int64_t bpr = ceil_div(wpr, 256);
+            const int8_t *from = src == 0 ? a : b;
+            launch_pack_paper(lf, dim3((unsigned)(N * bpr)), s, from, N, K, src == 0 ? (sgn ? 4 : 1) : 2, l, up, wpr,
+                              bpr, (uint64_t *)pl, (int)((K % 16 == 0) && aligned16(from)));
         }
     }
     return launch_status();
@@ -630,13 +713,14 @@ extern "C" nq_status nq_unpack(const void *d_packed_high, const void *d_packed_l
     if (cfg->layout == NQ_LAYOUT_DENSE) {
         NQ_DISPATCH_HL(h, l, launch_unpack_dense, sgn, d_packed_high, d_packed_low, N, K, d_high, d_low, s);
     } else {
-        const dim3 grid((unsigned)ceil_div(N * K, 256)), block(256);
+        const int64_t cpr = ceil_div(K, 16);                      // 16-element pieces of a row, one thread each
+        const dim3 grid((unsigned)ceil_div(N * cpr, 256)), block(256);
         if (d_high)
             hipLaunchKernelGGL(k_unpack_paper, grid, block, 0, s, (const uint64_t *)d_packed_high, N, K, h, 1,
-                               ceil_div(K, 64 / h), d_high);
+                               ceil_div(K, 64 / h), cpr, d_high, (int)((K % 16 == 0) && aligned16(d_high)));
         if (d_low)
             hipLaunchKernelGGL(k_unpack_paper, grid, block, 0, s, (const uint64_t *)d_packed_low, N, K, lf, sgn,
-                               ceil_div(K, 64 / lf), d_low);
+                               ceil_div(K, 64 / lf), cpr, d_low, (int)((K % 16 == 0) && aligned16(d_low)));
     }
     return launch_status();
 }
