@@ -5,7 +5,52 @@
 
 namespace nq {
 
-// One thread per four channels of one output pixel.
+// One thread per sixteen channels of one output pixel (C a multiple of 16, 16-byte aligned tensors): 16-byte
+// loads and stores; the maximum is taken on pairs of bytes moved to the top of 16-bit halves, where the packed
+// 16-bit maximum orders them like the signed bytes they are.  grid.x covers one output row (Wo * C / 16
+// threads), grid.y the output rows, grid.z the images (strided when there are more than the grid holds).
+typedef short p_v2s __attribute__((ext_vector_type(2)));
+
+__global__ void __launch_bounds__(256) k_maxpool_i8_v16(const int8_t *__restrict__ x, int64_t B, int H, int W, int C16,
+                                                         int Ho, int Wo, int ksize, int stride, int pad,
+                                                         int8_t *__restrict__ y)
+{
+    const unsigned ix = blockIdx.x * 256u + threadIdx.x;
+    if (ix >= (unsigned)(Wo * C16)) return;
+    const int ow = (int)(ix / (unsigned)C16), c16 = (int)(ix - (unsigned)ow * (unsigned)C16);
+    const int oh = blockIdx.y;
+    const uint4 *x4 = reinterpret_cast<const uint4 *>(x);
+    uint4 *y4 = reinterpret_cast<uint4 *>(y);
+    for (int64_t b = blockIdx.z; b < B; b += gridDim.z) {
+        uint32_t even[4], odd[4];            // bytes 0, 2 and bytes 1, 3 of each dword, as value * 256 in 16 bits
+#pragma unroll
+        for (int i = 0; i < 4; ++i) even[i] = odd[i] = 0x80008000u;       // -128
+        for (int kh = 0; kh < ksize; ++kh) {
+            const int ih = oh * stride - pad + kh;
+            if ((unsigned)ih >= (unsigned)H) continue;
+            for (int kw = 0; kw < ksize; ++kw) {
+                const int iw = ow * stride - pad + kw;
+                if ((unsigned)iw >= (unsigned)W) continue;
+                const uint4 v = x4[((b * H + ih) * W + iw) * C16 + c16];
+                const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t e = (d[i] << 8) & 0xFF00FF00u, o = d[i] & 0xFF00FF00u;
+                    const p_v2s me = __builtin_elementwise_max(__builtin_bit_cast(p_v2s, even[i]), __builtin_bit_cast(p_v2s, e));
+                    const p_v2s mo = __builtin_elementwise_max(__builtin_bit_cast(p_v2s, odd[i]), __builtin_bit_cast(p_v2s, o));
+                    even[i] = __builtin_bit_cast(uint32_t, me);
+                    odd[i] = __builtin_bit_cast(uint32_t, mo);
+                }
+            }
+        }
+        uint32_t r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = (odd[i] & 0xFF00FF00u) | ((even[i] >> 8) & 0x00FF00FFu);
+        y4[((b * Ho + oh) * Wo + ow) * C16 + c16] = make_uint4(r[0], r[1], r[2], r[3]);
+    }
+}
+
+// One thread per channel of one output pixel (any C, any alignment).
 __global__ void __launch_bounds__(256) k_maxpool_i8(const int8_t *__restrict__ x, int64_t total, int H, int W, int C,
                                                      int Ho, int Wo, int ksize, int stride, int pad,
                                                      int8_t *__restrict__ y)
@@ -59,6 +104,12 @@ extern "C" nq_status nq_maxpool_i8(const int8_t *d_x, int64_t B, int64_t H, int6
     const int64_t total = B * Ho * Wo * C;
     if (total == 0) return NQ_OK;
     if (!d_x || !d_y) return NQ_ERR_INVALID_ARG;
+    if (C % 16 == 0 && aligned16(d_x) && aligned16(d_y) && Wo * (C / 16) < 0x7fffffffLL && Ho <= 65535) {
+        const dim3 grid((unsigned)ceil_div(Wo * (C / 16), 256), (unsigned)Ho, (unsigned)(B < 65535 ? B : 65535));
+        hipLaunchKernelGGL(k_maxpool_i8_v16, grid, dim3(256), 0, (hipStream_t)stream, d_x, B, (int)H, (int)W,
+                           (int)(C / 16), (int)Ho, (int)Wo, ksize, stride, pad, d_y);
+        return launch_status();
+    }
     if (ceil_div(total, 256) > 0x7fffffffLL) return NQ_ERR_SHAPE;
     hipLaunchKernelGGL(k_maxpool_i8, dim3((unsigned)ceil_div(total, 256)), dim3(256), 0, (hipStream_t)stream, d_x,
                        total, (int)H, (int)W, (int)C, (int)Ho, (int)Wo, ksize, stride, pad, d_y);

@@ -188,6 +188,18 @@ def test_glue_kernels(nq, oracle):
     y = torch.empty((3, 9, 8, 64), dtype=torch.int8, device="cuda")
     nq.nq_maxpool_i8(dev(x), 3, 17, 15, 64, 3, 2, 1, y)
     assert np.array_equal(host(y), oracle.maxpool(x, 3, 2, 1))
+    # both max-pool kernels (16 channels per thread; one channel per thread for any C), windows that hang over
+    # every border, all-minimum inputs
+    for (B, H, W, C, k, s_, p_) in [(2, 9, 11, 48, 3, 2, 1), (2, 9, 11, 20, 3, 2, 1), (1, 5, 5, 16, 2, 2, 0),
+                                    (3, 8, 6, 32, 3, 1, 1), (1, 4, 4, 16, 5, 3, 2), (2, 7, 7, 10, 2, 1, 0)]:
+        for mode in ("uniform", "min"):
+            x = inputs.uniform_activations((B, H, W, C), seed=B + C)
+            if mode == "min":
+                x[:] = -128
+            Ho, Wo = (H + 2 * p_ - k) // s_ + 1, (W + 2 * p_ - k) // s_ + 1
+            y = torch.full((B, Ho, Wo, C), 77, dtype=torch.int8, device="cuda")
+            nq.nq_maxpool_i8(dev(x), B, H, W, C, k, s_, p_, y)
+            assert np.array_equal(host(y), oracle.maxpool(x, k, s_, p_)), (B, H, W, C, k, s_, p_, mode)
     x = inputs.uniform_activations((5, 7, 7, 200), seed=6)
     y = torch.empty((5, 200), dtype=torch.int8, device="cuda")
     nq.nq_avgpool_i8(dev(x), 5, 49, 200, 0.05, 11.0, y)
