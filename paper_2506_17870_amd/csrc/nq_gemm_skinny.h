@@ -144,17 +144,14 @@ void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, v
     // eight waves where every compute unit gets at most one block, the reduction is long enough to share and
     // there is one row tile (with two, measured slower: 25.8 us against 23.1 us at 64 x 8192 -> 8192)
     const bool wide = p.NB <= 256 && p.KB >= 32 && p.M <= 32;
-#define NQ_SK_LAUNCH_W(FULLV, EPIV, TMSV)                                                                          \
+#define NQ_SK_LAUNCH(FULLV, EPIV)                                                                                 \
     do {                                                                                                          \
         if (wide)                                                                                                 \
-            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, TMSV, 8>, grid, dim3(512), 0, st, ev_start, ev_stop, p); \
+            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, 1, 8>, grid, dim3(512), 0, st, ev_start, ev_stop, p); \
+        else if (p.M <= 32)                                                                                       \
+            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, 1, 4>, grid, dim3(256), 0, st, ev_start, ev_stop, p); \
         else                                                                                                      \
-            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, TMSV, 4>, grid, dim3(256), 0, st, ev_start, ev_stop, p); \
-    } while (0)
-#define NQ_SK_LAUNCH(FULLV, EPIV)                                   \
-    do {                                                            \
-        if (p.M <= 32) NQ_SK_LAUNCH_W(FULLV, EPIV, 1);              \
-        else NQ_SK_LAUNCH_W(FULLV, EPIV, 2);                        \
+            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, 2, 4>, grid, dim3(256), 0, st, ev_start, ev_stop, p); \
     } while (0)
 #define NQ_SK_MODES(FULLV)                                       \
     do {                                                         \
