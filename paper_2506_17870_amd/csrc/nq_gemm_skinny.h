@@ -9,9 +9,9 @@
 // the tile's packed dwords.
 // Every wave keeps its own accumulators; at the end they are added up through LDS (integer sums, so
 // the order does not matter) and wave 0 runs the epilogue.  Activations are small and shared by all
-// blocks (they stay in L2): a lane loads its 16-byte fragments straight from memory, rows past M
-// through the range check of buffer loads.  Weights and activations are requested SK_PD K steps
-// ahead in rolling register pipelines; nothing goes through LDS but the final sums.
+// blocks (they stay in L2); the block copies them chunk by chunk into LDS with whole-line loads and the
+// waves read their fragments there (rows past M through the range check of buffer loads).  Packed
+// weights are requested SK_PD K steps ahead in a rolling register pipeline.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -25,36 +25,101 @@ typedef int k_v4i __attribute__((ext_vector_type(4)));
 typedef int k_v16i __attribute__((ext_vector_type(16)));
 
 
-// TMS: 32-row tiles (1: M <= 32, 2: M <= 64).  NWS: waves per block (4 or 8).
-template <int H, int L, int FULL, int EPI, int TMS, int NWS>
+// Barrier of the block that orders LDS accesses only (a __syncthreads would also wait for every global load in
+// flight, i.e. drain the weight pipeline).
+__device__ __forceinline__ void sk_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Geometry of the activation chunks in LDS: a chunk is what CS consecutive K steps per wave read, i.e. a run
+// of 64 * CS * NWS bytes of every row; rows are padded by 16 bytes so that they fall on different banks.
+template <int TMS, int NWS>
+struct SkinnyChunk {
+    static constexpr int CS = (TMS == 1 && NWS == 4) ? 4 : 2;
+    static constexpr int SPAN = 64 * CS * NWS;
+    static constexpr int RS = SPAN + 16;
+    static constexpr int ROWS = 32 * TMS;
+    static constexpr int BUF = ROWS * RS + 16;                           // the last 16 bytes take pieces of no row
+    static constexpr int PIECES = ROWS * (SPAN / 16);
+    static constexpr int NPT = (PIECES + 64 * NWS - 1) / (64 * NWS);     // pieces a thread stages per chunk
+};
+
+template <int TMS, int NWS>
+constexpr int sk_lds_bytes()
+{
+    constexpr int chunks = 2 * SkinnyChunk<TMS, NWS>::BUF, sums = (NWS - 1) * TMS * 16 * 64 * 4;
+    return chunks > sums ? chunks : sums;
+}
+
+// TMS: 32-row tiles (1: M <= 32, 2: M <= 64).  NWS: waves per block (4 or 8).  STAGED: activations through
+// LDS (long reductions), else straight from memory into the lanes' fragments (short ones, where the extra
+// hop would only add to a latency-bound kernel).
+template <int H, int L, int FULL, int EPI, int TMS, int NWS, bool STAGED>
 __global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skinny(const GemmParams p)
 {
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
     using LP = LowPage<L, S, FULL>;
-    // K steps in flight per wave; three where four would not fit the register file
-    constexpr int SK_PD = (TMS == 2 && H + LP::DW > 8) ? 3 : 4;
+    using CH = SkinnyChunk<TMS, NWS>;
+    constexpr int SK_PD = 4;       // K steps of packed weights in flight per wave
+    constexpr int CS = CH::CS, RS = CH::RS, NPT = CH::NPT;
 
-    __shared__ int red[NWS - 1][TMS][16][64];
+    // two activation chunks; the partial sums of the waves use the same memory at the end (sk_lds_bytes)
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nb = blockIdx.x;
     const int wslot = epi_weight_slot<EPI>(lane);
 
-    // activations: row = lane & 31 (+ 32 per tile), bytes [64*kb + 32*g + 16*hf, +16) of the row
+    // Activations go through LDS: fetched straight from memory, a step's fragments are one cache line per lane
+    // and the look-ups, not the bytes, are what a compute unit runs out of (at 64 rows they cost more than the
+    // weight stream).  The block copies a run of every row per chunk with whole-line loads instead; rows past
+    // M and steps past K are out of the buffer's range and read as zero.
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.x), 0,
                                                                            (int)(p.M * p.K), 0x00020000);
+    constexpr uint32_t NOWHERE = 0x7fff0000u;
+    uint32_t st_x[NPT];     // byte offset of the piece in the activations for chunk 0
+    int st_lds[NPT];        // where it goes in a buffer
+    int st_k[NPT];          // its first k in chunk 0
+#pragma unroll
+    for (int i = 0; i < NPT; ++i) {
+        const int q = tid + 64 * NWS * i;
+        const int r = q / (CH::SPAN / 16), pc = q - r * (CH::SPAN / 16);
+        const bool real = q < CH::PIECES && r < p.M;
+        st_x[i] = real ? (uint32_t)(r * p.K + 16 * pc) : NOWHERE;
+        st_lds[i] = q < CH::PIECES ? r * RS + 16 * pc : CH::ROWS * RS;
+        st_k[i] = 16 * pc;
+    }
+    k_v4i stage[NPT];
+    const int k_end = p.KB * 64;         // weights past K are zero fields up to here; nothing is read beyond
+    auto stage_load = [&](int c) {
+#pragma unroll
+        for (int i = 0; i < NPT; ++i) {
+            const int k = st_k[i] + c * CH::SPAN;
+            const uint32_t at = (st_x[i] != NOWHERE && k < k_end) ? st_x[i] + (uint32_t)(c * CH::SPAN) : NOWHERE;
+            const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, at, 0, 0);
+            stage[i] = k_v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+        }
+    };
+    // the lane's fragments of local K step s of a chunk: row lane & 31 (+ 32 per tile), bytes
+    // [64*(wave + NWS*s) + 32*g + 16*hf, +16) of the run
+    const int a_lds = (lane & 31) * RS + 64 * wave + 32 * (lane >> 5);
+
+    // not STAGED: row = lane & 31 (+ 32 per tile), bytes [64*kb + 32*g + 16*hf, +16) of the row, requested with
+    // the weights of the step
     int a_row[TMS];
 #pragma unroll
     for (int i = 0; i < TMS; ++i) a_row[i] = (32 * i + (lane & 31)) * p.K + 32 * (lane >> 5);
+    k_v4i A[STAGED ? 1 : SK_PD][TMS][2];
 
     uint32_t P[SK_PD][H];
     uint32_t Q[SK_PD][LP::ARR];
-    k_v4i A[SK_PD][TMS][2];
     const int64_t tile0 = (int64_t)nb * p.KB;
-    // K steps past the end are requested like the last real one (weights) and out of range
-    // (activations, which read as zero): straight-line code, exact load counts
+    // K steps past the end are requested like the last real one; their activations are zero
     auto request = [&](int slot, int kb) {
         const int kbc = min(kb, p.KB - 1);
         const uint32_t *src = p.ph + (tile0 + kbc) * (H * 64);
@@ -65,14 +130,16 @@ __global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skin
 #pragma unroll
             for (int i = 0; i < LP::DW; ++i) Q[slot][i] = srcl[(unsigned)(i * 64 + wslot)];
         }
-        const int koff = kb < p.KB ? 64 * kb : 0x7fff0000;
+        if constexpr (!STAGED) {
+            const int koff = kb < p.KB ? 64 * kb : 0x7fff0000;
 #pragma unroll
-        for (int i = 0; i < TMS; ++i)
+            for (int i = 0; i < TMS; ++i)
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, a_row[i] + koff + 16 * hf, 0, 0);
-                A[slot][i][hf] = k_v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
-            }
+                for (int hf = 0; hf < 2; ++hf) {
+                    const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, a_row[i] + koff + 16 * hf, 0, 0);
+                    A[slot][i][hf] = k_v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+                }
+        }
     };
 
     k_v16i acc[TMS];
@@ -81,14 +148,27 @@ __global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skin
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0;
 
+    if constexpr (STAGED) stage_load(0);
 #pragma unroll
     for (int d = 0; d < SK_PD; ++d) request(d, wave + NWS * d);
 
-    // wave w: K steps w + NWS*j; all waves run the same number of rounds (the extra ones add zeros)
+    // wave w: K steps w + NWS*j; all waves run the same number of rounds (the extra ones add zeros) and meet
+    // at one barrier per chunk
     const int rounds = (p.KB + NWS - 1) / NWS;
     for (int j0 = 0; j0 < rounds; j0 += SK_PD) {
 #pragma unroll
         for (int d = 0; d < SK_PD; ++d) {
+            const int c = (j0 + d) / CS;           // chunk of this step
+            if (STAGED && d % CS == 0) {
+                // The buffer was last read two chunks ago, and every wave has passed the barrier of the chunk
+                // in between since.
+                uint8_t *buf = lds + (c & 1) * CH::BUF;
+#pragma unroll
+                for (int i = 0; i < NPT; ++i) *reinterpret_cast<k_v4i *>(buf + st_lds[i]) = stage[i];
+                stage_load(c + 1);                  // travels while this chunk is computed
+                sk_lds_barrier();
+            }
+            const uint8_t *frag = lds + (c & 1) * CH::BUF + a_lds + 64 * NWS * (d % CS);
             uint32_t D[8];
             HighCodec<H>::decode(P[d], D);
             LP::apply(Q[d], D);
@@ -96,7 +176,10 @@ __global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skin
 #pragma unroll
             for (int i = 0; i < TMS; ++i)
 #pragma unroll
-                for (int hf = 0; hf < 2; ++hf) a[i][hf] = A[d][i][hf];
+                for (int hf = 0; hf < 2; ++hf) {
+                    if constexpr (STAGED) a[i][hf] = *reinterpret_cast<const k_v4i *>(frag + 32 * i * RS + 16 * hf);
+                    else a[i][hf] = A[d][i][hf];
+                }
             request(d, wave + NWS * (j0 + d + SK_PD));
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
@@ -106,22 +189,26 @@ __global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skin
             }
         }
     }
+    if constexpr (STAGED) sk_lds_barrier();       // the chunk buffers are free for the partial sums
 
-    // ---- add the partial sums of the waves ---------------------------------------------------------------
+    // ---- add the partial sums of the waves -----------------------------------------------------------
+    int *red = reinterpret_cast<int *>(lds);          // [NWS - 1][TMS][16][64]
     if (wave > 0) {
+        int *mine = red + (wave - 1) * (TMS * 16 * 64) + lane;       // constant offsets from one address
 #pragma unroll
         for (int i = 0; i < TMS; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) red[wave - 1][i][r][lane] = acc[i][r];
+            for (int r = 0; r < 16; ++r) mine[(i * 16 + r) * 64] = acc[i][r];
     }
     __syncthreads();
     if (wave > 0) return;
+    const int *all = red + lane;
 #pragma unroll
     for (int w = 0; w < NWS - 1; ++w)
 #pragma unroll
         for (int i = 0; i < TMS; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][r] += red[w][i][r][lane];
+            for (int r = 0; r < 16; ++r) acc[i][r] += all[((w * TMS + i) * 16 + r) * 64];
 
     // ---- epilogue (Eq. 2 / Eq. 8) ----------------------------------------------------------------
     EpiCols<EPI> e;
@@ -144,14 +231,27 @@ void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, v
     // eight waves where every compute unit gets at most one block, the reduction is long enough to share and
     // there is one row tile (with two, measured slower: 25.8 us against 23.1 us at 64 x 8192 -> 8192)
     const bool wide = p.NB <= 256 && p.KB >= 32 && p.M <= 32;
-#define NQ_SK_LAUNCH(FULLV, EPIV)                                                                                 \
-    do {                                                                                                          \
-        if (wide)                                                                                                 \
-            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, 1, 8>, grid, dim3(512), 0, st, ev_start, ev_stop, p); \
-        else if (p.M <= 32)                                                                                       \
-            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, 1, 4>, grid, dim3(256), 0, st, ev_start, ev_stop, p); \
-        else                                                                                                      \
-            launch_timed(k_nested_gemm_skinny<H, L, FULLV, EPIV, 2, 4>, grid, dim3(256), 0, st, ev_start, ev_stop, p); \
+    // activations through LDS from 2048 columns on (a 64 x 512 x 512 layer: 4.4 us straight, 4.8 us staged)
+    const bool staged = p.KB >= 32;
+#define NQ_SK_ONE(FULLV, EPIV, TMSV, NWSV, STAGEDV)                                                     \
+    do {                                                                                                \
+        auto k = k_nested_gemm_skinny<H, L, FULLV, EPIV, TMSV, NWSV, STAGEDV>;                           \
+        constexpr int lds = STAGEDV ? sk_lds_bytes<TMSV, NWSV>() : (NWSV - 1) * TMSV * 4096;             \
+        static bool granted = false;   /* one per kernel instantiation */                               \
+        if (!granted) {                                                                                 \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k),                                \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);                 \
+            granted = true;                                                                             \
+        }                                                                                               \
+        launch_timed(k, grid, dim3(64 * NWSV), lds, st, ev_start, ev_stop, p);                          \
+    } while (0)
+#define NQ_SK_LAUNCH(FULLV, EPIV)                                       \
+    do {                                                                \
+        if (wide) NQ_SK_ONE(FULLV, EPIV, 1, 8, true);                   \
+        else if (p.M <= 32 && staged) NQ_SK_ONE(FULLV, EPIV, 1, 4, true); \
+        else if (p.M <= 32) NQ_SK_ONE(FULLV, EPIV, 1, 4, false);        \
+        else if (staged) NQ_SK_ONE(FULLV, EPIV, 2, 4, true);            \
+        else NQ_SK_ONE(FULLV, EPIV, 2, 4, false);                       \
     } while (0)
 #define NQ_SK_MODES(FULLV)                                       \
     do {                                                         \
