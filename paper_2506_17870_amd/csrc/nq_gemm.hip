@@ -310,8 +310,19 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     p.kw_magic = 65536 / g.KW + 1;
     const bool big_ok = plain_gemm || conv_gemm;
     bool big_wanted = g.M > 64 && w->N > 64 && w->K >= 256;
-    // short reductions with few output channels per block stay with the register-stationary kernel
-    if (conv_gemm && w->K <= 576) big_wanted = false;
+    // short reductions stay with the register-stationary kernel, which fetches the input once per 32 to 128
+    // output channels; with 512 channels or more out of 512 in, the large kernel's 256-column tiles win
+    // (strided 1x1, 28x28x512 -> 1024 at batch 128: 30 us against 48 us)
+    if (conv_gemm && w->K <= 576 && !(w->K >= 512 && w->N >= 512)) big_wanted = false;
+    // Filters over up to 128 output channels at stride 1 go to the windowed kernel (64 channels per block): the
+    // large-GEMM kernel's 256-column tile would be half empty (3x3, 28x28x128 -> 128 at batch 128: 38.8 us
+    // against 51.8 us; at stride 2 the large kernel stays ahead, 51 us against 57 us).
+    {
+        WindowGeom wg0;
+        size_t lds0 = 0;
+        if (conv_gemm && w->N <= 128 && g.stride == 1 && g.KH * g.KW > 1 && plan_window(g, d_x, &wg0, &lds0))
+            big_wanted = false;
+    }
     if (big_ok && (force == 4 || (force == 0 && big_wanted))) {
         const int64_t blocks = ceil_div(g.M, 64) * ceil_div(w->N, 256);
         if (blocks > 0x7fffffffLL) return NQ_ERR_SHAPE;
