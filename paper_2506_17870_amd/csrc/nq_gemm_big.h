@@ -70,6 +70,20 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
 
     const int iters = (p.KB + GB_KI - 1) / GB_KI;
 
+    // ---- first touch of the packed pages ----------------------------------------------------------
+    // In a network every launch meets weights that no cache holds.  The K loop asks for them four steps
+    // ahead, which covers the latency of L2 but not that of memory, and the blocks of a launch move in step:
+    // each new K step would wait for memory once more.  So every wave first touches one dword in each of 64
+    // cache lines of either page, the waves that share an L2 (blocks 8 apart run on the same XCD) covering
+    // the pages between them as far as they reach; the values are not used.
+    uint32_t touch_h = 0, touch_l = 0;
+    {
+        const int64_t line = ((int64_t)(blockIdx.x >> 3) * 4 + wave) * 64 + lane;
+        const int64_t dwords_h = (int64_t)p.NB * p.KB * (H * 64), dwords_l = (int64_t)p.NB * p.KB * (LP::DW * 64);
+        if (line * 32 < dwords_h) touch_h = p.ph[line * 32];
+        if (FULL != 0 && line * 32 < dwords_l) touch_l = p.pl[line * 32];
+    }
+
     // ---- activations -------------------------------------------------------------------------
     // LDS-direct load k of wave w fills panel slots [(APT*w + k)*64, +64) (16 bytes each): lane l
     // writes row 4*(APT*w + k) + (l >> 4), position l & 15, and therefore fetches piece
@@ -311,6 +325,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
         }
     }
 
+    asm volatile("" ::"v"(touch_h), "v"(touch_l));      // keeps the first-touch loads; they arrived long ago
     // ---- epilogue (Eq. 2 / Eq. 8): residual codes of all tiles first, then the arithmetic -------
     auto rows_of = [&](int i) {
         const int64_t left = p.M - (m0 + i * 32);
