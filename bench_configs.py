@@ -417,7 +417,7 @@ def c4():
             e0, e1 = binding.nq_event_create(), binding.nq_event_create()
             binding.nq_profile_next_launch(e0, e1)
             orig(*a, **k)
-            recs.append((e0, e1, a[1] if name == "nq_conv_full" else None, a[2]))
+            recs.append((e0, e1, a[1] if name == "nq_conv_full" else None, a[2], bool(a[3].d_residual)))
         return call
     for name in originals:
         setattr(binding, name, stamped(name))
@@ -429,7 +429,7 @@ def c4():
             setattr(binding, name, orig)
     layers = {}
     total = 0.0
-    for e0, e1, shape, wd in recs:
+    for e0, e1, shape, wd, has_res in recs:
         us = binding.nq_event_elapsed_ms(e0, e1) * 1e3
         binding.nq_event_destroy(e0)
         binding.nq_event_destroy(e1)
@@ -440,6 +440,9 @@ def c4():
             m, k = shape.B * ho * wo, shape.KH * shape.KW * shape.Cin
             key = f"{shape.KH}x{shape.KW} s{shape.stride} {shape.H}x{shape.W} {shape.Cin}->{shape.Cout}"
             lops, byts = 2.0 * m * shape.Cout * k, shape.B * shape.H * shape.W * shape.Cin + m * shape.Cout + shape.Cout * k
+            if has_res:                      # the block's last layer also reads the skip tensor
+                key += " + residual"
+                byts += m * shape.Cout
         else:
             key, lops, byts = f"fc {wd.K}->{wd.N}", 2.0 * B * wd.N * wd.K, B * wd.K + 4 * B * wd.N + wd.N * wd.K
         a = layers.setdefault(key, [0, 0.0, 0.0, 0.0])
