@@ -88,6 +88,10 @@ def test_epilogue_options(nq):
     # implicit GEMM on the large-GEMM kernel: several row tiles, ragged rows, K not a multiple of 256 or 64
     (2, 14, 14, 256, 256, 3, 3, 1, 1), (3, 15, 13, 32, 96, 3, 3, 2, 1), (1, 9, 9, 16, 130, 5, 5, 1, 2),
     (2, 12, 12, 128, 272, 1, 1, 2, 0),
+    # strided 1x1 on the register-stationary kernel (fetches only the pixels it needs): odd sizes, stride 3,
+    # several units per image, every K-step count of that kernel
+    (2, 13, 11, 64, 64, 1, 1, 2, 0), (1, 57, 57, 256, 96, 1, 1, 2, 0), (2, 9, 10, 512, 40, 1, 1, 3, 0),
+    (3, 28, 28, 128, 160, 1, 1, 2, 0),
     # few input channels: one matrix-core step per filter row, several units, ragged last unit
     (2, 64, 64, 3, 64, 7, 7, 2, 3), (1, 37, 36, 3, 48, 7, 7, 2, 3), (2, 12, 12, 4, 40, 3, 3, 1, 1),
     (1, 30, 28, 1, 32, 3, 3, 2, 0),
