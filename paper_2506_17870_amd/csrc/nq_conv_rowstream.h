@@ -96,7 +96,7 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
         const bool in_window = q < g.items;
         const bool in_row = in_window && (unsigned)iw < (unsigned)p.W;
         st_lds[j] = in_window ? pos * CKP + 16 * c : g.win_bytes;   // pieces past the window go to a spare slot
-        st_goff[j] = in_row ? ir * g.row_bytes + iw * g.pix_bytes + 16 * c : RS_HALO_OFFSET;
+        st_goff[j] = in_row ? (ir * p.W + iw) * p.Cin + 16 * c : RS_HALO_OFFSET;
     }
     r_v4u stage[RS_G][RS_LDMAX];
     auto load_unit = [&](int b, int rb, r_v4u (&stg)[RS_LDMAX]) {

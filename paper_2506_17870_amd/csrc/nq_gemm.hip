@@ -79,7 +79,7 @@ bool plan_rowstream(const Geometry &g, const int8_t *d_x, int64_t n_out, StreamG
         sg->wc_magic = (unsigned)(((uint64_t(1) << 32) + WC - 1) / WC);
         sg->wo_magic = (unsigned)(((uint64_t(1) << 32) + g.Wo - 1) / g.Wo);
         if (WC == 1) sg->wc_magic = 0xFFFFFFFFu;   // not reached: WC >= KW >= 1 and a 1-wide window has Cin pieces only
-        sg->img_bytes = (int)img_bytes; sg->row_bytes = g.W * Cin; sg->pix_bytes = Cin;
+        sg->img_bytes = (int)img_bytes; sg->row_bytes = g.W * Cin;
         const int cin64 = Cin / 64;
         for (int s = 0; s < 9; ++s) {
             const int tap = s / cin64, cb = s % cin64;
@@ -343,23 +343,9 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     }
     StreamGeom sg;
     int grid_x = 0;
-    // A strided 1x1 convolution reads one pixel in stride^2: it runs as a stride-1 1x1 convolution over the
-    // Ho x Wo pixels it needs, the window's rows and columns stride * W * Cin and stride * Cin bytes apart in
-    // memory, so that nothing else is fetched.
-    const bool thinned = g.KH == 1 && g.KW == 1 && g.stride > 1 && g.pad == 0;
-    Geometry gr = g;
-    if (thinned) { gr.H = g.Ho; gr.W = g.Wo; gr.stride = 1; }
-    if ((force == 0 || force == 3) && (int64_t)g.H * g.W * g.Cin <= (int64_t(1) << 29) &&
-        plan_rowstream(gr, d_x, w->N, &sg, &grid_x)) {
+    if ((force == 0 || force == 3) && plan_rowstream(g, d_x, w->N, &sg, &grid_x)) {
         if ((int64_t)(grid_x + 7) * ceil_div(w->N, 32) > 0x7fffffffLL) return NQ_ERR_SHAPE;
-        GemmParams pr = p;
-        if (thinned) {
-            pr.H = gr.H; pr.W = gr.W; pr.stride = 1;
-            sg.img_bytes = g.H * g.W * g.Cin;
-            sg.row_bytes = g.stride * g.W * g.Cin;
-            sg.pix_bytes = g.stride * g.Cin;
-        }
-        NQ_DISPATCH_HL(h, l, launch_nested_conv_rowstream, full, pr, sg, grid_x, s, ev0, ev1);
+        NQ_DISPATCH_HL(h, l, launch_nested_conv_rowstream, full, p, sg, grid_x, s, ev0, ev1);
         return launch_status();
     }
     WindowGeom wg;

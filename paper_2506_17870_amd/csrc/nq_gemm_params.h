@@ -55,8 +55,7 @@ struct StreamGeom {
     int grid_x, nblk;     // unit slots (a block takes units slot, slot + grid_x, ...) and channel-tile groups
     int step_b, step_rb;  // grid_x = step_b * RB + step_rb: how (image, row block) advance per unit
     int img_bytes;    // H * W * Cin
-    int row_bytes;    // bytes from one window row to the next in memory: W * Cin (a strided 1x1: stride * W * Cin)
-    int pix_bytes;    // bytes from one window column to the next: Cin (a strided 1x1: stride * Cin)
+    int row_bytes;    // W * Cin
     int tap_off[9];   // LDS byte offset of K step s: (kh*WC + kw)*(Cin+16) + 64*cb
 };
 
@@ -73,8 +72,7 @@ struct SmallCinGeom {
     int d0;           // byte offset of input column 0 inside an LDS row (zero halo before it), multiple of 4
     int row_stride;   // LDS bytes per input row, multiple of 4
     int row_dwords;   // W * Cin / 4
-    int row_bytes;    // bytes from one window row to the next in memory: W * Cin (a strided 1x1: stride * W * Cin)
-    int pix_bytes;    // bytes from one window column to the next: Cin (a strided 1x1: stride * Cin)
+    int row_bytes;    // W * Cin
     int img_bytes;    // H * W * Cin
     int win_bytes;    // LDS bytes of one window incl. slack, multiple of 16
     int grid_x;       // persistent blocks per channel group
