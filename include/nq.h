@@ -122,6 +122,8 @@ typedef struct {
                             /* the page enqueued before nq_page_out_low are done"         */
     int32_t free_event_armed;
     int32_t events_borrowed;/* internal: the events belong to the head of a group           */
+    int32_t group_head;     /* internal: other descriptors borrow this one's events         */
+    int32_t reserved_;      /* keeps the size a multiple of 8                               */
 } nq_weight;
 
 /* Fused epilogue of the GEMM / convolution (Eq. 2 and Eq. 8), fp32, in this order with
@@ -243,7 +245,11 @@ nq_status nq_page_in_low(nq_weight *w, void *copy_stream);
  * single calls do for one, with one event operation in all; nq_page_in_low_batch merges the
  * copies of pages that follow each other without a gap in both host and device memory (pages
  * carved in the same order out of one pinned arena and one device arena) into single transfers,
- * so a model is paged in with a few large copies instead of one small copy per layer. */
+ * so a model is paged in with a few large copies instead of one small copy per layer.
+ * The members of a group (count > 1) share their events, so they switch together: nq_page_out_low and
+ * nq_page_in_low on a single member return NQ_ERR_INVALID_ARG (two members paged in on different streams
+ * would overwrite each other's "page is in" point); use the batch calls, on the whole group or on any part
+ * of it, one call at a time. */
 nq_status nq_weight_init_group(nq_weight *const *ws, int64_t count);
 nq_status nq_page_out_low_batch(nq_weight *const *ws, int64_t count, void *stream);
 nq_status nq_page_in_low_batch(nq_weight *const *ws, int64_t count, void *copy_stream);
@@ -281,6 +287,18 @@ nq_status nq_gconv_full(const int8_t *d_x, const nq_conv_shape *shape, int group
                         const nq_epilogue *epi, void *d_y, void *stream);
 nq_status nq_gconv_part(const int8_t *d_x, const nq_conv_shape *shape, int groups, const nq_weight *w,
                         const nq_epilogue *epi, void *d_y, void *stream);
+
+/* Test and tuning aid, not needed in normal use: process-wide overrides of choices the library otherwise
+ * makes from the shape.  value 0 restores the library's own choice.  A forced kernel or tile height that
+ * does not apply to a shape is ignored for that call.  Meant to be set while no other thread is inside
+ * the library (the parity tests run every case once per kernel that can take it).
+ *   NQ_TUNE_KERNEL:   1 generic, 2 windowed, 3 register-stationary, 4 large GEMM, 5 few input channels,
+ *                     6 few rows
+ *   NQ_TUNE_BIG_TM:   2..5, rows per block of the large-GEMM kernel = 32 * value
+ *   NQ_TUNE_GC_UNITS: work units the patch planner of the depthwise / grouped kernel aims for
+ * NQ_ERR_INVALID_ARG for an unknown key or a negative value. */
+typedef enum { NQ_TUNE_KERNEL = 0, NQ_TUNE_BIG_TM = 1, NQ_TUNE_GC_UNITS = 2, NQ_TUNE_COUNT = 3 } nq_tune_key;
+nq_status nq_set_tuning(int key, int value);
 
 /* Profiling aid: the next nq_gemm_* / nq_conv_* / nq_gconv_* call made by this host thread attaches the two
  * hipEvent_t (either may be NULL) to its kernel dispatch, so that hipEventElapsedTime(start,

@@ -21,13 +21,14 @@ NQ_OK, NQ_ERR_INVALID_ARG, NQ_ERR_UNSUPPORTED, NQ_ERR_SHAPE, NQ_ERR_ALIGN, NQ_ER
 NQ_LOW_UNSIGNED_L, NQ_LOW_SIGNED_L1 = 0, 1
 NQ_LAYOUT_DENSE, NQ_LAYOUT_PAPER_U64 = 0, 1
 NQ_MAX_K = 65536
+NQ_TUNE_KERNEL, NQ_TUNE_BIG_TM, NQ_TUNE_GC_UNITS = 0, 1, 2
 
 EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "nq_quantize_decompose_pack",
            "nq_decompose", "nq_pack", "nq_decompose_pack", "nq_decompose_pack_batch",
            "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
            "nq_weight_init_group", "nq_page_out_low_batch", "nq_page_in_low_batch",
            "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_gconv_full", "nq_gconv_part",
-           "nq_profile_next_launch", "nq_event_create", "nq_event_destroy",
+           "nq_set_tuning", "nq_profile_next_launch", "nq_event_create", "nq_event_destroy",
            "nq_event_elapsed_ms", "nq_maxpool_i8", "nq_avgpool_i8"]
 
 
@@ -43,7 +44,8 @@ class nq_weight(ctypes.Structure):
                 ("h_low", ctypes.c_void_p), ("d_scale", ctypes.c_void_p),
                 ("low_resident", ctypes.c_int32), ("low_event_armed", ctypes.c_int32),
                 ("low_event", ctypes.c_void_p), ("free_event", ctypes.c_void_p),
-                ("free_event_armed", ctypes.c_int32), ("events_borrowed", ctypes.c_int32)]
+                ("free_event_armed", ctypes.c_int32), ("events_borrowed", ctypes.c_int32),
+                ("group_head", ctypes.c_int32), ("reserved_", ctypes.c_int32)]
 
 
 class nq_pack_job(ctypes.Structure):
@@ -95,6 +97,7 @@ _SIGS = {
     "nq_conv_part": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
     "nq_gconv_full": (_int, [_vp, _sp, _int, _wp, _ep, _vp, _vp]),
     "nq_gconv_part": (_int, [_vp, _sp, _int, _wp, _ep, _vp, _vp]),
+    "nq_set_tuning": (_int, [_int, _int]),
     "nq_profile_next_launch": (_int, [_vp, _vp]),
     "nq_event_create": (_int, [ctypes.POINTER(ctypes.c_void_p)]),
     "nq_event_destroy": (_int, [_vp]),
@@ -257,6 +260,10 @@ def nq_gconv_part(d_x, shape: nq_conv_shape, groups: int, w: nq_weight, epi: nq_
                               _stream(stream)), "nq_gconv_part")
 
 
+def nq_set_tuning(key: int, value: int):
+    _check(_lib.nq_set_tuning(key, value), "nq_set_tuning")
+
+
 def nq_profile_next_launch(start_event, stop_event):
     """Raw hipEvent_t handles (integers) or None."""
     _check(_lib.nq_profile_next_launch(start_event, stop_event), "nq_profile_next_launch")
@@ -311,7 +318,7 @@ class NestedWeight:
         assert self.low.numel() == low_bytes and self.low_host.numel() == low_bytes
         self.scale = torch.ones(max(N, 1), dtype=torch.float32, device=device)
         self.desc = nq_weight(cfg, N, K, self.high.data_ptr(), self.high.numel(), self.low.data_ptr(),
-                              self.low.numel(), self.low_host.data_ptr(), self.scale.data_ptr(), 0, 0, None, None, 0, 0)
+                              self.low.numel(), self.low_host.data_ptr(), self.scale.data_ptr(), 0, 0, None, None, 0, 0, 0, 0)
         if init:
             nq_weight_init(self.desc)
 

@@ -1,7 +1,7 @@
 // Host side of the inference entry points: argument checks, residency of the lower-bit
 // page (paper Sec. 3.2.3 / 3.3: the caller picks full-bit or part-bit; a paged-out page is
 // an error, never a silent downgrade), tile choice and launch.
-#include <stdlib.h>
+#include <atomic>
 
 #include "nq_common.h"
 #include "nq_gemm_params.h"
@@ -18,6 +18,9 @@ struct Geometry {
 // One-shot profiling hook: events handed over by nq_profile_next_launch, consumed by the next launch.
 thread_local void *g_ev_start = nullptr;
 thread_local void *g_ev_stop = nullptr;
+
+// Test and tuning overrides set through nq_set_tuning; 0 = the library's own choice.
+std::atomic<int> g_tune[NQ_TUNE_COUNT];
 
 // Decides whether the windowed convolution kernel applies and fills its geometry.
 bool plan_window(const Geometry &g, const int8_t *d_x, WindowGeom *wg, size_t *lds)
@@ -147,6 +150,8 @@ bool plan_grouped(const Geometry &g, int gs, int64_t C, GroupGeom *gg)
     const int CT = (int)ceil_div(C, 64);
     double best = -1.0;
     int bR = 0, bCW = 0;
+    const int tuned_units = g_tune[NQ_TUNE_GC_UNITS].load(std::memory_order_relaxed);
+    const double units_target = tuned_units > 0 ? (double)tuned_units : 512.0;
     const int cands[5] = {g.Wo, (g.Wo + 1) / 2, (g.Wo + 2) / 3, (g.Wo + 3) / 4, 16};
     for (int CW : cands) {
         if (CW > g.Wo) CW = g.Wo;
@@ -160,10 +165,9 @@ bool plan_grouped(const Geometry &g, int gs, int64_t C, GroupGeom *gg)
             const double units = (double)images * (double)ceil_div(g.Ho, R) * (double)ceil_div(g.Wo, CW) * CT;
             const int64_t pt = ceil_div(R * CW, 16);
             const double balance = (double)pt / (4.0 * (double)ceil_div(pt, 4));   // tiles are dealt to four waves
-            // NQ_GC_UNITS (tuning aid): how many (unit, channel tile) pairs a launch should at least have;
-            // measured best at one per resident block, larger patches beating more of them
-            const char *te = getenv("NQ_GC_UNITS");
-            const double target = te ? atof(te) : 512.0;
+            // how many (unit, channel tile) pairs a launch should at least have: measured best at one per
+            // resident block, larger patches beating more of them (NQ_TUNE_GC_UNITS overrides)
+            const double target = units_target;
             const double score = halo * fill * balance * (units >= target ? 1.0 : units / target);
             if (score > best) { best = score; bR = R; bCW = CW; }
         }
@@ -228,13 +232,6 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if (w->N > (1 << 24) || g.M > (int64_t(1) << 40) / (w->N > 0 ? w->N : 1)) return NQ_ERR_SHAPE;
 
     hipStream_t s = (hipStream_t)stream;
-    if (full && w->low_event_armed && w->low_event) {
-        // the page may still be in flight on the copy stream
-        if (hipStreamWaitEvent(s, (hipEvent_t)w->low_event, 0) != hipSuccess) {
-            (void)hipGetLastError();
-            return NQ_ERR_HIP;
-        }
-    }
 
     GemmParams p;
     p.x = d_x;
@@ -269,8 +266,33 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     else
         p.general = p.acc_dump != nullptr || p.resid != nullptr;
 
-    void *ev0 = g_ev_start, *ev1 = g_ev_stop;
-    g_ev_start = g_ev_stop = nullptr;
+    // Everything that can fail is checked before anything is enqueued: `commit` is called once the kernel
+    // and its geometry are fixed, right before the launch.  It makes the stream wait for a page that may
+    // still be in flight on the copy stream and takes the one-shot profiling events.
+    void *ev0 = nullptr, *ev1 = nullptr;
+    auto commit = [&]() -> bool {
+        if (full && w->low_event_armed && w->low_event) {
+            // Once the copy has completed no later launch needs to wait for it: the flag (an internal field of
+            // the caller's descriptor) is dropped, so that only the launches issued while the page travels pay
+            // for a wait.  Not while the stream is being captured: an event recorded inside a capture cannot
+            // be queried, and a replay needs the dependency every time.
+            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+            const bool capturing = hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
+            if (!capturing && hipEventQuery((hipEvent_t)w->low_event) == hipSuccess) {
+                const_cast<nq_weight *>(w)->low_event_armed = 0;
+            } else {
+                (void)hipGetLastError();   // hipErrorNotReady from the query is not an error
+                if (hipStreamWaitEvent(s, (hipEvent_t)w->low_event, 0) != hipSuccess) {
+                    (void)hipGetLastError();
+                    return false;
+                }
+            }
+        }
+        ev0 = g_ev_start;
+        ev1 = g_ev_stop;
+        g_ev_start = g_ev_stop = nullptr;
+        return true;
+    };
     if (words) {
         // 32-bit byte offsets into the activations, dword loads relative to their first byte
         if (g.M * w->K >= 0x7fff0000LL || ceil_div(g.M, 32) > 65535) return NQ_ERR_SHAPE;
@@ -281,6 +303,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         const int WH = (int)ceil_div(w->K, 64 / h);
         const int lf = low_field_bits(&w->cfg);
         const int WL = (int)ceil_div(w->K, 64 / lf);
+        if (!commit()) return NQ_ERR_HIP;
         launch_nested_gemm_words(full, h, l, p, WH, WL, s, ev0, ev1);
         return launch_status();
     }
@@ -290,14 +313,14 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         p.conv_big = 0;
         p.cin_shift = 0;
         p.kw_magic = 65536 / g.KW + 1;      // tap / KW == (tap * kw_magic) >> 16 for the few taps of a filter
+        if (!commit()) return NQ_ERR_HIP;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_grouped, full, p, gg, s, ev0, ev1);
         return launch_status();
     }
-    // NQ_KERNEL (tuning and test aid): 1 generic, 2 windowed, 3 register-stationary, 4 large GEMM,
+    // NQ_TUNE_KERNEL (test and tuning aid): 1 generic, 2 windowed, 3 register-stationary, 4 large GEMM,
     // 5 few input channels, 6 few rows;
     // a kernel that does not apply to the shape is never forced, the choice falls through.
-    const char *env = getenv("NQ_KERNEL");
-    const int force = env ? atoi(env) : 0;
+    const int force = g_tune[NQ_TUNE_KERNEL].load(std::memory_order_relaxed);
     const bool plain_gemm = g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && w->K % 256 == 0 && aligned16(d_x);
     // implicit GEMM on the same kernel: any filter over a power-of-two number (>= 16) of input channels
     const int64_t x_bytes = (g.M / ((int64_t)g.Ho * g.Wo)) * g.H * g.W * g.Cin;
@@ -326,18 +349,21 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if (big_ok && (force == 4 || (force == 0 && big_wanted))) {
         const int64_t blocks = ceil_div(g.M, 64) * ceil_div(w->N, 256);
         if (blocks > 0x7fffffffLL) return NQ_ERR_SHAPE;
-        NQ_DISPATCH_HL(h, l, launch_nested_gemm_big, full, p, s, ev0, ev1);
+        if (!commit()) return NQ_ERR_HIP;
+        NQ_DISPATCH_HL(h, l, launch_nested_gemm_big, full, p, g_tune[NQ_TUNE_BIG_TM].load(std::memory_order_relaxed), s, ev0, ev1);
         return launch_status();
     }
     // few rows: the packed weights are the traffic; one block per 32 columns, K split over the waves
     const bool skinny_ok = g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && g.M <= 64 && w->K % 16 == 0 &&
                            aligned16(d_x) && ceil_div(w->N, 32) <= 0x7fffffffLL;
     if (skinny_ok && (force == 6 || (force == 0 && w->K >= 256))) {
+        if (!commit()) return NQ_ERR_HIP;
         NQ_DISPATCH_HL(h, l, launch_nested_gemm_skinny, full, p, s, ev0, ev1);
         return launch_status();
     }
     SmallCinGeom cg;
     if ((force == 0 || force == 5) && plan_smallcin(g, d_x, w->N, &cg)) {
+        if (!commit()) return NQ_ERR_HIP;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_smallcin, full, p, cg, s, ev0, ev1);
         return launch_status();
     }
@@ -345,6 +371,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     int grid_x = 0;
     if ((force == 0 || force == 3) && plan_rowstream(g, d_x, w->N, &sg, &grid_x)) {
         if ((int64_t)(grid_x + 7) * ceil_div(w->N, 32) > 0x7fffffffLL) return NQ_ERR_SHAPE;
+        if (!commit()) return NQ_ERR_HIP;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_rowstream, full, p, sg, grid_x, s, ev0, ev1);
         return launch_status();
     }
@@ -353,12 +380,14 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if ((force == 0 || force == 2) && plan_window(g, d_x, &wg, &lds)) {
         const int64_t blocks_x = (g.M / ((int64_t)g.Ho * g.Wo)) * wg.RB;
         if (blocks_x > 0x7fffffffLL || ceil_div(w->N, 64) > 65535) return NQ_ERR_SHAPE;
+        if (!commit()) return NQ_ERR_HIP;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_window, full, 0, p, wg, lds, s, ev0, ev1);
         return launch_status();
     }
     const int tile = pick_tile(g.M, w->N);
     if (ceil_div(g.M, NQ_TILE_BM[tile]) > 0x7fffffffLL || ceil_div(w->N, NQ_TILE_BN[tile]) > 65535)
         return NQ_ERR_SHAPE;
+    if (!commit()) return NQ_ERR_HIP;
     NQ_DISPATCH_HL(h, l, launch_nested_gemm, full, tile, p, s, ev0, ev1);
     return launch_status();
 }
@@ -437,6 +466,13 @@ extern "C" nq_status nq_gconv_part(const int8_t *d_x, const nq_conv_shape *shape
                                    const nq_epilogue *epi, void *d_y, void *stream)
 {
     return gconv(false, d_x, shape, groups, w, epi, d_y, stream);
+}
+
+extern "C" nq_status nq_set_tuning(int key, int value)
+{
+    if (key < 0 || key >= NQ_TUNE_COUNT || value < 0) return NQ_ERR_INVALID_ARG;
+    g_tune[key].store(value, std::memory_order_relaxed);
+    return NQ_OK;
 }
 
 extern "C" nq_status nq_profile_next_launch(void *start_event, void *stop_event)

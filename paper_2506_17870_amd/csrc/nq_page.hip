@@ -49,6 +49,7 @@ extern "C" nq_status nq_weight_init(nq_weight *w)
     w->low_event_armed = 0;
     w->free_event_armed = 0;
     w->events_borrowed = 0;
+    w->group_head = 0;
     w->low_resident = 0;
     return NQ_OK;
 }
@@ -85,6 +86,7 @@ extern "C" nq_status nq_page_out_low(nq_weight *w, void *stream)
     // nothing is moved: the host copy is the master; only the point after which the device
     // slot may be overwritten is marked on `stream`
     if (!w) return NQ_ERR_INVALID_ARG;
+    if (w->events_borrowed || w->group_head) return NQ_ERR_INVALID_ARG;   // a group is switched by the batch calls
     if (w->free_event) {
         if (hipEventRecord((hipEvent_t)w->free_event, (hipStream_t)stream) != hipSuccess) {
             (void)hipGetLastError();
@@ -103,6 +105,7 @@ extern "C" nq_status nq_page_in_low(nq_weight *w, void *copy_stream)
     nq_status st = check_cfg(&w->cfg);
     if (st != NQ_OK) return st;
     if (!w->low_event) return NQ_ERR_INVALID_ARG;  // nq_weight_init was not called
+    if (w->events_borrowed || w->group_head) return NQ_ERR_INVALID_ARG;   // a group is switched by the batch calls
     const size_t need = nq_packed_bytes(w->N, w->K, low_field_bits(&w->cfg), w->cfg.layout);
     if (w->low_bytes < need) return NQ_ERR_RANGE;
     hipStream_t s = (hipStream_t)copy_stream;
@@ -139,6 +142,7 @@ extern "C" nq_status nq_weight_init_group(nq_weight *const *ws, int64_t count)
         if (!ws[i]) return NQ_ERR_INVALID_ARG;
     nq_status st = nq_weight_init(ws[0]);
     if (st != NQ_OK) return st;
+    ws[0]->group_head = count > 1 ? 1 : 0;
     for (int64_t i = 1; i < count; ++i) {
         nq_weight *w = ws[i];
         if ((st = check_cfg(&w->cfg)) != NQ_OK || (st = check_shape(w->N, w->K)) != NQ_OK) return st;
@@ -149,6 +153,7 @@ extern "C" nq_status nq_weight_init_group(nq_weight *const *ws, int64_t count)
         w->low_event = ws[0]->low_event;
         w->free_event = ws[0]->free_event;
         w->events_borrowed = 1;
+        w->group_head = 0;
         w->low_event_armed = 0;
         w->free_event_armed = 0;
         w->low_resident = 0;

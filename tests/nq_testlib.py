@@ -1,7 +1,5 @@
 """Shared plumbing of the GPU parity tests: run the same seeded inputs through the HIP path
 (via the C ABI binding) and through the CPU oracle.  No arithmetic of the method lives here."""
-import os
-
 import numpy as np
 import torch
 
@@ -35,23 +33,28 @@ class Case:
                 np.array_equal(host(self.W.low)[:self.o_low.size], self.o_low))
 
 
-# Kernel choices every case is run with: the library's own, then each kernel forced through the
-# NQ_KERNEL environment variable (1 generic, 2 windowed, 3 register-stationary, 4 large GEMM, 5 few
-# input channels, 6 few rows; a kernel
-# that does not apply to a shape is not forced, the library's choice runs again).
-KERNEL_CHOICES = ("", "1", "2", "3", "4", "5", "6")
+# Kernel choices every case is run with: the library's own, then each kernel forced through nq_set_tuning
+# (1 generic, 2 windowed, 3 register-stationary, 4 large GEMM, 5 few input channels, 6 few rows; a kernel
+# that does not apply to a shape is not forced, the library's choice runs again).  The large-GEMM kernel is
+# also run with every tile height it is built for (rows per block = 32 * TM, TM = 2..5): the library picks
+# the height from the shape, so without this a parity shape reaches one height only.
+KERNEL_CHOICES = ("", "1", "2", "3", "4", "4/tm2", "4/tm3", "4/tm4", "4/tm5", "5", "6")
 
 
-def each_kernel():
-    for k in KERNEL_CHOICES:
-        if k:
-            os.environ["NQ_KERNEL"] = k
-        else:
-            os.environ.pop("NQ_KERNEL", None)
+def set_choice(choice):
+    import paper_2506_17870_amd as nq
+    kernel, _, tm = choice.partition("/tm")
+    nq.nq_set_tuning(nq.NQ_TUNE_KERNEL, int(kernel) if kernel else 0)
+    nq.nq_set_tuning(nq.NQ_TUNE_BIG_TM, int(tm) if tm else 0)
+
+
+def each_kernel(choices=KERNEL_CHOICES):
+    for k in choices:
+        set_choice(k)
         try:
             yield k
         finally:
-            os.environ.pop("NQ_KERNEL", None)
+            set_choice("")
 
 
 def epi_pair(nq, case, full, M_shape, s_a=1.0, bias=None, residual=None, s_r=0.0, relu=False, out_int8=False,
@@ -99,7 +102,7 @@ def run_gemm_both(nq, case, x, full, **epi_kw):
             try:
                 check_outputs(host(y), host(keep["acc"]) if dump else None, y_ref, acc_ref, out_int8)
             except AssertionError as e:
-                raise AssertionError(f"{e} (NQ_KERNEL='{kernel}', accumulator dump {dump})") from None
+                raise AssertionError(f"{e} (kernel choice '{kernel}', accumulator dump {dump})") from None
 
 
 def run_conv_both(nq, case, x, shape, full, **epi_kw):
@@ -124,7 +127,7 @@ def run_conv_both(nq, case, x, shape, full, **epi_kw):
             try:
                 check_outputs(host(y), host(keep["acc"]) if dump else None, y_ref, acc_ref, out_int8)
             except AssertionError as e:
-                raise AssertionError(f"{e} (NQ_KERNEL='{kernel}', accumulator dump {dump})") from None
+                raise AssertionError(f"{e} (kernel choice '{kernel}', accumulator dump {dump})") from None
 
 
 def run_gconv_both(nq, case, x, shape, groups, full, **epi_kw):

@@ -210,3 +210,35 @@ def test_batch_paging_argument_checks_without_gpu(nq):
     with pytest.raises(nq.NQError) as e:
         nq.nq_weight_init_group([short])
     assert e.value.status == nq.NQ_ERR_RANGE
+
+
+def test_group_members_switch_through_the_batch_calls_only(nq):
+    # members of a group share their events; the single-page calls on one of them are refused on the host
+    a = 0x1000
+    cfg = nq.make_cfg(8, 2)
+    member = nq.nq_weight(cfg, 64, 64, a, 64 * 64 * 6 // 8, a, 64 * 64 * 2 // 8, a, a)
+    member.low_event, member.free_event = 0x10, 0x20     # never dereferenced: the check comes first
+    member.events_borrowed = 1
+    head = nq.nq_weight(cfg, 64, 64, a, 64 * 64 * 6 // 8, a, 64 * 64 * 2 // 8, a, a)
+    head.low_event, head.free_event = 0x10, 0x20
+    head.group_head = 1
+    for w in (member, head):
+        with pytest.raises(nq.NQError) as e:
+            nq.nq_page_in_low(w, 0)
+        assert e.value.status == nq.NQ_ERR_INVALID_ARG
+        with pytest.raises(nq.NQError) as e:
+            nq.nq_page_out_low(w, 0)
+        assert e.value.status == nq.NQ_ERR_INVALID_ARG
+        assert w.low_resident == 0 and w.free_event_armed == 0
+    member.low_event = member.free_event = None            # so that nothing tries to destroy the fake handles
+    head.low_event = head.free_event = None
+
+
+def test_tuning_setter_argument_checks(nq):
+    for key in (nq.NQ_TUNE_KERNEL, nq.NQ_TUNE_BIG_TM, nq.NQ_TUNE_GC_UNITS):
+        nq.nq_set_tuning(key, 3)
+        nq.nq_set_tuning(key, 0)
+    for key, value in ((-1, 0), (3, 0), (0, -1)):
+        with pytest.raises(nq.NQError) as e:
+            nq.nq_set_tuning(key, value)
+        assert e.value.status == nq.NQ_ERR_INVALID_ARG

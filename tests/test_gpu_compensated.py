@@ -106,7 +106,7 @@ def run_both_modes(nq, W, x, hi, w_full, scale, l, conv=None, out_int8=False):
                 try:
                     check_outputs(host(y), host(acc) if dump else None, y_ref, acc_ref, out_int8)
                 except AssertionError as e:
-                    raise AssertionError(f"{e} (full={full}, NQ_KERNEL='{kernel}', dump {dump})") from None
+                    raise AssertionError(f"{e} (full={full}, kernel choice '{kernel}', dump {dump})") from None
 
 
 @pytest.mark.parametrize("n,l", ALL_NL)

@@ -208,3 +208,69 @@ def test_glue_kernels(nq, oracle):
     y = torch.empty((5, 200), dtype=torch.int8, device="cuda")
     nq.nq_avgpool_i8(dev(x), 5, 49, 200, 0.05, 11.0, y)
     assert np.array_equal(host(y), oracle.avgpool(x, 0.05, 11.0))
+
+
+@pytest.mark.parametrize("fmt", ["unsigned", "compensated"])
+def test_large_kernel_every_tile_height(nq, fmt):
+    # The large-GEMM kernel is built for 64, 96, 128 and 160 rows per block and picks one from the shape.
+    # run_*_both force each height in turn (kernel choices "4/tm2" .. "4/tm5"): a GEMM and a 3x3 implicit
+    # GEMM with ragged row tiles, full-bit and part-bit, fp32, int8 and int8 + residual outputs.
+    from oracle import nq_oracle as oracle
+    n, l = 8, 2
+    low_format = nq.NQ_LOW_SIGNED_L1 if fmt == "compensated" else nq.NQ_LOW_UNSIGNED_L
+
+    def case_for(N, K, sigma, seed):
+        w_int, scale = inputs.weights(N, K, sigma, n, seed)
+        c = Case(nq, w_int, scale, n, l)
+        if fmt == "compensated":
+            # same weights in the compensated format: w_high rounded to nearest, signed (l+1)-bit lower part
+            c.cfg = nq.make_cfg(n, l, low_format)
+            c.W = nq.NestedWeight.from_int8(dev(w_int), dev(scale), c.cfg)
+            hi, _ = oracle.decompose(w_int, n, l, "rtn")
+            c.ow_part = hi.astype(np.int16)
+            c.ow_full = w_int.astype(np.int16)
+        return c
+
+    M, N, K = 700, 320, 512
+    case = case_for(N, K, 0.02, seed=77)
+    x = inputs.uniform_activations((M, K), seed=77)
+    res = inputs.uniform_activations((M, N), seed=78)
+    bias = inputs.small_floats(N, 0.3, seed=79)
+    for full in (True, False):
+        run_gemm_both(nq, case, x, full, s_a=0.02, bias=bias)
+        run_gemm_both(nq, case, x, full, s_a=0.02, bias=bias, relu=True, out_int8=True, inv_s_out=7.0)
+        run_gemm_both(nq, case, x, full, s_a=0.02, bias=bias, residual=res, s_r=0.04, relu=True, out_int8=True,
+                      inv_s_out=7.0)
+    B, H, W, Cin, Cout = 3, 15, 14, 64, 160
+    K = 9 * Cin
+    case = case_for(Cout, K, inputs.he_sigma(K), seed=80)
+    x = inputs.uniform_activations((B, H, W, Cin), seed=80)
+    for stride in (1, 2):
+        Ho, Wo = (H + 2 - 3) // stride + 1, (W + 2 - 3) // stride + 1
+        res = inputs.uniform_activations((B, Ho, Wo, Cout), seed=81)
+        bias = inputs.small_floats(Cout, 0.3, seed=82)
+        for full in (True, False):
+            run_conv_both(nq, case, x, (3, 3, stride, 1), full, s_a=0.02, bias=bias)
+            run_conv_both(nq, case, x, (3, 3, stride, 1), full, s_a=0.02, bias=bias, relu=True, out_int8=True,
+                          inv_s_out=5.0)
+            run_conv_both(nq, case, x, (3, 3, stride, 1), full, s_a=0.02, bias=bias, residual=res, s_r=0.04,
+                          relu=True, out_int8=True, inv_s_out=5.0)
+
+
+def test_failed_call_enqueues_nothing_and_keeps_the_timing_events(nq):
+    # a call that fails its checks must leave the one-shot profiling events for the next launch
+    N, K, M = 64, 256, 40
+    case = make_case(nq, N, K, 8, 2, seed=12)
+    x = dev(inputs.uniform_activations((M, K), seed=12))
+    y = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    ev0, ev1 = nq.nq_event_create(), nq.nq_event_create()
+    nq.nq_profile_next_launch(ev0, ev1)
+    short = nq.NestedWeight(N, K, case.cfg)
+    short.desc.high_bytes = 16
+    with pytest.raises(nq.NQError):
+        nq.nq_gemm_part(x, M, short.desc, nq.make_epilogue(0.02), y)
+    nq.nq_gemm_part(x, M, case.W.desc, nq.make_epilogue(0.02), y)
+    torch.cuda.synchronize()
+    assert nq.nq_event_elapsed_ms(ev0, ev1) > 0.0
+    nq.nq_event_destroy(ev0)
+    nq.nq_event_destroy(ev1)
