@@ -3,15 +3,22 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
-One step is one pass of the whole path over one batch of the ResNet-18-shaped 3x3
-convolution (batch 32, 56x56x64 -> 64, INT8 nesting INT6): decompose-and-pack the layer's
-INT8 weights, page the lower-bit page out, copy it back in from pinned host memory, run the
-part-bit convolution, then the full-bit convolution (which waits for the page).  By default
-the page travels on the compute stream: it is 9 KiB, its copy takes 4 us, and handing work
-between two hardware queues costs more than that per hand-over; --side-stream copies it on
-a second stream concurrently with the part-bit convolution instead.  Inputs are resident in
-HBM before the clock starts.  Prints one JSON line; see the design doc for how the roofline
-figures are derived.
+One step is one pass of the whole path over one batch of the largest single-GPU configuration: the
+ResNet-101-shaped conv/fc stack (104 convolutions + fc, 44.4 M weights, every layer INT8 nesting INT6) at
+batch 128, 224 x 224 x 3 input, int8 activations.  The weights are decomposed and packed once (setup), then
+every step switches the model down and up again and runs it in both modes:
+
+    nq_page_out_low_batch   downgrade: the lower-bit pages are paged out (nothing moves)
+    nq_page_in_low_batch    upgrade: 11.1 MB of lower-bit pages, one pinned host -> device copy
+    part-bit forward        105 nq_conv_part / nq_gemm_part launches + pooling (never reads the pages)
+    full-bit forward        105 nq_conv_full / nq_gemm_full launches + pooling (waits for the copy)
+
+By default all of it is issued on one stream; --side-stream sends the copy over a second stream so that it
+travels while the part-bit forward computes.  The step is captured once into a HIP graph and replayed, so the
+host issues one launch per step.  Inputs are resident in HBM before the clock starts; the only PCIe traffic in
+the timed region is the page-in, which is part of the path.  Prints one JSON line: whole-job TOPS, the roofline
+of the kernel instantiation that takes the largest share of the step, sub-records for the other
+configurations' dominant layers, and the CPU oracle on a reduced batch.
 """
 from __future__ import annotations
 
@@ -26,16 +33,18 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0     # MI355X HBM3E
-MFMA_INT8_PEAK_TOPS = 5000.0
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+MFMA_INT8_PEAK_TOPS = 5000.0     # MI355X dense int8 matrix-core peak
+RIDGE = MFMA_INT8_PEAK_TOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # op per byte above which the matrix cores bound a layer
 
-# HBM bytes per launch of the full-bit convolution from the FETCH_SIZE and WRITE_SIZE counters of a
-# profiling run, each scaled by what the same counter read for a 64 MiB streaming kernel (factors
-# 1.999 and 1.000).  They describe the kernel as it was when they were taken: `sources` is the
-# digest of the kernel's source files at that time, and a different digest reports no traffic.
-TRAFFIC = dict(fetch_bytes=int(6430.6 * 1024 * 1.999), write_bytes=int(25088.0 * 1024 * 1.000),
-               sources="22457a7f140f36d6")
-KERNEL_SOURCES = ("nq_conv_rowstream.h", "nq_epilogue.h", "nq_codec.h", "nq_gemm_params.h")
+# HBM bytes per launch of the dominant kernel from the FETCH_SIZE and WRITE_SIZE counters of a profiling run
+# (scaled by what the same counters read for a plain copy kernel of known size), keyed by the kernel
+# instantiation they were taken on and by a digest of the kernel's sources at that time: a different kernel or
+# digest reports no traffic.
+TRAFFIC = {}
+KERNEL_SOURCES = ("nq_gemm_big.h", "nq_epilogue.h", "nq_codec.h", "nq_gemm_params.h")
+FAMILY = {1: "k_nested_gemm", 2: "k_nested_conv_window", 3: "k_nested_conv_rowstream", 4: "k_nested_gemm_big",
+          5: "k_nested_conv_smallcin", 6: "k_nested_gemm_skinny", 7: "k_nested_conv_grouped", 8: "k_nested_gemm_words"}
 
 
 def kernel_sources_digest():
@@ -47,49 +56,127 @@ def kernel_sources_digest():
     return h.hexdigest()[:16]
 
 
-def cpu_baseline(inputs, cfg_conv, w_int, scale, x_all, s_a, bias, budget_s=12.0):
-    """The CPU oracle, as it stands, on a bounded sample (whole images) of the same workload."""
-    import numpy as np
+def forward_ops(ops, network, H, W):
+    """Integer operations (2 per multiply-add) of one image's forward pass."""
+    hw, macs = {0: (H, W)}, 0
+    for op in ops:
+        hs, ws = hw[op["src"]]
+        if op["op"] == "conv":
+            ho, wo = network.out_hw(hs, ws, op["k"], op["stride"], op["pad"])
+            macs += ho * wo * op["cout"] * op["k"] ** 2 * op["cin"]
+            hw[op["dst"]] = (ho, wo)
+        elif op["op"] == "maxpool":
+            hw[op["dst"]] = network.out_hw(hs, ws, op["k"], op["stride"], op["pad"])
+        elif op["op"] == "avgpool":
+            hw[op["dst"]] = (1, 1)
+        else:
+            macs += op["cin"] * op["cout"]
+    return 2.0 * macs
+
+
+def stamped_forward(model, binding, dx, s_x, full):
+    """One eager forward with every GEMM / convolution dispatch time-stamped (begin and end of the kernel
+    itself, what a kernel trace reports).  Returns one record per launch: the kernel instantiation the library
+    chose, its duration, its operations and its algorithmic bytes (input once, pages once, residual once,
+    output once)."""
+    recs, names = [], ("nq_conv_full", "nq_conv_part", "nq_gemm_full", "nq_gemm_part")
+    originals = {n: getattr(binding, n) for n in names}
+    h_bits, l_bits = model.n_bits - model.l_bits, model.l_bits
+
+    def stamped(name):
+        orig = originals[name]
+
+        def call(*a, **k):
+            e0, e1 = binding.nq_event_create(), binding.nq_event_create()
+            binding.nq_profile_next_launch(e0, e1)
+            orig(*a, **k)
+            fam, var = binding.nq_profile_last_kernel()
+            conv = name.startswith("nq_conv")
+            wd, epi = a[2], a[3]
+            if conv:
+                sh = a[1]
+                ho = (sh.H + 2 * sh.pad - sh.KH) // sh.stride + 1
+                wo = (sh.W + 2 * sh.pad - sh.KW) // sh.stride + 1
+                m, x_bytes = sh.B * ho * wo, sh.B * sh.H * sh.W * sh.Cin
+                layer = f"{sh.KH}x{sh.KW} s{sh.stride} {sh.H}x{sh.W} {sh.Cin}->{sh.Cout}"
+                filt = sh.KH * sh.KW > 1 or sh.stride > 1
+            else:
+                m, x_bytes = a[1], a[1] * wd.K
+                layer = f"fc {wd.K}->{wd.N}"
+                filt = False
+            out_bytes = m * wd.N * (1 if epi.out_int8 else 4)
+            pages = binding.nq_packed_bytes(wd.N, wd.K, h_bits) + (binding.nq_packed_bytes(wd.N, wd.K, l_bits) if full else 0)
+            byts = x_bytes + pages + out_bytes + (m * wd.N if epi.d_residual else 0) + 8 * wd.N
+            if epi.d_residual:
+                layer += " + residual"
+            inst = FAMILY.get(fam, "?") + f"<{h_bits},{l_bits},{'full' if full else 'part'}"
+            if fam == 4:
+                inst += f",{'int8' if epi.out_int8 else 'fp32'} out,TM={var},{'filter' if filt else 'plain'}"
+            inst += ">"
+            recs.append(dict(e=(e0, e1), inst=inst, layer=layer, ops=2.0 * m * wd.N * wd.K, bytes=byts))
+        return call
+    for n in names:
+        setattr(binding, n, stamped(n))
+    try:
+        model.forward(dx, s_x, full=full)
+        import torch
+        torch.cuda.synchronize()
+    finally:
+        for n, orig in originals.items():
+            setattr(binding, n, orig)
+    for r in recs:
+        e0, e1 = r.pop("e")
+        r["us"] = binding.nq_event_elapsed_ms(e0, e1) * 1e3
+        binding.nq_event_destroy(e0)
+        binding.nq_event_destroy(e1)
+    return recs
+
+
+def cpu_baseline(model_ops, weights, x, s_x, scales, n_bits, l_bits, ops_img):
+    """The CPU oracle, as it stands, on a reduced batch of the same workload (whole network, full-bit and
+    part-bit forward with the same activation steps): all OpenMP threads on the first images, one thread on
+    the first image.  Returns the record and the oracle's logits for the comparison with the GPU's."""
     from oracle import nq_oracle as oracle
-    n, l = cfg_conv["n_bits"], cfg_conv["l_bits"]
-    Cout, Cin, KH, KW = cfg_conv["Cout"], cfg_conv["Cin"], cfg_conv["KH"], cfg_conv["KW"]
-    K = KH * KW * Cin
-    ops_img = 2 * 2 * cfg_conv["H"] * cfg_conv["W"] * Cout * K       # full-bit + part-bit, stride 1 pad 1
+    from oracle.nq_oracle_cnn import oracle_cnn_forward
+    omp = ctypes.CDLL("libgomp.so.1")
+    nthreads = oracle.threads()
 
-    def run(nimg):
+    cache = {}
+
+    def run(nimg, threads):
+        omp.omp_set_num_threads(threads)
         t0 = time.perf_counter()
-        ph, pl = oracle.decompose_pack(w_int, n, l)
-        outs = []
-        for pages, part_l in ((None, l), (pl, 0)):
-            w = oracle.weights_from_pages(ph, pages, Cout, K, n, l).reshape(Cout, KH, KW, Cin)
-            acc = oracle.conv_acc(x_all[:nimg], w, cfg_conv["stride"], cfg_conv["pad"])
-            outs.append(oracle.epilogue(acc, s_a, scale, part_l_bits=part_l, bias=bias, relu=True))
-        return time.perf_counter() - t0, outs
-
-    run(1)                                                    # first call pays the library load
-    nimg = x_all.shape[0]
-    t, outs = run(nimg)
-    total, reps = t, 1
-    while total < budget_s and reps < 200:                    # repeat the batch up to the time budget
-        dt, _ = run(nimg)
-        total, reps = total + dt, reps + 1
-    return dict(value=ops_img * nimg * reps / total / 1e12, unit="TOPS", cores=oracle.threads(), kind="oracle",
-                sample=f"{reps} x the {nimg}-image batch of the same convolution (decompose+pack, part-bit, "
-                       f"full-bit), {total:.1f} s, plain C loops -O2 with OpenMP"), nimg, outs
+        lf, _, _ = oracle_cnn_forward(model_ops, weights, x[:nimg], s_x, n_bits, l_bits, True, scales, cache)
+        lp, _, _ = oracle_cnn_forward(model_ops, weights, x[:nimg], s_x, n_bits, l_bits, False, scales, cache)
+        omp.omp_set_num_threads(nthreads)
+        return time.perf_counter() - t0, lf, lp
+    # setup, not timed (as on the GPU side): the oracle decomposes, packs and unpacks every layer's weights once
+    run(1, nthreads)
+    n_all = 8
+    t_all, lf, lp = run(n_all, nthreads)
+    t_one, _, _ = run(1, 1)
+    rec = dict(value=2 * ops_img * n_all / t_all / 1e12, unit="TOPS", cores=nthreads, kind="oracle",
+               sample=f"whole ResNet-101-shaped network, full-bit + part-bit forward (direct convolution loops, "
+                      f"fp32 epilogue, pooling) on the first {n_all} of the batch's images with {nthreads} OpenMP "
+                      f"threads: {t_all:.1f} s; plain C loops -O2; weights decomposed, packed and unpacked once before",
+               single_thread=dict(value=2 * ops_img / t_one / 1e12, unit="TOPS", cores=1,
+                                  sample=f"the same on the first image with one thread: {t_one:.1f} s"))
+    return rec, n_all, lf, lp
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
-    ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--sets", type=int, default=8, help="distinct activation/output buffer sets rotated "
-                    "through, so that the working set exceeds the 256 MB Infinity Cache")
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=128, help="images per step (the configuration is quoted at 128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sub-records", action="store_true", help="skip the per-layer measurements of the other "
+                    "configurations (conv 56x56x64, bottleneck 3x3, ViT MLP)")
     ap.add_argument("--eager", action="store_true", help="issue every call of the timed steps from Python instead of "
-                    "replaying a captured HIP graph of `sets` consecutive steps")
-    ap.add_argument("--side-stream", action="store_true", help="copy the lower-bit page in on a second stream, "
-                    "concurrently with the part-bit convolution (default: on the compute stream, see DESIGN.md)")
+                    "replaying a captured HIP graph of one step")
+    ap.add_argument("--side-stream", action="store_true", help="copy the lower-bit pages in on a second stream, "
+                    "concurrently with the part-bit forward (default: on the compute stream)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs; "
@@ -99,151 +186,154 @@ def main():
     import torch
 
     import paper_2506_17870_amd as nq
-    from paper_2506_17870_amd import binding, inputs
+    from paper_2506_17870_amd import binding, inputs, network
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
-    lib = binding._lib
 
-    c = inputs.CONV_RESNET18
-    B, H, W, Cin, Cout, KH, KW = c["B"], c["H"], c["W"], c["Cin"], c["Cout"], c["KH"], c["KW"]
-    n_bits, l_bits = c["n_bits"], c["l_bits"]
-    h_bits = n_bits - l_bits
-    K = KH * KW * Cin
-    Ho, Wo = H, W
-    M = B * Ho * Wo
-    ops_conv = 2 * M * Cout * K
+    # ---- synthetic model and inputs, resident before the clock starts ----------------------
+    n_bits, l_bits, B, HW = 8, 2, args.batch, 224
+    ops = network.resnet101_plan()
+    weights = network.plan_weights(ops, n_bits, seed=0)
+    model = network.NestedCNN(ops, weights, n_bits, l_bits)          # nq_decompose_pack_batch: a1 + a2, once
+    x, s_x = inputs.gaussian_activations((B, HW, HW, 3), seed=0)
+    dx = torch.from_numpy(x).cuda()
+    model.allocate(B, HW, HW)
+    model.calibrate(dx, float(s_x))                                   # int8 steps of the activations, once
+    ops_img = forward_ops(ops, network, HW, HW)
+    ops_step = 2 * ops_img * B
+    low_bytes = model.low_page_bytes()
 
-    # ---- synthetic inputs, resident before the clock starts --------------------------------
-    w_int, scale = inputs.weights(Cout, K, inputs.he_sigma(K), n_bits, seed=0)
-    bias = inputs.small_floats(Cout, 0.1, seed=2)
-    s_a = 0.02
-    cfg = nq.make_cfg(n_bits, l_bits)
-    d_w_int = torch.from_numpy(w_int).cuda()
-    Wn = nq.NestedWeight.from_int8(d_w_int, torch.from_numpy(scale).cuda(), cfg)
-    d_bias = torch.from_numpy(bias).cuda()
-    R = max(1, args.sets)
-    x_host = [inputs.uniform_activations((B, H, W, Cin), seed=r) for r in range(R)]
-    xs = [torch.from_numpy(x).cuda() for x in x_host]
-    y_part = [torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device="cuda") for _ in range(R)]
-    y_full = [torch.empty((B, Ho, Wo, Cout), dtype=torch.float32, device="cuda") for _ in range(R)]
+    compute = torch.cuda.Stream()
+    side = torch.cuda.Stream() if args.side_stream else None
 
-    shape = nq.nq_conv_shape(B, H, W, Cin, Cout, KH, KW, c["stride"], c["pad"])
-    epi = nq.make_epilogue(s_a, d_bias, None, 0.0, True, False, 1.0, None)
-    compute = torch.cuda.current_stream()
-    copy = torch.cuda.Stream() if args.side_stream else compute
-    cs, ps = ctypes.c_void_p(compute.cuda_stream), ctypes.c_void_p(copy.cuda_stream)
-    wref, eref, sref, cref = ctypes.byref(Wn.desc), ctypes.byref(epi), ctypes.byref(shape), ctypes.byref(cfg)
-    p_w, p_hi, p_lo = ctypes.c_void_p(d_w_int.data_ptr()), ctypes.c_void_p(Wn.high.data_ptr()), \
-        ctypes.c_void_p(Wn.low.data_ptr())
-    p_x = [ctypes.c_void_p(t.data_ptr()) for t in xs]
-    p_yp = [ctypes.c_void_p(t.data_ptr()) for t in y_part]
-    p_yf = [ctypes.c_void_p(t.data_ptr()) for t in y_full]
+    def step(st):
+        model.page_out_low(st)                                       # a3: downgrade
+        model.page_in_low(side if side is not None else st)          # a4: upgrade travels ...
+        model.forward(dx, s_x, full=False, stream=st)                # a6 + a7 + a8: ... while part-bit computes
+        model.forward(dx, s_x, full=True, stream=st)                 # a5 + a7 + a8: waits for the pages
 
-    def step(i, ev=None):
-        r = i % R
-        rc = lib.nq_decompose_pack(p_w, Cout, K, cref, p_hi, p_lo, cs)          # a1 + a2
-        rc |= lib.nq_page_out_low(wref, cs)                                     # a3: downgrade
-        rc |= lib.nq_page_in_low(wref, ps)                                      # a4: upgrade (waits for the
-                                                                                # page-out point)
-        rc |= lib.nq_conv_part(p_x[r], sref, wref, eref, p_yp[r], cs)           # a6 + a7
-        if ev is not None:
-            lib.nq_profile_next_launch(ev[0], ev[1])                            # time stamps of this dispatch
-        rc |= lib.nq_conv_full(p_x[r], sref, wref, eref, p_yf[r], cs)           # a5 + a7, waits for the page
-        if rc:
-            raise RuntimeError(f"libnq returned an error in step {i}")
-
-    # One plain streaming kernel of known size (reads 64 MiB, writes 64 MiB, both initialised): the
-    # yardstick the HBM byte counters of a profiling run are scaled by.
-    cal_src = torch.ones(16 << 20, dtype=torch.int32, device="cuda")
-    cal_dst = torch.zeros_like(cal_src)
-    for _ in range(3):
-        torch.add(cal_src, 1, out=cal_dst)
-
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-
-    # ---- timed region: K steps.  The calls of R consecutive steps (one per buffer set) are captured
-    # once into a HIP graph and replayed, so the host issues one launch per R steps; K % R steps
-    # left over are issued call by call.
-    graph = None
-    if not args.eager and args.steps >= R:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            cap = torch.cuda.current_stream()
-            cs_saved, ps_saved = cs, ps
-            cs = ctypes.c_void_p(cap.cuda_stream)
-            if not args.side_stream:
-                ps = cs
-            for i in range(R):
-                step(i)
-            cs, ps = cs_saved, ps_saved
+    with torch.cuda.stream(compute):
+        for _ in range(max(args.warmup, 1)):
+            step(compute)
+        compute.synchronize()
+        graph = None
+        if not args.eager:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=compute):
+                step(compute)
+            graph.replay()
+            compute.synchronize()
         torch.cuda.synchronize()
-    n_replay = args.steps // R if graph is not None else 0
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(n_replay):
-        graph.replay()
-    for i in range(n_replay * R, args.steps):
-        step(i)
-    t_issue = time.perf_counter()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            if graph is not None:
+                graph.replay()
+            else:
+                step(compute)
+        t_issue = time.perf_counter()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     elapsed = t1 - t0
+    host_issue_ms = 1e3 * (t_issue - t0) / args.steps
     ms_per_step = 1e3 * elapsed / args.steps
-    value = 2 * ops_conv * args.steps / elapsed / 1e12
+    value = ops_step * args.steps / elapsed / 1e12
 
-    # ---- duration of the dominant kernel: the same steps once more, each full-bit convolution
-    # dispatch time-stamped (begin/end of the kernel itself, what a kernel trace reports)
-    n_probe = min(args.steps, 200)
-    events = [(ctypes.c_void_p(nq.nq_event_create()), ctypes.c_void_p(nq.nq_event_create()))
-              for _ in range(n_probe)]
-    for i in range(n_probe):
-        step(i, events[i])
+    # ---- where the step's time goes: every dispatch of one part-bit and one full-bit forward stamped ----
     torch.cuda.synchronize()
-    kern_ms = sorted(nq.nq_event_elapsed_ms(a, b) for a, b in events)
-    for a, b in events:
-        nq.nq_event_destroy(a)
-        nq.nq_event_destroy(b)
-    full_ms = sum(kern_ms) / len(kern_ms)
-    # algorithmic bytes of one full-bit convolution launch: activations once, both packed pages once,
-    # scales and bias once, fp32 outputs once
-    bytes_conv_full = (M * Cin * 1 + nq.nq_packed_bytes(Cout, K, h_bits) + nq.nq_packed_bytes(Cout, K, l_bits)
-                       + 2 * 4 * Cout + 4 * M * Cout)
-    achieved = bytes_conv_full / (full_ms * 1e-3) / 1e9
+    model.page_out_low()                                    # the events of the switch recorded eagerly again:
+    model.page_in_low()                                     # their last record was inside the captured step
+    torch.cuda.synchronize()
+    recs = []
+    for rep in range(3):
+        recs += stamped_forward(model, binding, dx, s_x, False) + stamped_forward(model, binding, dx, s_x, True)
+    groups = {}
+    for r in recs:
+        g = groups.setdefault(r["inst"], dict(n=0, us=0.0, ops=0.0, bytes=0.0, layers={}))
+        g["n"] += 1; g["us"] += r["us"]; g["ops"] += r["ops"]; g["bytes"] += r["bytes"]
+        g["layers"][r["layer"]] = g["layers"].get(r["layer"], 0) + 1
+    kern_us_step = sum(r["us"] for r in recs) / 3
+    inst, g = max(groups.items(), key=lambda kv: kv[1]["us"])
+    avg_us = g["us"] / g["n"]
+    ops_launch, bytes_launch = g["ops"] / g["n"], g["bytes"] / g["n"]
+    bound = "mfma" if ops_launch / bytes_launch > RIDGE else "hbm"
+    if bound == "mfma":
+        achieved, peak, unit = ops_launch / avg_us / 1e6, MFMA_INT8_PEAK_TOPS, "TOP/s"
+    else:
+        achieved, peak, unit = bytes_launch / avg_us / 1e3, HBM_PEAK_GBS, "GB/s"
     traffic = None
-    if TRAFFIC["sources"] == kernel_sources_digest():
-        traffic = TRAFFIC["fetch_bytes"] + TRAFFIC["write_bytes"]
-    roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                    traffic=traffic, kernel="k_nested_conv_rowstream<6,2,full> (nq_conv_full)",
-                    avg_kernel_us=1e3 * full_ms, median_kernel_us=1e3 * kern_ms[len(kern_ms) // 2],
-                    algorithmic_bytes=bytes_conv_full,
-                    mfma_tops=ops_conv / (full_ms * 1e-3) / 1e12,
-                    mfma_frac=ops_conv / (full_ms * 1e-3) / 1e12 / MFMA_INT8_PEAK_TOPS)
+    t = TRAFFIC.get(inst)
+    if t and t["sources"] == kernel_sources_digest():
+        traffic = t["fetch_bytes"] + t["write_bytes"]
+    roofline = dict(bound=bound, achieved=achieved, peak=peak, unit=unit, frac=achieved / peak, traffic=traffic,
+                    kernel=inst, launches_per_step=g["n"] // 3, avg_kernel_us=avg_us,
+                    share_of_step_kernel_time=g["us"] / 3 / kern_us_step,
+                    ops_per_launch=ops_launch, algorithmic_bytes=bytes_launch,
+                    layers={k: v // 3 for k, v in g["layers"].items()},
+                    hbm_frac=bytes_launch / avg_us / 1e3 / HBM_PEAK_GBS,
+                    mfma_frac=ops_launch / avg_us / 1e6 / MFMA_INT8_PEAK_TOPS)
+    by_inst = sorted(((k, v["us"] / 3, v["n"] // 3, v["ops"] / v["us"] / 1e6, v["bytes"] / v["us"] / 1e3)
+                      for k, v in groups.items()), key=lambda e: -e[1])
+    breakdown = [dict(kernel=k, us_per_step=round(us, 1), launches=n, tops=round(tops, 1), algorithmic_gbs=round(gbs))
+                 for k, us, n, tops, gbs in by_inst[:8]]
 
-    out = dict(metric="nested int8 conv TOPS (full-bit + part-bit)", value=value, unit="TOPS", n_gpus=1,
+    # ---- the switch alone: host -> device GB/s of the page-in ----
+    sw = torch.cuda.Stream()
+    t_in = []
+    for _ in range(7):
+        model.page_out_low()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        model.page_in_low(sw)
+        sw.synchronize()
+        t_in.append(time.perf_counter() - t0)
+    t_in = sorted(t_in)[len(t_in) // 2]
+    switch = dict(page_in_bytes=low_bytes, page_in_us=t_in * 1e6, h2d_gbs=low_bytes / t_in / 1e9, page_out_moves_bytes=0)
+
+    out = dict(metric="nested int8 GEMM/conv TOPS (full-bit + part-bit)", value=value, unit="TOPS", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True,
                scaling="weak", vs_baseline=None, dtype="int8", data="synthetic",
-               config=dict(workload="ResNet-18-shaped 3x3 conv, stride 1 pad 1, batch 32, 56x56x64 -> 64, NHWC int8 "
-                                    "activations, per-channel INT8 nesting INT6 (l=2), fp32 outputs with bias+ReLU; "
-                                    "step = decompose_pack + page-out + page-in + part-bit conv + full-bit conv"
-                                    + (" (page-in on a second stream)" if args.side_stream else ""),
-                           buffer_sets=R, ops_per_step=2 * ops_conv,
-                           host_issue_ms_per_step=1e3 * (t_issue - t0) / args.steps,
-                           issue="hip graph of %d steps" % R if graph is not None else "eager"),
-               roofline=roofline)
+               config=dict(workload=f"ResNet-101-shaped conv/fc stack (104 convolutions + fc, 44.4 M He-normal weights, "
+                                    f"all layers per-channel INT8 nesting INT6, l=2), batch {B}, 224x224x3 N(0,1) input, "
+                                    "int8 per-layer activations; step = page-out of all lower-bit pages + page-in "
+                                    f"({low_bytes / 1e6:.1f} MB pinned host->device"
+                                    + (", on a second stream" if side is not None else "")
+                                    + ") + part-bit forward + full-bit forward",
+                           batch=B, ops_per_step=ops_step, gmac_per_image=ops_img / 2e9,
+                           host_issue_ms_per_step=host_issue_ms,
+                           issue="hip graph of one step" if graph is not None else "eager",
+                           kernel_us_per_step=kern_us_step, mfma_frac_whole_step=value / MFMA_INT8_PEAK_TOPS),
+               roofline=roofline, kernels=breakdown, switch=switch)
+
+    if not args.no_sub_records:
+        import contextlib
+        import io
+        import bench_configs as bc
+        with contextlib.redirect_stdout(io.StringIO()):
+            sub = []
+            sub += bc.conv("c2 conv 3x3 56x56x64->64 batch 32 l=2", 32, 56, 56, 64, 64, 3, 1, 1, 2, out8=False, sets=8, quiet=True)
+            sub += bc.conv("c3 conv 3x3 14x14x256->256 batch 64 l=2", 64, 14, 14, 256, 256, 3, 1, 1, 2, quiet=True)
+            sub += bc.conv("c3 conv 3x3 14x14x256->256 batch 64 l=4", 64, 14, 14, 256, 256, 3, 1, 1, 4, quiet=True)
+            sub += bc.gemm("c5 ViT fc1 12608x768->3072 l=3", 12608, 768, 3072, 3, quiet=True)
+            sub += bc.gemm("c5 ViT fc1 12608x768->3072 l=3", 12608, 768, 3072, 3, out8=True, quiet=True)
+            sub += bc.gemm("c5 ViT fc2 12608x3072->768 l=3", 12608, 3072, 768, 3, quiet=True)
+            sub += bc.gemm("c5 ViT fc2 12608x3072->768 l=3", 12608, 3072, 768, 3, out8=True, quiet=True)
+        for r in sub:
+            us = r["kernel_us"]
+            r["tops"] = r.pop("ops") / us / 1e6
+            r["mfma_frac"] = r["tops"] / MFMA_INT8_PEAK_TOPS
+            r["hbm_frac"] = r["algorithmic_bytes"] / us / 1e3 / HBM_PEAK_GBS
+        out["sub_records"] = sub
 
     if not args.no_cpu_baseline:
-        base, nimg, outs = cpu_baseline(inputs, c, w_int, scale, x_host[0], s_a, bias)
-        # the timed loop's outputs for buffer set 0 must equal the oracle's on the sampled images
-        step(0)
-        torch.cuda.synchronize()
-        ok = (np.array_equal(y_part[0][:nimg].cpu().numpy(), outs[0]) and
-              np.array_equal(y_full[0][:nimg].cpu().numpy(), outs[1]))
-        if not ok:
-            raise RuntimeError("bench.py: GPU outputs differ from the oracle on the sampled images")
+        scales = {t: s for t, s in enumerate(model.out_scale) if s is not None}
+        base, nimg, lf, lp = cpu_baseline(ops, weights, x, float(s_x), scales, n_bits, l_bits, ops_img)
+        # the GPU's logits for the sampled images must equal the oracle's, in both modes
+        g_part = model.forward(dx, s_x, full=False).cpu().numpy()[:nimg].copy()
+        g_full = model.forward(dx, s_x, full=True).cpu().numpy()[:nimg].copy()
+        if not (np.array_equal(g_part, lp) and np.array_equal(g_full, lf)):
+            raise RuntimeError("bench.py: GPU logits differ from the oracle's on the sampled images")
         base["gpu_matches_oracle_on_sample"] = True
         out["cpu_baseline"] = base
     print(json.dumps(out))

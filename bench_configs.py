@@ -72,7 +72,7 @@ def header(title):
     print("|---|---|---|---|---|---|---|")
 
 
-def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8, layout=None):
+def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8, layout=None, quiet=False):
     layout = nq.NQ_LAYOUT_DENSE if layout is None else layout
     w_int, scale = inputs.weights(N, K, sigma, n_bits, 0)
     W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(),
@@ -81,6 +81,7 @@ def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8, layout=None
     xs = [torch.from_numpy(inputs.uniform_activations((M, K), i) >> (8 - n_bits)).cuda() for i in range(sets)]
     ys = [torch.empty((M, N), dtype=torch.int8 if out8 else torch.float32, device="cuda") for _ in range(sets)]
     epi = nq.make_epilogue(0.02, out_int8=out8, inv_out_scale=3.0)
+    results = []
     for full in (True, False):
         cnt = [0]
 
@@ -92,11 +93,15 @@ def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8, layout=None
             (nq.nq_gemm_full if full else nq.nq_gemm_part)(xs[i], M, W.desc, epi, ys[i])
         med, _ = kernel_us(fn)
         wb = nq.nq_packed_bytes(N, K, n_bits - l, layout) + (nq.nq_packed_bytes(N, K, l, layout) if full else 0)
-        row(name, ("full" if full else "part") + (" int8 out" if out8 else " fp32 out"), med, 2.0 * M * N * K,
-            M * K + wb + M * N * (1 if out8 else 4))
+        mode = ("full" if full else "part") + (" int8 out" if out8 else " fp32 out")
+        ops, byts = 2.0 * M * N * K, M * K + wb + M * N * (1 if out8 else 4)
+        if not quiet:
+            row(name, mode, med, ops, byts)
+        results.append(dict(layer=name, mode=mode, kernel_us=med, ops=ops, algorithmic_bytes=byts))
+    return results
 
 
-def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4):
+def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4, quiet=False):
     K = k * k * Cin
     w_int, scale = inputs.weights(Cout, K, inputs.he_sigma(K), 8, 0)
     W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
@@ -106,6 +111,7 @@ def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4):
           for _ in range(sets)]
     epi = nq.make_epilogue(0.02, relu=True, out_int8=out8, inv_out_scale=3.0)
     cs = nq.nq_conv_shape(B, H, W_, Cin, Cout, k, k, stride, pad)
+    results = []
     for full in (True, False):
         cnt = [0]
 
@@ -118,8 +124,12 @@ def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4):
         med, _ = kernel_us(fn)
         M = B * Ho * Wo
         wb = nq.nq_packed_bytes(Cout, K, 8 - l) + (nq.nq_packed_bytes(Cout, K, l) if full else 0)
-        row(name, ("full" if full else "part") + (" int8 out" if out8 else " fp32 out"), med, 2.0 * M * Cout * K,
-            B * H * W_ * Cin + wb + M * Cout * (1 if out8 else 4))
+        mode = ("full" if full else "part") + (" int8 out" if out8 else " fp32 out")
+        ops, byts = 2.0 * M * Cout * K, B * H * W_ * Cin + wb + M * Cout * (1 if out8 else 4)
+        if not quiet:
+            row(name, mode, med, ops, byts)
+        results.append(dict(layer=name, mode=mode, kernel_us=med, ops=ops, algorithmic_bytes=byts))
+    return results
 
 
 def gconv(name, B, H, W_, C, groups, k, stride, l, sets=6):
@@ -344,8 +354,7 @@ def c4():
     B = 128
     x, s_x = inputs.gaussian_activations((B, 224, 224, 3), seed=0)
     dx = torch.from_numpy(x).cuda()
-    model.forward(dx, s_x, full=True, calibrate=True)
-    torch.cuda.synchronize()
+    model.calibrate(dx, s_x)
     macs = 0
     h = w = 224
     hw = {0: (224, 224)}

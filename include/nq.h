@@ -174,6 +174,13 @@ size_t nq_packed_bytes(int64_t N, int64_t K, int field_bits, int layout);
 nq_status nq_quantize(const float *d_w, int64_t N, int64_t K, int n_bits, int8_t *d_w_int,
                       float *d_scale, void *stream);
 
+/* The step of Eq. 1 for a whole tensor, as the per-tensor quantisation of the 8-bit activations uses it
+ * (Sec. 4.2): d_scale[0] = max_i |d_x[i]| / (2^(n_bits-1) - 1), 1.0 for an all-zero (or empty) tensor; the
+ * quotient is taken in fp32.  Calibrating a network's activation steps needs nothing else from the device.
+ * In: device fp32[count], finite.  Out: device fp32[1] (also used as the accumulator: three small launches).
+ * n_bits in 2..8.  NQ_ERR_ALIGN if a pointer is not 4-byte aligned. */
+nq_status nq_tensor_scale(const float *d_x, int64_t count, int n_bits, float *d_scale, void *stream);
+
 /* Eq. 1 followed by the decomposition and packing of nq_decompose_pack (Alg. 1 steps 1-3) without the
  * int8 tensor in between: one pass over the fp32 weights for the channel scales, one that quantises,
  * splits and writes the pages.  Same pages as nq_quantize + nq_decompose_pack.  NQ_LAYOUT_DENSE only
@@ -304,6 +311,11 @@ nq_status nq_set_tuning(int key, int value);
  * hipEvent_t (either may be NULL) to its kernel dispatch, so that hipEventElapsedTime(start,
  * stop) is the execution time of that kernel alone.  One shot; events are the caller's. */
 nq_status nq_profile_next_launch(void *start_event, void *stop_event);
+/* Profiling aid: which kernel the last nq_gemm_* / nq_conv_* / nq_gconv_* launch of this host thread ran:
+ * *family as in NQ_TUNE_KERNEL (7 = depthwise / grouped, 8 = word pages; 0 before the first launch), *variant
+ * the tile height of the large-GEMM kernel (2..5), the tile shape of the generic kernel, else 0.  Lets a
+ * benchmark group its time stamps by kernel instantiation, as a kernel trace does.  Either pointer may be NULL. */
+nq_status nq_profile_last_kernel(int *family, int *variant);
 /* Timing events for the call above: create / destroy a hipEvent_t, and the milliseconds
  * between two completed events (blocks until stop_event has completed). */
 nq_status nq_event_create(void **event);

@@ -23,12 +23,12 @@ NQ_LAYOUT_DENSE, NQ_LAYOUT_PAPER_U64 = 0, 1
 NQ_MAX_K = 65536
 NQ_TUNE_KERNEL, NQ_TUNE_BIG_TM, NQ_TUNE_GC_UNITS = 0, 1, 2
 
-EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "nq_quantize_decompose_pack",
+EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "nq_tensor_scale", "nq_quantize_decompose_pack",
            "nq_decompose", "nq_pack", "nq_decompose_pack", "nq_decompose_pack_batch",
            "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
            "nq_weight_init_group", "nq_page_out_low_batch", "nq_page_in_low_batch",
            "nq_gemm_full", "nq_gemm_part", "nq_conv_full", "nq_conv_part", "nq_gconv_full", "nq_gconv_part",
-           "nq_set_tuning", "nq_profile_next_launch", "nq_event_create", "nq_event_destroy",
+           "nq_set_tuning", "nq_profile_next_launch", "nq_profile_last_kernel", "nq_event_create", "nq_event_destroy",
            "nq_event_elapsed_ms", "nq_maxpool_i8", "nq_avgpool_i8"]
 
 
@@ -78,6 +78,7 @@ _SIGS = {
     "nq_status_string": (ctypes.c_char_p, [_int]),
     "nq_packed_bytes": (ctypes.c_size_t, [_i64, _i64, _int, _int]),
     "nq_quantize": (_int, [_vp, _i64, _i64, _int, _vp, _vp, _vp]),
+    "nq_tensor_scale": (_int, [_vp, _i64, _int, _vp, _vp]),
     "nq_quantize_decompose_pack": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp, _vp]),
     "nq_decompose": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
     "nq_pack": (_int, [_vp, _vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
@@ -99,6 +100,7 @@ _SIGS = {
     "nq_gconv_part": (_int, [_vp, _sp, _int, _wp, _ep, _vp, _vp]),
     "nq_set_tuning": (_int, [_int, _int]),
     "nq_profile_next_launch": (_int, [_vp, _vp]),
+    "nq_profile_last_kernel": (_int, [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]),
     "nq_event_create": (_int, [ctypes.POINTER(ctypes.c_void_p)]),
     "nq_event_destroy": (_int, [_vp]),
     "nq_event_elapsed_ms": (_int, [_vp, _vp, ctypes.POINTER(ctypes.c_float)]),
@@ -166,6 +168,10 @@ def nq_pack(d_high, d_low, N, K, cfg, d_packed_high, d_packed_low, stream=None):
 
 def nq_quantize(d_w, N, K, n_bits, d_w_int, d_scale, stream=None):
     _check(_lib.nq_quantize(_ptr(d_w), N, K, n_bits, _ptr(d_w_int), _ptr(d_scale), _stream(stream)), "nq_quantize")
+
+
+def nq_tensor_scale(d_x, count, n_bits, d_scale, stream=None):
+    _check(_lib.nq_tensor_scale(_ptr(d_x), count, n_bits, _ptr(d_scale), _stream(stream)), "nq_tensor_scale")
 
 
 def nq_quantize_decompose_pack(d_w, N, K, cfg, d_scale, d_packed_high, d_packed_low, stream=None):
@@ -267,6 +273,13 @@ def nq_set_tuning(key: int, value: int):
 def nq_profile_next_launch(start_event, stop_event):
     """Raw hipEvent_t handles (integers) or None."""
     _check(_lib.nq_profile_next_launch(start_event, stop_event), "nq_profile_next_launch")
+
+
+def nq_profile_last_kernel():
+    """(family, variant) of the last GEMM / convolution launch of this thread."""
+    fam, var = ctypes.c_int(), ctypes.c_int()
+    _check(_lib.nq_profile_last_kernel(ctypes.byref(fam), ctypes.byref(var)), "nq_profile_last_kernel")
+    return fam.value, var.value
 
 
 def nq_event_create() -> int:

@@ -22,6 +22,11 @@ thread_local void *g_ev_stop = nullptr;
 // Test and tuning overrides set through nq_set_tuning; 0 = the library's own choice.
 std::atomic<int> g_tune[NQ_TUNE_COUNT];
 
+// What the last launch of this thread ran (nq_profile_last_kernel): kernel family as in NQ_TUNE_KERNEL
+// (7 = depthwise / grouped, 8 = word pages) and, for the large-GEMM kernel, its tile height.
+thread_local int g_last_family = 0;
+thread_local int g_last_variant = 0;
+
 // Decides whether the windowed convolution kernel applies and fills its geometry.
 bool plan_window(const Geometry &g, const int8_t *d_x, WindowGeom *wg, size_t *lds)
 {
@@ -304,6 +309,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         const int lf = low_field_bits(&w->cfg);
         const int WL = (int)ceil_div(w->K, 64 / lf);
         if (!commit()) return NQ_ERR_HIP;
+        g_last_family = 8; g_last_variant = 0;
         launch_nested_gemm_words(full, h, l, p, WH, WL, s, ev0, ev1);
         return launch_status();
     }
@@ -314,6 +320,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         p.cin_shift = 0;
         p.kw_magic = 65536 / g.KW + 1;      // tap / KW == (tap * kw_magic) >> 16 for the few taps of a filter
         if (!commit()) return NQ_ERR_HIP;
+        g_last_family = 7; g_last_variant = 0;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_grouped, full, p, gg, s, ev0, ev1);
         return launch_status();
     }
@@ -350,7 +357,9 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         const int64_t blocks = ceil_div(g.M, 64) * ceil_div(w->N, 256);
         if (blocks > 0x7fffffffLL) return NQ_ERR_SHAPE;
         if (!commit()) return NQ_ERR_HIP;
-        NQ_DISPATCH_HL(h, l, launch_nested_gemm_big, full, p, g_tune[NQ_TUNE_BIG_TM].load(std::memory_order_relaxed), s, ev0, ev1);
+        g_last_family = 4;
+        NQ_DISPATCH_HL(h, l, launch_nested_gemm_big, full, p, g_tune[NQ_TUNE_BIG_TM].load(std::memory_order_relaxed),
+                       &g_last_variant, s, ev0, ev1);
         return launch_status();
     }
     // few rows: the packed weights are the traffic; one block per 32 columns, K split over the waves
@@ -358,12 +367,14 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
                            aligned16(d_x) && ceil_div(w->N, 32) <= 0x7fffffffLL;
     if (skinny_ok && (force == 6 || (force == 0 && w->K >= 256))) {
         if (!commit()) return NQ_ERR_HIP;
+        g_last_family = 6; g_last_variant = 0;
         NQ_DISPATCH_HL(h, l, launch_nested_gemm_skinny, full, p, s, ev0, ev1);
         return launch_status();
     }
     SmallCinGeom cg;
     if ((force == 0 || force == 5) && plan_smallcin(g, d_x, w->N, &cg)) {
         if (!commit()) return NQ_ERR_HIP;
+        g_last_family = 5; g_last_variant = 0;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_smallcin, full, p, cg, s, ev0, ev1);
         return launch_status();
     }
@@ -372,6 +383,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if ((force == 0 || force == 3) && plan_rowstream(g, d_x, w->N, &sg, &grid_x)) {
         if ((int64_t)(grid_x + 7) * ceil_div(w->N, 32) > 0x7fffffffLL) return NQ_ERR_SHAPE;
         if (!commit()) return NQ_ERR_HIP;
+        g_last_family = 3; g_last_variant = 0;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_rowstream, full, p, sg, grid_x, s, ev0, ev1);
         return launch_status();
     }
@@ -381,6 +393,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         const int64_t blocks_x = (g.M / ((int64_t)g.Ho * g.Wo)) * wg.RB;
         if (blocks_x > 0x7fffffffLL || ceil_div(w->N, 64) > 65535) return NQ_ERR_SHAPE;
         if (!commit()) return NQ_ERR_HIP;
+        g_last_family = 2; g_last_variant = 0;
         NQ_DISPATCH_HL(h, l, launch_nested_conv_window, full, 0, p, wg, lds, s, ev0, ev1);
         return launch_status();
     }
@@ -388,6 +401,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if (ceil_div(g.M, NQ_TILE_BM[tile]) > 0x7fffffffLL || ceil_div(w->N, NQ_TILE_BN[tile]) > 65535)
         return NQ_ERR_SHAPE;
     if (!commit()) return NQ_ERR_HIP;
+    g_last_family = 1; g_last_variant = tile;
     NQ_DISPATCH_HL(h, l, launch_nested_gemm, full, tile, p, s, ev0, ev1);
     return launch_status();
 }
@@ -472,6 +486,13 @@ extern "C" nq_status nq_set_tuning(int key, int value)
 {
     if (key < 0 || key >= NQ_TUNE_COUNT || value < 0) return NQ_ERR_INVALID_ARG;
     g_tune[key].store(value, std::memory_order_relaxed);
+    return NQ_OK;
+}
+
+extern "C" nq_status nq_profile_last_kernel(int *family, int *variant)
+{
+    if (family) *family = g_last_family;
+    if (variant) *variant = g_last_variant;
     return NQ_OK;
 }
 

@@ -369,13 +369,14 @@ inline int gemm_big_pick_tm(int64_t M, int64_t N, bool filter)
 }
 
 template <int H, int L>
-void launch_nested_gemm_big(bool full, const GemmParams &p, int tm_forced, hipStream_t st, void *ev_start,
-                            void *ev_stop)
+void launch_nested_gemm_big(bool full, const GemmParams &p, int tm_forced, int *tm_used, hipStream_t st,
+                            void *ev_start, void *ev_stop)
 {
     const int nblocks = (p.N + GB_BN - 1) / GB_BN;
     const int mode = epi_mode(p);
     int tm = mode == EPI_ANY ? 4 : gemm_big_pick_tm(p.M, p.N, p.conv_big && p.KH * p.KW > 1);   // the element-wise epilogue is built for TM = 4 only
     if (mode != EPI_ANY && tm_forced >= 2 && tm_forced <= 5) tm = tm_forced;   // test / tuning aid
+    if (tm_used) *tm_used = tm;
 #define NQ_GB_LAUNCH(FULLV, EPIV, TMV, CONVV)                                               \
     do {                                                                                    \
         auto k = k_nested_gemm_big<H, L, FULLV, EPIV, TMV, CONVV>;                          \

@@ -29,6 +29,7 @@ template void launch_nested_conv_grouped<NQ_INST_H, NQ_INST_L>(bool, const GemmP
 #include "nq_gemm_big.h"
 
 namespace nq {
-template void launch_nested_gemm_big<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, int, hipStream_t, void *, void *);
+template void launch_nested_gemm_big<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, int, int *, hipStream_t, void *,
+                                                           void *);
 }
 #endif

@@ -134,10 +134,11 @@ template <int H, int L>
 void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop);
 
 // Large GEMM / 1x1 stride-1 convolution: 128 x 256 tiles, K advanced 256 per barrier.
-// tm_forced: 2..5 forces the rows per block (32 * tm), anything else leaves the choice to the launcher.
+// tm_forced: 2..5 forces the rows per block (32 * tm), anything else leaves the choice to the launcher;
+// tm_used, if not null, receives the height that was launched.
 template <int H, int L>
-void launch_nested_gemm_big(bool full, const GemmParams &p, int tm_forced, hipStream_t st, void *ev_start,
-                            void *ev_stop);
+void launch_nested_gemm_big(bool full, const GemmParams &p, int tm_forced, int *tm_used, hipStream_t st,
+                            void *ev_start, void *ev_stop);
 
 // GEMM over the paper's word pages (64 / k fields per 64-bit word); WH, WL: words per row of the two pages.
 // Not a template: nq_gemm_words.hip holds every nesting.

@@ -546,6 +546,60 @@ extern "C" nq_status nq_quantize(const float *d_w, int64_t N, int64_t K, int n_b
     return launch_status();
 }
 
+// Eq. 1's step for a whole tensor (per-tensor activation quantisation): absmax over all elements through
+// an atomic maximum on the bit patterns (non-negative floats order like unsigned integers), then one
+// thread turns it into absmax / qmax (1 for an all-zero tensor).  d_scale doubles as the accumulator.
+__global__ void k_tensor_absmax_begin(uint32_t *acc) { *acc = 0u; }
+
+__global__ void __launch_bounds__(256) k_tensor_absmax(const float *__restrict__ x, int64_t count, int vec_ok,
+                                                        uint32_t *__restrict__ acc)
+{
+    __shared__ float part[4];
+    float m = 0.0f;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    if (vec_ok) {
+        const float4 *xv = reinterpret_cast<const float4 *>(x);
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count / 4; i += stride) {
+            const float4 v = xv[i];
+            m = fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        }
+        for (int64_t i = count / 4 * 4 + (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += stride)
+            m = fmaxf(m, fabsf(x[i]));
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += stride) m = fmaxf(m, fabsf(x[i]));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]));
+        atomicMax(acc, __float_as_uint(m));
+    }
+}
+
+__global__ void k_tensor_absmax_end(float *scale, float qmax)
+{
+    const float m = *scale;
+    *scale = m > 0.0f ? m / qmax : 1.0f;
+}
+
+extern "C" nq_status nq_tensor_scale(const float *d_x, int64_t count, int n_bits, float *d_scale, void *stream)
+{
+    if (n_bits < 2 || n_bits > 8 || count < 0) return NQ_ERR_INVALID_ARG;
+    if (!d_scale || (count > 0 && !d_x)) return NQ_ERR_INVALID_ARG;
+    if (((uintptr_t)d_scale & 3u) != 0 || ((uintptr_t)d_x & 3u) != 0) return NQ_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(k_tensor_absmax_begin, dim3(1), dim3(1), 0, s, reinterpret_cast<uint32_t *>(d_scale));
+    if (count > 0) {
+        const int64_t blocks = ceil_div(count, 256 * 16);
+        hipLaunchKernelGGL(k_tensor_absmax, dim3((unsigned)(blocks < 2048 ? blocks : 2048)), dim3(256), 0, s, d_x, count,
+                           aligned16(d_x) ? 1 : 0, reinterpret_cast<uint32_t *>(d_scale));
+    }
+    hipLaunchKernelGGL(k_tensor_absmax_end, dim3(1), dim3(1), 0, s, d_scale, (float)((1 << (n_bits - 1)) - 1));
+    return launch_status();
+}
+
 extern "C" nq_status nq_quantize_decompose_pack(const float *d_w, int64_t N, int64_t K, const nq_cfg *cfg,
                                                 float *d_scale, void *d_packed_high, void *d_packed_low,
                                                 void *stream)

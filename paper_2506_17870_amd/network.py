@@ -118,6 +118,9 @@ class NestedCNN:
             if L is not None:
                 L[0].desc.low_resident = 1
         self.out_scale = [None] * (max(op["dst"] for op in ops) + 1)   # step of every int8 tensor
+        self.channels = {0: ops[0]["cin"]}                             # channels of every NHWC tensor
+        for op in ops:
+            self.channels[op["dst"]] = op["cout"] if op["op"] in ("conv", "fc") else self.channels[op["src"]]
 
     def low_page_bytes(self) -> int:
         return sum(nq.nq_packed_bytes(L[0].N, L[0].K, self.l_bits) for L in self.layers if L is not None)
@@ -128,53 +131,91 @@ class NestedCNN:
     def page_in_low(self, copy_stream=None):
         nq.nq_page_in_low_batch(self.descs, copy_stream)
 
-    def forward(self, x, in_scale: float, full: bool, calibrate: bool = False, keep=None):
-        """x: int8 NHWC device tensor.  Returns the fp32 logits [B, classes].
-        calibrate=True first runs every layer with fp32 output to fix its int8 step (absmax / 127)."""
-        B, H, W, _ = x.shape
-        tensors = {0: (x, H, W)}
-        self.out_scale[0] = float(in_scale)
-        logits = None
-        for op, L in zip(self.ops, self.layers):
-            src, hs, ws = tensors[op["src"]]
-            s_in = self.out_scale[op["src"]]
-            if op["op"] == "maxpool":
+    def allocate(self, B: int, H: int, W: int):
+        """Output tensors of every op for a batch of B images of H x W pixels, allocated once, so that a
+        forward pass allocates nothing (and can be captured into a HIP graph)."""
+        self.batch, self.in_hw = B, (H, W)
+        self.hw = {0: (H, W)}
+        self.buf = {}
+        for op in self.ops:
+            hs, ws = self.hw[op["src"]]
+            if op["op"] in ("conv", "maxpool"):
                 ho, wo = out_hw(hs, ws, op["k"], op["stride"], op["pad"])
-                y = torch.empty((B, ho, wo, src.shape[3]), dtype=torch.int8, device="cuda")
-                nq.nq_maxpool_i8(src, B, hs, ws, src.shape[3], op["k"], op["stride"], op["pad"], y)
-                self.out_scale[op["dst"]] = s_in
-                tensors[op["dst"]] = (y, ho, wo)
+                c = op["cout"] if op["op"] == "conv" else self.channels[op["src"]]
+                self.buf[op["dst"]] = torch.empty((B, ho, wo, c), dtype=torch.int8, device="cuda")
+                self.hw[op["dst"]] = (ho, wo)
             elif op["op"] == "avgpool":
-                C = src.shape[3]
-                if calibrate:
-                    self.out_scale[op["dst"]] = s_in            # a mean never exceeds the maximum
-                y = torch.empty((B, 1, 1, C), dtype=torch.int8, device="cuda")
-                nq.nq_avgpool_i8(src, B, hs * ws, C, s_in, 1.0 / self.out_scale[op["dst"]], y)
-                tensors[op["dst"]] = (y, 1, 1)
-            elif op["op"] == "fc":
-                Wt, bias = L
-                y = torch.empty((B, op["cout"]), dtype=torch.float32, device="cuda")
-                epi = nq.make_epilogue(s_in, bias)
-                (nq.nq_gemm_full if full else nq.nq_gemm_part)(src.view(B, -1), B, Wt.desc, epi, y)
-                logits = y
+                self.buf[op["dst"]] = torch.empty((B, 1, 1, self.channels[op["src"]]), dtype=torch.int8, device="cuda")
+                self.hw[op["dst"]] = (1, 1)
             else:
+                self.buf[op["dst"]] = torch.empty((B, op["cout"]), dtype=torch.float32, device="cuda")
+        return self
+
+    def calibrate(self, x, in_scale: float):
+        """Fixes the int8 step of every activation tensor for this input batch (per tensor, symmetric): each
+        convolution runs once in full-bit mode with fp32 output, nq_tensor_scale reduces it to absmax / 127
+        on the device, and the layer is run again with that step to feed the next one."""
+        B, H, W, _ = x.shape
+        if getattr(self, "batch", None) != B or self.in_hw != (H, W):
+            self.allocate(B, H, W)
+        d_step = torch.zeros(1, dtype=torch.float32, device="cuda")
+        self.out_scale[0] = float(in_scale)
+        for op, L in zip(self.ops, self.layers):
+            if op["op"] == "conv":
+                src = x if op["src"] == 0 else self.buf[op["src"]]
+                hs, ws = self.hw[op["src"]]
+                ho, wo = self.hw[op["dst"]]
                 Wt, bias = L
-                ho, wo = out_hw(hs, ws, op["k"], op["stride"], op["pad"])
                 shape = nq.nq_conv_shape(B, hs, ws, op["cin"], op["cout"], op["k"], op["k"], op["stride"], op["pad"])
                 res, s_r = None, 0.0
                 if op["residual"] is not None:
-                    res, s_r = tensors[op["residual"]][0], self.out_scale[op["residual"]]
-                fn = nq.nq_conv_full if full else nq.nq_conv_part
-                if calibrate:
-                    yf = torch.empty((B, ho, wo, op["cout"]), dtype=torch.float32, device="cuda")
-                    fn(src, shape, Wt.desc, nq.make_epilogue(s_in, bias, res, s_r, op["relu"]), yf)
-                    amax = float(yf.abs().max())
-                    self.out_scale[op["dst"]] = (amax / 127.0) if amax > 0 else 1.0
-                    del yf
-                y = torch.empty((B, ho, wo, op["cout"]), dtype=torch.int8, device="cuda")
-                epi = nq.make_epilogue(s_in, bias, res, s_r, op["relu"], True, 1.0 / self.out_scale[op["dst"]])
-                fn(src, shape, Wt.desc, epi, y)
-                tensors[op["dst"]] = (y, ho, wo)
+                    res, s_r = self.buf[op["residual"]], self.out_scale[op["residual"]]
+                yf = torch.empty((B, ho, wo, op["cout"]), dtype=torch.float32, device="cuda")
+                nq.nq_conv_full(src, shape, Wt.desc, nq.make_epilogue(self.out_scale[op["src"]], bias, res, s_r,
+                                                                      op["relu"]), yf)
+                nq.nq_tensor_scale(yf, yf.numel(), 8, d_step)
+                self.out_scale[op["dst"]] = float(d_step.cpu()[0])
+                del yf
+            elif op["op"] in ("maxpool", "avgpool"):
+                self.out_scale[op["dst"]] = self.out_scale[op["src"]]   # neither a maximum nor a mean exceeds the input range
+            self._run_op(op, L, x, B, True, None)
+        torch.cuda.synchronize()
+
+    def _run_op(self, op, L, x, B, full, stream):
+        src = x if op["src"] == 0 else self.buf[op["src"]]
+        hs, ws = self.hw[op["src"]]
+        s_in = self.out_scale[op["src"]]
+        y = self.buf[op["dst"]]
+        if op["op"] == "maxpool":
+            nq.nq_maxpool_i8(src, B, hs, ws, src.shape[3], op["k"], op["stride"], op["pad"], y, stream)
+        elif op["op"] == "avgpool":
+            nq.nq_avgpool_i8(src, B, hs * ws, src.shape[3], s_in, 1.0 / self.out_scale[op["dst"]], y, stream)
+        elif op["op"] == "fc":
+            Wt, bias = L
+            (nq.nq_gemm_full if full else nq.nq_gemm_part)(src.view(B, -1), B, Wt.desc, nq.make_epilogue(s_in, bias), y,
+                                                           stream)
+        else:
+            Wt, bias = L
+            shape = nq.nq_conv_shape(B, hs, ws, op["cin"], op["cout"], op["k"], op["k"], op["stride"], op["pad"])
+            res, s_r = None, 0.0
+            if op["residual"] is not None:
+                res, s_r = self.buf[op["residual"]], self.out_scale[op["residual"]]
+            epi = nq.make_epilogue(s_in, bias, res, s_r, op["relu"], True, 1.0 / self.out_scale[op["dst"]])
+            (nq.nq_conv_full if full else nq.nq_conv_part)(src, shape, Wt.desc, epi, y, stream)
+
+    def forward(self, x, in_scale: float, full: bool, keep=None, stream=None):
+        """x: int8 NHWC device tensor.  Returns the fp32 logits [B, classes] (a buffer of the model: the next
+        forward overwrites it).  The int8 step of every tensor (out_scale) must have been set, by calibrate()
+        or by the caller.  keep, if a dict, receives every op's output tensor."""
+        B, H, W, _ = x.shape
+        if getattr(self, "batch", None) != B or self.in_hw != (H, W):
+            self.allocate(B, H, W)
+        self.out_scale[0] = float(in_scale)
+        logits = None
+        for op, L in zip(self.ops, self.layers):
+            self._run_op(op, L, x, B, full, stream)
+            if op["op"] == "fc":
+                logits = self.buf[op["dst"]]
             if keep is not None:
-                keep[op["dst"]] = tensors.get(op["dst"], (logits,))[0]
+                keep[op["dst"]] = self.buf[op["dst"]]
         return logits

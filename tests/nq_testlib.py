@@ -156,46 +156,4 @@ def run_gconv_both(nq, case, x, shape, groups, full, **epi_kw):
             raise AssertionError(f"{e} (accumulator dump {dump})") from None
 
 
-def oracle_cnn_forward(ops, weights, x, in_scale, n_bits, l_bits, full, scales=None):
-    """Walks a plan of paper_2506_17870_amd.network on the CPU oracle.  With scales=None every conv is first
-    dequantised to fp32 to fix its int8 step (absmax / 127), which is returned for the other runs."""
-    calibrate = scales is None
-    scales = {} if calibrate else dict(scales)
-    scales[0] = float(in_scale)
-    tensors = {0: x}
-    logits = None
-    for op, w in zip(ops, weights):
-        src = tensors[op["src"]]
-        s_in = scales[op["src"]]
-        if op["op"] == "maxpool":
-            tensors[op["dst"]] = oracle.maxpool(src, op["k"], op["stride"], op["pad"])
-            scales[op["dst"]] = s_in
-        elif op["op"] == "avgpool":
-            if calibrate:
-                scales[op["dst"]] = s_in
-            y = oracle.avgpool(src, s_in, 1.0 / scales[op["dst"]])
-            tensors[op["dst"]] = y.reshape(y.shape[0], 1, 1, y.shape[1])
-        else:
-            w_int, scale, bias = w
-            N, K = w_int.shape
-            ph, pl = oracle.decompose_pack(w_int, n_bits, l_bits)
-            wq = oracle.weights_from_pages(ph, pl if full else None, N, K, n_bits, l_bits)
-            part_l = 0 if full else l_bits
-            if op["op"] == "fc":
-                acc = oracle.gemm_acc(src.reshape(src.shape[0], -1), wq)
-                logits = oracle.epilogue(acc, s_in, scale, part_l_bits=part_l, bias=bias)
-                continue
-            k = op["k"]
-            acc = oracle.conv_acc(src, wq.reshape(N, k, k, op["cin"]), op["stride"], op["pad"])
-            res, s_r = None, 0.0
-            if op["residual"] is not None:
-                res, s_r = tensors[op["residual"]], scales[op["residual"]]
-            if calibrate:
-                yf = oracle.epilogue(acc, s_in, scale, part_l_bits=part_l, bias=bias, residual=res, s_r=s_r,
-                                     relu=op["relu"])
-                amax = float(np.abs(yf).max())
-                scales[op["dst"]] = (amax / 127.0) if amax > 0 else 1.0
-            tensors[op["dst"]] = oracle.epilogue(acc, s_in, scale, part_l_bits=part_l, bias=bias, residual=res,
-                                                 s_r=s_r, relu=op["relu"], out_int8=True,
-                                                 inv_s_out=1.0 / scales[op["dst"]])
-    return logits, tensors, scales
+from oracle.nq_oracle_cnn import oracle_cnn_forward  # noqa: E402,F401  (re-exported for the network tests)

@@ -118,3 +118,22 @@ def test_float_weights_to_outputs(nq):
         (nq.nq_gemm_full if full else nq.nq_gemm_part)(dev(x), M, W.desc, nq.make_epilogue(0.02, d_acc_dump=acc), y)
         torch.cuda.synchronize()
         check_outputs(host(y), host(acc), y_ref, acc_ref, False)
+
+
+@pytest.mark.parametrize("count", [1, 3, 255, 4096, 100_003, 3_000_000])
+def test_tensor_scale(nq, count):
+    # Eq. 1's step for a whole tensor (per-tensor activation quantisation): absmax / 127 in fp32, 1 for zeros
+    rng = np.random.default_rng(count)
+    for variant in ("gauss", "zeros", "peak_last", "unaligned"):
+        v = rng.normal(0.0, 3.0, size=count + 1).astype(np.float32)
+        first = 1 if variant == "unaligned" else 0          # a tensor that starts 4 bytes off a 16-byte boundary
+        if variant == "zeros":
+            v[:] = 0.0
+        if variant == "peak_last":
+            v[first + count - 1] = -1e20
+        src = dev(v)[first:first + count]
+        out = torch.full((1,), 77.0, dtype=torch.float32, device="cuda")
+        nq.nq_tensor_scale(src, count, 8, out)
+        torch.cuda.synchronize()
+        _, s_ref = oracle.quantize(v[first:first + count].reshape(1, -1), 8)
+        assert host(out).view(np.uint32)[0] == s_ref.view(np.uint32)[0], (variant, count)

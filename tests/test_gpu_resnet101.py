@@ -30,8 +30,10 @@ def test_resnet101_full_part_full():
     logits_op, tens_op, _ = oracle_cnn_forward(ops, weights, x, s_x, n_bits, l_bits, full=False, scales=scales)
 
     model = network.NestedCNN(ops, weights, n_bits, l_bits)
+    # the walker's own calibration (fp32-output pass + nq_tensor_scale per layer) finds the oracle's steps
+    model.calibrate(dev(x), s_x)
     for t, s in scales.items():
-        model.out_scale[t] = s
+        assert model.out_scale[t] == s, f"calibrated step of tensor {t} differs: {model.out_scale[t]} vs {s}"
 
     def check(full, logits_ref, tens_ref):
         keep = {}
