@@ -42,9 +42,9 @@ RIDGE = MFMA_INT8_PEAK_TOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # op per byte above 
 # instantiation they were taken on and by a digest of the kernel's sources at that time: a different kernel or
 # digest reports no traffic.
 TRAFFIC = {}
-KERNEL_SOURCES = ("nq_gemm_big.h", "nq_epilogue.h", "nq_codec.h", "nq_gemm_params.h")
+KERNEL_SOURCES = ("nq_gemm_big.h", "nq_gemm_stat.h", "nq_epilogue.h", "nq_codec.h", "nq_gemm_params.h")
 FAMILY = {1: "k_nested_gemm", 2: "k_nested_conv_window", 3: "k_nested_conv_rowstream", 4: "k_nested_gemm_big",
-          5: "k_nested_conv_smallcin", 6: "k_nested_gemm_skinny", 7: "k_nested_conv_grouped", 8: "k_nested_gemm_words"}
+          5: "k_nested_conv_smallcin", 6: "k_nested_gemm_skinny", 7: "k_nested_conv_grouped", 8: "k_nested_gemm_words", 9: "k_nested_gemm_stat"}
 
 
 def kernel_sources_digest():
@@ -112,6 +112,8 @@ def stamped_forward(model, binding, dx, s_x, full):
             inst = FAMILY.get(fam, "?") + f"<{h_bits},{l_bits},{'full' if full else 'part'}"
             if fam == 4:
                 inst += f",{'int8' if epi.out_int8 else 'fp32'} out,TM={var},{'filter' if filt else 'plain'}"
+            if fam == 9:
+                inst += f",{'int8' if epi.out_int8 else 'fp32'} out,K={wd.K},WN={var}"
             inst += ">"
             recs.append(dict(e=(e0, e1), inst=inst, layer=layer, ops=2.0 * m * wd.N * wd.K, bytes=byts))
         return call
@@ -276,7 +278,7 @@ def main():
     by_inst = sorted(((k, v["us"] / 3, v["n"] // 3, v["ops"] / v["us"] / 1e6, v["bytes"] / v["us"] / 1e3)
                       for k, v in groups.items()), key=lambda e: -e[1])
     breakdown = [dict(kernel=k, us_per_step=round(us, 1), launches=n, tops=round(tops, 1), algorithmic_gbs=round(gbs))
-                 for k, us, n, tops, gbs in by_inst[:8]]
+                 for k, us, n, tops, gbs in by_inst[:14]]
 
     # ---- the switch alone: host -> device GB/s of the page-in ----
     sw = torch.cuda.Stream()

@@ -300,11 +300,14 @@ nq_status nq_gconv_part(const int8_t *d_x, const nq_conv_shape *shape, int group
  * does not apply to a shape is ignored for that call.  Meant to be set while no other thread is inside
  * the library (the parity tests run every case once per kernel that can take it).
  *   NQ_TUNE_KERNEL:   1 generic, 2 windowed, 3 register-stationary, 4 large GEMM, 5 few input channels,
- *                     6 few rows
- *   NQ_TUNE_BIG_TM:   2..5, rows per block of the large-GEMM kernel = 32 * value
+ *                     6 few rows, 9 stationary-weights GEMM (short reductions)
+ *   NQ_TUNE_BIG_TM:   2..5, rows per block of the large-GEMM kernel = 32 * value; 6 = 128 rows with one block
+ *                     per compute unit (the whole register file: deeper weight pipeline)
  *   NQ_TUNE_GC_UNITS: work units the patch planner of the depthwise / grouped kernel aims for
+ *   NQ_TUNE_STAT_ROWS: 1 gives every block of the stationary-weights GEMM one run of consecutive rows instead of
+ *                     dealing the row tiles to the blocks in turn
  * NQ_ERR_INVALID_ARG for an unknown key or a negative value. */
-typedef enum { NQ_TUNE_KERNEL = 0, NQ_TUNE_BIG_TM = 1, NQ_TUNE_GC_UNITS = 2, NQ_TUNE_COUNT = 3 } nq_tune_key;
+typedef enum { NQ_TUNE_KERNEL = 0, NQ_TUNE_BIG_TM = 1, NQ_TUNE_GC_UNITS = 2, NQ_TUNE_STAT_ROWS = 3, NQ_TUNE_COUNT = 4 } nq_tune_key;
 nq_status nq_set_tuning(int key, int value);
 
 /* Profiling aid: the next nq_gemm_* / nq_conv_* / nq_gconv_* call made by this host thread attaches the two
@@ -313,7 +316,8 @@ nq_status nq_set_tuning(int key, int value);
 nq_status nq_profile_next_launch(void *start_event, void *stop_event);
 /* Profiling aid: which kernel the last nq_gemm_* / nq_conv_* / nq_gconv_* launch of this host thread ran:
  * *family as in NQ_TUNE_KERNEL (7 = depthwise / grouped, 8 = word pages; 0 before the first launch), *variant
- * the tile height of the large-GEMM kernel (2..5), the tile shape of the generic kernel, else 0.  Lets a
+ * the tile height of the large-GEMM kernel (2..5), the tile shape of the generic kernel, the waves along N
+ * of the stationary-weights GEMM, else 0.  Lets a
  * benchmark group its time stamps by kernel instantiation, as a kernel trace does.  Either pointer may be NULL. */
 nq_status nq_profile_last_kernel(int *family, int *variant);
 /* Timing events for the call above: create / destroy a hipEvent_t, and the milliseconds

@@ -21,7 +21,7 @@ NQ_OK, NQ_ERR_INVALID_ARG, NQ_ERR_UNSUPPORTED, NQ_ERR_SHAPE, NQ_ERR_ALIGN, NQ_ER
 NQ_LOW_UNSIGNED_L, NQ_LOW_SIGNED_L1 = 0, 1
 NQ_LAYOUT_DENSE, NQ_LAYOUT_PAPER_U64 = 0, 1
 NQ_MAX_K = 65536
-NQ_TUNE_KERNEL, NQ_TUNE_BIG_TM, NQ_TUNE_GC_UNITS = 0, 1, 2
+NQ_TUNE_KERNEL, NQ_TUNE_BIG_TM, NQ_TUNE_GC_UNITS, NQ_TUNE_STAT_ROWS = 0, 1, 2, 3
 
 EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "nq_tensor_scale", "nq_quantize_decompose_pack",
            "nq_decompose", "nq_pack", "nq_decompose_pack", "nq_decompose_pack_batch",

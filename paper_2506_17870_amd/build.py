@@ -3,7 +3,7 @@
     python -m paper_2506_17870_amd.build [--force]
 
 Objects go to _build/ next to this file, the library to paper_2506_17870_amd/libnq.so.
-Three translation units per nesting (h, l) hold the GEMM/convolution kernels, so the
+Four translation units per nesting (h, l) hold the GEMM/convolution kernels, so the
 units compile in parallel; the GEMM over the paper's word pages is one unit for all nestings.
 """
 from __future__ import annotations
@@ -30,21 +30,29 @@ def _units():
     units = [(os.path.join(CSRC, f + ".hip"), os.path.join(OBJ, f + ".o"), [])
              for f in ("nq_pack", "nq_page", "nq_glue", "nq_gemm", "nq_gemm_words")]   # nq_yardsticks.hip is a program of its own
     for h, l in NESTINGS:
-        for part in (1, 0, 2):
+        for part in (1, 0, 2, 3):
             units.append((os.path.join(CSRC, "nq_gemm_inst.hip"), os.path.join(OBJ, f"nq_gemm_inst_{h}{l}_{part}.o"),
                           [f"-DNQ_INST_H={h}", f"-DNQ_INST_L={l}", f"-DNQ_INST_PART={part}"]))
     return units
 
 
-def _newest_source():
-    paths = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
-    paths.append(os.path.join(os.path.dirname(HERE), "include", "nq.h"))
-    return max(os.path.getmtime(p) for p in paths)
+def _stale(unit) -> bool:
+    """A unit is rebuilt when its object is missing or older than any file it was compiled from (the compiler
+    writes the list next to the object, -MMD)."""
+    src, obj, _ = unit
+    dep = obj[:-2] + ".d"
+    if not os.path.exists(obj) or not os.path.exists(dep):
+        return True
+    with open(dep) as f:
+        text = f.read().replace("\\\n", " ")
+    files = text.split(":", 1)[1].split() if ":" in text else [src]
+    t = os.path.getmtime(obj)
+    return any((not os.path.exists(x)) or os.path.getmtime(x) > t for x in files)
 
 
 def _compile(unit):
     src, obj, defs = unit
-    cmd = ["hipcc", *FLAGS, *defs, "-c", src, "-o", obj]
+    cmd = ["hipcc", *FLAGS, *defs, "-MMD", "-MF", obj[:-2] + ".d", "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {os.path.basename(obj)}:\n{r.stderr[-4000:]}")
@@ -53,9 +61,8 @@ def _compile(unit):
 
 def build(force: bool = False, jobs: int | None = None) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    newest = _newest_source()
     units = _units()
-    todo = [u for u in units if force or not os.path.exists(u[1]) or os.path.getmtime(u[1]) < newest]
+    todo = [u for u in units if force or _stale(u)]
     jobs = jobs or min(8, os.cpu_count() or 1)
     with concurrent.futures.ThreadPoolExecutor(max_workers=jobs) as pool:
         list(pool.map(_compile, todo))

@@ -23,7 +23,7 @@ thread_local void *g_ev_stop = nullptr;
 std::atomic<int> g_tune[NQ_TUNE_COUNT];
 
 // What the last launch of this thread ran (nq_profile_last_kernel): kernel family as in NQ_TUNE_KERNEL
-// (7 = depthwise / grouped, 8 = word pages) and, for the large-GEMM kernel, its tile height.
+// (7 = depthwise / grouped, 8 = word pages, 9 = stationary-weights GEMM) and, for the large-GEMM kernel, its tile height.
 thread_local int g_last_family = 0;
 thread_local int g_last_variant = 0;
 
@@ -206,6 +206,56 @@ bool plan_grouped(const Geometry &g, int gs, int64_t C, GroupGeom *gg)
     return true;
 }
 
+// Decides whether the stationary-weights GEMM applies (1x1 filter without padding, K = 64, 128 or 256) and
+// works out its geometry.
+bool plan_stat(const Geometry &g, const int8_t *d_x, int64_t N, int64_t K, StatGeom *sg)
+{
+    if (g.KH != 1 || g.KW != 1 || g.pad != 0 || g.Cin != K) return false;
+    if (K != 64 && K != 128 && K != 256) return false;
+    if (!aligned16(d_x) || N < 1) return false;
+    const int64_t howo = (int64_t)g.Ho * g.Wo;
+    const int64_t images = g.M / howo;
+    const int64_t x_bytes = images * g.H * g.W * g.Cin;
+    if (x_bytes >= 0x7fff0000LL - 65536 || g.M >= (int64_t(1) << 31) - 512) return false;
+    const bool strided = g.stride > 1;
+    // the divisions by Ho * Wo and by Wo are multiplications by a rounded-up reciprocal: exact while
+    // dividend * divisor < 2^32 (dividends: a row index inside an image plus one tile; a pixel index)
+    if (strided && ((howo + 256) * howo >= (int64_t(1) << 32) || howo * g.Wo >= (int64_t(1) << 32))) return false;
+    sg->ks = (int)(K / 64);
+    sg->wn = N <= 64 ? 1 : (N <= 128 ? 2 : 4);
+    sg->cgroups = (int)ceil_div(N, 64 * sg->wn);
+    if (sg->cgroups > 0x3fffff) return false;
+    // persistent blocks, two per compute unit; whole groups of eight slots (one per XCD) where there are that
+    // many; every slot the same number of rows, at least one 32-row tile
+    int64_t nslots = 512 / sg->cgroups;
+    if (nslots < 1) nslots = 1;
+    if (nslots >= 8) nslots -= nslots % 8;
+    if (nslots > ceil_div(g.M, 32)) nslots = ceil_div(g.M, 32);
+    // Row tiles are dealt to the blocks in turn (tile t to slot t % nslots): the blocks then stream one region of
+    // the tensors together, which measured 7-10 % faster than giving every block one run of consecutive rows
+    // (NQ_TUNE_STAT_ROWS = 1), although the runs are the more even split.
+    sg->interleave = g_tune[NQ_TUNE_STAT_ROWS].load(std::memory_order_relaxed) != 1;
+    if (sg->interleave) {
+        if (nslots > ceil_div(g.M, st_bm(sg->wn))) nslots = ceil_div(g.M, st_bm(sg->wn));
+        sg->rps = 0;
+        sg->nslots = (int)nslots;
+    } else {
+        sg->rps = (int)ceil_div(g.M, nslots);
+        sg->nslots = (int)ceil_div(g.M, sg->rps);
+    }
+    sg->strided = strided;
+    sg->howo = (int)howo;
+    sg->howo_magic = (unsigned)(((uint64_t(1) << 32) + howo - 1) / howo);
+    sg->wo_magic = (unsigned)(((uint64_t(1) << 32) + g.Wo - 1) / g.Wo);
+    if (howo == 1) sg->howo_magic = 0;              // divisor 1: the kernel takes the dividend as it is
+    if (g.Wo == 1) sg->wo_magic = 0;
+    sg->img_bytes = g.H * g.W * g.Cin;
+    sg->row_step = g.stride * g.W * g.Cin;
+    sg->col_step = g.stride * g.Cin;
+    sg->x_bytes = (int)x_bytes;
+    return true;
+}
+
 int pick_tile(int64_t M, int64_t N)
 {
     if (N <= 64) return 0;
@@ -325,7 +375,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         return launch_status();
     }
     // NQ_TUNE_KERNEL (test and tuning aid): 1 generic, 2 windowed, 3 register-stationary, 4 large GEMM,
-    // 5 few input channels, 6 few rows;
+    // 5 few input channels, 6 few rows, 9 stationary-weights GEMM;
     // a kernel that does not apply to the shape is never forced, the choice falls through.
     const int force = g_tune[NQ_TUNE_KERNEL].load(std::memory_order_relaxed);
     const bool plain_gemm = g.KH == 1 && g.KW == 1 && g.stride == 1 && g.pad == 0 && w->K % 256 == 0 && aligned16(d_x);
@@ -352,6 +402,14 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         size_t lds0 = 0;
         if (conv_gemm && w->N <= 128 && g.stride == 1 && g.KH * g.KW > 1 && plan_window(g, d_x, &wg0, &lds0))
             big_wanted = false;
+    }
+    // short reductions without a filter window: weights stationary in registers, rows streamed
+    StatGeom tg;
+    if ((force == 9 || (force == 0 && g.M > 64)) && plan_stat(g, d_x, w->N, w->K, &tg)) {
+        if (!commit()) return NQ_ERR_HIP;
+        g_last_family = 9; g_last_variant = tg.wn;
+        NQ_DISPATCH_HL(h, l, launch_nested_gemm_stat, full, p, tg, s, ev0, ev1);
+        return launch_status();
     }
     if (big_ok && (force == 4 || (force == 0 && big_wanted))) {
         const int64_t blocks = ceil_div(g.M, 64) * ceil_div(w->N, 256);

@@ -42,9 +42,12 @@ constexpr int GB_ROW = GB_KI * 64;                       // LDS bytes per panel 
 // blocks fits the 256 compute units with little left over.  TM <= 4 fits two blocks per unit
 // (the element-wise epilogue needs more registers and runs one block per unit rather than spill).
 // FULL: 0 part-bit, 1 full-bit (unsigned lower part), 2 full-bit (compensated signed lower part).
-template <int H, int L, int FULL, int EPI, int TM, bool CONV>
-__global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
+// TMX: 2..5 = TM; 6 = TM 4 with the compute unit to itself (SOLO: 512 registers, the deep weight pipeline).
+template <int H, int L, int FULL, int EPI, int TMX, bool CONV>
+__global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
 {
+    constexpr int TM = TMX == 6 ? 4 : TMX;
+    constexpr bool SOLO = TMX >= 5;
     constexpr int GB_BM = 32 * TM;
     constexpr int GB_PANEL = GB_BM * GB_ROW;             // bytes per LDS panel
     constexpr int S = 8 - H;
@@ -52,7 +55,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     using LP = LowPage<L, S, FULL>;
     // weights are requested PD K steps ahead (registers permitting: TM = 4 shares the compute unit with a
     // second block and has 256 registers, TM >= 5 has 512)
-    constexpr int TN = 2, PD = (TM == 4 && (FULL || H == 7) ? 2 : 4);
+    constexpr int TN = 2, PD = (TM == 4 && !SOLO && (FULL || H == 7) ? 2 : 4);
     constexpr int APT = 2 * TM;                          // LDS-direct loads per wave and iteration (4 rows each)
 
     extern __shared__ __attribute__((aligned(16))) uint8_t panel[];
@@ -101,8 +104,12 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
         CONV ? (int)((int64_t)(p.M / ((int64_t)p.Ho * p.Wo)) * p.H * p.W * p.Cin) : (int)(rows_here * p.K), 0x00020000);
     int a_goff[4];                                       // GEMM: offset of the lane's piece in rows 0..3
     // CONV: per row of the block, the byte offset of filter tap (0,0) and the packed (ih0, iw0) of the
-    // pixel, in a small LDS table behind the panels (worked out once, one row per thread)
+    // pixel, worked out once, one row per thread, and handed to the lanes that request the row through a
+    // small LDS table behind the panels
     int2 *rowtab = reinterpret_cast<int2 *>(panel + 2 * GB_PANEL);
+    // with 96 or 128 rows per block (two blocks share the unit's registers) there is no room for them
+    constexpr bool ROWREG = CONV && (TM <= 2 || SOLO);
+    int2 rowreg[ROWREG ? APT : 1];
     if constexpr (CONV) {
         if (tid < GB_BM) {
             const int HoWo = p.Ho * p.Wo;
@@ -116,6 +123,13 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
                                     (m < p.M ? ih0 : -16384) * 65536 + (iw0 & 0xffff));
         }
         __syncthreads();
+        // a lane requests the same APT rows in every iteration: their entries move to registers once (read
+        // from LDS inside the K loop, every request would wait for the table and, with it, for every
+        // fragment read in flight)
+        if constexpr (ROWREG) {
+#pragma unroll
+            for (int k = 0; k < APT; ++k) rowreg[k] = rowtab[4 * (wave * APT + k) + (lane >> 4)];
+        }
     } else {
 #pragma unroll
         for (int par = 0; par < 4; ++par)
@@ -135,8 +149,9 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
             tap_hw[par] = kk < p.K ? (kh << 16) | kw : -16384 * 65536;
         }
     };
-    // requests the loads k0 <= k < k1 of iteration `it` (all of them: k0 = 0, k1 = APT)
-    auto load_a = [&](int it, uint8_t *dst, int k0, int k1) {
+    // requests the loads k0 <= k < k1 of iteration `it` (all of them: k0 = 0, k1 = APT); CONV: rows[k - kbase] is
+    // the table entry of the row load k fetches
+    auto load_a = [&](int it, uint8_t *dst, int k0, int k1, const int2 *rows, int kbase) {
         // An iteration that does not exist is requested out of range, which moves no data.  No branch:
         // the loop body is the same straight-line code every time, which lets the compiler count
         // outstanding loads exactly instead of waiting conservatively.
@@ -144,7 +159,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
 #pragma unroll
             for (int k = 0; k < APT; ++k) {
                 if (k < k0 || k >= k1) continue;
-                const int2 row = rowtab[4 * (wave * APT + k) + (lane >> 4)];
+                const int2 row = rows[k - kbase];
                 const int ih = (row.y >> 16) + (tap_hw[k & 3] >> 16);
                 const int iw = (int)(int16_t)(row.y & 0xffff) + (tap_hw[k & 3] & 0xffff);
                 const bool in = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
@@ -206,7 +221,14 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
     // in this order (the fences keep it): the loop's waits count on the panel being requested before
     // the weights, and on the weights of K step d before those of d + 1
     if constexpr (CONV) set_taps(0);
-    load_a(0, panel, 0, APT);
+    if constexpr (CONV && !ROWREG) {
+        int2 rows0[APT];
+#pragma unroll
+        for (int k = 0; k < APT; ++k) rows0[k] = rowtab[4 * (wave * APT + k) + (lane >> 4)];
+        load_a(0, panel, 0, APT, rows0, 0);
+    } else {
+        load_a(0, panel, 0, APT, rowreg, 0);
+    }
 #pragma unroll
     for (int d = 0; d < PD; ++d) {
         __builtin_amdgcn_sched_barrier(0);
@@ -262,6 +284,61 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (CONV) set_taps(it + 1);
 
+        if constexpr (SOLO) {
+            // One wave per SIMD: nothing hides a stall, so the K step is written as plain data flow and the
+            // instruction scheduler is told the pattern to weave: after every MFMA a handful of vector
+            // instructions (the next step's decoding, addresses), every second one an LDS read, and the
+            // step's memory requests spread evenly.  The fragments of step d + 1 are read during step d, so
+            // that no MFMA waits for LDS inside an iteration; only the first step after the barrier does.
+            constexpr int NF = 2 * TM;
+            g_v4i af[2][NF];
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+                af[0][f] = *reinterpret_cast<const g_v4i *>(cur + a_read[0][f / TM] + (f % TM) * 32 * GB_ROW);
+#pragma unroll
+            for (int d = 0; d < GB_KI; ++d) {
+                const int kb = it * GB_KI + d;
+                __builtin_amdgcn_sched_barrier(0);
+                if (d + 1 < GB_KI) {
+#pragma unroll
+                    for (int f = 0; f < NF; ++f)
+                        af[(d + 1) & 1][f] =
+                            *reinterpret_cast<const g_v4i *>(cur + a_read[d + 1][f / TM] + (f % TM) * 32 * GB_ROW);
+                }
+#pragma unroll
+                for (int f = 0; f < NF; ++f)
+#pragma unroll
+                    for (int t = 0; t < TN; ++t)
+                        acc[f % TM][t] = epi_mfma<EPI>(bfrag[t][f / TM], af[d & 1][f], acc[f % TM][t]);
+                g_v4i bnext[TN][2];
+#pragma unroll
+                for (int t = 0; t < TN; ++t) {
+                    uint32_t Dn[8];
+                    HighCodec<H>::decode(P[(d + 1) % PD][t], Dn);
+                    LP::apply(Q[(d + 1) % PD][t], Dn);
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2)
+                        bnext[t][h2] = g_v4i{(int)Dn[4 * h2], (int)Dn[4 * h2 + 1], (int)Dn[4 * h2 + 2],
+                                             (int)Dn[4 * h2 + 3]};
+                }
+                if (d < GB_KI - 1)
+                    load_a(it + 1, nxt, d * APT / (GB_KI - 1), (d + 1) * APT / (GB_KI - 1), rowreg, 0);
+                load_b(P[d % PD], Q[d % PD], kb + PD, 0, NBL);
+#pragma unroll
+                for (int m = 0; m < NF * TN; ++m) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);           // vector ALU in its shadow
+                    if (m % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // an LDS read
+                    if (m % 4 == 3) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);   // memory requests
+                    else __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int h2 = 0; h2 < 2; ++h2) bfrag[t][h2] = bnext[t][h2];
+            }
+        } else {
 #pragma unroll
         for (int d = 0; d < GB_KI; ++d) {
             const int kb = it * GB_KI + d;
@@ -280,6 +357,18 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
                 }
             }
 
+            // CONV without room for the whole row table in registers: the entries this K step's requests need
+            // are read with the step's first fragments, so that no request waits for the table in mid-step
+            constexpr int RS = (APT + GB_KI - 2) / (GB_KI - 1);
+            const int rs_k0 = d * APT / (GB_KI - 1);
+            int2 rowstep[RS];
+            if constexpr (CONV && !ROWREG) {
+                if (d < GB_KI - 1) {
+#pragma unroll
+                    for (int k = 0; k < RS; ++k)
+                        rowstep[k] = rowtab[4 * (wave * APT + min(rs_k0 + k, APT - 1)) + (lane >> 4)];
+                }
+            }
             // fragment f = (hf, i): LDS reads four fragments ahead of their MFMAs
             g_v4i af[PF];
 #pragma unroll
@@ -311,7 +400,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
                 // previous step, or at the start of this one)
                 if (d < GB_KI - 1)
                     load_a(it + 1, nxt, (d * NF + f) * APT / ((GB_KI - 1) * NF),
-                           (d * NF + f + 1) * APT / ((GB_KI - 1) * NF));
+                           (d * NF + f + 1) * APT / ((GB_KI - 1) * NF), ROWREG ? rowreg : rowstep, ROWREG ? 0 : rs_k0);
                 load_b(P[d % PD], Q[d % PD], kb + PD, f * NBL / NF, (f + 1) * NBL / NF);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -321,6 +410,7 @@ __global__ void __launch_bounds__(256, (TM <= 4 && EPI != EPI_ANY ? 2 : 1)) k_ne
 #pragma unroll
                     for (int h2 = 0; h2 < 2; ++h2) bfrag[t][h2] = bnext[t][h2];
             }
+        }
         }
     }
 
@@ -375,13 +465,16 @@ void launch_nested_gemm_big(bool full, const GemmParams &p, int tm_forced, int *
     const int nblocks = (p.N + GB_BN - 1) / GB_BN;
     const int mode = epi_mode(p);
     int tm = mode == EPI_ANY ? 4 : gemm_big_pick_tm(p.M, p.N, p.conv_big && p.KH * p.KW > 1);   // the element-wise epilogue is built for TM = 4 only
-    if (mode != EPI_ANY && tm_forced >= 2 && tm_forced <= 5) tm = tm_forced;   // test / tuning aid
+    // 128-row blocks that have a compute unit each anyway take its whole register file (variant 6)
+    if (tm == 4 && mode != EPI_ANY && ((p.M + 127) / 128) * nblocks <= 256) tm = 6;
+    if (mode != EPI_ANY && tm_forced >= 2 && tm_forced <= 6) tm = tm_forced;   // test / tuning aid
     if (tm_used) *tm_used = tm;
 #define NQ_GB_LAUNCH(FULLV, EPIV, TMV, CONVV)                                               \
     do {                                                                                    \
         auto k = k_nested_gemm_big<H, L, FULLV, EPIV, TMV, CONVV>;                          \
-        const size_t lds = 2 * (size_t)(32 * TMV) * GB_ROW + (CONVV ? 8 * 32 * TMV : 0);    \
-        const int64_t mblocks = (p.M + 32 * TMV - 1) / (32 * TMV);                          \
+        constexpr int ROWS = 32 * (TMV == 6 ? 4 : TMV);                                     \
+        const size_t lds = 2 * (size_t)ROWS * GB_ROW + (CONVV ? 8 * ROWS : 0);              \
+        const int64_t mblocks = (p.M + ROWS - 1) / ROWS;                                    \
         static bool granted = false;                                                        \
         if (!granted) {                                                                     \
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k),                    \
@@ -395,6 +488,7 @@ void launch_nested_gemm_big(bool full, const GemmParams &p, int tm_forced, int *
         if (tm == 2) NQ_GB_LAUNCH(FULLV, EPIV, 2, CONVV);        \
         else if (tm == 3) NQ_GB_LAUNCH(FULLV, EPIV, 3, CONVV);   \
         else if (tm == 5) NQ_GB_LAUNCH(FULLV, EPIV, 5, CONVV);   \
+        else if (tm == 6) NQ_GB_LAUNCH(FULLV, EPIV, 6, CONVV);   \
         else NQ_GB_LAUNCH(FULLV, EPIV, 4, CONVV);                \
     } while (0)
 #define NQ_GB_MODE(FULLV, CONVV)                                         \

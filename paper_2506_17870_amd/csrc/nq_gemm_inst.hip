@@ -1,6 +1,6 @@
-// Three translation units per nesting, compiled with -DNQ_INST_H=<h> -DNQ_INST_L=<l> and
-// -DNQ_INST_PART=0 (generic, windowed, register-stationary and few-channel kernels), 1 (large-GEMM kernels)
-// or 2 (depthwise / grouped convolution), so that the units build in parallel.
+// Four translation units per nesting, compiled with -DNQ_INST_H=<h> -DNQ_INST_L=<l> and
+// -DNQ_INST_PART=0 (generic, windowed, register-stationary and few-channel kernels), 1 (large-GEMM kernels),
+// 2 (depthwise / grouped convolution) or 3 (stationary-weights GEMM), so that the units build in parallel.
 #if NQ_INST_PART == 0
 #include "nq_conv_rowstream.h"
 #include "nq_conv_smallcin.h"
@@ -24,6 +24,13 @@ template void launch_nested_conv_smallcin<NQ_INST_H, NQ_INST_L>(bool, const Gemm
 namespace nq {
 template void launch_nested_conv_grouped<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, const GroupGeom &,
                                                                hipStream_t, void *, void *);
+}
+#elif NQ_INST_PART == 3
+#include "nq_gemm_stat.h"
+
+namespace nq {
+template void launch_nested_gemm_stat<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, const StatGeom &, hipStream_t,
+                                                            void *, void *);
 }
 #else
 #include "nq_gemm_big.h"

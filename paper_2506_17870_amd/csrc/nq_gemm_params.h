@@ -99,6 +99,39 @@ struct GroupGeom {
     int64_t x_bytes;  // B * H * W * C (< 2^31)
 };
 
+// Geometry of the stationary-weights GEMM (1x1 convolutions with 64, 128 or 256 input channels at any stride,
+// GEMMs with that K): persistent blocks, each a column group of 64 * wn columns and a slot of row tiles.
+struct StatGeom {
+    int ks;            // K steps of 64: 1, 2 or 4
+    int wn;            // waves along N: 4, 2 or 1 (256, 128 or 64 columns per block)
+    int rps;           // rows per slot: a block takes the rows [slot * rps, (slot + 1) * rps), tile by tile
+    int nslots;        // slots = ceil(M / rps)
+    int cgroups;       // column groups = ceil(N / (64 * wn))
+    int interleave;    // 1: a block takes the tiles slot, slot + nslots, ... instead of a run of rps rows
+    int strided;       // 1: row m is pixel (oh * stride, ow * stride) of its image (strided 1x1 convolution)
+    int howo;          // Ho * Wo
+    unsigned howo_magic, wo_magic;   // ceil(2^32 / d): n / d == umulhi(n, magic) as long as n * d < 2^32; 0 for d = 1
+    int img_bytes;     // H * W * Cin
+    int row_step;      // stride * W * Cin: input bytes from one output row to the next
+    int col_step;      // stride * Cin
+    int x_bytes;       // bytes of the whole input (< 2^31 - 2^16)
+};
+
+// Block tile of the stationary-weights GEMM: waves side by side along N (wn of them, 64 columns each), the
+// rest stacked along M with one or two 32-row tiles each; panels of the ring (as many as fit, up to four); dynamic
+// LDS of the kernel.
+constexpr int st_tm(int wn) { return wn == 4 ? 2 : 1; }
+constexpr int st_bm(int wn) { return (4 / wn) * 32 * st_tm(wn); }
+constexpr int st_ring(int ks, int wn)
+{
+    const int panel = st_bm(wn) * 64 * ks;
+    return 4 * panel <= 72 * 1024 ? 4 : (3 * panel <= 72 * 1024 ? 3 : 2);
+}
+constexpr size_t st_lds_bytes(int ks, int wn)
+{
+    return (size_t)st_ring(ks, wn) * st_bm(wn) * 64 * ks + 1024 /* dump */ + 4 * 2 * 64 * sizeof(float) /* constants */;
+}
+
 // Tile shapes: 0 = 256x64 (narrow outputs), 1 = 128x256 (large), 2 = 64x256 (few rows).
 constexpr int NQ_TILE_BM[3] = {256, 128, 64};
 constexpr int NQ_TILE_BN[3] = {64, 256, 256};
@@ -139,6 +172,11 @@ void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, v
 template <int H, int L>
 void launch_nested_gemm_big(bool full, const GemmParams &p, int tm_forced, int *tm_used, hipStream_t st,
                             void *ev_start, void *ev_stop);
+
+// Short reductions (K = 64, 128, 256): weights stationary in registers, persistent blocks over row tiles.
+template <int H, int L>
+void launch_nested_gemm_stat(bool full, const GemmParams &p, const StatGeom &g, hipStream_t st, void *ev_start,
+                             void *ev_stop);
 
 // GEMM over the paper's word pages (64 / k fields per 64-bit word); WH, WL: words per row of the two pages.
 // Not a template: nq_gemm_words.hip holds every nesting.

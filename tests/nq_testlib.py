@@ -34,11 +34,13 @@ class Case:
 
 
 # Kernel choices every case is run with: the library's own, then each kernel forced through nq_set_tuning
-# (1 generic, 2 windowed, 3 register-stationary, 4 large GEMM, 5 few input channels, 6 few rows; a kernel
+# (1 generic, 2 windowed, 3 register-stationary, 4 large GEMM, 5 few input channels, 6 few rows, 9 stationary
+# weights; a kernel
 # that does not apply to a shape is not forced, the library's choice runs again).  The large-GEMM kernel is
 # also run with every tile height it is built for (rows per block = 32 * TM, TM = 2..5): the library picks
-# the height from the shape, so without this a parity shape reaches one height only.
-KERNEL_CHOICES = ("", "1", "2", "3", "4", "4/tm2", "4/tm3", "4/tm4", "4/tm5", "5", "6")
+# the height from the shape, so without this a parity shape reaches one height only ("tm6": 128 rows with the
+# compute unit to itself).
+KERNEL_CHOICES = ("", "1", "2", "3", "4", "4/tm2", "4/tm3", "4/tm4", "4/tm5", "4/tm6", "5", "6", "9")
 
 
 def set_choice(choice):

@@ -235,10 +235,10 @@ def test_group_members_switch_through_the_batch_calls_only(nq):
 
 
 def test_tuning_setter_argument_checks(nq):
-    for key in (nq.NQ_TUNE_KERNEL, nq.NQ_TUNE_BIG_TM, nq.NQ_TUNE_GC_UNITS):
+    for key in (nq.NQ_TUNE_KERNEL, nq.NQ_TUNE_BIG_TM, nq.NQ_TUNE_GC_UNITS, nq.NQ_TUNE_STAT_ROWS):
         nq.nq_set_tuning(key, 3)
         nq.nq_set_tuning(key, 0)
-    for key, value in ((-1, 0), (3, 0), (0, -1)):
+    for key, value in ((-1, 0), (4, 0), (0, -1)):
         with pytest.raises(nq.NQError) as e:
             nq.nq_set_tuning(key, value)
         assert e.value.status == nq.NQ_ERR_INVALID_ARG
