@@ -275,6 +275,29 @@ nq_status nq_gemm_full(const int8_t *d_x, int64_t M, const nq_weight *w, const n
 nq_status nq_gemm_part(const int8_t *d_x, int64_t M, const nq_weight *w, const nq_epilogue *epi,
                        void *d_y, void *stream);
 
+/* Many few-row GEMMs in one launch (Sec. 3.3: a deployed model is a stack of nested layers; at small batch the
+ * packed pages are the traffic, and a launch per layer of a few blocks each is bound by the launches, not by
+ * the pages).  `jobs` is a HOST array of `count` problems, read before the call returns; each is what one
+ * nq_gemm_full (full_bit != 0) or nq_gemm_part call takes, with the epilogue by value.  Same results as `count`
+ * single calls.  Built for the few-row regime: every M <= 64, K a multiple of 16, d_x 16-byte aligned, dense
+ * pages, one nesting and lower-part format for all problems, and one output kind for all (fp32 without
+ * residual, or int8 with N a multiple of 16 and aligned pointers; no accumulator dump): NQ_ERR_UNSUPPORTED /
+ * NQ_ERR_ALIGN otherwise, and the caller issues single calls.  The problems are handed to the kernel as a
+ * table in device memory: d_workspace (16-byte aligned, at least nq_gemm_batch_workspace_bytes(count), caller
+ * owned) receives it by a copy ordered on `stream`, and must not be reused by other work until the launch
+ * has finished.  Full-bit: every lower-bit page must be resident (NQ_ERR_NOT_RESIDENT); the stream waits for
+ * pages still in flight. */
+typedef struct {
+    const int8_t *d_x;      /* device int8[M][K], K = w->K      */
+    int64_t M;
+    const nq_weight *w;
+    nq_epilogue epi;
+    void *d_y;              /* device fp32[M][N] or int8[M][N]  */
+} nq_gemm_job;
+size_t nq_gemm_batch_workspace_bytes(int64_t count);
+nq_status nq_gemm_batch(const nq_gemm_job *jobs, int64_t count, int full_bit, void *d_workspace,
+                        size_t workspace_bytes, void *stream);
+
 /* The same two modes as an implicit-GEMM convolution: d_x is int8[B][H][W][Cin], the
  * output is [B][Ho][Wo][Cout]; w->N == Cout and w->K == KH*KW*Cin; the epilogue's
  * residual and accumulator dump are indexed like the output. */

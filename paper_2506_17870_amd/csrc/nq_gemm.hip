@@ -2,6 +2,8 @@
 // page (paper Sec. 3.2.3 / 3.3: the caller picks full-bit or part-bit; a paged-out page is
 // an error, never a silent downgrade), tile choice and launch.
 #include <atomic>
+#include <cstring>
+#include <vector>
 
 #include "nq_common.h"
 #include "nq_gemm_params.h"
@@ -265,30 +267,37 @@ int pick_tile(int64_t M, int64_t N)
 
 // gs: 0 for a GEMM or a dense convolution, else the channels per group of a grouped convolution
 // (the caller has checked that the shape is one the grouped kernel takes).
-nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *w, const nq_epilogue *epi,
-              void *d_y, void *stream, int gs = 0)
+// The checks every inference call makes on its descriptor and pointers.  *empty: nothing to compute.
+nq_status check_problem(bool full, const int8_t *d_x, int64_t M, const nq_weight *w, const nq_epilogue *epi,
+                        const void *d_y, bool *empty)
 {
+    *empty = false;
     if (!w || !epi) return NQ_ERR_INVALID_ARG;
     nq_status st = check_cfg(&w->cfg);
     if (st != NQ_OK) return st;
-    // the paper's word pages (Sec. 3.3.4) are read by the plain GEMM only
-    const bool words = w->cfg.layout == NQ_LAYOUT_PAPER_U64;
-    if (words && (gs > 0 || g.KH != 1 || g.KW != 1 || g.stride != 1 || g.pad != 0)) return NQ_ERR_UNSUPPORTED;
     if ((st = check_shape(w->N, w->K)) != NQ_OK) return st;
-    if (g.M < 0) return NQ_ERR_INVALID_ARG;
-    const int h = w->cfg.n_bits - w->cfg.l_bits, l = w->cfg.l_bits;
+    if (M < 0) return NQ_ERR_INVALID_ARG;
+    const int h = w->cfg.n_bits - w->cfg.l_bits;
     if (full && !w->low_resident) return NQ_ERR_NOT_RESIDENT;
-    if (g.M == 0 || w->N == 0) return NQ_OK;
+    if (M == 0 || w->N == 0) {
+        *empty = true;
+        return NQ_OK;
+    }
     if (w->K == 0) return NQ_ERR_SHAPE;
     if (!d_x || !d_y || !w->d_high || !w->d_scale || (full && !w->d_low)) return NQ_ERR_INVALID_ARG;
     if (!aligned16(w->d_high) || (full && !aligned16(w->d_low))) return NQ_ERR_ALIGN;
     if (w->high_bytes < nq_packed_bytes(w->N, w->K, h, w->cfg.layout)) return NQ_ERR_RANGE;
     if (full && w->low_bytes < nq_packed_bytes(w->N, w->K, low_field_bits(&w->cfg), w->cfg.layout)) return NQ_ERR_RANGE;
-    if (w->N > (1 << 24) || g.M > (int64_t(1) << 40) / (w->N > 0 ? w->N : 1)) return NQ_ERR_SHAPE;
+    if (w->N > (1 << 24) || M > (int64_t(1) << 40) / (w->N > 0 ? w->N : 1)) return NQ_ERR_SHAPE;
+    return NQ_OK;
+}
 
-    hipStream_t s = (hipStream_t)stream;
-
-    GemmParams p;
+// Kernel arguments of a checked problem.
+void fill_params(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *w, const nq_epilogue *epi,
+                 void *d_y, GemmParams *out)
+{
+    GemmParams &p = *out;
+    const int l = w->cfg.l_bits;
     p.x = d_x;
     p.ph = (const uint32_t *)w->d_high;
     p.pl = full ? (const uint32_t *)w->d_low : nullptr;
@@ -320,29 +329,59 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
                     !aligned16(p.scale) || !aligned16(p.bias);
     else
         p.general = p.acc_dump != nullptr || p.resid != nullptr;
+    p.conv_big = 0;
+    p.cin_shift = 0;
+    p.kw_magic = 0;
+}
+
+// Makes `s` wait for a lower-bit page that may still be in flight on its copy stream.
+bool wait_for_page(const nq_weight *w, hipStream_t s)
+{
+    if (!(w->low_event_armed && w->low_event)) return true;
+    // Once the copy has completed no later launch needs to wait for it: the flag (an internal field of
+    // the caller's descriptor) is dropped, so that only the launches issued while the page travels pay
+    // for a wait.  Not while the stream is being captured: an event recorded inside a capture cannot
+    // be queried, and a replay needs the dependency every time.
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    const bool capturing = hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
+    if (!capturing && hipEventQuery((hipEvent_t)w->low_event) == hipSuccess) {
+        const_cast<nq_weight *>(w)->low_event_armed = 0;
+        return true;
+    }
+    (void)hipGetLastError();   // hipErrorNotReady from the query is not an error
+    if (hipStreamWaitEvent(s, (hipEvent_t)w->low_event, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return true;
+}
+
+// gs: 0 for a GEMM or a dense convolution, else the channels per group of a grouped convolution
+// (the caller has checked that the shape is one the grouped kernel takes).
+nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *w, const nq_epilogue *epi,
+              void *d_y, void *stream, int gs = 0)
+{
+    if (!w || !epi) return NQ_ERR_INVALID_ARG;
+    nq_status st = check_cfg(&w->cfg);
+    if (st != NQ_OK) return st;
+    // the paper's word pages (Sec. 3.3.4) are read by the plain GEMM only
+    const bool words = w->cfg.layout == NQ_LAYOUT_PAPER_U64;
+    if (words && (gs > 0 || g.KH != 1 || g.KW != 1 || g.stride != 1 || g.pad != 0)) return NQ_ERR_UNSUPPORTED;
+    bool empty = false;
+    if ((st = check_problem(full, d_x, g.M, w, epi, d_y, &empty)) != NQ_OK || empty) return st;
+    const int h = w->cfg.n_bits - w->cfg.l_bits, l = w->cfg.l_bits;
+
+    hipStream_t s = (hipStream_t)stream;
+
+    GemmParams p;
+    fill_params(full, d_x, g, w, epi, d_y, &p);
 
     // Everything that can fail is checked before anything is enqueued: `commit` is called once the kernel
     // and its geometry are fixed, right before the launch.  It makes the stream wait for a page that may
     // still be in flight on the copy stream and takes the one-shot profiling events.
     void *ev0 = nullptr, *ev1 = nullptr;
     auto commit = [&]() -> bool {
-        if (full && w->low_event_armed && w->low_event) {
-            // Once the copy has completed no later launch needs to wait for it: the flag (an internal field of
-            // the caller's descriptor) is dropped, so that only the launches issued while the page travels pay
-            // for a wait.  Not while the stream is being captured: an event recorded inside a capture cannot
-            // be queried, and a replay needs the dependency every time.
-            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-            const bool capturing = hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
-            if (!capturing && hipEventQuery((hipEvent_t)w->low_event) == hipSuccess) {
-                const_cast<nq_weight *>(w)->low_event_armed = 0;
-            } else {
-                (void)hipGetLastError();   // hipErrorNotReady from the query is not an error
-                if (hipStreamWaitEvent(s, (hipEvent_t)w->low_event, 0) != hipSuccess) {
-                    (void)hipGetLastError();
-                    return false;
-                }
-            }
-        }
+        if (full && !wait_for_page(w, s)) return false;
         ev0 = g_ev_start;
         ev1 = g_ev_stop;
         g_ev_start = g_ev_stop = nullptr;
@@ -476,6 +515,92 @@ nq_status gemm(bool full, const int8_t *d_x, int64_t M, const nq_weight *w, cons
     return run(full, d_x, g, w, epi, d_y, stream);
 }
 
+// ---- many few-row GEMMs in one launch ------------------------------------------------------------------------
+// Layout of the table the batch kernel reads: `count` problems, then the running count of their blocks.
+size_t batch_table_bytes(int64_t count)
+{
+    return (size_t)count * sizeof(GemmParams) + (size_t)(count + 1) * sizeof(int);
+}
+
+nq_status gemm_batch(const nq_gemm_job *jobs, int64_t count, int full_bit, void *d_table, size_t table_bytes,
+                     void *stream)
+{
+    if (count < 0 || (count > 0 && !jobs)) return NQ_ERR_INVALID_ARG;
+    if (count == 0) return NQ_OK;
+    if (count > (int64_t(1) << 20)) return NQ_ERR_SHAPE;
+    if (!d_table || ((uintptr_t)d_table & 15u) != 0) return d_table ? NQ_ERR_ALIGN : NQ_ERR_INVALID_ARG;
+    if (table_bytes < batch_table_bytes(count)) return NQ_ERR_RANGE;
+    const bool full = full_bit != 0;
+    // The table is staged in host memory that stays valid until this thread's next call; the copy below is
+    // ordered on the stream like the launch that reads it.
+    thread_local std::vector<unsigned char> staging;
+    staging.resize(batch_table_bytes(count));
+    GemmParams *hp = reinterpret_cast<GemmParams *>(staging.data());
+    int *hfirst = reinterpret_cast<int *>(staging.data() + (size_t)count * sizeof(GemmParams));
+    const nq_cfg cfg0 = jobs[0].w ? jobs[0].w->cfg : nq_cfg{0, 0, 0, 0};
+    int mode0 = -1;
+    bool two_tiles = false, staged = false;
+    int64_t blocks = 0, live = 0;
+    for (int64_t i = 0; i < count; ++i) {
+        const nq_gemm_job &j = jobs[i];
+        bool empty = false;
+        nq_status st = check_problem(full, j.d_x, j.M, j.w, &j.epi, j.d_y, &empty);
+        if (st != NQ_OK) return st;
+        // one kernel instantiation serves the whole table: same nesting and format, dense pages, few rows,
+        // the 16-byte activation path, one epilogue layout
+        if (j.w->cfg.n_bits != cfg0.n_bits || j.w->cfg.l_bits != cfg0.l_bits || j.w->cfg.low_format != cfg0.low_format ||
+            j.w->cfg.layout != NQ_LAYOUT_DENSE)
+            return NQ_ERR_UNSUPPORTED;
+        if (empty) continue;
+        if (j.M > 64 || j.w->K % 16 != 0) return NQ_ERR_UNSUPPORTED;
+        if (!aligned16(j.d_x)) return NQ_ERR_ALIGN;
+        if (j.M * j.w->K >= 0x7fff0000LL) return NQ_ERR_SHAPE;
+        Geometry g;
+        g.M = j.M;
+        g.H = g.W = g.Ho = g.Wo = g.KH = g.KW = g.stride = 1;
+        g.pad = 0;
+        g.Cin = (int)j.w->K;
+        fill_params(full, j.d_x, g, j.w, &j.epi, j.d_y, &hp[live]);
+        const int mode = hp[live].general ? 2 : (hp[live].out_int8 ? 1 : 0);
+        if (mode == 2) return NQ_ERR_UNSUPPORTED;           // accumulator dump, ragged N, fp32 output with residual
+        if (mode0 < 0) mode0 = mode;
+        if (mode != mode0) return NQ_ERR_UNSUPPORTED;
+        two_tiles = two_tiles || j.M > 32;
+        staged = staged || hp[live].KB >= 32;
+        hfirst[live] = (int)blocks;
+        blocks += hp[live].NB;
+        if (blocks > 0x7fffffffLL) return NQ_ERR_SHAPE;
+        ++live;
+    }
+    if (live == 0) return NQ_OK;
+    hfirst[live] = (int)blocks;
+    // compact layout on the device: `live` problems, then live + 1 running counts
+    std::memmove(staging.data() + (size_t)live * sizeof(GemmParams), hfirst, (size_t)(live + 1) * sizeof(int));
+    hipStream_t s = (hipStream_t)stream;
+    if (full) {
+        const void *last = nullptr;
+        for (int64_t i = 0; i < count; ++i) {            // one wait per distinct event (a group shares one)
+            const nq_weight *w = jobs[i].w;
+            if (jobs[i].M == 0 || w->N == 0 || w->low_event == last) continue;
+            last = w->low_event;
+            if (!wait_for_page(w, s)) return NQ_ERR_HIP;
+        }
+    }
+    const size_t bytes = (size_t)live * sizeof(GemmParams) + (size_t)(live + 1) * sizeof(int);
+    if (hipMemcpyAsync(d_table, staging.data(), bytes, hipMemcpyHostToDevice, s) != hipSuccess) {
+        (void)hipGetLastError();
+        return NQ_ERR_HIP;
+    }
+    const GemmParams *d_jobs = reinterpret_cast<const GemmParams *>(d_table);
+    const int *d_first = reinterpret_cast<const int *>((const unsigned char *)d_table + (size_t)live * sizeof(GemmParams));
+    const int h = cfg0.n_bits - cfg0.l_bits, l = cfg0.l_bits;
+    const int fmode = full ? (cfg0.low_format == NQ_LOW_SIGNED_L1 ? 2 : 1) : 0;
+    g_last_family = 6; g_last_variant = 1;
+    NQ_DISPATCH_HL(h, l, launch_nested_gemm_skinny_batch, fmode, mode0, two_tiles, staged, d_jobs, d_first, (int)live,
+                   (int)blocks, s);
+    return launch_status();
+}
+
 nq_status conv(bool full, const int8_t *d_x, const nq_conv_shape *sh, const nq_weight *w, const nq_epilogue *epi,
                void *d_y, void *stream)
 {
@@ -538,6 +663,17 @@ extern "C" nq_status nq_gconv_part(const int8_t *d_x, const nq_conv_shape *shape
                                    const nq_epilogue *epi, void *d_y, void *stream)
 {
     return gconv(false, d_x, shape, groups, w, epi, d_y, stream);
+}
+
+extern "C" size_t nq_gemm_batch_workspace_bytes(int64_t count)
+{
+    return count > 0 ? batch_table_bytes(count) : 0;
+}
+
+extern "C" nq_status nq_gemm_batch(const nq_gemm_job *jobs, int64_t count, int full_bit, void *d_workspace,
+                                   size_t workspace_bytes, void *stream)
+{
+    return gemm_batch(jobs, count, full_bit, d_workspace, workspace_bytes, stream);
 }
 
 extern "C" nq_status nq_set_tuning(int key, int value)

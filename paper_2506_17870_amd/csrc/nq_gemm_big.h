@@ -446,6 +446,9 @@ inline int gemm_big_pick_tm(int64_t M, int64_t N, bool filter)
     // A filter (implicit GEMM with a gather per tap) whose 128-row blocks would not even fill the compute units
     // once runs better as twice as many 64-row blocks, two per unit (3x3, 14x14x256 -> 256 at batch 128 inside
     // the ResNet-101 forward: 29.2 us against 31.0 us; 3x3 stride 2, 28x28x256 -> 256: 27.6 us against 34.8 us).
+    // With at least three quarters of the compute units busy the 128-row blocks win after all, each with a unit to
+    // itself (variant 6, chosen by the launcher: 24.8 us against 27.3 us for the first of these layers).
+    if (filter && ((M + 127) / 128) * nblocks <= 256 && ((M + 127) / 128) * nblocks >= 190) return 4;
     if (filter && ((M + 127) / 128) * nblocks <= 256 && ((M + 63) / 64) * nblocks <= 512) return 2;
     int best = 4;
     double best_cost = 1e30;

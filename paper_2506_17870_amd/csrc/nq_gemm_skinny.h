@@ -57,8 +57,9 @@ constexpr int sk_lds_bytes()
 // TMS: 32-row tiles (1: M <= 32, 2: M <= 64).  NWS: waves per block (4 or 8).  STAGED: activations through
 // LDS (long reductions), else straight from memory into the lanes' fragments (short ones, where the extra
 // hop would only add to a latency-bound kernel).
+// The work of one block: column tile nb of the problem p.  lds: the block's dynamic LDS.
 template <int H, int L, int FULL, int EPI, int TMS, int NWS, bool STAGED>
-__global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skinny(const GemmParams p)
+__device__ __forceinline__ void skinny_block(const GemmParams &p, const int nb, uint8_t *lds)
 {
     constexpr int S = 8 - H;
     constexpr int SHIFT = FULL ? (8 - H - L) : S;
@@ -67,12 +68,9 @@ __global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skin
     constexpr int SK_PD = 4;       // K steps of packed weights in flight per wave
     constexpr int CS = CH::CS, RS = CH::RS, NPT = CH::NPT;
 
-    // two activation chunks; the partial sums of the waves use the same memory at the end (sk_lds_bytes)
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-
+    // lds: two activation chunks; the partial sums of the waves use the same memory at the end (sk_lds_bytes)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int nb = blockIdx.x;
     const int wslot = epi_weight_slot<EPI>(lane);
 
     // Activations go through LDS: fetched straight from memory, a step's fragments are one cache line per lane
@@ -221,6 +219,65 @@ __global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skin
         epi_resid_load<EPI>(p, 32 * i, rows, nb * 32, lane, res);
         epi_tile<EPI>(p, acc[i], SHIFT, e, 32 * i, rows, nb * 32, lane, res);
     }
+}
+
+template <int H, int L, int FULL, int EPI, int TMS, int NWS, bool STAGED>
+__global__ void __launch_bounds__(64 * NWS, NWS == 4 ? 2 : 1) k_nested_gemm_skinny(const GemmParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    skinny_block<H, L, FULL, EPI, TMS, NWS, STAGED>(p, blockIdx.x, lds);
+}
+
+// Many small layers in one launch (the weights of a stack of layers are the traffic, and a launch per layer
+// of a few blocks each is launch bound): the problems wait as a table in device memory, `first` holds the
+// running count of their blocks, and a block finds its problem by binary search (everything uniform, so the
+// search and the copy of the problem's parameters run on the scalar unit).
+template <int H, int L, int FULL, int EPI, int TMS, bool STAGED>
+__global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny_batch(const GemmParams *__restrict__ jobs,
+                                                                      const int *__restrict__ first, const int count)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+    const int b = blockIdx.x;
+    int lo = 0, hi = count - 1;                  // the last job with first[job] <= b
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (first[mid] <= b) lo = mid; else hi = mid - 1;
+    }
+    const GemmParams p = jobs[lo];
+    skinny_block<H, L, FULL, EPI, TMS, 4, STAGED>(p, b - first[lo], lds);
+}
+
+// Launches the batch kernel: one instantiation for the whole table (mode: epilogue layout shared by all
+// problems; two_tiles: some problem has more than 32 rows; staged: some reduction is 2048 or longer).
+template <int H, int L>
+void launch_nested_gemm_skinny_batch(int fmode, int mode, bool two_tiles, bool staged, const GemmParams *d_jobs,
+                                     const int *d_first, int count, int blocks, hipStream_t st)
+{
+#define NQ_SKB_ONE(FULLV, EPIV, TMSV, STAGEDV)                                                          \
+    do {                                                                                                \
+        auto k = k_nested_gemm_skinny_batch<H, L, FULLV, EPIV, TMSV, STAGEDV>;                           \
+        constexpr int lds = STAGEDV ? sk_lds_bytes<TMSV, 4>() : 3 * TMSV * 4096;                         \
+        static bool granted = false;                                                                    \
+        if (!granted) {                                                                                 \
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(k),                                \
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);                 \
+            granted = true;                                                                             \
+        }                                                                                               \
+        hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(256), lds, st, d_jobs, d_first, count);      \
+    } while (0)
+#define NQ_SKB_SHAPE(FULLV, EPIV)                                        \
+    do {                                                                 \
+        if (two_tiles && staged) NQ_SKB_ONE(FULLV, EPIV, 2, true);       \
+        else if (two_tiles) NQ_SKB_ONE(FULLV, EPIV, 2, false);           \
+        else if (staged) NQ_SKB_ONE(FULLV, EPIV, 1, true);               \
+        else NQ_SKB_ONE(FULLV, EPIV, 1, false);                          \
+    } while (0)
+#define NQ_SKB_MODES(FULLV)                                      \
+    do {                                                         \
+        if (mode == EPI_I8) NQ_SKB_SHAPE(FULLV, EPI_I8);         \
+        else NQ_SKB_SHAPE(FULLV, EPI_F32);                       \
+    } while (0)
+    if (fmode == 2) NQ_SKB_MODES(2); else if (fmode == 1) NQ_SKB_MODES(1); else NQ_SKB_MODES(0);
 }
 
 template <int H, int L>
