@@ -298,6 +298,16 @@ size_t nq_gemm_batch_workspace_bytes(int64_t count);
 nq_status nq_gemm_batch(const nq_gemm_job *jobs, int64_t count, int full_bit, void *d_workspace,
                         size_t workspace_bytes, void *stream);
 
+/* nq_gemm_batch for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid it): the table goes into an array of the library's own in device memory instead
+ * of a workspace, so the call allocates nothing and takes no workspace argument.  At most
+ * NQ_GEMM_BATCH_STATIC_MAX problems per call (NQ_ERR_SHAPE beyond that).  Every GPU the process uses holds
+ * its own copy of that array (about 0.4 MB) until the process ends.  All calls on one GPU share it: a call
+ * overwrites the table of the call before, so two calls whose launches may overlap on one GPU (different
+ * streams, or threads) race; calls on one stream are safe. */
+#define NQ_GEMM_BATCH_STATIC_MAX 2048
+nq_status nq_gemm_batch_static(const nq_gemm_job *jobs, int64_t count, int full_bit, void *stream);
+
 /* The same two modes as an implicit-GEMM convolution: d_x is int8[B][H][W][Cin], the
  * output is [B][Ho][Wo][Cout]; w->N == Cout and w->K == KH*KW*Cin; the epilogue's
  * residual and accumulator dump are indexed like the output. */

@@ -27,7 +27,7 @@ EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "
            "nq_decompose", "nq_pack", "nq_decompose_pack", "nq_decompose_pack_batch",
            "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
            "nq_weight_init_group", "nq_page_out_low_batch", "nq_page_in_low_batch",
-           "nq_gemm_full", "nq_gemm_part", "nq_gemm_batch_workspace_bytes", "nq_gemm_batch", "nq_conv_full", "nq_conv_part", "nq_gconv_full", "nq_gconv_part",
+           "nq_gemm_full", "nq_gemm_part", "nq_gemm_batch_workspace_bytes", "nq_gemm_batch", "nq_gemm_batch_static", "nq_conv_full", "nq_conv_part", "nq_gconv_full", "nq_gconv_part",
            "nq_set_tuning", "nq_profile_next_launch", "nq_profile_last_kernel", "nq_event_create", "nq_event_destroy",
            "nq_event_elapsed_ms", "nq_maxpool_i8", "nq_avgpool_i8"]
 
@@ -62,6 +62,9 @@ class nq_epilogue(ctypes.Structure):
 class nq_gemm_job(ctypes.Structure):
     _fields_ = [("d_x", ctypes.c_void_p), ("M", ctypes.c_int64), ("w", ctypes.POINTER(nq_weight)),
                 ("epi", nq_epilogue), ("d_y", ctypes.c_void_p)]
+
+
+NQ_GEMM_BATCH_STATIC_MAX = 2048
 
 
 class nq_conv_shape(ctypes.Structure):
@@ -101,6 +104,7 @@ _SIGS = {
     "nq_gemm_part": (_int, [_vp, _i64, _wp, _ep, _vp, _vp]),
     "nq_gemm_batch_workspace_bytes": (ctypes.c_size_t, [_i64]),
     "nq_gemm_batch": (_int, [ctypes.POINTER(nq_gemm_job), _i64, _int, _vp, ctypes.c_size_t, _vp]),
+    "nq_gemm_batch_static": (_int, [ctypes.POINTER(nq_gemm_job), _i64, _int, _vp]),
     "nq_conv_full": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
     "nq_conv_part": (_int, [_vp, _sp, _wp, _ep, _vp, _vp]),
     "nq_gconv_full": (_int, [_vp, _sp, _int, _wp, _ep, _vp, _vp]),
@@ -269,6 +273,10 @@ def nq_gemm_batch(jobs, full_bit, d_workspace, stream=None):
     _check(_lib.nq_gemm_batch(_jobs(jobs), len(jobs), int(full_bit), _ptr(d_workspace),
                               d_workspace.numel() * d_workspace.element_size() if d_workspace is not None else 0,
                               _stream(stream)), "nq_gemm_batch")
+
+
+def nq_gemm_batch_static(jobs, full_bit, stream=None):
+    _check(_lib.nq_gemm_batch_static(_jobs(jobs), len(jobs), int(full_bit), _stream(stream)), "nq_gemm_batch_static")
 
 
 def nq_conv_full(d_x, shape: nq_conv_shape, w: nq_weight, epi: nq_epilogue, d_y, stream=None):

@@ -3,6 +3,7 @@
 // an error, never a silent downgrade), tile choice and launch.
 #include <atomic>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "nq_common.h"
@@ -522,6 +523,36 @@ size_t batch_table_bytes(int64_t count)
     return (size_t)count * sizeof(GemmParams) + (size_t)(count + 1) * sizeof(int);
 }
 
+// Scratch of nq_gemm_batch_static: the same table in a device array of the library itself, for callers that
+// cannot allocate.  Every GPU the library runs on holds its own copy; host code reaches it through the address
+// hipGetSymbolAddress returns for the current device, never through the array's name.
+constexpr int64_t BATCH_STATIC_MAX = NQ_GEMM_BATCH_STATIC_MAX;
+static __device__ __align__(256) unsigned char g_batch_scratch[BATCH_STATIC_MAX * sizeof(GemmParams) +
+                                                               (BATCH_STATIC_MAX + 1) * sizeof(int)];
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES];        // per device, filled on the first call made with that device current
+
+nq_status static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) {
+        (void)hipGetLastError();
+        return NQ_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *q = nullptr;
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(g_batch_scratch)) != hipSuccess || !q) {
+            (void)hipGetLastError();
+            return NQ_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = q;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return NQ_OK;
+}
+
 nq_status gemm_batch(const nq_gemm_job *jobs, int64_t count, int full_bit, void *d_table, size_t table_bytes,
                      void *stream)
 {
@@ -674,6 +705,16 @@ extern "C" nq_status nq_gemm_batch(const nq_gemm_job *jobs, int64_t count, int f
                                    size_t workspace_bytes, void *stream)
 {
     return gemm_batch(jobs, count, full_bit, d_workspace, workspace_bytes, stream);
+}
+
+extern "C" nq_status nq_gemm_batch_static(const nq_gemm_job *jobs, int64_t count, int full_bit, void *stream)
+{
+    if (count > BATCH_STATIC_MAX) return NQ_ERR_SHAPE;      // beyond the library's own table
+    if (count <= 0) return count < 0 ? NQ_ERR_INVALID_ARG : NQ_OK;
+    void *scratch = nullptr;
+    nq_status st = static_scratch(&scratch);
+    if (st != NQ_OK) return st;
+    return gemm_batch(jobs, count, full_bit, scratch, sizeof(g_batch_scratch), stream);
 }
 
 extern "C" nq_status nq_set_tuning(int key, int value)
