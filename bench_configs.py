@@ -321,6 +321,22 @@ def c1_stack():
         print(f"  {'full' if full else 'part'}-bit: {ms:.2f} ms = {ms * 1e3 / L:.2f} us per layer, {wb / ms / 1e6:.0f} GB/s of packed "
               f"weights, {2.0 * M * N * K * L / ms / 1e9:.1f} TOPS (launch bound: a 64-row layer is one wave of 16 blocks)")
         del graph
+    # the same stack as ONE launch: nq_gemm_batch, the problems as a table in device memory
+    jobs = [(x, M, W.desc, epi, y) for W in layers]
+    ws = torch.empty(nq.nq_gemm_batch_workspace_bytes(L), dtype=torch.uint8, device="cuda")
+    for full in (True, False):
+        us = wall_us(lambda: nq.nq_gemm_batch(jobs, full, ws), n=10)
+
+        def fn(ev):
+            if ev:
+                nq.nq_profile_next_launch(ev[0], ev[1])
+            nq.nq_gemm_batch(jobs, full, ws)
+        kus, _ = kernel_us(fn, n=10)
+        wb = L * (nq.nq_packed_bytes(N, K, 6) + (low_bytes if full else 0))
+        print(f"  {'full' if full else 'part'}-bit, one nq_gemm_batch call: kernel {kus:.0f} us = {kus / L:.3f} us per layer, "
+              f"{wb / kus / 1e3:.0f} GB/s of packed weights ({100 * wb / kus / 1e3 / HBM_PEAK:.1f} % of HBM peak), "
+              f"{2.0 * M * N * K * L / kus / 1e6:.1f} TOPS; call to call, with the host filling the table of {L} problems: "
+              f"{us / 1e3:.2f} ms")
 
 
 def c2():
@@ -546,7 +562,9 @@ def page():
             best = min(best, (time.perf_counter() - t0) * 1e6)
         b = nq.nq_packed_bytes(N, K, l)
         print(f"| {name} | {best:.0f} | {b / best / 1e3:.1f} |")
-    # overlap: part-bit GEMMs on the compute stream while the page is copied on the other stream
+    # overlap: part-bit GEMMs on the compute stream while a page travels on the other stream.  The GEMM is timed
+    # by the time stamps of its own dispatch (what a kernel trace shows), so host-side costs of the switching
+    # calls cannot leak into it; those are timed separately, call by call, on the host clock.
     M, K, N, l = 12608, 3072, 768, 3
     w_int, scale = inputs.weights(N, K, 0.02, 8, 0)
     W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
@@ -554,14 +572,58 @@ def page():
     y = torch.empty((M, N), dtype=torch.float32, device="cuda")
     epi = nq.make_epilogue(0.02)
     side = torch.cuda.Stream()
-    alone = wall_us(lambda: nq.nq_gemm_part(x, M, W.desc, epi, y), n=30)
 
-    def both():
-        nq.nq_page_out_low(W.desc)
-        nq.nq_page_in_low(W.desc, side)
+    def gemm_fn(ev):
+        if ev:
+            nq.nq_profile_next_launch(ev[0], ev[1])
         nq.nq_gemm_part(x, M, W.desc, epi, y)
-    with_copy = wall_us(both, n=30)
-    print(f"\npart-bit fc2 GEMM alone {alone:.1f} us; with a concurrent page-in of its 0.88 MB page {with_copy:.1f} us")
+    alone, _ = kernel_us(gemm_fn)
+    print(f"\npart-bit fc2 GEMM (12608 x 3072 -> 768, fp32 out), kernel time alone: {alone:.1f} us")
+    print("\n| page travelling meanwhile | GEMM kernel us (median of the launches that ran during the copy) | copy us | GB/s |")
+    print("|---|---|---|---|")
+    big = nq.NestedWeight(16384, 16384, nq.make_cfg(8, 2))          # a 64 MiB lower-bit page of its own
+    for name, Wp, n_gemm in (("its own 0.88 MB page", W, 1), ("a 64 MiB page", big, 24)):
+        times, copies = [], []
+        for _ in range(7):
+            nq.nq_page_out_low(Wp.desc)
+            torch.cuda.synchronize()
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            evs = [(nq.nq_event_create(), nq.nq_event_create()) for _ in range(n_gemm)]
+            with torch.cuda.stream(side):
+                c0.record()
+                nq.nq_page_in_low(Wp.desc, side)
+                c1.record()
+            for ev in evs:
+                gemm_fn(ev)
+            torch.cuda.synchronize()
+            copy_us = c0.elapsed_time(c1) * 1e3
+            ks = [nq.nq_event_elapsed_ms(a, b) * 1e3 for a, b in evs]
+            # the launches that can have overlapped the copy: those that began within its duration
+            during = ks[:max(1, min(n_gemm, int(copy_us / max(alone, 1.0))))]
+            times += during
+            copies.append(copy_us)
+            for a, b in evs:
+                nq.nq_event_destroy(a)
+                nq.nq_event_destroy(b)
+        times.sort()
+        copies.sort()
+        byts = nq.nq_packed_bytes(Wp.N, Wp.K, Wp.cfg.l_bits)
+        cu = copies[len(copies) // 2]
+        print(f"| {name} | {times[len(times) // 2]:.1f} | {cu:.0f} | {byts / cu / 1e3:.1f} |")
+    # host cost of the switching calls (one descriptor; host clock around each call, median of 200)
+    def host_us(fn):
+        ts = []
+        for _ in range(200):
+            t0 = time.perf_counter()
+            fn()
+            ts.append((time.perf_counter() - t0) * 1e6)
+        torch.cuda.synchronize()
+        return sorted(ts)[len(ts) // 2]
+    t_out = host_us(lambda: nq.nq_page_out_low(W.desc))
+    t_in = host_us(lambda: (nq.nq_page_out_low(W.desc), nq.nq_page_in_low(W.desc, side)))
+    t_launch = host_us(lambda: nq.nq_gemm_part(x, M, W.desc, epi, y))
+    print(f"\nhost time per call: nq_page_out_low {t_out:.1f} us, page-out + nq_page_in_low (event wait, copy, event "
+          f"record) {t_in:.1f} us, nq_gemm_part launch {t_launch:.1f} us")
 
 
 def sweep():

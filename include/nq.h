@@ -343,7 +343,7 @@ nq_status nq_gconv_part(const int8_t *d_x, const nq_conv_shape *shape, int group
 typedef enum { NQ_TUNE_KERNEL = 0, NQ_TUNE_BIG_TM = 1, NQ_TUNE_GC_UNITS = 2, NQ_TUNE_STAT_ROWS = 3, NQ_TUNE_COUNT = 4 } nq_tune_key;
 nq_status nq_set_tuning(int key, int value);
 
-/* Profiling aid: the next nq_gemm_* / nq_conv_* / nq_gconv_* call made by this host thread attaches the two
+/* Profiling aid: the next nq_gemm_* (nq_gemm_batch included) / nq_conv_* / nq_gconv_* call made by this host thread attaches the two
  * hipEvent_t (either may be NULL) to its kernel dispatch, so that hipEventElapsedTime(start,
  * stop) is the execution time of that kernel alone.  One shot; events are the caller's. */
 nq_status nq_profile_next_launch(void *start_event, void *stop_event);

@@ -627,8 +627,10 @@ nq_status gemm_batch(const nq_gemm_job *jobs, int64_t count, int full_bit, void 
     const int h = cfg0.n_bits - cfg0.l_bits, l = cfg0.l_bits;
     const int fmode = full ? (cfg0.low_format == NQ_LOW_SIGNED_L1 ? 2 : 1) : 0;
     g_last_family = 6; g_last_variant = 1;
+    void *ev0 = g_ev_start, *ev1 = g_ev_stop;            // one-shot profiling events, as for a single launch
+    g_ev_start = g_ev_stop = nullptr;
     NQ_DISPATCH_HL(h, l, launch_nested_gemm_skinny_batch, fmode, mode0, two_tiles, staged, d_jobs, d_first, (int)live,
-                   (int)blocks, s);
+                   (int)blocks, s, ev0, ev1);
     return launch_status();
 }
 

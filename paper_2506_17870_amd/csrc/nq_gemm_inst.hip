@@ -11,7 +11,7 @@
 namespace nq {
 template void launch_nested_gemm_skinny<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, hipStream_t, void *, void *);
 template void launch_nested_gemm_skinny_batch<NQ_INST_H, NQ_INST_L>(int, int, bool, bool, const GemmParams *, const int *,
-                                                                    int, int, hipStream_t);
+                                                                    int, int, hipStream_t, void *, void *);
 template void launch_nested_gemm<NQ_INST_H, NQ_INST_L>(bool, int, const GemmParams &, hipStream_t, void *, void *);
 template void launch_nested_conv_window<NQ_INST_H, NQ_INST_L>(bool, int, const GemmParams &, const WindowGeom &,
                                                               size_t, hipStream_t, void *, void *);

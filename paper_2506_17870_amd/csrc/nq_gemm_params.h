@@ -170,7 +170,8 @@ void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, v
 // running count of their blocks), fmode 0 part-bit, 1 full-bit, 2 full-bit compensated; mode EPI_F32 or EPI_I8.
 template <int H, int L>
 void launch_nested_gemm_skinny_batch(int fmode, int mode, bool two_tiles, bool staged, const GemmParams *d_jobs,
-                                     const int *d_first, int count, int blocks, hipStream_t st);
+                                     const int *d_first, int count, int blocks, hipStream_t st, void *ev_start,
+                                     void *ev_stop);
 
 // Large GEMM / 1x1 stride-1 convolution: 128 x 256 tiles, K advanced 256 per barrier.
 // tm_forced: 2..5 forces the rows per block (32 * tm), anything else leaves the choice to the launcher;

@@ -251,7 +251,8 @@ __global__ void __launch_bounds__(256, 2) k_nested_gemm_skinny_batch(const GemmP
 // problems; two_tiles: some problem has more than 32 rows; staged: some reduction is 2048 or longer).
 template <int H, int L>
 void launch_nested_gemm_skinny_batch(int fmode, int mode, bool two_tiles, bool staged, const GemmParams *d_jobs,
-                                     const int *d_first, int count, int blocks, hipStream_t st)
+                                     const int *d_first, int count, int blocks, hipStream_t st, void *ev_start,
+                                     void *ev_stop)
 {
 #define NQ_SKB_ONE(FULLV, EPIV, TMSV, STAGEDV)                                                          \
     do {                                                                                                \
@@ -263,7 +264,7 @@ void launch_nested_gemm_skinny_batch(int fmode, int mode, bool two_tiles, bool s
                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);                 \
             granted = true;                                                                             \
         }                                                                                               \
-        hipLaunchKernelGGL(k, dim3((unsigned)blocks), dim3(256), lds, st, d_jobs, d_first, count);      \
+        launch_timed(k, dim3((unsigned)blocks), dim3(256), lds, st, ev_start, ev_stop, d_jobs, d_first, count); \
     } while (0)
 #define NQ_SKB_SHAPE(FULLV, EPIV)                                        \
     do {                                                                 \
