@@ -134,7 +134,7 @@ def stamped_forward(model, binding, dx, s_x, full):
     return recs
 
 
-def cpu_baseline(model_ops, weights, x, s_x, scales, n_bits, l_bits, ops_img):
+def cpu_baseline(model_ops, float_weights, x_float, scales, n_bits, l_bits, ops_img):
     """The CPU oracle, as it stands, on a reduced batch of the same workload (whole network, full-bit and
     part-bit forward with the same activation steps): all OpenMP threads on the first images, one thread on
     the first image.  Returns the record and the oracle's logits for the comparison with the GPU's."""
@@ -142,6 +142,10 @@ def cpu_baseline(model_ops, weights, x, s_x, scales, n_bits, l_bits, ops_img):
     from oracle.nq_oracle_cnn import oracle_cnn_forward
     omp = ctypes.CDLL("libgomp.so.1")
     nthreads = oracle.threads()
+    # the oracle quantises the same float draws itself (Eq. 1): weights per output channel, the input batch per tensor
+    weights = [None if w is None else oracle.quantize(w[0], n_bits) + (w[1],) for w in float_weights]
+    x, s_x = oracle.quantize(x_float.reshape(1, -1), 8)
+    x, s_x = x.reshape(x_float.shape), float(s_x[0])
 
     cache = {}
 
@@ -197,10 +201,10 @@ def main():
     # ---- synthetic model and inputs, resident before the clock starts ----------------------
     n_bits, l_bits, B, HW = 8, 2, args.batch, 224
     ops = network.resnet101_plan()
-    weights = network.plan_weights(ops, n_bits, seed=0)
-    model = network.NestedCNN(ops, weights, n_bits, l_bits)          # nq_decompose_pack_batch: a1 + a2, once
-    x, s_x = inputs.gaussian_activations((B, HW, HW, 3), seed=0)
-    dx = torch.from_numpy(x).cuda()
+    weights = network.plan_float_weights(ops, seed=0)
+    model = network.NestedCNN(ops, weights, n_bits, l_bits)          # nq_quantize + nq_decompose_pack_batch: a1 + a2, once
+    x_float = inputs.gaussian_floats((B, HW, HW, 3), seed=0)
+    dx, s_x = network.quantize_tensor(x_float)                       # int8 codes of the input batch, on the device
     model.allocate(B, HW, HW)
     model.calibrate(dx, float(s_x))                                   # int8 steps of the activations, once
     ops_img = forward_ops(ops, network, HW, HW)
@@ -330,7 +334,7 @@ def main():
 
     if not args.no_cpu_baseline:
         scales = {t: s for t, s in enumerate(model.out_scale) if s is not None}
-        base, nimg, lf, lp = cpu_baseline(ops, weights, x, float(s_x), scales, n_bits, l_bits, ops_img)
+        base, nimg, lf, lp = cpu_baseline(ops, weights, x_float, scales, n_bits, l_bits, ops_img)
         # the GPU's logits for the sampled images must equal the oracle's, in both modes
         g_part = model.forward(dx, s_x, full=False).cpu().numpy()[:nimg].copy()
         g_full = model.forward(dx, s_x, full=True).cpu().numpy()[:nimg].copy()

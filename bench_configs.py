@@ -24,6 +24,16 @@ from paper_2506_17870_amd import inputs, network  # noqa: E402
 MFMA_PEAK, HBM_PEAK = 5000.0, 8000.0   # TOPS (int8 dense), GB/s
 
 
+def weights(N, K, sigma, n_bits=8, seed=0):
+    """INT-n codes [N,K] and per-channel steps of N(0, sigma) weights, quantised on the device (nq_quantize,
+    Eq. 1) and copied back as NumPy arrays."""
+    d_w = torch.from_numpy(inputs.float_weights(N, K, sigma, seed)).cuda()
+    d_int = torch.empty((N, K), dtype=torch.int8, device="cuda")
+    d_step = torch.empty(N, dtype=torch.float32, device="cuda")
+    nq.nq_quantize(d_w, N, K, n_bits, d_int, d_step)
+    return d_int.cpu().numpy(), d_step.cpu().numpy()
+
+
 def kernel_us(fn, n=50):
     """Median and minimum dispatch duration of the GEMM/conv launch made by fn(events).  The warm-up is long
     enough for the clocks to settle (a handful of launches is not: the first figures then read 15 % high)."""
@@ -74,7 +84,7 @@ def header(title):
 
 def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8, layout=None, quiet=False):
     layout = nq.NQ_LAYOUT_DENSE if layout is None else layout
-    w_int, scale = inputs.weights(N, K, sigma, n_bits, 0)
+    w_int, scale = weights(N, K, sigma, n_bits, 0)
     W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(),
                                   nq.make_cfg(n_bits, l, layout=layout))
     # INT6 nesting runs with 6-bit activations (Sec. 4.2): int8 codes in [-32, 31]
@@ -103,7 +113,7 @@ def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8, layout=None
 
 def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4, quiet=False):
     K = k * k * Cin
-    w_int, scale = inputs.weights(Cout, K, inputs.he_sigma(K), 8, 0)
+    w_int, scale = weights(Cout, K, inputs.he_sigma(K), 8, 0)
     W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
     Ho, Wo = network.out_hw(H, W_, k, stride, pad)
     xs = [torch.from_numpy(inputs.uniform_activations((B, H, W_, Cin), i)).cuda() for i in range(sets)]
@@ -137,7 +147,7 @@ def gconv(name, B, H, W_, C, groups, k, stride, l, sets=6):
     gs = C // groups
     K = k * k * gs
     pad = k // 2
-    w_int, scale = inputs.weights(C, K, inputs.he_sigma(K), 8, 0)
+    w_int, scale = weights(C, K, inputs.he_sigma(K), 8, 0)
     W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
     Ho, Wo = (H + 2 * pad - k) // stride + 1, (W_ + 2 * pad - k) // stride + 1
     xs = [torch.from_numpy(inputs.uniform_activations((B, H, W_, C), i)).cuda() for i in range(sets)]
@@ -195,7 +205,7 @@ def lib():
         except Exception as e:   # the library path is optional context
             print(f"| {name} | not available ({type(e).__name__}) | | | |")
             continue
-        w_int, scale = inputs.weights(N, K, 0.02, 8, 0)
+        w_int, scale = weights(N, K, 0.02, 8, 0)
         W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, 3))
         ys = [torch.empty((M, N), dtype=torch.int8, device="cuda") for _ in range(2)]
         epi = nq.make_epilogue(0.02, out_int8=True, inv_out_scale=3.0)
@@ -230,6 +240,9 @@ def cpu():
         pass
     omp = ctypes.CDLL("libgomp.so.1")
     nthreads = oracle.threads()
+
+    def oracle_weights(N, K, sigma, n_bits, seed):
+        return oracle.quantize(inputs.float_weights(N, K, sigma, seed), n_bits)
     print(f"\n### CPU oracle timing: {model}, os.cpu_count() = {os.cpu_count()}, OpenMP threads used = {nthreads}\n")
     print("| configuration | GOP | 1 thread s | 1 thread GOPS | all threads s | all threads GOPS |")
     print("|---|---|---|---|---|---|")
@@ -246,22 +259,22 @@ def cpu():
         one = f"{t_one:.2f} | {gop / t_one:.1f}" if t_one else "not run | "
         print(f"| {name} | {gop:.2f} | {one} | {t_all:.3f} | {gop / t_all:.1f} |", flush=True)
     c = inputs.LINEAR_SMALL
-    w = inputs.weights(c["N"], c["K"], c["sigma"], 8, 0)[0].astype(np.int16)
+    w = oracle_weights(c["N"], c["K"], c["sigma"], 8, 0)[0].astype(np.int16)
     x = inputs.uniform_activations((c["M"], c["K"]), 0)
     row("c1 linear 64x512->512", 2e-9 * c["M"] * c["N"] * c["K"], lambda: oracle.gemm_acc(x, w))
     c = inputs.CONV_RESNET18
     K = 9 * c["Cin"]
-    w = inputs.weights(c["Cout"], K, inputs.he_sigma(K), 8, 0)[0].astype(np.int16).reshape(c["Cout"], 3, 3, c["Cin"])
+    w = oracle_weights(c["Cout"], K, inputs.he_sigma(K), 8, 0)[0].astype(np.int16).reshape(c["Cout"], 3, 3, c["Cin"])
     x = inputs.uniform_activations((c["B"], c["H"], c["W"], c["Cin"]), 0)
     row("c2 conv 3x3 56x56x64->64, batch 32", 2e-9 * c["B"] * c["H"] * c["W"] * c["Cout"] * K, lambda: oracle.conv_acc(x, w, 1, 1))
     for g in inputs.BOTTLENECK_RESNET101:
         K = g["KH"] * g["KW"] * g["Cin"]
-        w = inputs.weights(g["Cout"], K, inputs.he_sigma(K), 8, 0)[0].astype(np.int16).reshape(g["Cout"], g["KH"], g["KW"], g["Cin"])
+        w = oracle_weights(g["Cout"], K, inputs.he_sigma(K), 8, 0)[0].astype(np.int16).reshape(g["Cout"], g["KH"], g["KW"], g["Cin"])
         x = inputs.uniform_activations((64, 14, 14, g["Cin"]), 0)
         row(f"c3 {g['KH']}x{g['KW']} {g['Cin']}->{g['Cout']}, batch 64, 14x14", 2e-9 * 64 * 196 * g["Cout"] * K,
             lambda: oracle.conv_acc(x, w, g["stride"], g["pad"]))
     for g in inputs.VIT_MLP:
-        w = inputs.weights(g["N"], g["K"], g["sigma"], 8, 0)[0].astype(np.int16)
+        w = oracle_weights(g["N"], g["K"], g["sigma"], 8, 0)[0].astype(np.int16)
         x = inputs.uniform_activations((g["M"], g["K"]), 0)
         row(f"c5 ViT {g['K']}->{g['N']}, M = {g['M']}", 2e-9 * g["M"] * g["N"] * g["K"], lambda: oracle.gemm_acc(x, w))
     omp.omp_set_num_threads(nthreads)
@@ -283,7 +296,7 @@ def c1_stack():
     launches, replayed as a HIP graph so that the host is out of the picture."""
     L, M, K, N = 1024, 64, 512, 512
     cfg = nq.make_cfg(8, 2)
-    w_int, scale = inputs.weights(N, K, 0.02, 8, 0)
+    w_int, scale = weights(N, K, 0.02, 8, 0)
     d_w, d_s = torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda()
     low_bytes = nq.nq_packed_bytes(N, K, 2)
     arena = torch.empty(L * low_bytes, dtype=torch.uint8, device="cuda")
@@ -365,11 +378,10 @@ def c5():
 def c4():
     print("\n### config 4: ResNet-101 conv/fc stack, batch 128, 224x224x3, all layers INT(8|6)\n")
     ops = network.resnet101_plan()
-    weights = network.plan_weights(ops, 8, seed=0)
+    weights = network.plan_float_weights(ops, seed=0)
     model = network.NestedCNN(ops, weights, 8, 2)
     B = 128
-    x, s_x = inputs.gaussian_activations((B, 224, 224, 3), seed=0)
-    dx = torch.from_numpy(x).cuda()
+    dx, s_x = network.quantize_tensor(inputs.gaussian_floats((B, 224, 224, 3), seed=0))
     model.calibrate(dx, s_x)
     macs = 0
     h = w = 224
@@ -497,14 +509,15 @@ def pack():
         del w, ph, pl
     # the whole ResNet-101 weight set (105 tensors, 44.4 M weights), one launch per layer, back to back
     plan = network.resnet101_plan()
-    ws = network.plan_weights(plan, 8, seed=0)
+    ws = network.plan_float_weights(plan, seed=0)
     tensors = []
     for wgt in ws:
         if wgt is None:
             continue
-        w_int = wgt[0]
-        n_, k_ = w_int.shape[0], int(np.prod(w_int.shape[1:]))
-        tensors.append((torch.from_numpy(np.ascontiguousarray(w_int.reshape(n_, k_))).cuda(), n_, k_,
+        n_, k_ = wgt[0].shape
+        d_int = torch.empty((n_, k_), dtype=torch.int8, device="cuda")
+        nq.nq_quantize(torch.from_numpy(wgt[0]).cuda(), n_, k_, 8, d_int, torch.empty(n_, dtype=torch.float32, device="cuda"))
+        tensors.append((d_int, n_, k_,
                         torch.empty(nq.nq_packed_bytes(n_, k_, 6), dtype=torch.uint8, device="cuda"),
                         torch.empty(nq.nq_packed_bytes(n_, k_, 2), dtype=torch.uint8, device="cuda")))
     total = sum(n_ * k_ for _, n_, k_, _, _ in tensors)
@@ -566,7 +579,7 @@ def page():
     # by the time stamps of its own dispatch (what a kernel trace shows), so host-side costs of the switching
     # calls cannot leak into it; those are timed separately, call by call, on the host clock.
     M, K, N, l = 12608, 3072, 768, 3
-    w_int, scale = inputs.weights(N, K, 0.02, 8, 0)
+    w_int, scale = weights(N, K, 0.02, 8, 0)
     W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
     x = torch.from_numpy(inputs.uniform_activations((M, K), 0)).cuda()
     y = torch.empty((M, N), dtype=torch.float32, device="cuda")
@@ -650,7 +663,7 @@ def words():
     N = K = 4096
     for l in (1, 2, 3, 4):
         h = 8 - l
-        w_int, scale = inputs.weights(N, K, 0.02, 8, l)
+        w_int, scale = weights(N, K, 0.02, 8, l)
         cw = nq.make_cfg(8, l, layout=nq.NQ_LAYOUT_PAPER_U64)
         cd = nq.make_cfg(8, l)
         bw = nq.nq_packed_bytes(N, K, h, nq.NQ_LAYOUT_PAPER_U64) + nq.nq_packed_bytes(N, K, l, nq.NQ_LAYOUT_PAPER_U64)

@@ -181,6 +181,13 @@ nq_status nq_quantize(const float *d_w, int64_t N, int64_t K, int n_bits, int8_t
  * n_bits in 2..8.  NQ_ERR_ALIGN if a pointer is not 4-byte aligned. */
 nq_status nq_tensor_scale(const float *d_x, int64_t count, int n_bits, float *d_scale, void *stream);
 
+/* Eq. 1 for a whole tensor, scale and codes: nq_tensor_scale, then d_codes[i] = Clip(round-half-to-even(d_x[i] /
+ * d_scale[0]), -2^(n_bits-1), 2^(n_bits-1) - 1) with the fp32 division of nq_quantize.  This is how a float input
+ * batch becomes the 8-bit activations of the first layer (Sec. 4.2).  In: device fp32[count], finite.  Out: device
+ * int8[count], fp32[1]; caller owned.  count up to 2^41; NQ_ERR_SHAPE beyond, other errors as nq_tensor_scale. */
+nq_status nq_quantize_tensor(const float *d_x, int64_t count, int n_bits, int8_t *d_codes, float *d_scale,
+                             void *stream);
+
 /* Eq. 1 followed by the decomposition and packing of nq_decompose_pack (Alg. 1 steps 1-3) without the
  * int8 tensor in between: one pass over the fp32 weights for the channel scales, one that quantises,
  * splits and writes the pages.  Same pages as nq_quantize + nq_decompose_pack.  NQ_LAYOUT_DENSE only

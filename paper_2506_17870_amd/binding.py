@@ -23,7 +23,7 @@ NQ_LAYOUT_DENSE, NQ_LAYOUT_PAPER_U64 = 0, 1
 NQ_MAX_K = 65536
 NQ_TUNE_KERNEL, NQ_TUNE_BIG_TM, NQ_TUNE_GC_UNITS, NQ_TUNE_STAT_ROWS = 0, 1, 2, 3
 
-EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "nq_tensor_scale", "nq_quantize_decompose_pack",
+EXPORTS = ["nq_version", "nq_status_string", "nq_packed_bytes", "nq_quantize", "nq_tensor_scale", "nq_quantize_tensor", "nq_quantize_decompose_pack",
            "nq_decompose", "nq_pack", "nq_decompose_pack", "nq_decompose_pack_batch",
            "nq_unpack", "nq_weight_init", "nq_weight_destroy", "nq_page_out_low", "nq_page_in_low",
            "nq_weight_init_group", "nq_page_out_low_batch", "nq_page_in_low_batch",
@@ -87,6 +87,7 @@ _SIGS = {
     "nq_packed_bytes": (ctypes.c_size_t, [_i64, _i64, _int, _int]),
     "nq_quantize": (_int, [_vp, _i64, _i64, _int, _vp, _vp, _vp]),
     "nq_tensor_scale": (_int, [_vp, _i64, _int, _vp, _vp]),
+    "nq_quantize_tensor": (_int, [_vp, _i64, _int, _vp, _vp, _vp]),
     "nq_quantize_decompose_pack": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp, _vp]),
     "nq_decompose": (_int, [_vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
     "nq_pack": (_int, [_vp, _vp, _i64, _i64, _cfgp, _vp, _vp, _vp]),
@@ -183,6 +184,11 @@ def nq_quantize(d_w, N, K, n_bits, d_w_int, d_scale, stream=None):
 
 def nq_tensor_scale(d_x, count, n_bits, d_scale, stream=None):
     _check(_lib.nq_tensor_scale(_ptr(d_x), count, n_bits, _ptr(d_scale), _stream(stream)), "nq_tensor_scale")
+
+
+def nq_quantize_tensor(d_x, count, n_bits, d_codes, d_scale, stream=None):
+    _check(_lib.nq_quantize_tensor(_ptr(d_x), count, n_bits, _ptr(d_codes), _ptr(d_scale), _stream(stream)),
+           "nq_quantize_tensor")
 
 
 def nq_quantize_decompose_pack(d_w, N, K, cfg, d_scale, d_packed_high, d_packed_low, stream=None):

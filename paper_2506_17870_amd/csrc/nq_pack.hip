@@ -600,6 +600,21 @@ extern "C" nq_status nq_tensor_scale(const float *d_x, int64_t count, int n_bits
     return launch_status();
 }
 
+extern "C" nq_status nq_quantize_tensor(const float *d_x, int64_t count, int n_bits, int8_t *d_codes, float *d_scale,
+                                        void *stream)
+{
+    if (count > 0 && !d_codes) return NQ_ERR_INVALID_ARG;
+    if (ceil_div(count, 1024) > 0x7fffffff) return NQ_ERR_SHAPE;
+    const nq_status st = nq_tensor_scale(d_x, count, n_bits, d_scale, stream);
+    if (st != NQ_OK || count == 0) return st;
+    // the whole tensor as one row of k_quantize_codes: 1024 elements per block, 16-byte loads where the pointers allow
+    const int vec_ok = (count % 4 == 0) && aligned16(d_x) && ((uintptr_t)d_codes % 4 == 0);
+    const int64_t chunks = ceil_div(count, 1024);
+    hipLaunchKernelGGL(k_quantize_codes, dim3((unsigned)chunks), dim3(256), 0, (hipStream_t)stream, d_x, count, chunks,
+                       n_bits, d_scale, d_codes, vec_ok);
+    return launch_status();
+}
+
 extern "C" nq_status nq_quantize_decompose_pack(const float *d_w, int64_t N, int64_t K, const nq_cfg *cfg,
                                                 float *d_scale, void *d_packed_high, void *d_packed_low,
                                                 void *stream)

@@ -70,6 +70,42 @@ __global__ void __launch_bounds__(256, OCC) k_mfma(int iters, int *out, int seed
     if (s == 0x12345678) out[threadIdx.x] = s;   // keeps the work alive, practically never true
 }
 
+// NV independent one-cycle-per-lane VALU instructions (adds on eight separate chains) after every MFMA:
+// how much vector work a wave can put in the shadow of its own matrix-core instructions.
+template <int NV, int OCC>
+__global__ void __launch_bounds__(256, OCC) k_mfma_valu(int iters, int *out, int seed)
+{
+    v4i a[4], b[2];
+    for (int i = 0; i < 4; ++i) a[i] = v4i{seed + (int)threadIdx.x + i, 1 + i, 2, 3};
+    for (int t = 0; t < 2; ++t) b[t] = v4i{3, 2 + t, 1, seed};
+    v16i acc[4][2];
+    for (int i = 0; i < 4; ++i)
+        for (int t = 0; t < 2; ++t)
+            for (int r = 0; r < 16; ++r) acc[i][t][r] = 0;
+    int x[8];
+    for (int j = 0; j < 8; ++j) x[j] = seed + j;
+    const int y = seed * 7 + (int)threadIdx.x;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                acc[i][t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[t], acc[i][t], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int j = 0; j < NV; ++j) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[(i * 2 + t + j) & 7]) : "v"(y));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    int s = 0;
+    for (int j = 0; j < 8; ++j) s += x[j];
+    for (int i = 0; i < 4; ++i)
+        for (int t = 0; t < 2; ++t)
+            for (int r = 0; r < 16; ++r) s += acc[i][t][r];
+    if (s == 0x12345678) out[threadIdx.x] = s;
+}
+
 __global__ void k_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
@@ -167,6 +203,22 @@ int main()
     MFMA_RUN(1, 2, 512, "2 waves/SIMD, 4 x 2 distinct operands")
     MFMA_RUN(2, 2, 512, "2 waves/SIMD, + 4 VALU per 2 MFMAs")
     MFMA_RUN(3, 2, 512, "2 waves/SIMD, + 1 VALU per MFMA")
+    printf("# the same MFMA stream with NV independent VALU adds after every MFMA (MFMA alone: 32 clocks; an add: 4 clocks of issue)\n");
+#define MFMA_VALU_RUN(NV, OCC, BLOCKS)                                                                            \
+    {                                                                                                             \
+        const float ms = time_ms([&](int) { hipLaunchKernelGGL((k_mfma_valu<NV, OCC>), dim3(BLOCKS), dim3(256), 0, 0, \
+                                                               iters, out, 1); }, 3);                             \
+        printf(" %6.1f", (double)BLOCKS * 4 * iters * 8 * 65536.0 / ms / 1e9);                                     \
+    }
+    printf("NV =            0      1      2      3      4      5      6      7      8     10     12     16\n1 wave/SIMD ");
+    MFMA_VALU_RUN(0, 1, 256) MFMA_VALU_RUN(1, 1, 256) MFMA_VALU_RUN(2, 1, 256) MFMA_VALU_RUN(3, 1, 256) MFMA_VALU_RUN(4, 1, 256)
+    MFMA_VALU_RUN(5, 1, 256) MFMA_VALU_RUN(6, 1, 256) MFMA_VALU_RUN(7, 1, 256) MFMA_VALU_RUN(8, 1, 256) MFMA_VALU_RUN(10, 1, 256)
+    MFMA_VALU_RUN(12, 1, 256) MFMA_VALU_RUN(16, 1, 256)
+    printf(" TOPS\n2 waves/SIMD");
+    MFMA_VALU_RUN(0, 2, 512) MFMA_VALU_RUN(1, 2, 512) MFMA_VALU_RUN(2, 2, 512) MFMA_VALU_RUN(3, 2, 512) MFMA_VALU_RUN(4, 2, 512)
+    MFMA_VALU_RUN(5, 2, 512) MFMA_VALU_RUN(6, 2, 512) MFMA_VALU_RUN(7, 2, 512) MFMA_VALU_RUN(8, 2, 512) MFMA_VALU_RUN(10, 2, 512)
+    MFMA_VALU_RUN(12, 2, 512) MFMA_VALU_RUN(16, 2, 512)
+    printf(" TOPS\n");
 
     printf("# memory: 16-byte accesses, grid-stride kernels\n");
     for (size_t mb : {32, 256, 2048}) {

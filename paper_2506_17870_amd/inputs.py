@@ -1,36 +1,22 @@
 """Seeded synthetic inputs with the shapes and value distributions of the paper's
 workloads (ImageNet CNN layers and ViT MLPs, Sec. 4.1): NumPy only, no method arithmetic.
 
-The hot path starts from per-channel INT-n weights and int8 activations, so these
-generators hand out integers: Gaussian draws rounded to the nearest code on a per-channel
-(weights) or per-tensor (activations) grid.  Decomposition, packing, GEMM and dequantisation
-are not done here.  Both the HIP tests/benchmark and the CPU oracle's tests are fed from
-this one module so that they see identical bytes.
+These generators hand out random draws only: fp32 values (what a trained layer or the
+previous layer would hand to the quantiser of Eq. 1) and uniform int8 codes.  Quantisation,
+decomposition, packing, GEMM and dequantisation are not done here: the library quantises on
+the device (nq_quantize), the tests quantise with the CPU oracle.  Both the HIP
+tests/benchmark and the CPU oracle's tests are fed from this one module so that they see
+identical bytes.
 """
 from __future__ import annotations
 
 import numpy as np
 
 
-def int_grid(values: np.ndarray, n_bits: int, axis=None):
-    """Round `values` to signed n-bit codes on an absmax grid; returns (codes int8, step fp32)."""
-    v = np.asarray(values, np.float32)
-    qmax = np.float32((1 << (n_bits - 1)) - 1)
-    amax = np.max(np.abs(v), axis=axis, keepdims=axis is not None).astype(np.float32)
-    step = np.where(amax > 0, amax / qmax, np.float32(1.0)).astype(np.float32)
-    codes = np.clip(np.rint(v / step), -(1 << (n_bits - 1)), (1 << (n_bits - 1)) - 1).astype(np.int8)
-    return codes, (step.reshape(-1) if axis is not None else np.float32(step))
-
-
 def float_weights(N: int, K: int, sigma: float, seed: int = 0) -> np.ndarray:
     """fp32 N(0, sigma) weights [N,K] (the values a trained layer would hand to the quantiser)."""
     rng = np.random.default_rng(seed)
     return rng.normal(0.0, sigma, size=(N, K)).astype(np.float32)
-
-
-def weights(N: int, K: int, sigma: float, n_bits: int = 8, seed: int = 0):
-    """INT-n codes [N,K] of N(0, sigma) weights and their per-output-channel steps fp32[N]."""
-    return int_grid(float_weights(N, K, sigma, seed), n_bits, axis=1)
 
 
 def he_sigma(fan_in: int) -> float:
@@ -43,17 +29,16 @@ def uniform_activations(shape, seed: int = 0) -> np.ndarray:
     return rng.integers(-128, 128, size=shape, dtype=np.int64).astype(np.int8)
 
 
-def relu_activations(shape, seed: int = 0):
-    """int8 codes of ReLU-clipped N(0,1) data on a per-tensor absmax grid; returns (codes, step)."""
+def relu_floats(shape, seed: int = 0) -> np.ndarray:
+    """fp32 ReLU-clipped N(0,1) data (what a layer after a ReLU hands to the activation quantiser)."""
     rng = np.random.default_rng(seed + 2000003)
-    a = np.maximum(rng.normal(0.0, 1.0, size=shape), 0.0).astype(np.float32)
-    return int_grid(a, 8)
+    return np.maximum(rng.normal(0.0, 1.0, size=shape), 0.0).astype(np.float32)
 
 
-def gaussian_activations(shape, seed: int = 0):
-    """int8 codes of N(0,1) data on a per-tensor absmax grid; returns (codes, step)."""
+def gaussian_floats(shape, seed: int = 0) -> np.ndarray:
+    """fp32 N(0,1) data (a normalised image batch, a token matrix)."""
     rng = np.random.default_rng(seed + 3000003)
-    return int_grid(rng.normal(0.0, 1.0, size=shape).astype(np.float32), 8)
+    return rng.normal(0.0, 1.0, size=shape).astype(np.float32)
 
 
 def small_floats(n: int, scale: float, seed: int = 0) -> np.ndarray:

@@ -53,8 +53,8 @@ def resnet101_plan(num_classes: int = 1000):
     return ops
 
 
-def plan_weights(ops, n_bits: int = 8, seed: int = 0):
-    """INT-n codes, per-channel steps and a small bias for every conv / fc of the plan (NumPy)."""
+def plan_float_weights(ops, seed: int = 0):
+    """fp32 He-normal weights [Cout, KH*KW*Cin] and a small bias for every conv / fc of the plan (NumPy draws)."""
     out = []
     for i, op in enumerate(ops):
         if op["op"] not in ("conv", "fc"):
@@ -62,10 +62,20 @@ def plan_weights(ops, n_bits: int = 8, seed: int = 0):
             continue
         k = op.get("k", 1)
         K = k * k * op["cin"]
-        w_int, scale = inputs.weights(op["cout"], K, inputs.he_sigma(K), n_bits, seed=seed + i)
+        w = inputs.float_weights(op["cout"], K, inputs.he_sigma(K), seed=seed + i)
         bias = inputs.small_floats(op["cout"], 0.02, seed=seed + 7 * i)
-        out.append((w_int, scale, bias))
+        out.append((w, bias))
     return out
+
+
+def quantize_tensor(x_float, n_bits: int = 8):
+    """Per-tensor int8 codes of an fp32 activation tensor (NumPy or torch), on the device (nq_quantize_tensor,
+    Eq. 1).  Returns (codes, cuda int8, same shape; step, float)."""
+    d_x = torch.as_tensor(x_float, dtype=torch.float32).cuda().contiguous()
+    codes = torch.empty(d_x.shape, dtype=torch.int8, device="cuda")
+    step = torch.empty(1, dtype=torch.float32, device="cuda")
+    nq.nq_quantize_tensor(d_x, d_x.numel(), n_bits, codes, step)
+    return codes, float(step.cpu()[0])
 
 
 def out_hw(h, w, k, stride, pad):
@@ -76,6 +86,8 @@ class NestedCNN:
     """Device-side owner of the nested weights of a plan and walker of the graph."""
 
     def __init__(self, ops, weights, n_bits=8, l_bits=2):
+        """weights: per op None or (fp32 weights [N,K], fp32 bias [N]), as plan_float_weights() returns them; they
+        are quantised to INT-n on the device (nq_quantize, Eq. 1), decomposed and packed."""
         self.ops, self.n_bits, self.l_bits = ops, n_bits, l_bits
         self.cfg = nq.make_cfg(n_bits, l_bits)
         # every layer's lower-bit page is a slice of one device arena and one pinned host arena, in the
@@ -92,8 +104,8 @@ class NestedCNN:
             if w is None:
                 self.layers.append(None)
                 continue
-            w_int, scale, bias = w
-            N, K = w_int.shape
+            w_float, bias = w
+            N, K = w_float.shape
             need = max(nq.nq_packed_bytes(N, K, l_bits), 16)
             W = nq.NestedWeight(N, K, self.cfg, low=self.low_arena[off:off + need],
                                 low_host=self.low_arena_host[off:off + need], init=False)
@@ -102,15 +114,16 @@ class NestedCNN:
             self.layers.append((W, torch.from_numpy(bias).cuda()))
         self.descs = [L[0].desc for L in self.layers if L is not None]
         nq.nq_weight_init_group(self.descs)
-        # all layers are decomposed and packed by one batched call, then the arena of lower-bit pages is
-        # copied once to its pinned master copy
+        # every layer is quantised per output channel on the device; all layers are then decomposed and packed by
+        # one batched call, and the arena of lower-bit pages is copied once to its pinned master copy
         jobs, keep = [], []
         for L, w in zip(self.layers, weights):
             if L is not None:
                 d_w = torch.from_numpy(w[0]).cuda()
-                keep.append(d_w)
-                jobs.append((d_w, L[0].N, L[0].K, L[0].high, L[0].low))
-                L[0].scale.copy_(torch.from_numpy(w[1]))
+                d_w_int = torch.empty(w[0].shape, dtype=torch.int8, device="cuda")
+                nq.nq_quantize(d_w, L[0].N, L[0].K, n_bits, d_w_int, L[0].scale)
+                keep.append(d_w_int)
+                jobs.append((d_w_int, L[0].N, L[0].K, L[0].high, L[0].low))
         nq.nq_decompose_pack_batch(jobs, self.cfg)
         self.low_arena_host.copy_(self.low_arena)
         torch.cuda.synchronize()

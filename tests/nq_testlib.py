@@ -1,9 +1,38 @@
 """Shared plumbing of the GPU parity tests: run the same seeded inputs through the HIP path
-(via the C ABI binding) and through the CPU oracle.  No arithmetic of the method lives here."""
+(via the C ABI binding) and through the CPU oracle.  No arithmetic of the method lives here: the
+quantised test inputs below are the seeded float draws of the input module put through the oracle's
+quantiser (Eq. 1)."""
 import numpy as np
 import torch
 
 from oracle import nq_oracle as oracle
+from paper_2506_17870_amd import inputs
+
+
+def weights(N, K, sigma, n_bits=8, seed=0):
+    """INT-n codes [N,K] of N(0, sigma) weights and their per-output-channel steps fp32[N] (oracle, Eq. 1)."""
+    return oracle.quantize(inputs.float_weights(N, K, sigma, seed), n_bits)
+
+
+def tensor_codes(a, n_bits=8):
+    """Per-tensor quantisation of an activation tensor (oracle, Eq. 1 with the whole tensor as one row)."""
+    codes, step = oracle.quantize(np.ascontiguousarray(a, np.float32).reshape(1, -1), n_bits)
+    return codes.reshape(a.shape), np.float32(step[0])
+
+
+def relu_activations(shape, seed=0):
+    return tensor_codes(inputs.relu_floats(shape, seed))
+
+
+def gaussian_activations(shape, seed=0):
+    return tensor_codes(inputs.gaussian_floats(shape, seed))
+
+
+def plan_weights(ops, n_bits=8, seed=0):
+    """(codes, steps, bias) of every conv / fc of a network plan: the plan's float weights through the oracle."""
+    from paper_2506_17870_amd import network
+    return [None if w is None else oracle.quantize(w[0], n_bits) + (w[1],)
+            for w in network.plan_float_weights(ops, seed)]
 
 
 def dev(a):

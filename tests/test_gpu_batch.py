@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import Case, check_outputs, dev, host
 from oracle import nq_oracle as oracle
 from paper_2506_17870_amd import inputs
@@ -23,7 +24,7 @@ def make_jobs(nq, shapes, n, l, out_int8, seed=0, fmt=None):
     """One nested layer + activations per (M, N, K); returns the job list and what the oracle needs."""
     jobs, refs = [], []
     for i, (M, N, K) in enumerate(shapes):
-        w_int, scale = inputs.weights(N, K, 0.02, n, seed + i)
+        w_int, scale = tl.weights(N, K, 0.02, n, seed + i)
         case = Case(nq, w_int, scale, n, l)
         x = inputs.uniform_activations((M, K), seed=seed + 100 + i) >> (8 - n)
         bias = inputs.small_floats(N, 0.1, seed=i)

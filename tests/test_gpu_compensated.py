@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import check_outputs, dev, each_kernel, host
 from oracle import nq_oracle as oracle
 from paper_2506_17870_amd import inputs
@@ -112,7 +113,7 @@ def run_both_modes(nq, W, x, hi, w_full, scale, l, conv=None, out_int8=False):
 @pytest.mark.parametrize("n,l", ALL_NL)
 def test_gemm_with_round_to_nearest_high(nq, n, l):
     N, K, M = 96, 320, 70
-    w, scale = inputs.weights(N, K, 0.02, n, seed=n + l)
+    w, scale = tl.weights(N, K, 0.02, n, seed=n + l)
     cfg = nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1)
     W = nq.NestedWeight.from_int8(dev(w), dev(scale), cfg)
     hi, _ = oracle.decompose(w, n, l, "rtn")
@@ -125,7 +126,7 @@ def test_gemm_with_round_to_nearest_high(nq, n, l):
 @pytest.mark.parametrize("n,l", [(8, 4), (8, 2), (8, 1), (6, 3), (6, 1)])
 @pytest.mark.parametrize("M,N,K", [(200, 160, 512), (330, 96, 768), (40, 96, 512), (16, 128, 1024)])
 def test_gemm_shapes_of_the_specialised_kernels(nq, n, l, M, N, K):
-    w, scale = inputs.weights(N, K, 0.02, n, seed=M + n + l)
+    w, scale = tl.weights(N, K, 0.02, n, seed=M + n + l)
     cfg = nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1)
     W = nq.NestedWeight.from_int8(dev(w), dev(scale), cfg)
     hi, _ = oracle.decompose(w, n, l, "rtn")
@@ -144,7 +145,7 @@ def test_gemm_shapes_of_the_specialised_kernels(nq, n, l, M, N, K):
 def test_convolution_shapes_of_the_specialised_kernels(nq, n, l, Cin, Cout, KH, stride, pad, HW):
     B = 2
     K = KH * KH * Cin
-    w, scale = inputs.weights(Cout, K, inputs.he_sigma(K), n, seed=Cin + KH + n + l)
+    w, scale = tl.weights(Cout, K, inputs.he_sigma(K), n, seed=Cin + KH + n + l)
     cfg = nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1)
     W = nq.NestedWeight.from_int8(dev(w), dev(scale), cfg)
     hi, _ = oracle.decompose(w, n, l, "rtn")
@@ -159,7 +160,7 @@ def test_externally_supplied_high(nq, rounding):
     # residual: full-bit must give back the original weights, part-bit must use exactly that w_high
     n, l = 8, 3
     N, K, M = 130, 448, 150
-    w, scale = inputs.weights(N, K, 0.02, n, seed=7)
+    w, scale = tl.weights(N, K, 0.02, n, seed=7)
     hi, res = oracle.decompose(w, n, l, rounding)
     lo = oracle.low_encode(res, l, oracle.LOW_SIGNED_L1)
     assert np.array_equal(oracle.compose(hi, lo, l), w.astype(np.int16))
@@ -173,7 +174,7 @@ def test_convolution_and_switching(nq):
     n, l = 8, 2
     B, H, Wd, Cin, Cout = 2, 12, 11, 64, 96
     K = 9 * Cin
-    w, scale = inputs.weights(Cout, K, inputs.he_sigma(K), n, seed=11)
+    w, scale = tl.weights(Cout, K, inputs.he_sigma(K), n, seed=11)
     cfg = nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1)
     W = nq.NestedWeight.from_int8(dev(w), dev(scale), cfg)
     hi, _ = oracle.decompose(w, n, l, "rtn")

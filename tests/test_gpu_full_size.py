@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import Case, run_conv_both, run_gemm_both
 from paper_2506_17870_amd import inputs
 
@@ -22,7 +23,7 @@ def test_resnet18_conv_full_batch(nq):
     # batch 32, 56x56x64 -> 64, 3x3 stride 1 pad 1, INT8 nesting INT6; bias + ReLU, fp32 out (as bench.py)
     c = inputs.CONV_RESNET18
     K = 9 * c["Cin"]
-    w_int, scale = inputs.weights(c["Cout"], K, inputs.he_sigma(K), 8, seed=0)
+    w_int, scale = tl.weights(c["Cout"], K, inputs.he_sigma(K), 8, seed=0)
     case = Case(nq, w_int, scale, 8, 2)
     x = inputs.uniform_activations((c["B"], c["H"], c["W"], c["Cin"]), seed=0)
     bias = inputs.small_floats(c["Cout"], 0.1, seed=2)
@@ -34,12 +35,12 @@ def test_resnet18_conv_full_batch(nq):
 @pytest.mark.parametrize("l", [2, 4])
 def test_resnet101_bottleneck_full_batch(nq, l):
     # batch 64, 14x14: 1x1 1024->256, 3x3 256->256, 1x1 256->1024; ReLU-clipped N(0,1) activations
-    x0, s0 = inputs.relu_activations((64, 14, 14, 1024), seed=7)
+    x0, s0 = tl.relu_activations((64, 14, 14, 1024), seed=7)
     for i, g in enumerate(inputs.BOTTLENECK_RESNET101):
         K = g["KH"] * g["KW"] * g["Cin"]
-        w_int, scale = inputs.weights(g["Cout"], K, inputs.he_sigma(K), 8, seed=10 * l + i)
+        w_int, scale = tl.weights(g["Cout"], K, inputs.he_sigma(K), 8, seed=10 * l + i)
         case = Case(nq, w_int, scale, 8, l)
-        x = x0 if g["Cin"] == 1024 else inputs.relu_activations((64, 14, 14, g["Cin"]), seed=i)[0]
+        x = x0 if g["Cin"] == 1024 else tl.relu_activations((64, 14, 14, g["Cin"]), seed=i)[0]
         for full in (True, False):
             run_conv_both(nq, case, x, (g["KH"], g["KW"], g["stride"], g["pad"]), full, s_a=float(s0), relu=True,
                           out_int8=True, inv_s_out=6.0)
@@ -51,9 +52,9 @@ def test_resnet101_bottleneck_full_batch(nq, l):
 def test_vit_mlp_full_size(nq, idx):
     # M = 12608 (197 x 64), fc1 768 -> 3072 and fc2 3072 -> 768, INT8 nesting INT5 (l = 3)
     g = inputs.VIT_MLP[idx]
-    w_int, scale = inputs.weights(g["N"], g["K"], g["sigma"], 8, seed=idx)
+    w_int, scale = tl.weights(g["N"], g["K"], g["sigma"], 8, seed=idx)
     case = Case(nq, w_int, scale, 8, g["l_bits"])
-    x, s_a = inputs.gaussian_activations((g["M"], g["K"]), seed=idx)
+    x, s_a = tl.gaussian_activations((g["M"], g["K"]), seed=idx)
     bias = inputs.small_floats(g["N"], 0.05, seed=idx)
     for full in (True, False):
         run_gemm_both(nq, case, x, full, s_a=float(s_a), bias=bias)
@@ -65,16 +66,16 @@ def test_resnet101_early_layers_full_resolution(nq):
     # input channels (few-channel kernel, several units per block) and the first bottleneck's 1x1 64 -> 256
     # at 56 x 56 (register-stationary kernel with four channel tiles per block), with the residual epilogue
     K = 7 * 7 * 3
-    w_int, scale = inputs.weights(64, K, inputs.he_sigma(K), 8, seed=41)
+    w_int, scale = tl.weights(64, K, inputs.he_sigma(K), 8, seed=41)
     case = Case(nq, w_int, scale, 8, 2)
-    x, s_x = inputs.gaussian_activations((4, 224, 224, 3), seed=41)
+    x, s_x = tl.gaussian_activations((4, 224, 224, 3), seed=41)
     bias = inputs.small_floats(64, 0.1, seed=42)
     for full in (True, False):
         run_conv_both(nq, case, x, (7, 7, 2, 3), full, s_a=float(s_x), bias=bias, relu=True, out_int8=True,
                       inv_s_out=9.0)
-    w_int, scale = inputs.weights(256, 64, inputs.he_sigma(64), 8, seed=43)
+    w_int, scale = tl.weights(256, 64, inputs.he_sigma(64), 8, seed=43)
     case = Case(nq, w_int, scale, 8, 2)
-    x, s_x = inputs.relu_activations((4, 56, 56, 64), seed=43)
+    x, s_x = tl.relu_activations((4, 56, 56, 64), seed=43)
     res = inputs.uniform_activations((4, 56, 56, 256), seed=44)
     for full in (True, False):
         run_conv_both(nq, case, x, (1, 1, 1, 0), full, s_a=float(s_x), residual=res, s_r=0.04, relu=True,
@@ -88,7 +89,7 @@ def test_depthwise_layers_full_batch(nq, geom):
     from nq_testlib import run_gconv_both
     hw, C, groups, k, stride = geom
     K = k * k * (C // groups)
-    w_int, scale = inputs.weights(C, K, inputs.he_sigma(K), 8, seed=hw + C)
+    w_int, scale = tl.weights(C, K, inputs.he_sigma(K), 8, seed=hw + C)
     case = Case(nq, w_int, scale, 8, 3)
     x = inputs.uniform_activations((32, hw, hw, C), seed=hw)
     bias = inputs.small_floats(C, 0.1, seed=1)
@@ -119,7 +120,7 @@ def test_weight_bound_linear_long_rows(nq, M, l):
     # few rows against a long reduction (the weight-bound stand-in of the linear configuration: the packed
     # pages are the traffic); N small enough that every block has a compute unit to itself
     N, K = 2048, 8192
-    w_int, scale = inputs.weights(N, K, 0.02, 8, seed=50 + l)
+    w_int, scale = tl.weights(N, K, 0.02, 8, seed=50 + l)
     case = Case(nq, w_int, scale, 8, l)
     x = inputs.uniform_activations((M, K), seed=51 + l)
     bias = inputs.small_floats(N, 0.05, seed=l)

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import Case, dev, host, run_conv_both, run_gemm_both
 from paper_2506_17870_amd import inputs
 
@@ -21,7 +22,7 @@ def nq():
 
 
 def make_case(nq, N, K, n, l, sigma=0.02, seed=0):
-    w_int, scale = inputs.weights(N, K, sigma, n, seed)
+    w_int, scale = tl.weights(N, K, sigma, n, seed)
     return Case(nq, w_int, scale, n, l)
 
 
@@ -69,7 +70,7 @@ def test_extreme_values(nq):
 def test_epilogue_options(nq):
     N, K, M = 160, 256, 150
     case = make_case(nq, N, K, 8, 3, seed=5)
-    x, s_a = inputs.gaussian_activations((M, K), seed=5)
+    x, s_a = tl.gaussian_activations((M, K), seed=5)
     bias = inputs.small_floats(N, 0.5, seed=1)
     res = inputs.uniform_activations((M, N), seed=9)
     for full in (True, False):
@@ -127,7 +128,7 @@ def test_bottleneck_block_chain(nq):
     # requantisation between the layers and the residual added in the last epilogue; l = 2 and l = 4
     B = 4
     for l in (2, 4):
-        x0, s0 = inputs.relu_activations((B, 14, 14, 1024), seed=l)
+        x0, s0 = tl.relu_activations((B, 14, 14, 1024), seed=l)
         act, s_in = x0, float(s0)
         from oracle import nq_oracle as oracle
         for i, g in enumerate(inputs.BOTTLENECK_RESNET101):
@@ -220,7 +221,7 @@ def test_large_kernel_every_tile_height(nq, fmt):
     low_format = nq.NQ_LOW_SIGNED_L1 if fmt == "compensated" else nq.NQ_LOW_UNSIGNED_L
 
     def case_for(N, K, sigma, seed):
-        w_int, scale = inputs.weights(N, K, sigma, n, seed)
+        w_int, scale = tl.weights(N, K, sigma, n, seed)
         c = Case(nq, w_int, scale, n, l)
         if fmt == "compensated":
             # same weights in the compensated format: w_high rounded to nearest, signed (l+1)-bit lower part

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import Case, dev, run_gconv_both
 from paper_2506_17870_amd import inputs
 
@@ -19,7 +20,7 @@ def nq():
 
 
 def make_case(nq, C, K, n, l, seed):
-    w_int, scale = inputs.weights(C, K, inputs.he_sigma(K), n, seed)
+    w_int, scale = tl.weights(C, K, inputs.he_sigma(K), n, seed)
     return Case(nq, w_int, scale, n, l)
 
 
@@ -80,7 +81,7 @@ def test_extreme_values_and_compensated_format(nq):
     # compensated lower part (signed l + 1 bits, round-to-nearest w_high)
     n, l, gs = 8, 3, 4
     K = 9 * gs
-    w, scale = inputs.weights(C, K, inputs.he_sigma(K), n, seed=21)
+    w, scale = tl.weights(C, K, inputs.he_sigma(K), n, seed=21)
     W_ = nq.NestedWeight.from_int8(dev(w), dev(scale), nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1))
     hi, _ = oracle.decompose(w, n, l, "rtn")
     x = inputs.uniform_activations((2, H, W, C), seed=8)

@@ -137,3 +137,28 @@ def test_tensor_scale(nq, count):
         torch.cuda.synchronize()
         _, s_ref = oracle.quantize(v[first:first + count].reshape(1, -1), 8)
         assert host(out).view(np.uint32)[0] == s_ref.view(np.uint32)[0], (variant, count)
+
+
+@pytest.mark.parametrize("count", [1, 3, 1023, 1025, 4096, 100_003, 3_000_000])
+def test_quantize_tensor(nq, count):
+    # Eq. 1 for a whole tensor: the step of nq_tensor_scale and the codes, ties to even, clipped, both bit exact
+    rng = np.random.default_rng(1000 + count)
+    for variant, n_bits in (("gauss", 8), ("gauss", 6), ("zeros", 8), ("ties", 8), ("unaligned", 8)):
+        v = rng.normal(0.0, 3.0, size=count + 1).astype(np.float32)
+        first = 1 if variant == "unaligned" else 0
+        if variant == "zeros":
+            v[:] = 0.0
+        if variant == "ties":
+            # absmax 127 makes the step 1: halves must round to even, values beyond the range must clip
+            v[:] = rng.integers(-140, 141, size=count + 1).astype(np.float32) + 0.5
+            v[first] = 127.0
+            v = np.clip(v, -127.0, 127.0) if count > 1 else v
+        src = dev(v)[first:first + count]
+        codes = torch.full((count + 8,), 55, dtype=torch.int8, device="cuda")
+        step = torch.full((1,), 77.0, dtype=torch.float32, device="cuda")
+        nq.nq_quantize_tensor(src, count, n_bits, codes, step)
+        torch.cuda.synchronize()
+        c_ref, s_ref = oracle.quantize(v[first:first + count].reshape(1, -1), n_bits)
+        assert host(step).view(np.uint32)[0] == s_ref.view(np.uint32)[0], (variant, count)
+        assert np.array_equal(host(codes)[:count], c_ref.reshape(-1)), (variant, count)
+        assert np.all(host(codes)[count:] == 55), "wrote past the end"

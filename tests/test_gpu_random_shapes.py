@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import Case, run_conv_both, run_gconv_both, run_gemm_both
 from paper_2506_17870_amd import inputs
 
@@ -42,7 +43,7 @@ def test_random_gemm(nq, seed):
     M = int(rng.choice([1, 7, 16, 33, 64, 65, 100, 200, 333, 700]))
     N = int(rng.choice([1, 16, 31, 32, 48, 64, 96, 130, 256, 272, 400]))
     K = int(rng.choice([1, 16, 63, 64, 100, 128, 256, 320, 512, 768, 1000, 1024]))
-    w_int, scale = inputs.weights(N, K, 0.02, n, seed)
+    w_int, scale = tl.weights(N, K, 0.02, n, seed)
     case = Case(nq, w_int, scale, n, l)
     x = inputs.uniform_activations((M, K), seed=seed) >> (8 - n)
     kw = epilogue_options(rng, (M,), N)
@@ -63,7 +64,7 @@ def test_random_convolution(nq, seed):
     W = int(rng.integers(max(KH, 4), 21))
     B = int(rng.integers(1, 4))
     K = KH * KH * Cin
-    w_int, scale = inputs.weights(Cout, K, inputs.he_sigma(K), n, seed)
+    w_int, scale = tl.weights(Cout, K, inputs.he_sigma(K), n, seed)
     case = Case(nq, w_int, scale, n, l)
     x = inputs.uniform_activations((B, H, W, Cin), seed=seed) >> (8 - n)
     Ho, Wo = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KH) // stride + 1
@@ -85,7 +86,7 @@ def test_random_grouped_convolution(nq, seed):
     W = int(rng.integers(max(KH, 3), 24))
     B = int(rng.integers(1, 4))
     K = KH * KH * gs
-    w_int, scale = inputs.weights(C, K, inputs.he_sigma(K), n, seed)
+    w_int, scale = tl.weights(C, K, inputs.he_sigma(K), n, seed)
     case = Case(nq, w_int, scale, n, l)
     x = inputs.uniform_activations((B, H, W, C), seed=seed) >> (8 - n)
     Ho, Wo = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KH) // stride + 1

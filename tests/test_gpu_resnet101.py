@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import dev, host, oracle_cnn_forward
 from paper_2506_17870_amd import inputs
 
@@ -22,14 +23,15 @@ def test_resnet101_full_part_full():
     n_bits, l_bits = 8, 2
     ops = network.resnet101_plan()
     assert sum(1 for op in ops if op["op"] == "conv") == 104
-    weights = network.plan_weights(ops, n_bits, seed=0)
+    weights = tl.plan_weights(ops, n_bits, seed=0)
     assert sum(w[0].size for w in weights if w is not None) == 44_442_816   # conv + fc weights of ResNet-101
-    x, s_x = inputs.gaussian_activations((BATCH, 224, 224, 3), seed=0)
+    x, s_x = tl.gaussian_activations((BATCH, 224, 224, 3), seed=0)
 
     logits_o, tens_o, scales = oracle_cnn_forward(ops, weights, x, s_x, n_bits, l_bits, full=True)
     logits_op, tens_op, _ = oracle_cnn_forward(ops, weights, x, s_x, n_bits, l_bits, full=False, scales=scales)
 
-    model = network.NestedCNN(ops, weights, n_bits, l_bits)
+    # the network quantises the same float draws on the device (nq_quantize); the oracle's codes came from its own
+    model = network.NestedCNN(ops, network.plan_float_weights(ops, seed=0), n_bits, l_bits)
     # the walker's own calibration (fp32-output pass + nq_tensor_scale per layer) finds the oracle's steps
     model.calibrate(dev(x), s_x)
     for t, s in scales.items():

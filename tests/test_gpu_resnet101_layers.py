@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import Case, dev, host
 from oracle import nq_oracle as oracle
 from paper_2506_17870_amd import inputs
@@ -51,7 +52,7 @@ def test_layer_at_batch_128(nq, shape):
     H, W, Cin, Cout, k, stride, pad, relu, has_res = shape
     K = k * k * Cin
     seed = H + Cin + Cout + k + stride
-    w_int, scale = inputs.weights(Cout, K, inputs.he_sigma(K), 8, seed=seed)
+    w_int, scale = tl.weights(Cout, K, inputs.he_sigma(K), 8, seed=seed)
     case = Case(nq, w_int, scale, 8, 2)
     assert case.pages_match()
     x = inputs.uniform_activations((BATCH, H, W, Cin), seed=seed)

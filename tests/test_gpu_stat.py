@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import Case, dev, run_conv_both, run_gemm_both
 from paper_2506_17870_amd import inputs
 
@@ -23,7 +24,7 @@ def nq():
 
 def make_case(nq, N, K, n, l, seed, compensated=False):
     from oracle import nq_oracle as oracle
-    w_int, scale = inputs.weights(N, K, inputs.he_sigma(K), n, seed)
+    w_int, scale = tl.weights(N, K, inputs.he_sigma(K), n, seed)
     c = Case(nq, w_int, scale, n, l)
     if compensated:
         c.cfg = nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1)

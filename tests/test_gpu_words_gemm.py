@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import nq_testlib as tl
 from nq_testlib import check_outputs, dev, host
 from oracle import nq_oracle as oracle
 from paper_2506_17870_amd import inputs
@@ -81,7 +82,7 @@ SHAPES = [(1, 1, 1), (16, 70, 333), (45, 33, 64), (3, 32, 7), (33, 96, 1000), (1
 def test_words_gemm_all_nestings(nq, n, l, signed):
     for si, (M, N, K) in enumerate(SHAPES):
         seed = 1000 * n + 100 * l + 10 * si + int(signed)
-        w_int, scale = inputs.weights(N, K, 0.05, n, seed=seed)
+        w_int, scale = tl.weights(N, K, 0.05, n, seed=seed)
         x = inputs.uniform_activations((M, K), seed=seed + 1)
         ph, pl, w_full, w_high = oracle_side(w_int, n, l, signed)
         W = weight_from_pages(nq, ph, pl, scale, N, K, n, l, signed)
@@ -93,7 +94,7 @@ def test_words_gemm_all_nestings(nq, n, l, signed):
 def test_words_gemm_epilogues(nq, n, l, signed):
     M, N, K = 37, 80, 520
     rng = np.random.default_rng(7 * n + l)
-    w_int, scale = inputs.weights(N, K, 0.05, n, seed=5 + l)
+    w_int, scale = tl.weights(N, K, 0.05, n, seed=5 + l)
     x = inputs.uniform_activations((M, K), seed=6 + l)
     bias = rng.normal(0, 0.5, N).astype(np.float32)
     residual = rng.integers(-128, 128, (M, N)).astype(np.int8)
@@ -131,7 +132,7 @@ def test_gpu_packed_word_pages_feed_the_gemm(nq):
     """Pages packed by nq_decompose_pack in the word layout equal the oracle's and run through the same GEMM."""
     n, l = 8, 3
     M, N, K = 16, 64, 700
-    w_int, scale = inputs.weights(N, K, 0.05, n, seed=3)
+    w_int, scale = tl.weights(N, K, 0.05, n, seed=3)
     x = inputs.uniform_activations((M, K), seed=4)
     ph, pl, w_full, w_high = oracle_side(w_int, n, l, False)
     cfg = nq.make_cfg(n, l, nq.NQ_LOW_UNSIGNED_L, nq.NQ_LAYOUT_PAPER_U64)
@@ -145,7 +146,7 @@ def test_gpu_packed_word_pages_feed_the_gemm(nq):
 def test_word_pages_argument_checks(nq):
     n, l = 8, 2
     N, K, M = 32, 128, 4
-    w_int, scale = inputs.weights(N, K, 0.05, n, seed=1)
+    w_int, scale = tl.weights(N, K, 0.05, n, seed=1)
     cfg = nq.make_cfg(n, l, nq.NQ_LOW_UNSIGNED_L, nq.NQ_LAYOUT_PAPER_U64)
     W = nq.NestedWeight.from_int8(dev(w_int), dev(scale), cfg)
     epi = nq.make_epilogue(1.0)
@@ -169,7 +170,7 @@ def test_word_pages_argument_checks(nq):
 def test_words_gemm_at_the_measured_size(nq, l, signed):
     """16 x 8192 -> 8192, the size the word-page tables are measured at; every output compared."""
     n, M, N, K = 8, 16, 8192, 8192
-    w_int, scale = inputs.weights(N, K, 0.02, n, seed=40 + l)
+    w_int, scale = tl.weights(N, K, 0.02, n, seed=40 + l)
     x = inputs.uniform_activations((M, K), seed=41 + l)
     ph, pl, w_full, w_high = oracle_side(w_int, n, l, signed)
     W = weight_from_pages(nq, ph, pl, scale, N, K, n, l, signed)
