@@ -210,6 +210,14 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
         }
     };
 
+    // With the compute unit's whole register file the per-channel constants of the epilogue are fetched here, behind
+    // the first panel's latency, instead of after the K loop, where nothing would hide theirs.
+    EpiCols<EPI> ecols[SOLO ? TN : 1];
+    if constexpr (SOLO) {
+#pragma unroll
+        for (int t = 0; t < TN; ++t) epi_cols<EPI>(p, n0 + (wave * TN + t) * 32, lane, FULL, ecols[t]);
+    }
+
     g_v16i acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -430,7 +438,8 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
     for (int t = 0; t < TN; ++t) {
         const int nt0 = n0 + (wave * TN + t) * 32;
         EpiCols<EPI> e;
-        epi_cols<EPI>(p, nt0, lane, FULL, e);
+        if constexpr (SOLO) e = ecols[t];
+        else epi_cols<EPI>(p, nt0, lane, FULL, e);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             epi_tile<EPI>(p, acc[i][t], SHIFT, e, m0 + i * 32, rows_of(i), nt0, lane, res[t * TM + i]);
