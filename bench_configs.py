@@ -278,8 +278,8 @@ def cpu():
         x = inputs.uniform_activations((g["M"], g["K"]), 0)
         row(f"c5 ViT {g['K']}->{g['N']}, M = {g['M']}", 2e-9 * g["M"] * g["N"] * g["K"], lambda: oracle.gemm_acc(x, w))
     omp.omp_set_num_threads(nthreads)
-    print("\n(c4, 2 TOP per forward, is timed by bench.py's cpu_baseline only through its c2-shaped layer; a whole forward "
-          "on the oracle is what tests/test_gpu_resnet101.py runs at a reduced batch.)")
+    print("\n(c4, 2 TOP per forward: bench.py's cpu_baseline runs the whole network on the oracle, 8 images on all threads and "
+          "one image on one thread.)")
 
 
 def c1():

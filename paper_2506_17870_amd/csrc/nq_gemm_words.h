@@ -122,10 +122,16 @@ __device__ __forceinline__ void words_lds_barrier()
 // row's last word is zero padded.  The words themselves stream from memory, eight steps ahead per wave, across
 // the chunks.
 // FIFTH: the sixteen bytes may start inside a dword and reach into a fifth one.
-template <int KB, bool SGN, bool FIFTH, int NW>
+// CONV: the rows are the output pixels of a convolution and k runs over (kh, kw, ci) of the NHWC input (Sec. 4.1's
+// CNN layers from the paper's own pages): a row is not contiguous in memory, so the staging gathers it, dword by
+// dword when the number of input channels is a multiple of four (a dword then lies inside one filter tap), else
+// byte by byte; taps outside the image and k >= K are requested out of range and read as zero.  Every row then
+// starts at k = 0 of its own (no alignment to inherit from memory): x_row0 is not used, cv is the geometry.
+template <int KB, bool SGN, bool FIFTH, int NW, bool CONV>
 __device__ __forceinline__ void words_page_steps(const __amdgpu_buffer_rsrc_t wrs, int row_off, int W,
                                                  const __amdgpu_buffer_rsrc_t xrs, uint32_t x_row0, int x_rows, int K,
-                                                 uint8_t *lds, int tid, int wave, int g, e_v16i &acc)
+                                                 uint8_t *lds, int tid, int wave, int g, e_v16i &acc,
+                                                 const GemmParams &cv, int64_t m0)
 {
     using WF = WordFields<KB, SGN>;
     using WC = WordChunk<KB, NW>;
@@ -142,6 +148,7 @@ __device__ __forceinline__ void words_page_steps(const __amdgpu_buffer_rsrc_t wr
     // ---- staging plan of this thread: piece q of the chunk is piece q % PPR of row q / PPR ----------------
     uint32_t st_x[NPT];     // byte offset of the piece's row in the activations (NOWHERE past M)
     int st_lds[NPT];        // where the piece goes in a buffer
+    int st_base[CONV ? NPT : 1], st_hw[CONV ? NPT : 1];   // CONV: offset of tap (0,0) of the row's pixel, (ih0 << 16) | (iw0 & 0xffff)
 #pragma unroll
     for (int i = 0; i < NPT; ++i) {
         const int q = tid + 64 * NW * i;
@@ -149,6 +156,18 @@ __device__ __forceinline__ void words_page_steps(const __amdgpu_buffer_rsrc_t wr
         const bool real = r < 32;
         st_x[i] = real && r < x_rows ? x_row0 + (uint32_t)(r * K) : NOWHERE;
         st_lds[i] = real ? r * RS + 16 * pi : 32 * RS;
+        if constexpr (CONV) {
+            const int64_t m = m0 + r;
+            const bool row_ok = real && r < x_rows;
+            const int HoWo = cv.Ho * cv.Wo;
+            const int mm = row_ok ? (int)m : 0;
+            const int b = mm / HoWo, rem = mm - b * HoWo;
+            const int oh = rem / cv.Wo, ow = rem - oh * cv.Wo;
+            const int ih0 = oh * cv.stride - cv.pad, iw0 = ow * cv.stride - cv.pad;
+            st_base[i] = ((b * cv.H + ih0) * cv.W + iw0) * cv.Cin;
+            // a row that does not exist gets a pixel row that no tap brings into the image
+            st_hw[i] = (row_ok ? ih0 : -16384) * 65536 + (iw0 & 0xffff);
+        }
     }
     e_v4i stage[NPT];
     auto stage_load = [&](int c) {
@@ -157,15 +176,57 @@ __device__ __forceinline__ void words_page_steps(const __amdgpu_buffer_rsrc_t wr
         for (int i = 0; i < NPT; ++i) {
             const int q = tid + 64 * NW * i;
             const int pi = q % PPR;
-            // the row's run starts in the dword that holds its byte k_lo
-            const uint32_t at = st_x[i] == NOWHERE ? NOWHERE : ((st_x[i] + k_lo) & ~3u) + (uint32_t)(16 * pi);
-            const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrs, at, 0, 0);
-            stage[i] = e_v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+            if constexpr (!CONV) {
+                // the row's run starts in the dword that holds its byte k_lo
+                const uint32_t at = st_x[i] == NOWHERE ? NOWHERE : ((st_x[i] + k_lo) & ~3u) + (uint32_t)(16 * pi);
+                const auto v = __builtin_amdgcn_raw_buffer_load_b128(xrs, at, 0, 0);
+                stage[i] = e_v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+            } else {
+                // the sixteen bytes k0 .. k0 + 15 of the pixel's row of the implicit GEMM
+                const int k0 = (int)(k_lo & ~3u) + 16 * pi;
+                const int ih0 = st_hw[i] >> 16, iw0 = (int)(int16_t)(st_hw[i] & 0xffff);
+                const int kwc = cv.KW * cv.Cin;
+                int kh = k0 / kwc;
+                const int rem = k0 - kh * kwc;
+                int kw = rem / cv.Cin;
+                int ci = rem - kw * cv.Cin;
+                auto where = [&](int k) -> uint32_t {
+                    const bool in = k < K && (unsigned)(ih0 + kh) < (unsigned)cv.H && (unsigned)(iw0 + kw) < (unsigned)cv.W;
+                    return in ? (uint32_t)(st_base[i] + (kh * cv.W + kw) * cv.Cin + ci) : NOWHERE;
+                };
+                auto advance = [&](int by) {
+                    ci += by;
+                    if (ci >= cv.Cin) {
+                        ci -= cv.Cin;
+                        if (++kw == cv.KW) { kw = 0; ++kh; }
+                    }
+                };
+                uint32_t d[4];
+                if ((cv.Cin & 3) == 0) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        d[j] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(xrs, where(k0 + 4 * j), 0, 0);
+                        advance(4);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        d[j] = 0u;
+#pragma unroll
+                        for (int bb = 0; bb < 4; ++bb) {
+                            const uint32_t v = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(xrs, where(k0 + 4 * j + bb), 0, 0) & 0xffu;
+                            d[j] |= v << (8 * bb);
+                            advance(1);
+                        }
+                    }
+                }
+                stage[i] = e_v4i{(int)d[0], (int)d[1], (int)d[2], (int)d[3]};
+            }
         }
     };
     // the lane's own row: where its bytes are in a buffer
     const int xr = lane & 31;
-    const uint32_t x_mine = xr < x_rows ? x_row0 + (uint32_t)(xr * K) : 0u;
+    const uint32_t x_mine = CONV ? 0u : (xr < x_rows ? x_row0 + (uint32_t)(xr * K) : 0u);
     uint32_t x_use = x_mine + (uint32_t)(XSTEP * wave + (G == 1 ? F * g : 16 * g));   // first byte of the next step
 
     uint2 Wd[8];
@@ -213,29 +274,31 @@ __device__ __forceinline__ void words_page_steps(const __amdgpu_buffer_rsrc_t wr
     words_lds_barrier();      // the buffers are free for the next page or for the partial sums
 }
 
-template <int KB, bool SGN, int NW>
+template <int KB, bool SGN, int NW, bool CONV>
 __device__ __forceinline__ void words_page(const __amdgpu_buffer_rsrc_t wrs, int row_off, int W,
                                            const __amdgpu_buffer_rsrc_t xrs, uint32_t x_row0, int x_rows, int K,
-                                           uint8_t *lds, int tid, int wave, int g, e_v16i &acc)
+                                           uint8_t *lds, int tid, int wave, int g, e_v16i &acc, const GemmParams &cv,
+                                           int64_t m0)
 {
     using WF = WordFields<KB, SGN>;
     // No fifth dword where a step has at most thirteen fields (up to three bytes are lost to the alignment),
     // nor where every step starts on a multiple of sixteen bytes of a row and the rows start on dwords.
     constexpr bool on16 = KB == 1 || KB == 2 || KB == 4;
     if constexpr (WF::NF <= 13) {
-        words_page_steps<KB, SGN, false, NW>(wrs, row_off, W, xrs, x_row0, x_rows, K, lds, tid, wave, g, acc);
+        words_page_steps<KB, SGN, false, NW, CONV>(wrs, row_off, W, xrs, x_row0, x_rows, K, lds, tid, wave, g, acc, cv, m0);
     } else {
-        if (on16 && (K & 3) == 0)
-            words_page_steps<KB, SGN, false, NW>(wrs, row_off, W, xrs, x_row0, x_rows, K, lds, tid, wave, g, acc);
+        // (the gathered rows of a convolution all start at k = 0 of a buffer row)
+        if (on16 && (CONV || (K & 3) == 0))
+            words_page_steps<KB, SGN, false, NW, CONV>(wrs, row_off, W, xrs, x_row0, x_rows, K, lds, tid, wave, g, acc, cv, m0);
         else
-            words_page_steps<KB, SGN, true, NW>(wrs, row_off, W, xrs, x_row0, x_rows, K, lds, tid, wave, g, acc);
+            words_page_steps<KB, SGN, true, NW, CONV>(wrs, row_off, W, xrs, x_row0, x_rows, K, lds, tid, wave, g, acc, cv, m0);
     }
 }
 
 // HB: bits of the higher-bit fields.  MODE 0: part-bit; 1: unsigned lower-bit fields of LB = l bits; 2: signed
 // lower-bit fields of LB = l + 1 bits (compensated format, Sec. 3.3.3).  WH, WL: words per row of the pages.
 // NW: waves per block (4, or 8 where a layer has few blocks).
-template <int HB, int LB, int MODE, int NW>
+template <int HB, int LB, int MODE, int NW, bool CONV>
 __global__ void __launch_bounds__(64 * NW) k_nested_gemm_words(const GemmParams p, int WH, int WL)
 {
     constexpr int EPI = EPI_ANY;
@@ -253,8 +316,11 @@ __global__ void __launch_bounds__(64 * NW) k_nested_gemm_words(const GemmParams 
     const int cn = epi_weight_slot<EPI>(lane) & 31;
     // The range ends with the dword that holds the last activation (the host checks that they start on one):
     // what that dword holds behind it stands at k >= K of the last row and meets zero weights.
-    const __amdgpu_buffer_rsrc_t xrs =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.x), 0, (int)((p.M * p.K + 3) & ~int64_t(3)), 0x00020000);
+    // CONV: the whole input tensor (the host keeps it below 2 GiB)
+    const __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(p.x), 0,
+        CONV ? (int)(((p.M / ((int64_t)p.Ho * p.Wo)) * p.H * p.W * p.Cin + 3) & ~int64_t(3)) : (int)((p.M * p.K + 3) & ~int64_t(3)),
+        0x00020000);
     const uint32_t x_row0 = (uint32_t)(m0 * p.K);
     const int x_rows = p.M - m0 < 32 ? (int)(p.M - m0) : 32;
 
@@ -265,7 +331,7 @@ __global__ void __launch_bounds__(64 * NW) k_nested_gemm_words(const GemmParams 
         const uint2 *rows_h = reinterpret_cast<const uint2 *>(p.ph) + (int64_t)nb * 32 * WH;
         const __amdgpu_buffer_rsrc_t wrs =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint2 *>(rows_h), 0, cols * WH * 8, 0x00020000);
-        words_page<HB, true, NW>(wrs, cn * WH * 8, WH, xrs, x_row0, x_rows, p.K, lds, tid, wave, g, acc);
+        words_page<HB, true, NW, CONV>(wrs, cn * WH * 8, WH, xrs, x_row0, x_rows, p.K, lds, tid, wave, g, acc, p, m0);
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] >>= 8 - HB;
@@ -277,7 +343,7 @@ __global__ void __launch_bounds__(64 * NW) k_nested_gemm_words(const GemmParams 
         const uint2 *rows_l = reinterpret_cast<const uint2 *>(p.pl) + (int64_t)nb * 32 * WL;
         const __amdgpu_buffer_rsrc_t wrs =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<uint2 *>(rows_l), 0, cols * WL * 8, 0x00020000);
-        words_page<LB, MODE == 2, NW>(wrs, cn * WL * 8, WL, xrs, x_row0, x_rows, p.K, lds, tid, wave, g, acl);
+        words_page<LB, MODE == 2, NW, CONV>(wrs, cn * WL * 8, WL, xrs, x_row0, x_rows, p.K, lds, tid, wave, g, acl, p, m0);
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = acc[r] * (1 << L) + (acl[r] >> (MODE == 2 ? 8 - LB : 0));
     }

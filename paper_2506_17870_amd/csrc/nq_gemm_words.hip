@@ -22,13 +22,20 @@ static void launch_words(const GemmParams &p, int WH, int WL, hipStream_t st, vo
     // than that, eight waves per block share a page's steps.
     const dim3 grid((unsigned)p.NB, (unsigned)((p.M + 31) / 32));
     const bool wide = (int64_t)grid.x * grid.y < 512 && WH >= 128;
-    if (wide) {
-        auto k = k_nested_gemm_words<HB, LB, MODE, 8>;
+    // a filter other than 1x1 stride 1 gathers its rows from the NHWC input (four waves only)
+    const bool gather = p.KH != 1 || p.KW != 1 || p.stride != 1 || p.pad != 0;
+    if (gather) {
+        auto k = k_nested_gemm_words<HB, LB, MODE, 4, true>;
+        constexpr size_t lds = words_lds_bytes<HB, LB, 4>();
+        words_grant_lds(k, lds);
+        launch_timed(k, grid, dim3(256), lds, st, ev_start, ev_stop, p, WH, WL);
+    } else if (wide) {
+        auto k = k_nested_gemm_words<HB, LB, MODE, 8, false>;
         constexpr size_t lds = words_lds_bytes<HB, LB, 8>();
         words_grant_lds(k, lds);
         launch_timed(k, grid, dim3(512), lds, st, ev_start, ev_stop, p, WH, WL);
     } else {
-        auto k = k_nested_gemm_words<HB, LB, MODE, 4>;
+        auto k = k_nested_gemm_words<HB, LB, MODE, 4, false>;
         constexpr size_t lds = words_lds_bytes<HB, LB, 4>();
         words_grant_lds(k, lds);
         launch_timed(k, grid, dim3(256), lds, st, ev_start, ev_stop, p, WH, WL);
