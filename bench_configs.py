@@ -111,10 +111,11 @@ def gemm(name, M, K, N, l, out8=False, sets=4, sigma=0.02, n_bits=8, layout=None
     return results
 
 
-def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4, quiet=False):
+def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4, quiet=False, layout=None):
     K = k * k * Cin
     w_int, scale = weights(Cout, K, inputs.he_sigma(K), 8, 0)
-    W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
+    cfg = nq.make_cfg(8, l) if layout is None else nq.make_cfg(8, l, layout=layout)
+    W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), cfg)
     Ho, Wo = network.out_hw(H, W_, k, stride, pad)
     xs = [torch.from_numpy(inputs.uniform_activations((B, H, W_, Cin), i)).cuda() for i in range(sets)]
     ys = [torch.empty((B, Ho, Wo, Cout), dtype=torch.int8 if out8 else torch.float32, device="cuda")
@@ -133,7 +134,8 @@ def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4, quiet=
             (nq.nq_conv_full if full else nq.nq_conv_part)(xs[i], cs, W.desc, epi, ys[i])
         med, _ = kernel_us(fn)
         M = B * Ho * Wo
-        wb = nq.nq_packed_bytes(Cout, K, 8 - l) + (nq.nq_packed_bytes(Cout, K, l) if full else 0)
+        lay = nq.NQ_LAYOUT_DENSE if layout is None else layout
+        wb = nq.nq_packed_bytes(Cout, K, 8 - l, lay) + (nq.nq_packed_bytes(Cout, K, l, lay) if full else 0)
         mode = ("full" if full else "part") + (" int8 out" if out8 else " fp32 out")
         ops, byts = 2.0 * M * Cout * K, B * H * W_ * Cin + wb + M * Cout * (1 if out8 else 4)
         if not quiet:
@@ -696,6 +698,11 @@ def words():
     header("the same for a large batch: ViT fc1 12608 x 768 -> 3072, fp32 out (word pages are read once per 32 rows)")
     gemm("INT(8|5) dense pages", 12608, 768, 3072, 3, sets=2)
     gemm("INT(8|5) word pages", 12608, 768, 3072, 3, sets=2, layout=nq.NQ_LAYOUT_PAPER_U64)
+    header("convolutions straight from the word pages (rows gathered from the NHWC input), batch 8, int8 out")
+    conv("3x3 14x14 256->256 dense pages", 8, 14, 14, 256, 256, 3, 1, 1, 2, sets=2)
+    conv("3x3 14x14 256->256 word pages", 8, 14, 14, 256, 256, 3, 1, 1, 2, sets=2, layout=nq.NQ_LAYOUT_PAPER_U64)
+    conv("7x7 s2 224x224 3->64 dense pages", 8, 224, 224, 3, 64, 7, 2, 3, 2, sets=2)
+    conv("7x7 s2 224x224 3->64 word pages", 8, 224, 224, 3, 64, 7, 2, 3, 2, sets=2, layout=nq.NQ_LAYOUT_PAPER_U64)
 
 
 if __name__ == "__main__":

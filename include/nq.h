@@ -86,11 +86,11 @@ typedef enum { NQ_LOW_UNSIGNED_L = 0, NQ_LOW_SIGNED_L1 = 1 } nq_low_format;
  * NQ_LAYOUT_PAPER_U64: the paper's packed-bit tensor (Sec. 3.3.4): 64/k (integer
  *   division) fields per unsigned 64-bit word, field j in bits [j*k, (j+1)*k), spare top
  *   bits zero (readers ignore them), each row starts a new word, the last word of a row
- *   zero padded.  This layout can be packed and unpacked, and nq_gemm_full / nq_gemm_part
- *   read it directly (a model stored as the paper packs it needs no repacking; the
- *   activations must then start on a 4-byte boundary and M * K stay below 2^31 - 2^16).
- *   It is the slower way in: the dense pages are what the kernels are built around, and
- *   the convolution entry points read nothing else (NQ_ERR_UNSUPPORTED). */
+ *   zero padded.  This layout can be packed and unpacked, and nq_gemm_* and nq_conv_* read
+ *   it directly (a model stored as the paper packs it needs no repacking; the activations
+ *   must then start on a 4-byte boundary and stay below 2^31 - 2^16 bytes).  It is the
+ *   slower way in: the dense pages are what the kernels are built around, and the grouped
+ *   convolution reads nothing else (NQ_ERR_UNSUPPORTED). */
 typedef enum { NQ_LAYOUT_DENSE = 0, NQ_LAYOUT_PAPER_U64 = 1 } nq_layout;
 
 typedef struct {
@@ -316,8 +316,11 @@ nq_status nq_gemm_batch(const nq_gemm_job *jobs, int64_t count, int full_bit, vo
 nq_status nq_gemm_batch_static(const nq_gemm_job *jobs, int64_t count, int full_bit, void *stream);
 
 /* The same two modes as an implicit-GEMM convolution: d_x is int8[B][H][W][Cin], the
- * output is [B][Ho][Wo][Cout]; w->N == Cout and w->K == KH*KW*Cin; the epilogue's
- * residual and accumulator dump are indexed like the output. */
+ * output is [B][Ho][Wo][Cout]; w->N == Cout and w->K == KH*KW*Cin with k = (kh*KW + kw)*Cin + ci; the
+ * epilogue's residual and accumulator dump are indexed like the output.  Pages in either layout: from
+ * NQ_LAYOUT_PAPER_U64 pages (Sec. 3.3.4) a 1x1 stride-1 filter runs as the GEMM over the pixels and any other
+ * filter gathers its rows from the input (d_x 4-byte aligned and smaller than 2 GiB, H, W < 16000:
+ * NQ_ERR_ALIGN / NQ_ERR_SHAPE otherwise). */
 nq_status nq_conv_full(const int8_t *d_x, const nq_conv_shape *shape, const nq_weight *w,
                        const nq_epilogue *epi, void *d_y, void *stream);
 nq_status nq_conv_part(const int8_t *d_x, const nq_conv_shape *shape, const nq_weight *w,

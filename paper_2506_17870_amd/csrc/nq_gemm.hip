@@ -365,9 +365,9 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     if (!w || !epi) return NQ_ERR_INVALID_ARG;
     nq_status st = check_cfg(&w->cfg);
     if (st != NQ_OK) return st;
-    // the paper's word pages (Sec. 3.3.4) are read by the plain GEMM only
+    // the paper's word pages (Sec. 3.3.4) are read by the GEMM and the dense convolution, not by the grouped one
     const bool words = w->cfg.layout == NQ_LAYOUT_PAPER_U64;
-    if (words && (gs > 0 || g.KH != 1 || g.KW != 1 || g.stride != 1 || g.pad != 0)) return NQ_ERR_UNSUPPORTED;
+    if (words && gs > 0) return NQ_ERR_UNSUPPORTED;
     bool empty = false;
     if ((st = check_problem(full, d_x, g.M, w, epi, d_y, &empty)) != NQ_OK || empty) return st;
     const int h = w->cfg.n_bits - w->cfg.l_bits, l = w->cfg.l_bits;
@@ -389,8 +389,12 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         return true;
     };
     if (words) {
-        // 32-bit byte offsets into the activations, dword loads relative to their first byte
-        if (g.M * w->K >= 0x7fff0000LL || ceil_div(g.M, 32) > 65535) return NQ_ERR_SHAPE;
+        // 32-bit byte offsets into the activations (a filter other than 1x1 stride 1 gathers its rows from the whole
+        // input tensor, pixel coordinates in 16 bits), dword loads relative to their first byte
+        const bool gather = g.KH != 1 || g.KW != 1 || g.stride != 1 || g.pad != 0;
+        const int64_t x_bytes = gather ? (g.M / ((int64_t)g.Ho * g.Wo)) * g.H * g.W * g.Cin : g.M * w->K;
+        if (x_bytes >= 0x7fff0000LL || ceil_div(g.M, 32) > 65535) return NQ_ERR_SHAPE;
+        if (gather && (g.H > 16000 || g.W > 16000 || g.pad > 255 || g.KH > 255 || g.KW > 255)) return NQ_ERR_SHAPE;
         if ((reinterpret_cast<uintptr_t>(d_x) & 3u) != 0) return NQ_ERR_ALIGN;
         p.conv_big = 0;
         p.cin_shift = 0;

@@ -156,10 +156,16 @@ def test_word_pages_argument_checks(nq):
     with pytest.raises(nq.NQError) as e:
         nq.nq_gemm_full(xb[1:1 + M * K], M, W.desc, epi, y)
     assert e.value.status == nq.NQ_ERR_ALIGN
-    # convolutions read the dense pages only
+    # a convolution whose input does not start on a dword
     cs = nq.nq_conv_shape(1, 4, 4, 8, N, 4, 4, 1, 0)
     with pytest.raises(nq.NQError) as e:
-        nq.nq_conv_full(xb, cs, W.desc, epi, y)
+        nq.nq_conv_full(xb[1:1 + 128], cs, W.desc, epi, y)
+    assert e.value.status == nq.NQ_ERR_ALIGN
+    # grouped convolutions read the dense pages only
+    Wg = nq.NestedWeight.from_int8(dev(w_int[:, :18].copy()), dev(scale), cfg)
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_gconv_full(xb, nq.nq_conv_shape(1, 4, 4, 32, 32, 3, 3, 1, 1), 16, Wg.desc, epi,
+                         torch.zeros((4, 4, 32), dtype=torch.float32, device="cuda"))
     assert e.value.status == nq.NQ_ERR_UNSUPPORTED
     # nothing to do
     nq.nq_gemm_full(xb, 0, W.desc, epi, y)
@@ -176,3 +182,90 @@ def test_words_gemm_at_the_measured_size(nq, l, signed):
     W = weight_from_pages(nq, ph, pl, scale, N, K, n, l, signed)
     run_both(nq, W, x, w_full, scale, l, True, s_a=0.02)
     run_both(nq, W, x, w_high, scale, l, False, s_a=0.02)
+
+
+# Convolutions straight from the word pages: (B, H, W, Cin, Cout, KH, KW, stride, pad).  Channel counts that are and
+# are not multiples of four (dword and byte gathers), the 7x7 stem over 3 channels, strides, padding wider than the
+# filter needs, 1x1 with a stride (gathered) and without (the plain GEMM over the pixels), K of one word and less,
+# ragged pixel tiles and channel tiles.
+CONV_GEOMS = [
+    (2, 9, 8, 16, 40, 3, 3, 1, 1),
+    (1, 12, 11, 3, 24, 7, 7, 2, 3),
+    (3, 7, 7, 20, 33, 3, 3, 2, 1),
+    (2, 6, 5, 6, 16, 1, 1, 2, 0),
+    (2, 6, 5, 6, 16, 1, 1, 1, 0),
+    (1, 5, 5, 5, 8, 5, 5, 1, 2),
+    (2, 10, 9, 64, 70, 3, 3, 1, 1),
+    (1, 4, 4, 1, 3, 2, 2, 1, 1),
+    (4, 8, 8, 32, 64, 1, 3, 1, 1),
+]
+
+
+def run_conv_both(nq, W, x, geom, w_ref, scale, l, full, **opt):
+    B, H, Wd, Cin, Cout, KH, KW, stride, pad = geom
+    s_a = opt.get("s_a", 0.031)
+    acc_ref = oracle.conv_acc(x, w_ref.reshape(Cout, KH, KW, Cin), stride, pad)
+    Ho, Wo = acc_ref.shape[1:3]
+    y_ref = oracle.epilogue(acc_ref, s_a=s_a, s_w=scale, part_l_bits=0 if full else l, bias=opt.get("bias"),
+                            residual=opt.get("residual"), s_r=opt.get("s_r", 0.0), relu=opt.get("relu", False),
+                            out_int8=opt.get("out_int8", False), inv_s_out=opt.get("inv_s_out", 1.0))
+    fn = nq.nq_conv_full if full else nq.nq_conv_part
+    cs = nq.nq_conv_shape(B, H, Wd, Cin, Cout, KH, KW, stride, pad)
+    dx = dev(x)
+    for dump in (True, False):
+        acc = torch.empty((B, Ho, Wo, Cout), dtype=torch.int32, device="cuda") if dump else None
+        d_bias = dev(opt["bias"]) if opt.get("bias") is not None else None
+        d_res = dev(opt["residual"]) if opt.get("residual") is not None else None
+        epi = nq.make_epilogue(s_a, d_bias, d_res, opt.get("s_r", 0.0), opt.get("relu", False), opt.get("out_int8", False),
+                               opt.get("inv_s_out", 1.0), acc)
+        y = torch.full((B, Ho, Wo, Cout), 77, dtype=torch.int8 if opt.get("out_int8") else torch.float32, device="cuda")
+        fn(dx, cs, W.desc, epi, y)
+        torch.cuda.synchronize()
+        check_outputs(host(y), host(acc) if dump else None, y_ref, acc_ref, opt.get("out_int8", False))
+
+
+@pytest.mark.parametrize("geom", CONV_GEOMS, ids=lambda g: "x".join(str(v) for v in g))
+def test_words_conv_geometries(nq, geom):
+    B, H, Wd, Cin, Cout, KH, KW, stride, pad = geom
+    K = KH * KW * Cin
+    for n, l, signed in ((8, 2, False), (8, 3, True), (6, 2, False), (8, 5, False)):
+        seed = sum(geom) + 10 * n + l
+        w_int, scale = tl.weights(Cout, K, inputs.he_sigma(K), n, seed=seed)
+        x = inputs.uniform_activations((B, H, Wd, Cin), seed=seed + 1)
+        ph, pl, w_full, w_high = oracle_side(w_int, n, l, signed)
+        W = weight_from_pages(nq, ph, pl, scale, Cout, K, n, l, signed)
+        run_conv_both(nq, W, x, geom, w_full, scale, l, True)
+        run_conv_both(nq, W, x, geom, w_high, scale, l, False)
+
+
+@pytest.mark.parametrize("n,l", ALL_NL)
+def test_words_conv_all_nestings_with_epilogues(nq, n, l):
+    geom = (2, 9, 7, 12, 48, 3, 3, 1, 1)
+    B, H, Wd, Cin, Cout, KH, KW, stride, pad = geom
+    K = KH * KW * Cin
+    rng = np.random.default_rng(31 * n + l)
+    w_int, scale = tl.weights(Cout, K, inputs.he_sigma(K), n, seed=70 + n + l)
+    x = inputs.uniform_activations((B, H, Wd, Cin), seed=71 + n + l)
+    bias = rng.normal(0, 0.5, Cout).astype(np.float32)
+    residual = rng.integers(-128, 128, (B, H, Wd, Cout)).astype(np.int8)
+    for signed in (False, True):
+        ph, pl, w_full, w_high = oracle_side(w_int, n, l, signed)
+        W = weight_from_pages(nq, ph, pl, scale, Cout, K, n, l, signed)
+        for full, w_ref in ((True, w_full), (False, w_high)):
+            run_conv_both(nq, W, x, geom, w_ref, scale, l, full, bias=bias, relu=True)
+            run_conv_both(nq, W, x, geom, w_ref, scale, l, full, bias=bias, residual=residual, s_r=0.02, relu=True,
+                          out_int8=True, inv_s_out=1.0 / 0.07)
+
+
+def test_words_conv_resnet_layer_shapes(nq):
+    """A 3x3 bottleneck convolution (14 x 14 x 256 -> 256) and the 7x7 stem at a reduced batch: several row tiles, long rows."""
+    n, l = 8, 2
+    for geom in ((2, 14, 14, 256, 256, 3, 3, 1, 1), (1, 56, 56, 3, 64, 7, 7, 2, 3)):
+        B, H, Wd, Cin, Cout, KH, KW, stride, pad = geom
+        K = KH * KW * Cin
+        w_int, scale = tl.weights(Cout, K, inputs.he_sigma(K), n, seed=90 + Cin)
+        x = inputs.uniform_activations((B, H, Wd, Cin), seed=91 + Cin)
+        ph, pl, w_full, w_high = oracle_side(w_int, n, l, False)
+        W = weight_from_pages(nq, ph, pl, scale, Cout, K, n, l, False)
+        run_conv_both(nq, W, x, geom, w_full, scale, l, True, relu=True, out_int8=True, inv_s_out=1.0 / 0.2)
+        run_conv_both(nq, W, x, geom, w_high, scale, l, False, relu=True, out_int8=True, inv_s_out=1.0 / 0.2)
