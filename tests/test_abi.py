@@ -146,8 +146,11 @@ def test_gemm_argument_checks_without_gpu(nq):
     with pytest.raises(nq.NQError) as e:
         nq.nq_gemm_part(a + 2, 8, w, epi, a, stream=0)      # activations off a dword boundary
     assert e.value.status == nq.NQ_ERR_ALIGN
-    with pytest.raises(nq.NQError) as e:                    # convolutions read the dense pages only
-        nq.nq_conv_part(a, nq.nq_conv_shape(1, 8, 8, 16, 64, 2, 2, 1, 0), w, epi, a, stream=0)
+    with pytest.raises(nq.NQError) as e:                    # a convolution's input off a dword boundary
+        nq.nq_conv_part(a + 2, nq.nq_conv_shape(1, 8, 8, 16, 64, 2, 2, 1, 0), w, epi, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_ALIGN
+    with pytest.raises(nq.NQError) as e:                    # grouped convolutions read the dense pages only
+        nq.nq_gconv_part(a, nq.nq_conv_shape(1, 8, 8, 64, 64, 4, 4, 1, 0), 16, w, epi, a, stream=0)
     assert e.value.status == nq.NQ_ERR_UNSUPPORTED
     w.high_bytes = 64 * 64 * 6 // 8
     w.cfg.layout = nq.NQ_LAYOUT_DENSE
