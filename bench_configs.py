@@ -144,19 +144,20 @@ def conv(name, B, H, W_, Cin, Cout, k, stride, pad, l, out8=True, sets=4, quiet=
     return results
 
 
-def gconv(name, B, H, W_, C, groups, k, stride, l, sets=6):
+def gconv(name, B, H, W_, C, groups, k, stride, l, sets=6, Cout=None):
     """One depthwise / grouped layer, int8 in and out with bias and ReLU; full-bit and part-bit."""
-    gs = C // groups
+    Cin, C = C, (Cout or C)
+    gs = Cin // groups
     K = k * k * gs
     pad = k // 2
     w_int, scale = weights(C, K, inputs.he_sigma(K), 8, 0)
     W = nq.NestedWeight.from_int8(torch.from_numpy(w_int).cuda(), torch.from_numpy(scale).cuda(), nq.make_cfg(8, l))
     Ho, Wo = (H + 2 * pad - k) // stride + 1, (W_ + 2 * pad - k) // stride + 1
-    xs = [torch.from_numpy(inputs.uniform_activations((B, H, W_, C), i)).cuda() for i in range(sets)]
+    xs = [torch.from_numpy(inputs.uniform_activations((B, H, W_, Cin), i)).cuda() for i in range(sets)]
     ys = [torch.empty((B, Ho, Wo, C), dtype=torch.int8, device="cuda") for _ in range(sets)]
     bias = torch.from_numpy(inputs.small_floats(C, 0.1, 1)).cuda()
     epi = nq.make_epilogue(0.02, d_bias=bias, relu=True, out_int8=True, inv_out_scale=3.0)
-    cs = nq.nq_conv_shape(B, H, W_, C, C, k, k, stride, pad)
+    cs = nq.nq_conv_shape(B, H, W_, Cin, C, k, k, stride, pad)
     for full in (True, False):
         cnt = [0]
 
@@ -168,7 +169,7 @@ def gconv(name, B, H, W_, C, groups, k, stride, l, sets=6):
             (nq.nq_gconv_full if full else nq.nq_gconv_part)(xs[i], cs, groups, W.desc, epi, ys[i])
         med, _ = kernel_us(fn)
         M = B * Ho * Wo
-        byts = B * H * W_ * C + M * C + nq.nq_packed_bytes(C, K, 8 - l) + (nq.nq_packed_bytes(C, K, l) if full else 0)
+        byts = B * H * W_ * Cin + M * C + nq.nq_packed_bytes(C, K, 8 - l) + (nq.nq_packed_bytes(C, K, l) if full else 0)
         gbs = byts / med / 1e3
         print(f"| {name} | {'full' if full else 'part'} | {med:.2f} | {byts / 1e6:.2f} | {gbs:.0f} | "
               f"{100 * gbs / HBM_PEAK:.1f} | {2.0 * M * C * K / med / 1e6:.2f} |")
@@ -188,6 +189,10 @@ def dw():
     gconv("EfficientNet-B0 dw 5x5 28x28x240 s1", 32, 28, 28, 240, 240, 5, 1, 3)
     gconv("EfficientNet-B0 dw 5x5 14x14x672 s1", 32, 14, 14, 672, 672, 5, 1, 3)
     gconv("ResNeXt 32x4d 3x3 56x56x128 g32", 32, 56, 56, 128, 32, 3, 1, 3)
+    # wider groups and unequal channel counts: the direct kernel (vector ALU)
+    gconv("ResNeXt 32x8d 3x3 56x56x256 g32 (groups of 8)", 32, 56, 56, 256, 32, 3, 1, 3)
+    gconv("ShuffleNet g3 1x1 28x28 240->60", 32, 28, 28, 240, 3, 1, 1, 3, Cout=60)
+    gconv("ShuffleNet g3 1x1 28x28 60->240", 32, 28, 28, 60, 3, 1, 1, 3, Cout=240)
 
 
 def lib():

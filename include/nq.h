@@ -327,12 +327,14 @@ nq_status nq_conv_part(const int8_t *d_x, const nq_conv_shape *shape, const nq_w
                        const nq_epilogue *epi, void *d_y, void *stream);
 
 /* Depthwise / grouped convolution in the same two modes (the layers of the lightweight CNNs of
- * Sec. 4: as many output as input channels, C = Cin = Cout, split into `groups` groups of
- * gs = C / groups channels; output channel c sums over the gs input channels of its own group).
- * d_x int8[B][H][W][C], output [B][Ho][Wo][C]; w->N == C, w->K == KH*KW*gs with k = (kh*KW + kw)*gs + ci.
- * Built for gs in {1, 2, 4}, C a multiple of 16, KH*KW <= 28, d_x 16-byte aligned and smaller than
- * 2 GiB: NQ_ERR_UNSUPPORTED / NQ_ERR_ALIGN / NQ_ERR_SHAPE otherwise (a layer with wider groups is
- * `groups` calls of nq_conv_* on channel slices copied out by the caller). */
+ * Sec. 4): Cin and Cout are split into `groups` groups of gs = Cin / groups input and Cout / groups output
+ * channels; output channel c sums over the gs input channels of group c / (Cout / groups).
+ * d_x int8[B][H][W][Cin], output [B][Ho][Wo][Cout]; w->N == Cout, w->K == KH*KW*gs with k = (kh*KW + kw)*gs + ci.
+ * Dense pages only (NQ_ERR_UNSUPPORTED for the word layout); groups must divide both channel counts and d_x be
+ * smaller than 2 GiB (NQ_ERR_SHAPE).  Two kernels: depthwise layers and groups of 2 or 4 channels with
+ * Cin == Cout a multiple of 16, up to 28 taps and a 16-byte aligned d_x run on the matrix cores; every other
+ * shape (wider groups, the grouped 1x1 layers whose channel counts differ, odd channel counts, any alignment)
+ * runs as a direct convolution on the vector ALU: same results, about a tenth of the speed. */
 nq_status nq_gconv_full(const int8_t *d_x, const nq_conv_shape *shape, int groups, const nq_weight *w,
                         const nq_epilogue *epi, void *d_y, void *stream);
 nq_status nq_gconv_part(const int8_t *d_x, const nq_conv_shape *shape, int groups, const nq_weight *w,

@@ -359,8 +359,10 @@ bool wait_for_page(const nq_weight *w, hipStream_t s)
 
 // gs: 0 for a GEMM or a dense convolution, else the channels per group of a grouped convolution
 // (the caller has checked that the shape is one the grouped kernel takes).
+// gs_out: 0, or the output channels per group of a grouped convolution that the kernel for 1, 2 or 4 channels per
+// group does not take (then gs is the input channels per group, and the direct kernel runs).
 nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *w, const nq_epilogue *epi,
-              void *d_y, void *stream, int gs = 0)
+              void *d_y, void *stream, int gs = 0, int gs_out = 0)
 {
     if (!w || !epi) return NQ_ERR_INVALID_ARG;
     nq_status st = check_cfg(&w->cfg);
@@ -405,6 +407,20 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
         if (!commit()) return NQ_ERR_HIP;
         g_last_family = 8; g_last_variant = 0;
         launch_nested_gemm_words(full, h, l, p, WH, WL, s, ev0, ev1);
+        return launch_status();
+    }
+    if (gs > 0 && gs_out > 0) {
+        p.conv_big = 0;
+        p.cin_shift = 0;
+        p.kw_magic = 0;
+        p.general = 1;
+        // four consecutive k are one aligned dword of the input when the group width, the channel count and the
+        // pointer are multiples of four
+        const int quads = gs % 4 == 0 && g.Cin % 4 == 0 && (reinterpret_cast<uintptr_t>(d_x) & 3u) == 0;
+        if (ceil_div(g.M, 32) > 0x7fffffffLL || ceil_div(w->N, 64) > 65535) return NQ_ERR_SHAPE;
+        if (!commit()) return NQ_ERR_HIP;
+        g_last_family = 10; g_last_variant = quads;
+        NQ_DISPATCH_HL(h, l, launch_nested_conv_grouped_any, full, p, gs, gs_out, quads, s, ev0, ev1);
         return launch_status();
     }
     if (gs > 0) {
@@ -670,13 +686,15 @@ nq_status gconv(bool full, const int8_t *d_x, const nq_conv_shape *sh, int group
     if (sh->H > 32768 || sh->W > 32768 || sh->Cin > NQ_MAX_K || sh->KH > 64 || sh->KW > 64 || sh->pad > 64 ||
         sh->stride > 64)
         return NQ_ERR_SHAPE;
-    if (sh->Cin != sh->Cout || sh->Cin % groups != 0) return NQ_ERR_SHAPE;
-    const int64_t gs = sh->Cin / groups;
+    if (sh->Cin % groups != 0 || sh->Cout % groups != 0 || sh->Cout < 1) return NQ_ERR_SHAPE;
+    const int64_t gs = sh->Cin / groups, gs_out = sh->Cout / groups;
     if (w->N != sh->Cout || w->K != (int64_t)sh->KH * sh->KW * gs) return NQ_ERR_SHAPE;
     if (sh->H + 2 * sh->pad < sh->KH || sh->W + 2 * sh->pad < sh->KW) return NQ_ERR_SHAPE;
-    // what the kernel is built for: groups inside a run of 4 channels, 16-byte pieces of a pixel, up to 28 taps
-    if ((gs != 1 && gs != 2 && gs != 4) || sh->Cin % 16 != 0 || sh->KH * sh->KW > 28) return NQ_ERR_UNSUPPORTED;
-    if (!aligned16(d_x)) return NQ_ERR_ALIGN;
+    // what the matrix-core kernel is built for: as many output as input channels, groups inside a run of 4
+    // channels, 16-byte pieces of a pixel, up to 28 taps, 16-byte aligned input; everything else (wider groups,
+    // unequal channel counts, odd channel counts, any alignment) goes to the direct kernel
+    const bool narrow = sh->Cin == sh->Cout && (gs == 1 || gs == 2 || gs == 4) && sh->Cin % 16 == 0 &&
+                        sh->KH * sh->KW <= 28 && aligned16(d_x);
     const int64_t Ho = (sh->H + 2 * sh->pad - sh->KH) / sh->stride + 1;
     const int64_t Wo = (sh->W + 2 * sh->pad - sh->KW) / sh->stride + 1;
     if (sh->B * sh->H * sh->W * sh->Cin >= 0x7fff0000LL || sh->B * Ho * Wo >= (int64_t(1) << 31) - 64)
@@ -685,7 +703,7 @@ nq_status gconv(bool full, const int8_t *d_x, const nq_conv_shape *sh, int group
     g.M = sh->B * Ho * Wo;
     g.H = (int)sh->H; g.W = (int)sh->W; g.Cin = (int)sh->Cin; g.Ho = (int)Ho; g.Wo = (int)Wo;
     g.KH = sh->KH; g.KW = sh->KW; g.stride = sh->stride; g.pad = sh->pad;
-    return run(full, d_x, g, w, epi, d_y, stream, (int)gs);
+    return run(full, d_x, g, w, epi, d_y, stream, (int)gs, narrow ? 0 : (int)gs_out);
 }
 
 }  // namespace

@@ -22,10 +22,13 @@ template void launch_nested_conv_smallcin<NQ_INST_H, NQ_INST_L>(bool, const Gemm
 }
 #elif NQ_INST_PART == 2
 #include "nq_conv_grouped.h"
+#include "nq_conv_grouped_any.h"
 
 namespace nq {
 template void launch_nested_conv_grouped<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, const GroupGeom &,
                                                                hipStream_t, void *, void *);
+template void launch_nested_conv_grouped_any<NQ_INST_H, NQ_INST_L>(bool, const GemmParams &, int, int, int, hipStream_t,
+                                                                   void *, void *);
 }
 #elif NQ_INST_PART == 3
 #include "nq_gemm_stat.h"

@@ -162,6 +162,11 @@ template <int H, int L>
 void launch_nested_conv_grouped(bool full, const GemmParams &p, const GroupGeom &g, hipStream_t st, void *ev_start,
                                 void *ev_stop);
 
+// Grouped convolution with groups of any width and unequal channel counts (direct, on the vector ALU).
+template <int H, int L>
+void launch_nested_conv_grouped_any(bool full, const GemmParams &p, int gs_in, int gs_out, int quads, hipStream_t st,
+                                    void *ev_start, void *ev_stop);
+
 // Few rows (M <= 64): one block per 32-column tile, the waves split K.
 template <int H, int L>
 void launch_nested_gemm_skinny(bool full, const GemmParams &p, hipStream_t st, void *ev_start, void *ev_stop);

@@ -162,13 +162,15 @@ def run_conv_both(nq, case, x, shape, full, **epi_kw):
 
 
 def run_gconv_both(nq, case, x, shape, groups, full, **epi_kw):
-    """Depthwise / grouped convolution: case holds [C, KH*KW*gs] weights, k = (kh*KW + kw)*gs + ci."""
-    B, H, W, C = x.shape
+    """Depthwise / grouped convolution: case holds [Cout, KH*KW*gs] weights, k = (kh*KW + kw)*gs + ci, gs = Cin / groups
+    (Cout = case.N need not equal Cin)."""
+    B, H, W, Cin = x.shape
     KH, KW, stride, pad = shape
-    gs = C // groups
+    gs = Cin // groups
+    C = case.N
     Ho, Wo = oracle.conv_out_hw(H, W, KH, KW, stride, pad)
     out_int8 = epi_kw.get("out_int8", False)
-    cs = nq.nq_conv_shape(B, H, W, C, C, KH, KW, stride, pad)
+    cs = nq.nq_conv_shape(B, H, W, Cin, C, KH, KW, stride, pad)
     fn = nq.nq_gconv_full if full else nq.nq_gconv_part
     w4 = (case.ow_full if full else case.ow_part).reshape(C, KH, KW, gs)
     acc_ref = oracle.conv_grouped_acc(x, w4, groups, stride, pad)

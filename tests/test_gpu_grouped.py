@@ -98,17 +98,93 @@ def test_extreme_values_and_compensated_format(nq):
         assert np.array_equal(host(y), oracle.epilogue(acc_ref, 0.02, scale, part_l_bits=0 if full else l))
 
 
-def test_unsupported_shapes_are_refused(nq):
+def test_shapes_that_are_refused(nq):
     x = torch.zeros((1, 8, 8, 64), dtype=torch.int8, device="cuda")
     y = torch.zeros((1, 8, 8, 64), dtype=torch.float32, device="cuda")
     epi = nq.make_epilogue(0.02)
-    for C, groups, KH, status in ((64, 8, 3, "NQ_ERR_UNSUPPORTED"),      # groups of 8
-                                  (64, 64, 7, "NQ_ERR_UNSUPPORTED"),     # 49 taps
-                                  (24, 24, 3, "NQ_ERR_UNSUPPORTED"),     # channels not a multiple of 16
-                                  (64, 5, 3, "NQ_ERR_SHAPE")):           # groups do not divide the channels
-        gs = max(C // groups, 1)
-        W_ = nq.NestedWeight(C, KH * KH * gs, nq.make_cfg(8, 2))
-        cs = nq.nq_conv_shape(1, 8, 8, C, C, KH, KH, 1, KH // 2)
-        with pytest.raises(nq.NQError) as e:
-            nq.nq_gconv_part(x, cs, groups, W_.desc, epi, y)
-        assert e.value.status == getattr(nq, status), (C, groups, KH)
+    W_ = nq.NestedWeight(64, 9 * 12, nq.make_cfg(8, 2))
+    with pytest.raises(nq.NQError) as e:       # groups do not divide the channels
+        nq.nq_gconv_part(x, nq.nq_conv_shape(1, 8, 8, 64, 64, 3, 3, 1, 1), 5, W_.desc, epi, y)
+    assert e.value.status == nq.NQ_ERR_SHAPE
+    W_ = nq.NestedWeight(48, 9 * 16, nq.make_cfg(8, 2))
+    with pytest.raises(nq.NQError) as e:       # groups divide the input channels but not the output channels
+        nq.nq_gconv_part(x, nq.nq_conv_shape(1, 8, 8, 64, 48, 3, 3, 1, 1), 32, W_.desc, epi, y)
+    assert e.value.status == nq.NQ_ERR_SHAPE
+
+
+# Shapes the matrix-core kernel does not take and the direct kernel does: (B, H, W, Cin, Cout, groups, KH, stride, pad)
+ANY_GEOMS = [
+    (2, 9, 8, 64, 64, 8, 3, 1, 1),        # ResNeXt-style groups of 8
+    (1, 10, 10, 128, 128, 4, 3, 2, 1),    # groups of 32, stride 2
+    (2, 7, 7, 48, 120, 3, 1, 1, 0),       # ShuffleNet-style grouped 1x1, 3 groups, more output than input channels
+    (2, 7, 7, 60, 24, 3, 1, 1, 0),        # ... and fewer: 20 in, 8 out per group
+    (1, 9, 9, 24, 24, 24, 3, 1, 1),       # depthwise over a channel count that is not a multiple of 16
+    (1, 11, 11, 32, 32, 32, 7, 1, 3),     # depthwise 7x7: 49 taps
+    (2, 6, 5, 9, 6, 3, 3, 1, 1),          # groups of 3 input channels: bytes fetched one by one
+    (1, 8, 8, 10, 70, 2, 3, 2, 1),        # groups of 5 in, 35 out; more than one 64-channel run of lanes
+    (1, 5, 5, 16, 16, 1, 3, 1, 1),        # one group: a dense convolution
+    (3, 4, 4, 12, 12, 3, 2, 1, 0),        # even filter, no padding
+]
+
+
+@pytest.mark.parametrize("geom", ANY_GEOMS, ids=lambda g: "x".join(str(v) for v in g))
+def test_wide_groups_and_unequal_channel_counts(nq, geom):
+    B, H, W, Cin, Cout, groups, KH, stride, pad = geom
+    gs = Cin // groups
+    K = KH * KH * gs
+    Ho, Wo = (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KH) // stride + 1
+    x = inputs.uniform_activations((B, H, W, Cin), seed=Cin + H)
+    bias = inputs.small_floats(Cout, 0.1, seed=3)
+    res = inputs.uniform_activations((B, Ho, Wo, Cout), seed=Cout)
+    for n, l in ((8, 2), (8, 5), (6, 3)):
+        case = make_case(nq, Cout, K, n, l, seed=sum(geom) + n + l)
+        for full in (True, False):
+            run_gconv_both(nq, case, x, (KH, KH, stride, pad), groups, full, s_a=0.02)
+            run_gconv_both(nq, case, x, (KH, KH, stride, pad), groups, full, s_a=0.02, bias=bias, residual=res, s_r=0.04,
+                           relu=True, out_int8=True, inv_s_out=5.0)
+    assert nq.nq_profile_last_kernel()[0] == 10
+
+
+def test_wide_groups_every_nesting_compensated_and_unaligned(nq):
+    from oracle import nq_oracle as oracle
+    B, H, W, Cin, Cout, groups, KH = 2, 8, 7, 40, 24, 2, 3
+    gs = Cin // groups
+    K = KH * KH * gs
+    xbuf = dev(inputs.uniform_activations((B * H * W * Cin + 4,), seed=5))
+    for n, l in [(8, l) for l in range(1, 7)] + [(6, l) for l in range(1, 5)]:
+        for fmt in ("unsigned", "compensated"):
+            case = make_case(nq, Cout, K, n, l, seed=10 * n + l)
+            if fmt == "compensated":
+                case.cfg = nq.make_cfg(n, l, nq.NQ_LOW_SIGNED_L1)
+                case.W = nq.NestedWeight.from_int8(dev(case.w_int), dev(case.scale), case.cfg)
+                hi, _ = oracle.decompose(case.w_int, n, l, "rtn")
+                case.ow_part = hi.astype(np.int16)
+                case.ow_full = case.w_int.astype(np.int16)
+            for first in (0, 1):            # an input tensor that starts one byte off a dword boundary
+                xv = xbuf[first:first + B * H * W * Cin].view(B, H, W, Cin)
+                x = xv.cpu().numpy()
+                w4 = case.ow_full.reshape(Cout, KH, KH, gs)
+                acc_ref = oracle.conv_grouped_acc(x, w4, groups, 1, 1)
+                acc = torch.empty((B, H, W, Cout), dtype=torch.int32, device="cuda")
+                y = torch.empty((B, H, W, Cout), dtype=torch.float32, device="cuda")
+                nq.nq_gconv_full(xv, nq.nq_conv_shape(B, H, W, Cin, Cout, KH, KH, 1, 1), groups, case.W.desc,
+                                 nq.make_epilogue(0.02, d_acc_dump=acc), y)
+                torch.cuda.synchronize()
+                assert np.array_equal(acc.cpu().numpy(), acc_ref), (n, l, fmt, first)
+                y_ref = oracle.epilogue(acc_ref, 0.02, case.scale)
+                assert np.array_equal(y.cpu().numpy(), y_ref), (n, l, fmt, first)
+
+
+def test_resnext_and_shufflenet_layers_reduced_batch(nq):
+    """ResNeXt-50 32x8d stage-1 grouped 3x3 (56 x 56 x 256, 32 groups of 8) and a ShuffleNet (g = 3) stage-2 pair of grouped
+    1x1 layers (28 x 28: 240 -> 60 and 60 -> 240), batch 2."""
+    for (B, H, W, Cin, Cout, groups, KH, stride, pad) in ((2, 56, 56, 256, 256, 32, 3, 1, 1), (2, 28, 28, 240, 60, 3, 1, 1, 0),
+                                                          (2, 28, 28, 60, 240, 3, 1, 1, 0)):
+        gs = Cin // groups
+        K = KH * KH * gs
+        case = make_case(nq, Cout, K, 8, 2, seed=Cin + Cout)
+        x = inputs.uniform_activations((B, H, W, Cin), seed=Cin)
+        bias = inputs.small_floats(Cout, 0.1, seed=4)
+        for full in (True, False):
+            run_gconv_both(nq, case, x, (KH, KH, stride, pad), groups, full, s_a=0.02, bias=bias, relu=True, out_int8=True,
+                           inv_s_out=5.0)
