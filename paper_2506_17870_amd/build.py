@@ -71,6 +71,9 @@ def build(force: bool = False, jobs: int | None = None) -> str:
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("link failed:\n" + r.stderr[-4000:])
+    # a kernel template that the host pass fails to instantiate shows up only as an undefined symbol at load time
+    import ctypes
+    ctypes.CDLL(LIB, mode=os.RTLD_NOW)
     ysrc = os.path.join(CSRC, "nq_yardsticks.hip")
     if force or not os.path.exists(YARDSTICKS) or os.path.getmtime(YARDSTICKS) < os.path.getmtime(ysrc):
         r = subprocess.run(["hipcc", *[f for f in FLAGS if f != "-fPIC"], ysrc, "-o", YARDSTICKS],

@@ -159,6 +159,61 @@ __device__ __forceinline__ void epi_tile_f32(const GemmParams &p, const e_v16i a
     }
 }
 
+// EPI_I8 arithmetic of one output row's sixteen channels: the requantised codes, packed, not stored.
+__device__ __forceinline__ e_v4i epi_codes16(const GemmParams &p, const e_v16i acc, int shift, const EpiCols<EPI_I8> &e,
+                                             const e_v4i &res)
+{
+    const float lo = p.relu ? 0.0f : -__builtin_inff();
+    float y[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        y[r] = (float)(acc[r] >> shift) * e.c[r];
+        y[r] = y[r] + e.bias[r];
+    }
+    if (p.resid) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int code = (int)(int8_t)((unsigned)res[r >> 2] >> (8 * (r & 3)));
+            const float rv = p.resid_scale * (float)code;
+            y[r] = y[r] + rv;
+        }
+    }
+    e_v4i q;
+    if (p.relu && p.inv_out_scale > 0.0f) {
+        // With a ReLU and a positive output scale, clamp(rint(max(y, 0) * inv), -128, 127) is
+        // rint(med3(y * inv, 0, 127)): rounding and a positive factor keep the order and map 0 to 0, so
+        // the ReLU can be taken after the scaling, where it is the lower end of one three-operand clamp,
+        // and rounding commutes with a clamp to whole numbers.  The rounding itself (to nearest, ties to
+        // even) is done by the float -> unsigned byte pack.
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            unsigned d = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float v = __builtin_amdgcn_fmed3f(y[4 * j + i] * p.inv_out_scale, 0.0f, 127.0f);
+                d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
+            }
+            q[j] = (int)d;
+        }
+    } else {
+        // The rounded code plus 128 goes through the saturating float -> unsigned byte pack, which
+        // clamps it to [0, 255] (the clamp of the code to [-128, 127]); the offset is taken off
+        // again by flipping the top bit of every byte.  The sum is exact for every code that is
+        // not clamped anyway.
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            unsigned d = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float v = rintf(fmaxf(y[4 * j + i], lo) * p.inv_out_scale) + 128.0f;
+                d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
+            }
+            q[j] = (int)(d ^ 0x80808080u);
+        }
+    }
+    return q;
+}
+
 // Swapped layouts: the lane's sixteen consecutive channels nl0 .. nl0 + 15 of output row o / N; o is the
 // element offset of channel nl0 in that row.  res: the residual codes from epi_resid_load (EPI_I8).
 template <int EPI>
@@ -188,54 +243,7 @@ __device__ __forceinline__ void epi_row16(const GemmParams &p, const e_v16i acc,
         }
     } else {
         if (nl0 >= p.N) return;
-        float y[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            y[r] = (float)(acc[r] >> shift) * e.c[r];
-            y[r] = y[r] + e.bias[r];
-        }
-        if (p.resid) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int code = (int)(int8_t)((unsigned)res[r >> 2] >> (8 * (r & 3)));
-                const float rv = p.resid_scale * (float)code;
-                y[r] = y[r] + rv;
-            }
-        }
-        e_v4i q;
-        if (p.relu && p.inv_out_scale > 0.0f) {
-            // With a ReLU and a positive output scale, clamp(rint(max(y, 0) * inv), -128, 127) is
-            // rint(med3(y * inv, 0, 127)): rounding and a positive factor keep the order and map 0 to 0, so
-            // the ReLU can be taken after the scaling, where it is the lower end of one three-operand clamp,
-            // and rounding commutes with a clamp to whole numbers.  The rounding itself (to nearest, ties to
-            // even) is done by the float -> unsigned byte pack.
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                unsigned d = 0;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float v = __builtin_amdgcn_fmed3f(y[4 * j + i] * p.inv_out_scale, 0.0f, 127.0f);
-                    d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
-                }
-                q[j] = (int)d;
-            }
-        } else {
-            // The rounded code plus 128 goes through the saturating float -> unsigned byte pack, which
-            // clamps it to [0, 255] (the clamp of the code to [-128, 127]); the offset is taken off
-            // again by flipping the top bit of every byte.  The sum is exact for every code that is
-            // not clamped anyway.
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                unsigned d = 0;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float v = rintf(fmaxf(y[4 * j + i], lo) * p.inv_out_scale) + 128.0f;
-                    d = __builtin_amdgcn_cvt_pk_u8_f32(v, i, d);
-                }
-                q[j] = (int)(d ^ 0x80808080u);
-            }
-        }
-        *reinterpret_cast<e_v4i *>(reinterpret_cast<int8_t *>(p.y) + o) = q;
+        *reinterpret_cast<e_v4i *>(reinterpret_cast<int8_t *>(p.y) + o) = epi_codes16(p, acc, shift, e, res);
     }
 }
 

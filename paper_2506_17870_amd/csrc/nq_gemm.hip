@@ -220,6 +220,7 @@ bool plan_stat(const Geometry &g, const int8_t *d_x, int64_t N, int64_t K, StatG
     const int64_t images = g.M / howo;
     const int64_t x_bytes = images * g.H * g.W * g.Cin;
     if (x_bytes >= 0x7fff0000LL - 65536 || g.M >= (int64_t(1) << 31) - 512) return false;
+    if (g.M * N >= 0x7fff0000LL - 65536) return false;      // int8 outputs and residual codes: 32-bit byte offsets
     const bool strided = g.stride > 1;
     // the divisions by Ho * Wo and by Wo are multiplications by a rounded-up reciprocal: exact while
     // dividend * divisor < 2^32 (dividends: a row index inside an image plus one tile; a pixel index)

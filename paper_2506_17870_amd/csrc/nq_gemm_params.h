@@ -125,11 +125,14 @@ constexpr int st_bm(int wn) { return (4 / wn) * 32 * st_tm(wn); }
 constexpr int st_ring(int ks, int wn)
 {
     const int panel = st_bm(wn) * 64 * ks;
-    return 4 * panel <= 72 * 1024 ? 4 : (3 * panel <= 72 * 1024 ? 3 : 2);
+    return 4 * panel <= 56 * 1024 ? 4 : (3 * panel <= 56 * 1024 ? 3 : 2);
 }
+// bytes of the residual staging area: one KB per 32 x 32 tile of every wave
+constexpr int st_resid_bytes(int wn) { return 4 * st_tm(wn) * 2 * 1024; }
 constexpr size_t st_lds_bytes(int ks, int wn)
 {
-    return (size_t)st_ring(ks, wn) * st_bm(wn) * 64 * ks + 1024 /* dump */ + 4 * 2 * 64 * sizeof(float) /* constants */;
+    return (size_t)st_ring(ks, wn) * st_bm(wn) * 64 * ks + 1024 /* dump */ + 4 * 2 * 64 * sizeof(float) /* constants */ +
+           st_resid_bytes(wn);
 }
 
 // Tile shapes: 0 = 256x64 (narrow outputs), 1 = 128x256 (large), 2 = 64x256 (few rows).

@@ -35,6 +35,7 @@ namespace nq {
 
 typedef int s_v4i __attribute__((ext_vector_type(4)));
 typedef int s_v16i __attribute__((ext_vector_type(16)));
+typedef unsigned s_u4v __attribute__((__vector_size__(4 * sizeof(unsigned))));    // what the 16-byte buffer store takes
 
 constexpr int ST_OOR = 0x7fff0000;            // beyond every descriptor range (the host keeps inputs smaller)
 
@@ -58,6 +59,7 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
     extern __shared__ __attribute__((aligned(16))) uint8_t ring[];
     uint8_t *dump = ring + RD * PANEL;
     float *cols_lds = reinterpret_cast<float *>(dump + 1024);
+    uint8_t *resid_lds = dump + 1024 + 4 * 2 * 64 * sizeof(float);    // [wave][TN * TM tiles][64 lanes x 16 bytes]
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -146,11 +148,62 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
         }
     };
 
-    __builtin_amdgcn_sched_barrier(0);                       // weights first, then the panels, in this order
+    // ---- int8 outputs: residual codes and output codes as buffer accesses ------------------------------
+    // The tile loop of the int8 epilogue has no load into registers and a fixed number of vector-memory
+    // instructions per tile, so that every wait in it is an exact count (loads and stores share one counter, and
+    // a wait the compiler places for a register load with stores in flight is a wait for everything).  The
+    // residual codes therefore travel global -> LDS directly like the panels (a lane's sixteen bytes land at
+    // 16 * lane of the tile's KB: read back without bank conflicts), one tile ahead, and both they and the output
+    // codes go through range-checked descriptors: what a lane has no row or channel for is requested out of
+    // range (reads zero, writes nothing) instead of being branched around.
+    constexpr int NS = TM * TN;                              // residual loads = stores per wave and tile
+    const int64_t out_bytes = p.M * p.N;                     // the host keeps M * N below 2^31 - 2^16
+    const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int8_t *>(p.resid), 0, p.resid ? (int)out_bytes : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t yrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<int8_t *>(p.y), 0, (int)out_bytes, 0x00020000);
+    uint8_t *my_resid = resid_lds + wave * (NS * 1024);
+    // byte offset of the lane's sixteen channels of row (lane & 31) of tile (t, i) of the block's tile `it` in the
+    // output (and the residual), or out of range.  (Plain code in both users: a lambda called from inside another
+    // lambda of this kernel makes the host pass drop the kernel's stub.)
+#define NQ_ST_OUT_OFF(IT, T, I)                                                                                     \
+    (((IT) < nt && (lane & 31) < r_end - (r_begin + (int64_t)(IT) * r_step + wm * 32 * TM + (I) * 32) &&           \
+      (nb0 + (T)) * 32 + 16 * (lane >> 5) < p.N)                                                                    \
+         ? (int)((r_begin + (int64_t)(IT) * r_step + wm * 32 * TM + (I) * 32 + (lane & 31)) * p.N + (nb0 + (T)) * 32 + \
+                 16 * (lane >> 5))                                                                                  \
+         : ST_OOR)
+    auto load_resid_lds = [&](int it) {
 #pragma unroll
-    for (int i = 0; i < RD; ++i) {
-        load_panel(i);
+        for (int t = 0; t < TN; ++t)
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int off = NQ_ST_OUT_OFF(it, t, i);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rrsrc, (lds_ptr)(my_resid + (t * TM + i) * 1024), 16, off, 0, 0, 0);
+            }
+    };
+
+    __builtin_amdgcn_sched_barrier(0);                       // weights first, then the panels, in this order
+    if constexpr (EPI == EPI_I8) {
+        // the order of a tile of the loop below: residual codes, newest panel, stores (here: NS stores of nothing)
+#pragma unroll
+        for (int i = 0; i < RD - 1; ++i) {
+            load_panel(i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        load_resid_lds(0);
         __builtin_amdgcn_sched_barrier(0);
+        load_panel(RD - 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < NS; ++j)
+            __builtin_amdgcn_raw_buffer_store_b128(s_u4v{(unsigned)j, 0u, 0u, 0u}, yrsrc, ST_OOR + 4096 * j + 16 * lane, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    } else {
+#pragma unroll
+        for (int i = 0; i < RD; ++i) {
+            load_panel(i);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // ---- per-lane constants -------------------------------------------------------------------------
@@ -210,7 +263,8 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
     };
-    wait_loads(std::integral_constant<int, (RD - 1) * LW>{});   // panel 0 (and the weights before it) are in
+    // panel 0 (and the weights before it) are in: everything requested after it may still travel
+    wait_loads(std::integral_constant<int, (RD - 1) * LW + (EPI == EPI_I8 ? 2 * NS : 0)>{});
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
 
@@ -227,6 +281,83 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
             for (int i = 0; i < TM; ++i)
                 epi_resid_load<EPI>(p, m0 + i * 32, it < nt ? rows_of(m0, i) : 0, (nb0 + t) * 32, lane, res[t * TM + i]);
     };
+    if constexpr (EPI == EPI_I8) {
+        for (int it = 0; it < nt; ++it) {
+            const uint8_t *cur = ring + (it % RD) * PANEL;
+
+            s_v16i acc[TM][TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int t = 0; t < TN; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][t][r] = 0;
+            constexpr int NF = 2 * KS * TM, PF = NF < 4 ? NF : 4;
+            s_v4i af[PF];
+#pragma unroll
+            for (int f = 0; f < PF; ++f)
+                af[f] = *reinterpret_cast<const s_v4i *>(cur + a_read[(f / TM) >> 1][(f / TM) & 1] + (f % TM) * 32 * ROWB);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                const int i = f % TM, s = (f / TM) >> 1, hf = (f / TM) & 1;
+                const s_v4i a = af[f % PF];
+                __builtin_amdgcn_sched_barrier(0);
+                if (f + PF < NF)
+                    af[f % PF] = *reinterpret_cast<const s_v4i *>(
+                        cur + a_read[((f + PF) / TM) >> 1][((f + PF) / TM) & 1] + ((f + PF) % TM) * 32 * ROWB);
+#pragma unroll
+                for (int t = 0; t < TN; ++t) {
+                    const s_v4i bfrag = s_v4i{(int)W8[t][s][4 * hf], (int)W8[t][s][4 * hf + 1], (int)W8[t][s][4 * hf + 2],
+                                              (int)W8[t][s][4 * hf + 3]};
+                    acc[i][t] = epi_mfma<EPI>(bfrag, a, acc[i][t]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+
+            // This tile's residual codes and the next tile's panel must have landed (this wave's share; the barrier
+            // collects the others'), and every wave must be done with the current panel before it is requested
+            // again.  Issue order per tile: residual codes of the next tile, the panel RD tiles ahead, this tile's
+            // NS stores.  The newer of the two things waited for is the residual request of the previous tile (with
+            // a ring of two: the panel requested after it); what was issued after it, one panel and NS stores (NS
+            // stores), may stay in flight: no wait for the acknowledgements of the latest stores.
+            wait_loads(std::integral_constant<int, (RD >= 3 ? LW : 0) + NS>{});
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+            e_v4i res[NS];
+#pragma unroll
+            for (int j = 0; j < NS; ++j) res[j] = *reinterpret_cast<const e_v4i *>(my_resid + j * 1024 + 16 * lane);
+            // the codes are in registers before their place in LDS is requested again
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0) only
+            __builtin_amdgcn_sched_barrier(0);
+            load_resid_lds(it + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            load_panel(it + RD);                             // into the panel this tile has just been read from
+            __builtin_amdgcn_sched_barrier(0);
+
+            // ---- epilogue (Eq. 2 / Eq. 8) ------------------------------------------------------------
+#pragma unroll
+            for (int t = 0; t < TN; ++t) {
+                EpiCols<EPI_I8> e;
+                const e_v4f *cl = reinterpret_cast<const e_v4f *>(my_cols + 64 * t + 32 * rg);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const e_v4f cc = cl[q], bb = cl[4 + q];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) { e.c[4 * q + i] = cc[i]; e.bias[4 * q + i] = bb[i]; }
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const e_v4i q = epi_codes16(p, acc[i][t], SHIFT, e, res[t * TM + i]);
+                    __builtin_amdgcn_raw_buffer_store_b128(s_u4v{(unsigned)q[0], (unsigned)q[1], (unsigned)q[2], (unsigned)q[3]},
+                                                           yrsrc, NQ_ST_OUT_OFF(it, t, i), 0, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        return;
+    }
+#undef NQ_ST_OUT_OFF
     e_v4i res[TM * TN], res_next[TM * TN];
     load_resid(0, res);
 
