@@ -89,14 +89,19 @@ __global__ void __launch_bounds__(256) k_nested_conv_grouped_any(const GemmParam
                 const int tap = k0 / gs_in, ci = k0 - tap * gs_in;
                 const int kh = tap / p.KW, kw = tap - kh * p.KW;
                 const int toff = (kh * p.W + kw) * p.Cin + ci + x_first;
+                // all pixels' dwords are requested before the first is used (a pixel whose tap lies outside the image
+                // reads the tensor's first dword of the group instead and contributes zero): eight loads in flight
+                // instead of one
+                int xv[GA_PIX];
 #pragma unroll
                 for (int q = 0; q < GA_PIX; ++q) {
                     const int ih = pix_ih0[q] + kh, iw = pix_iw0[q] + kw;
-                    if ((unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W) {
-                        const int xv = *reinterpret_cast<const int *>(p.x + pix_off[q] + toff);
-                        acc[q] = __builtin_amdgcn_sdot4(xv, (int)D[j], acc[q], false);
-                    }
+                    const bool in = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                    xv[q] = *reinterpret_cast<const int *>(p.x + (in ? pix_off[q] + toff : x_first));
+                    if (!in) xv[q] = 0;
                 }
+#pragma unroll
+                for (int q = 0; q < GA_PIX; ++q) acc[q] = __builtin_amdgcn_sdot4(xv[q], (int)D[j], acc[q], false);
             } else {
 #pragma unroll
                 for (int bb = 0; bb < 4; ++bb) {
@@ -106,12 +111,16 @@ __global__ void __launch_bounds__(256) k_nested_conv_grouped_any(const GemmParam
                     const int kh = tap / p.KW, kw = tap - kh * p.KW;
                     const int toff = (kh * p.W + kw) * p.Cin + ci + x_first;
                     const int wv = (int)(int8_t)(D[j] >> (8 * bb));
+                    int xb[GA_PIX];
 #pragma unroll
                     for (int q = 0; q < GA_PIX; ++q) {
                         const int ih = pix_ih0[q] + kh, iw = pix_iw0[q] + kw;
-                        if ((unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
-                            acc[q] += (int)p.x[pix_off[q] + toff] * wv;
+                        const bool in = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                        xb[q] = (int)p.x[in ? pix_off[q] + toff : x_first];
+                        if (!in) xb[q] = 0;
                     }
+#pragma unroll
+                    for (int q = 0; q < GA_PIX; ++q) acc[q] += xb[q] * wv;
                 }
             }
         }
