@@ -1,5 +1,4 @@
-#!/usr/bin/env python3
-"""Per-configuration measurements behind the tables of the design doc and profiles/ (bench.py stays the one-line
+"""Per-configuration measurements: one table per configuration of the evaluation (bench.py stays the one-line
 benchmark).  Every kernel time is the begin/end time stamp of the dispatch itself; buffers are rotated so that
 activations and outputs come from HBM, not from the Infinity Cache.
 
