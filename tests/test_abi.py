@@ -96,6 +96,22 @@ def test_host_side_argument_checks(nq):
         nq.nq_quantize(a, 4, nq.NQ_MAX_K + 1, 8, a, a, stream=0)
     assert e.value.status == nq.NQ_ERR_SHAPE
     nq.nq_quantize(a, 0, 16, 8, a, a, stream=0)
+    # the per-tensor form: width, pointers, alignment (all refused before anything is launched)
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize_tensor(a, 10, 9, a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize_tensor(a, 10, 8, None, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize_tensor(a, 10, 8, a, None, stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_quantize_tensor(a + 2, 10, 8, a, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_ALIGN
+    with pytest.raises(nq.NQError) as e:
+        nq.nq_tensor_scale(a, -1, 8, a, stream=0)
+    assert e.value.status == nq.NQ_ERR_INVALID_ARG
     with pytest.raises(nq.NQError) as e:
         nq.nq_quantize_decompose_pack(a, 4, 4, nq.make_cfg(8, 2, layout=nq.NQ_LAYOUT_PAPER_U64), a, a, a, stream=0)
     assert e.value.status == nq.NQ_ERR_UNSUPPORTED
