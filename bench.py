@@ -184,6 +184,8 @@ def main():
                     "configurations (conv 56x56x64, bottleneck 3x3, ViT MLP)")
     ap.add_argument("--eager", action="store_true", help="issue every call of the timed steps from Python instead of "
                     "replaying a captured HIP graph of one step")
+    ap.add_argument("--branch-stream", action="store_true", help="issue the projection shortcut of every stage's first "
+                    "block on a second stream, beside the block's main path")
     ap.add_argument("--side-stream", action="store_true", help="copy the lower-bit pages in on a second stream, "
                     "concurrently with the part-bit forward (default: on the compute stream)")
     args = ap.parse_args()
@@ -216,12 +218,13 @@ def main():
 
     compute = torch.cuda.Stream()
     side = torch.cuda.Stream() if args.side_stream else None
+    branch = torch.cuda.Stream() if args.branch_stream else None    # the projection shortcuts of the network's blocks
 
     def step(st):
         model.page_out_low(st)                                       # a3: downgrade
         model.page_in_low(side if side is not None else st)          # a4: upgrade travels ...
-        model.forward(dx, s_x, full=False, stream=st)                # a6 + a7 + a8: ... while part-bit computes
-        model.forward(dx, s_x, full=True, stream=st)                 # a5 + a7 + a8: waits for the pages
+        model.forward(dx, s_x, full=False, stream=st, branch_stream=branch)   # a6 + a7 + a8: ... while part-bit computes
+        model.forward(dx, s_x, full=True, stream=st, branch_stream=branch)    # a5 + a7 + a8: waits for the pages
 
     with torch.cuda.stream(compute):
         for _ in range(max(args.warmup, 1)):

@@ -162,6 +162,13 @@ class NestedCNN:
                 self.hw[op["dst"]] = (1, 1)
             else:
                 self.buf[op["dst"]] = torch.empty((B, op["cout"]), dtype=torch.float32, device="cuda")
+        # ops that are a branch of the graph: convolutions whose output is used only as the residual of a later layer
+        # (the projection shortcuts of the first block of every stage)
+        used_as_residual = {op["residual"] for op in self.ops if op.get("residual") is not None}
+        used_as_input = {op["src"] for op in self.ops}
+        self.branch_ops = {i for i, op in enumerate(self.ops)
+                           if op["op"] == "conv" and op["dst"] in used_as_residual and op["dst"] not in used_as_input}
+        self.branch_events = {i: (torch.cuda.Event(), torch.cuda.Event()) for i in self.branch_ops}
         return self
 
     def calibrate(self, x, in_scale: float):
@@ -216,17 +223,33 @@ class NestedCNN:
             epi = nq.make_epilogue(s_in, bias, res, s_r, op["relu"], True, 1.0 / self.out_scale[op["dst"]])
             (nq.nq_conv_full if full else nq.nq_conv_part)(src, shape, Wt.desc, epi, y, stream)
 
-    def forward(self, x, in_scale: float, full: bool, keep=None, stream=None):
+    def forward(self, x, in_scale: float, full: bool, keep=None, stream=None, branch_stream=None):
         """x: int8 NHWC device tensor.  Returns the fp32 logits [B, classes] (a buffer of the model: the next
         forward overwrites it).  The int8 step of every tensor (out_scale) must have been set, by calibrate()
-        or by the caller.  keep, if a dict, receives every op's output tensor."""
+        or by the caller.  keep, if a dict, receives every op's output tensor.
+        branch_stream: a second stream (torch.cuda.Stream) for the branches of the graph: the projection shortcut of
+        a block does not depend on the block's main path, so it is issued there and joined (events, also under HIP
+        graph capture) before the layer that adds it; its launch, prologue and tail then overlap the main path."""
         B, H, W, _ = x.shape
         if getattr(self, "batch", None) != B or self.in_hw != (H, W):
             self.allocate(B, H, W)
         self.out_scale[0] = float(in_scale)
         logits = None
-        for op, L in zip(self.ops, self.layers):
-            self._run_op(op, L, x, B, full, stream)
+        main = stream if stream is not None else torch.cuda.current_stream()
+        joins = {}                                   # tensor id -> event its branch recorded
+        for i, (op, L) in enumerate(zip(self.ops, self.layers)):
+            on_branch = branch_stream is not None and i in self.branch_ops
+            if on_branch:
+                fork, join = self.branch_events[i]
+                fork.record(main)                    # the branch starts from what the main path has produced so far
+                branch_stream.wait_event(fork)
+                self._run_op(op, L, x, B, full, branch_stream)
+                join.record(branch_stream)
+                joins[op["dst"]] = join
+            else:
+                if op.get("residual") in joins:
+                    main.wait_event(joins.pop(op["residual"]))
+                self._run_op(op, L, x, B, full, stream)
             if op["op"] == "fc":
                 logits = self.buf[op["dst"]]
             if keep is not None:

@@ -37,9 +37,9 @@ def test_resnet101_full_part_full():
     for t, s in scales.items():
         assert model.out_scale[t] == s, f"calibrated step of tensor {t} differs: {model.out_scale[t]} vs {s}"
 
-    def check(full, logits_ref, tens_ref):
+    def check(full, logits_ref, tens_ref, branch_stream=None):
         keep = {}
-        logits = model.forward(dev(x), s_x, full=full, keep=keep)
+        logits = model.forward(dev(x), s_x, full=full, keep=keep, branch_stream=branch_stream)
         torch.cuda.synchronize()
         for op in ops:
             if op["op"] == "fc":
@@ -58,5 +58,12 @@ def test_resnet101_full_part_full():
     side = torch.cuda.Stream()
     model.page_in_low(side)                                 # upgrade: 104 + 1 pages over a second stream
     check(True, logits_o, tens_o)
+    # the projection shortcuts issued on a second stream beside their blocks' main paths: the same tensors
+    assert len(model.branch_ops) == 4
+    branch = torch.cuda.Stream()
+    for buf in model.buf.values():
+        buf.zero_()
+    check(True, logits_o, tens_o, branch_stream=branch)
+    check(False, logits_op, tens_op, branch_stream=branch)
     # the part-bit model is a different, coarser model: its logits differ from the full-bit ones
     assert not np.array_equal(logits_o, logits_op)
