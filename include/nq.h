@@ -360,8 +360,8 @@ nq_status nq_set_tuning(int key, int value);
  * stop) is the execution time of that kernel alone.  One shot; events are the caller's. */
 nq_status nq_profile_next_launch(void *start_event, void *stop_event);
 /* Profiling aid: which kernel the last nq_gemm_* / nq_conv_* / nq_gconv_* launch of this host thread ran:
- * *family as in NQ_TUNE_KERNEL (7 = depthwise / grouped, 8 = word pages; 0 before the first launch), *variant
- * the tile height of the large-GEMM kernel (2..5), the tile shape of the generic kernel, the waves along N
+ * *family as in NQ_TUNE_KERNEL (7 = depthwise / grouped on the matrix cores, 8 = word pages, 10 = direct grouped
+ * convolution; 0 before the first launch), *variant the tile height of the large-GEMM kernel (2..6), the tile shape of the generic kernel, the waves along N
  * of the stationary-weights GEMM, else 0.  Lets a
  * benchmark group its time stamps by kernel instantiation, as a kernel trace does.  Either pointer may be NULL. */
 nq_status nq_profile_last_kernel(int *family, int *variant);
