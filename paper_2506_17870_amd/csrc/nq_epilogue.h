@@ -132,6 +132,17 @@ __device__ __forceinline__ void epi_resid_load(const GemmParams &p, int64_t m0, 
     }
 }
 
+// Waits until every outstanding load has landed, and tells the compiler so.  Kernels call it once between the
+// last load of their epilogue and its first store: after it no register is the target of a load in flight, so
+// the compiler has no reason to wait on the memory counter again, which, once stores are in flight, would be
+// a wait for their acknowledgements (loads and stores share the counter and are counted in order).
+__device__ __forceinline__ void epi_join()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);                   // vmcnt(0); the other counters are left alone
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 __device__ __forceinline__ float epi_quantise(float y, float inv_out_scale)
 {
     const float q = rintf(y * inv_out_scale);

@@ -99,9 +99,18 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
     // GEMM: descriptor over the rows of this block; rows past M are out of range.
     // CONV: descriptor over the whole input tensor (the host keeps it below 2 GiB).
     const int64_t rows_here = (p.M - m0) < GB_BM ? (p.M - m0) : GB_BM;
+    // (descriptors go through readfirstlane: one that the compiler believes to differ between lanes, e.g. because a
+    // 64-bit product was computed on the vector ALU, is served by a loop over its distinct values at every use)
+    auto uniform_ptr = [](const void *q) {
+        const uint64_t a = reinterpret_cast<uint64_t>(q);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+        return reinterpret_cast<void *>(((uint64_t)hi << 32) | lo);
+    };
     const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<int8_t *>(p.x) + (CONV ? 0 : m0 * p.K), 0,
-        CONV ? (int)((int64_t)(p.M / ((int64_t)p.Ho * p.Wo)) * p.H * p.W * p.Cin) : (int)(rows_here * p.K), 0x00020000);
+        uniform_ptr(p.x + (CONV ? 0 : m0 * p.K)), 0,
+        __builtin_amdgcn_readfirstlane(CONV ? (int)((int64_t)(p.M / ((int64_t)p.Ho * p.Wo)) * p.H * p.W * p.Cin)
+                                            : (int)(rows_here * p.K)),
+        0x00020000);
     int a_goff[4];                                       // GEMM: offset of the lane's piece in rows 0..3
     // CONV: per row of the block, the byte offset of filter tap (0,0) and the packed (ih0, iw0) of the
     // pixel, worked out once, one row per thread, and handed to the lanes that request the row through a
@@ -189,30 +198,46 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
     int64_t tile0[TN];
 #pragma unroll
     for (int t = 0; t < TN; ++t) tile0[t] = (int64_t)min(nb0 + t, p.NB - 1) * p.KB;
+    // The wave's rows of tiles are read through buffer descriptors whose base is the wave's first tile: what varies
+    // from request to request is then a small scalar offset (tile and K step) next to a constant lane offset, and
+    // no address arithmetic is left for the vector ALU.  A K step that does not exist is requested out of range:
+    // it returns zeros at once and moves nothing.
+    const int tspan = __builtin_amdgcn_readfirstlane((int)(tile0[TN - 1] - tile0[0] + p.KB));
+    const __amdgpu_buffer_rsrc_t hrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(uniform_ptr(p.ph + tile0[0] * (H * 64)), 0, tspan * (H * 256), 0x00020000);
+    const __amdgpu_buffer_rsrc_t lrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        uniform_ptr(FULL != 0 ? p.pl + tile0[0] * (LP::DW * 64) : p.ph), 0, FULL != 0 ? tspan * (LP::DW * 256) : 0,
+        0x00020000);
+    int trel[TN];
+#pragma unroll
+    for (int t = 0; t < TN; ++t) trel[t] = __builtin_amdgcn_readfirstlane((int)(tile0[t] - tile0[0]));
     // dword j of a pipeline slot: j < TN*H is higher-bit dword (t = j / H, i = j % H), the rest are the
     // lower-bit dwords; load_b requests the dwords j0 <= j < j1 of K step kb
     constexpr int NBL = TN * (H + LP::DW);
     auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][LP::ARR], int kb, int j0, int j1) {
-        const int kbc = min(kb, p.KB - 1);               // the refills of the last iteration are never used
+        // (the range check covers the lane offset only, so that is where "out of range" goes; the scalar offset
+        // always names a real tile)
+        const int voff = (!SOLO || kb < p.KB) ? wslot * 4 : OOR;   // (two blocks per unit hide the useless last refills)
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
-            const uint32_t *src = p.ph + (tile0[t] + kbc) * (H * 64);
+            const int tk = trel[t] + min(kb, p.KB - 1);
 #pragma unroll
             for (int i = 0; i < H; ++i)
-                if (t * H + i >= j0 && t * H + i < j1) Pd[t][i] = src[(unsigned)(i * 64 + wslot)];
+                if (t * H + i >= j0 && t * H + i < j1)
+                    Pd[t][i] = __builtin_amdgcn_raw_buffer_load_b32(hrsrc, voff + i * 256, tk * (H * 256), 0);
             if constexpr (FULL != 0) {
-                const uint32_t *srcl = p.pl + (tile0[t] + kbc) * (LP::DW * 64);
 #pragma unroll
                 for (int i = 0; i < LP::DW; ++i)
                     if (TN * H + t * LP::DW + i >= j0 && TN * H + t * LP::DW + i < j1)
-                        Qd[t][i] = srcl[(unsigned)(i * 64 + wslot)];
+                        Qd[t][i] = __builtin_amdgcn_raw_buffer_load_b32(lrsrc, voff + i * 256, tk * (LP::DW * 256), 0);
             }
         }
     };
 
     // With the compute unit's whole register file the per-channel constants of the epilogue are fetched here, behind
     // the first panel's latency, instead of after the K loop, where nothing would hide theirs.
-    EpiCols<EPI> ecols[SOLO ? TN : 1];
+    constexpr bool COLS_FIRST = SOLO || EPI == EPI_F32;       // constants of all column tiles before the first store
+    EpiCols<EPI> ecols[COLS_FIRST ? TN : 1];
     if constexpr (SOLO) {
 #pragma unroll
         for (int t = 0; t < TN; ++t) epi_cols<EPI>(p, n0 + (wave * TN + t) * 32, lane, FULL, ecols[t]);
@@ -268,6 +293,8 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
     // the weights of a step are decoded at its start.
     constexpr bool AHEAD = PD >= 4;
     g_v4i bfrag[TN][2];                                   // decoded weights of the current K step
+    constexpr bool WOVEN = SOLO && TM == 4;
+    g_v4i bfr[WOVEN ? 2 : 1][TN][2];                      // woven K step: of the current and of the next step
     if constexpr (AHEAD) {
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
@@ -275,10 +302,16 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
             HighCodec<H>::decode(P[0][t], D);
             LP::apply(Q[0][t], D);
 #pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
+            for (int hf = 0; hf < 2; ++hf) {
                 bfrag[t][hf] = g_v4i{(int)D[4 * hf], (int)D[4 * hf + 1], (int)D[4 * hf + 2], (int)D[4 * hf + 3]};
+                bfr[0][t][hf] = bfrag[t][hf];
+                if constexpr (WOVEN) bfr[1][t][hf] = bfrag[t][hf];
+            }
         }
     }
+    // keeps the first-touch loads alive up to here and no further: loads complete in order and the first panel was
+    // requested after them, so the loop's first wait covers them anyway, and their registers are free for the loop
+    asm volatile("" ::"v"(touch_h), "v"(touch_l));
     for (int it = 0; it < iters; ++it) {
         uint8_t *cur = panel + (it & 1) * GB_PANEL;
         uint8_t *nxt = panel + ((it + 1) & 1) * GB_PANEL;
@@ -292,8 +325,49 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (CONV) set_taps(it + 1);
 
-        if constexpr (SOLO) {
-            // One wave per SIMD: nothing hides a stall, so the K step is written as plain data flow and the
+        if constexpr (SOLO && TM == 4) {
+            // One wave per SIMD: nothing hides a stall, and whatever the wave issues between two MFMAs beyond what
+            // fits in the shadow of the first delays the second.  So the K step is woven by hand, one fenced slot
+            // per MFMA: the MFMA, then (every second slot) the LDS read of one fragment of step d + 1, the decoding
+            // of ONE dword of step d + 1's weights (the codec is called whole and everything but that dword is dead
+            // code), one or two refills of the pipeline slot decoded during the previous step, and now and then one
+            // of the next panel's requests.  Left to the scheduler the same work came out in bursts of sixty
+            // instructions between two MFMAs (3950 -> 3440 clocks per four K steps on a 1024 -> 256 layer).
+            constexpr int NF = 2 * TM, NM = NF * TN;
+            g_v4i af[2][NF];
+#pragma unroll
+            for (int f = 0; f < NF; ++f)
+                af[0][f] = *reinterpret_cast<const g_v4i *>(cur + a_read[0][f / TM] + (f % TM) * 32 * GB_ROW);
+#pragma unroll
+            for (int d = 0; d < GB_KI; ++d) {
+                const int kb = it * GB_KI + d;
+                const int k0 = d * APT / (GB_KI - 1), k1 = (d + 1) * APT / (GB_KI - 1);   // this step's panel requests
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    const int f = m / TN, t = m % TN;
+                    __builtin_amdgcn_sched_barrier(0);
+                    acc[f % TM][t] = epi_mfma<EPI>(bfr[d & 1][t][f / TM], af[d & 1][f], acc[f % TM][t]);
+                    if (d + 1 < GB_KI && m % TN == 0)
+                        af[(d + 1) & 1][f] = *reinterpret_cast<const g_v4i *>(cur + a_read[d + 1][f / TM] +
+                                                                              (f % TM) * 32 * GB_ROW);
+#pragma unroll
+                    for (int q = m * 8 * TN / NM; q < (m + 1) * 8 * TN / NM; ++q) {   // one dword (TM = 4), or none
+                        uint32_t Dn[8];
+                        HighCodec<H>::decode(P[(d + 1) % PD][q / 8], Dn);
+                        LP::apply(Q[(d + 1) % PD][q / 8], Dn);
+                        bfr[(d + 1) & 1][q / 8][(q % 8) / 4][q % 4] = (int)Dn[q % 8];
+                    }
+                    load_b(P[d % PD], Q[d % PD], kb + PD, m * NBL / NM, (m + 1) * NBL / NM);
+                    if (d < GB_KI - 1) {
+#pragma unroll
+                        for (int k = 0; k < APT; ++k)
+                            if (k >= k0 && k < k1 && (k - k0) * NM / (k1 - k0) + 1 == m) load_a(it + 1, nxt, k, k + 1, rowreg, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        } else if constexpr (SOLO) {
+            // (160-row blocks: the hand-woven form above runs out of registers)  The K step is written as plain data flow and the
             // instruction scheduler is told the pattern to weave: after every MFMA a handful of vector
             // instructions (the next step's decoding, addresses), every second one an LDS read, and the
             // step's memory requests spread evenly.  The fragments of step d + 1 are read during step d, so
@@ -422,23 +496,34 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
         }
     }
 
-    asm volatile("" ::"v"(touch_h), "v"(touch_l));      // keeps the first-touch loads; they arrived long ago
-    // ---- epilogue (Eq. 2 / Eq. 8): residual codes of all tiles first, then the arithmetic -------
+    // ---- epilogue (Eq. 2 / Eq. 8): every load first, then one wait, then arithmetic and stores -------
+    // Loads and stores share one counter and it counts in order: a wait for a load that the compiler places
+    // after a store has been issued is a wait for that store's acknowledgement as well.  It places one
+    // wherever a register is reused that a load may still be writing, and the residual requests below are
+    // conditional, so on the path without a residual they stay "pending" in its books for good: every tile's
+    // arithmetic then waited for the previous tile's store to come back from memory (half of the epilogue's
+    // time).  Hence the order here: per-channel constants and residual codes of all tiles are requested,
+    // epi_join() waits for everything once, and from there to the end nothing is loaded.
     auto rows_of = [&](int i) {
         const int64_t left = p.M - (m0 + i * 32);
         return left > 32 ? 32 : (left < 0 ? 0 : (int)left);
     };
+    if constexpr (COLS_FIRST && !SOLO) {
+#pragma unroll
+        for (int t = 0; t < TN; ++t) epi_cols<EPI>(p, n0 + (wave * TN + t) * 32, lane, FULL, ecols[t]);
+    }
     e_v4i res[TM * TN];
 #pragma unroll
     for (int t = 0; t < TN; ++t)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             epi_resid_load<EPI>(p, m0 + i * 32, rows_of(i), n0 + (wave * TN + t) * 32, lane, res[t * TM + i]);
+    epi_join();
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int nt0 = n0 + (wave * TN + t) * 32;
         EpiCols<EPI> e;
-        if constexpr (SOLO) e = ecols[t];
+        if constexpr (COLS_FIRST) e = ecols[t];
         else epi_cols<EPI>(p, nt0, lane, FULL, e);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
