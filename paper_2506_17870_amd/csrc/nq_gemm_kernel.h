@@ -202,7 +202,7 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
             }
     }
 
-    // ---- epilogue (Eq. 2 / Eq. 8): residual codes of all tiles first, then the arithmetic -------
+    // ---- epilogue (Eq. 2 / Eq. 8): every load first, one wait (see epi_join), then arithmetic and stores -------
     const int64_t mw0 = m0 + wm * (BM / WM);
     auto rows_of = [&](int i) {
         const int64_t left = p.M - (mw0 + i * 32);
@@ -214,11 +214,21 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             epi_resid_load<EPI>(p, mw0 + i * 32, rows_of(i), n0 + (wn * TN + t) * 32, lane, res[t * TM + i]);
+    // (the sixteen-channel constants of the swapped layouts are too many registers to hold for every column tile:
+    // those are fetched per column tile, at the price of one wait for the previous tile's stores)
+    constexpr bool COLS_FIRST = EPI == EPI_F32;
+    EpiCols<EPI> ecols[COLS_FIRST ? TN : 1];
+    if constexpr (COLS_FIRST) {
+#pragma unroll
+        for (int t = 0; t < TN; ++t) epi_cols<EPI>(p, n0 + (wn * TN + t) * 32, lane, FULL, ecols[t]);
+    }
+    epi_join();
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         const int nt0 = n0 + (wn * TN + t) * 32;
         EpiCols<EPI> e;
-        epi_cols<EPI>(p, nt0, lane, FULL, e);
+        if constexpr (COLS_FIRST) e = ecols[t];
+        else epi_cols<EPI>(p, nt0, lane, FULL, e);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             epi_tile<EPI>(p, acc[i][t], SHIFT, e, mw0 + i * 32, rows_of(i), nt0, lane, res[t * TM + i]);
