@@ -69,28 +69,45 @@ struct EpiCols {
     float bias[NC];  // bias[n] or 0
 };
 
+// EPI_I8: the scale and bias of the sixteen channels nl0 .. nl0 + 15 as they come from memory, so that a kernel can
+// request them long before it needs the constants made from them (epi_cols16_finish).
+struct EpiRaw16 {
+    e_v4f s[4], b[4];
+};
+__device__ __forceinline__ void epi_cols16_fetch(const GemmParams &p, int nl0, EpiRaw16 &raw)
+{
+    const int n = nl0 < p.N ? nl0 : 0;
+    const e_v4f *s4 = reinterpret_cast<const e_v4f *>(p.scale + n);
+    const e_v4f *b4 = reinterpret_cast<const e_v4f *>(p.bias + n);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        raw.s[j] = s4[j];
+        raw.b[j] = e_v4f{0.0f, 0.0f, 0.0f, 0.0f};
+        if (p.bias) raw.b[j] = b4[j];
+    }
+}
+__device__ __forceinline__ void epi_cols16_finish(const GemmParams &p, bool full, const EpiRaw16 &raw, EpiCols<EPI_I8> &e)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float c = p.act_scale * raw.s[j][i];
+            if (!full) c = c * p.part_mul;
+            e.c[4 * j + i] = c;
+            e.bias[4 * j + i] = raw.b[j][i];
+        }
+}
+
 // Constants of the sixteen channels nl0 .. nl0 + 15 (swapped layouts).
 template <int EPI>
 __device__ __forceinline__ void epi_cols16(const GemmParams &p, int nl0, bool full, EpiCols<EPI> &e)
 {
     static_assert(EPI != EPI_F32, "sixteen channels per lane: swapped layouts only");
     if constexpr (EPI == EPI_I8) {
-        const int n = nl0 < p.N ? nl0 : 0;
-        const e_v4f *s4 = reinterpret_cast<const e_v4f *>(p.scale + n);
-        const e_v4f *b4 = reinterpret_cast<const e_v4f *>(p.bias + n);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const e_v4f s = s4[j];
-            e_v4f b = e_v4f{0.0f, 0.0f, 0.0f, 0.0f};
-            if (p.bias) b = b4[j];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float c = p.act_scale * s[i];
-                if (!full) c = c * p.part_mul;
-                e.c[4 * j + i] = c;
-                e.bias[4 * j + i] = b[i];
-            }
-        }
+        EpiRaw16 raw;
+        epi_cols16_fetch(p, nl0, raw);
+        epi_cols16_finish(p, full, raw, e);
     } else {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {

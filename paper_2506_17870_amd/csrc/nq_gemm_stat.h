@@ -80,8 +80,41 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
     if (r_begin >= r_end) return;
     const int nt = (int)((r_end - r_begin + r_step - 1) / r_step);
 
-    // ---- weights: every K step of the wave's two column tiles, requested first --------------------
     const int nb0 = (cg * WN + wn) * TN;
+    // ---- lane constants of the requests, worked out before the first load is issued -------------------
+    // (a 32-bit multiply-add is a 64-bit instruction whose unused upper halves the register allocator puts
+    // anywhere, e.g. on a register that a load in flight is about to write, which costs a wait for that load)
+    constexpr int NS = TM * TN;                              // residual loads = stores per wave and tile
+    // wave-wide load j of this wave fills panel bytes [(wave * LW + j) * 1024, + 1024): lane l writes piece
+    // slot q = (wave * LW + j) * 64 + l = (row, position), and therefore fetches piece c = position ^ f(row)
+    int ld_row[LW], ld_c16[LW];
+#pragma unroll
+    for (int j = 0; j < LW; ++j) {
+        const int q = (wave * LW + j) * 64 + lane;
+        const int row = q / P, pos = q % P;
+        ld_row[j] = row;
+        ld_c16[j] = 16 * (pos ^ ((row / (16 / SW)) & (SW - 1)));
+    }
+    int pan_lane[LW];
+#pragma unroll
+    for (int j = 0; j < LW; ++j) pan_lane[j] = ld_row[j] * ROWB + ld_c16[j];
+    // output / residual offsets: lane part of tile (t, i) = out0 + i * n32 + t * 32 (see NQ_ST_OUT_OFF below)
+    const int brow0 = wm * 32 * TM + (lane & 31), ch0 = nb0 * 32 + 16 * (lane >> 5);
+    const int out0 = brow0 * (int)p.N + ch0, n32 = 32 * (int)p.N;
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- per-channel scale and bias (int8 epilogue): the oldest requests of the kernel ----------------
+    // Requested here and turned into the epilogue's constants after everything else has been requested: the
+    // counter of outstanding loads counts in order, so a load that is waited for after the panels have been
+    // requested is a wait for the panels, the whole input of the block, twice over (once per column tile).
+    EpiRaw16 craw[EPI == EPI_I8 ? TN : 1];
+    if constexpr (EPI == EPI_I8) {
+#pragma unroll
+        for (int t = 0; t < TN; ++t) epi_cols16_fetch(p, (nb0 + t) * 32 + 16 * (lane >> 5), craw[t]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    // ---- weights: every K step of the wave's two column tiles ----------------------------------------
     uint32_t W8[TN][KS][H + LP::DW > 8 ? H + LP::DW : 8];    // packed dwords on arrival, decoded afterwards
     {
         const int wslot = epi_weight_slot<EPI>(lane);        // channel order that suits the epilogue
@@ -107,32 +140,29 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
     typedef __attribute__((address_space(3))) void *lds_ptr;
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.x), 0, g.x_bytes, 0x00020000);
-    // wave-wide load j of this wave fills panel bytes [(wave * LW + j) * 1024, + 1024): lane l writes piece
-    // slot q = (wave * LW + j) * 64 + l = (row, position), and therefore fetches piece c = position ^ f(row)
-    int ld_row[LW], ld_c16[LW];
-#pragma unroll
-    for (int j = 0; j < LW; ++j) {
-        const int q = (wave * LW + j) * 64 + lane;
-        const int row = q / P, pos = q % P;
-        ld_row[j] = row;
-        ld_c16[j] = 16 * (pos ^ ((row / (16 / SW)) & (SW - 1)));
-    }
     // requests the rows of this block's i-th tile into panel i % RD; a tile that does not exist is requested
     // out of range into the dump area, so that every wave issues the same loads whatever happens (the waits
-    // below count them)
+    // below count them).  The offset of a request is a scalar (the tile's first row) plus a lane part that never
+    // changes, added on the vector ALU: handed over in the instruction's scalar offset operand instead, the
+    // base of the output tiles gave wrong bytes in four lanes of every sixteen of the blocks that are second on
+    // their compute unit (cause not established), so no request of this kernel uses that operand.
     auto load_panel = [&](int i) {
         const bool real = i < nt;
         const int64_t m0 = r_begin + (int64_t)i * r_step;
+        const int64_t left = r_end - m0;
+        const int rl = real ? (left < BM ? (int)left : BM) : 0;          // rows of the tile that exist
         uint8_t *dst = ring + (i % RD) * PANEL;
-        int b0 = 0, rem0 = 0;
+        int b0 = 0, rem0 = 0, pbase = 0;
         if (g.strided) {
             b0 = (int)(m0 / g.howo);
             rem0 = (int)(m0 - (int64_t)b0 * g.howo);
+        } else if (real) {
+            pbase = (int)(m0 * ROWB);
         }
 #pragma unroll
         for (int j = 0; j < LW; ++j) {
             const int k = wave * LW + j;
-            const bool in = real && k < NWL && m0 + ld_row[j] < r_end;
+            const bool in = k < NWL && ld_row[j] < rl;
             int off;
             if (g.strided) {
                 const unsigned n = (unsigned)(rem0 + ld_row[j]);
@@ -141,7 +171,7 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
                 const unsigned oh = g.wo_magic ? __umulhi(r, g.wo_magic) : r, ow = r - oh * (unsigned)p.Wo;
                 off = (b0 + (int)qb) * g.img_bytes + (int)oh * g.row_step + (int)ow * g.col_step + ld_c16[j];
             } else {
-                off = (int)(m0 + ld_row[j]) * ROWB + ld_c16[j];
+                off = pbase + pan_lane[j];
             }
             uint8_t *d = (real && k < NWL) ? dst + k * 1024 : dump;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_ptr)d, 16, in ? off : ST_OOR, 0, 0, 0);
@@ -156,31 +186,33 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
     // 16 * lane of the tile's KB: read back without bank conflicts), one tile ahead, and both they and the output
     // codes go through range-checked descriptors: what a lane has no row or channel for is requested out of
     // range (reads zero, writes nothing) instead of being branched around.
-    constexpr int NS = TM * TN;                              // residual loads = stores per wave and tile
     const int64_t out_bytes = p.M * p.N;                     // the host keeps M * N below 2^31 - 2^16
     const __amdgpu_buffer_rsrc_t rrsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<int8_t *>(p.resid), 0, p.resid ? (int)out_bytes : 0, 0x00020000);
     const __amdgpu_buffer_rsrc_t yrsrc =
         __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<int8_t *>(p.y), 0, (int)out_bytes, 0x00020000);
     uint8_t *my_resid = resid_lds + wave * (NS * 1024);
-    // byte offset of the lane's sixteen channels of row (lane & 31) of tile (t, i) of the block's tile `it` in the
-    // output (and the residual), or out of range.  (Plain code in both users: a lambda called from inside another
-    // lambda of this kernel makes the host pass drop the kernel's stub.)
-#define NQ_ST_OUT_OFF(IT, T, I)                                                                                     \
-    (((IT) < nt && (lane & 31) < r_end - (r_begin + (int64_t)(IT) * r_step + wm * 32 * TM + (I) * 32) &&           \
-      (nb0 + (T)) * 32 + 16 * (lane >> 5) < p.N)                                                                    \
-         ? (int)((r_begin + (int64_t)(IT) * r_step + wm * 32 * TM + (I) * 32 + (lane & 31)) * p.N + (nb0 + (T)) * 32 + \
-                 16 * (lane >> 5))                                                                                  \
-         : ST_OOR)
-    auto load_resid_lds = [&](int it) {
-#pragma unroll
-        for (int t = 0; t < TN; ++t)
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int off = NQ_ST_OUT_OFF(it, t, i);
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rrsrc, (lds_ptr)(my_resid + (t * TM + i) * 1024), 16, off, 0, 0, 0);
-            }
-    };
+    // Offset of the lane's sixteen channels of row (lane & 31) of tile (t, i) of the block's tile `it` in the output
+    // (and the residual): a scalar, the tile's first row, plus a lane part that never changes, the sum replaced by
+    // "out of range" for rows the tile does not have and channels past N.
+#define NQ_ST_TILE(IT, RL, BASE)                                                            \
+    const int64_t tm0_##RL = r_begin + (int64_t)(IT) * r_step, left_##RL = r_end - tm0_##RL; \
+    const int RL = (IT) < nt ? (left_##RL < BM ? (int)left_##RL : BM) : 0;                   \
+    const int BASE = (IT) < nt ? (int)(tm0_##RL * p.N) : 0
+#define NQ_ST_OUT_OFF(RL, BASE, T, I) \
+    ((brow0 + (I) * 32 < (RL) && ch0 + (T) * 32 < (int)p.N) ? (BASE) + out0 + (I) * n32 + (T) * 32 : (int)ST_OOR)
+    // requests the residual codes of the block's tile IT into the wave's staging area.  (Macros and plain integers on
+    // purpose: with a lambda called from a lambda here, and again with small per-tile index arrays in place of
+    // brow0 / out0, the host pass silently dropped the kernel's stub, which shows only when the library is loaded;
+    // the build loads it for that reason.)
+#define NQ_ST_LOAD_RESID(IT, RL, BASE)                                                                            \
+    do {                                                                                                          \
+        NQ_ST_TILE(IT, RL, BASE);                                                                                 \
+        _Pragma("unroll") for (int t_ = 0; t_ < TN; ++t_)                                                         \
+            _Pragma("unroll") for (int i_ = 0; i_ < TM; ++i_)                                                     \
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rrsrc, (lds_ptr)(my_resid + (t_ * TM + i_) * 1024), 16,  \
+                                                         NQ_ST_OUT_OFF(RL, BASE, t_, i_), 0, 0, 0);               \
+    } while (0)
 
     __builtin_amdgcn_sched_barrier(0);                       // weights first, then the panels, in this order
     if constexpr (EPI == EPI_I8) {
@@ -190,7 +222,7 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
             load_panel(i);
             __builtin_amdgcn_sched_barrier(0);
         }
-        load_resid_lds(0);
+        NQ_ST_LOAD_RESID(0, rl0, base0);
         __builtin_amdgcn_sched_barrier(0);
         load_panel(RD - 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -224,7 +256,8 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
 #pragma unroll
     for (int t = 0; t < TN; ++t) {
         EpiCols<EPI> ec;
-        epi_cols<EPI>(p, (nb0 + t) * 32, lane, FULL, ec);
+        if constexpr (EPI == EPI_I8) epi_cols16_finish(p, FULL, craw[t], ec);
+        else epi_cols<EPI>(p, (nb0 + t) * 32, lane, FULL, ec);
         if constexpr (EPI == EPI_F32) {
             my_cols[64 * t + (lane & 31)] = ec.c[0];
             my_cols[64 * t + 32 + (lane & 31)] = ec.bias[0];
@@ -330,12 +363,13 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0) only
             __builtin_amdgcn_sched_barrier(0);
-            load_resid_lds(it + 1);
+            NQ_ST_LOAD_RESID(it + 1, rl_n, base_n);
             __builtin_amdgcn_sched_barrier(0);
             load_panel(it + RD);                             // into the panel this tile has just been read from
             __builtin_amdgcn_sched_barrier(0);
 
             // ---- epilogue (Eq. 2 / Eq. 8) ------------------------------------------------------------
+            NQ_ST_TILE(it, rl_out, base_out);
 #pragma unroll
             for (int t = 0; t < TN; ++t) {
                 EpiCols<EPI_I8> e;
@@ -350,14 +384,16 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
                 for (int i = 0; i < TM; ++i) {
                     const e_v4i q = epi_codes16(p, acc[i][t], SHIFT, e, res[t * TM + i]);
                     __builtin_amdgcn_raw_buffer_store_b128(s_u4v{(unsigned)q[0], (unsigned)q[1], (unsigned)q[2], (unsigned)q[3]},
-                                                           yrsrc, NQ_ST_OUT_OFF(it, t, i), 0, 0);
+                                                           yrsrc, NQ_ST_OUT_OFF(rl_out, base_out, t, i), 0, 0);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
         }
         return;
     }
+#undef NQ_ST_LOAD_RESID
 #undef NQ_ST_OUT_OFF
+#undef NQ_ST_TILE
     e_v4i res[TM * TN], res_next[TM * TN];
     load_resid(0, res);
 
