@@ -73,8 +73,9 @@ typedef enum { NQ_LOW_UNSIGNED_L = 0, NQ_LOW_SIGNED_L1 = 1 } nq_low_format;
  * NQ_LAYOUT_DENSE: exactly k bits per element on the shape padded to N%32 == 0,
  *   K%64 == 0 (zero fields in the padding).  Tiles of 32 rows x 64 columns, row-block
  *   major, each k*256 bytes.  Inside a tile, dword (i, slot) is at dword offset
- *   i*64 + slot, i in [0,k), slot = 32*g + r with r the row in the tile and g the half
- *   of the 64 columns.  The slot's 32 columns are c = 32*g + 4*j + b (j in [0,8) the
+ *   slot*k + i, i in [0,k) (the k dwords of a slot are contiguous, so that a kernel fetches
+ *   them with one or two wide loads), slot = 32*g + r with r the row in the tile and g the
+ *   half of the 64 columns.  The slot's 32 columns are c = 32*g + 4*j + b (j in [0,8) the
  *   position, b in [0,4) the byte lane); byte b of dword (i, slot) is byte B_i of the
  *   group (slot, b), which stores the fields F_0..F_7 of positions 0..7:
  *     higher-bit page ("carrier"): with s = 8-k, bits [7..s] of B_i hold F_i for i < k;

@@ -213,7 +213,8 @@ int oq_unpack_paper(const uint64_t *in, int64_t N, int64_t K, int k,
  * the padded shape).  N is padded to a multiple of 32 and K to a multiple
  * of 64 with zero fields.  A tile is 32 rows x 64 columns; tiles are stored
  * row-block major, column-block minor, each tile k*64 dwords:
- *   dword (i, slot), i in [0,k), slot in [0,64), sits at i*64 + slot;
+ *   dword (i, slot), i in [0,k), slot in [0,64), sits at slot*k + i (the k
+ *   dwords of a slot are contiguous);
  *   slot = 32*g + r : r = row within the tile, g = which half of the 64
  *   columns; the slot's 32 columns are c = 32*g + 4*j + b, j in [0,8)
  *   "position", b in [0,4) "byte lane"; byte b of dword (i,slot) is byte i
@@ -273,7 +274,7 @@ int oq_pack_dense(const int8_t *v, int64_t N, int64_t K, int k, int kind,
                 if (!((field >> t) & 1u)) continue;
                 int byte, bit;
                 dense_bit_place(kind, k, j, t, &byte, &bit);
-                tile[(byte * 64 + slot) * 4 + b] |= (uint8_t)(1u << bit);
+                tile[(slot * k + byte) * 4 + b] |= (uint8_t)(1u << bit);
             }
         }
     return OQ_OK;
@@ -295,7 +296,7 @@ int oq_unpack_dense(const uint8_t *in, int64_t N, int64_t K, int k, int kind,
             for (int t = 0; t < k; ++t) {
                 int byte, bit;
                 dense_bit_place(kind, k, j, t, &byte, &bit);
-                if ((tile[(byte * 64 + slot) * 4 + b] >> bit) & 1u) field |= 1u << t;
+                if ((tile[(slot * k + byte) * 4 + b] >> bit) & 1u) field |= 1u << t;
             }
             v[n * K + c] = (int8_t)widen(field, k, is_signed);
         }

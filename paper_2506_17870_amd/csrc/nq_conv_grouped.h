@@ -120,12 +120,12 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_grouped(const GemmParams
             const int64_t tile = (int64_t)nb * p.KB + kb;
             uint32_t P[H];
 #pragma unroll
-            for (int i = 0; i < H; ++i) P[i] = p.ph[tile * (H * 64) + i * 64 + lane];
+            for (int i = 0; i < H; ++i) P[i] = p.ph[tile * (H * 64) + lane * H + i];
             HighCodec<H>::decode(P, D);
             if constexpr (FULL != 0) {
                 uint32_t Q[LP::ARR];
 #pragma unroll
-                for (int i = 0; i < LP::DW; ++i) Q[i] = p.pl[tile * (LP::DW * 64) + i * 64 + lane];
+                for (int i = 0; i < LP::DW; ++i) Q[i] = p.pl[tile * (LP::DW * 64) + lane * LP::DW + i];
                 LP::apply(Q, D);
             }
         }

@@ -72,10 +72,10 @@ __global__ void __launch_bounds__(256) k_nested_conv_grouped_any(const GemmParam
         const int slot = 32 * (k32 & 1) + r;
         uint32_t P[H], Q[LP::ARR], D[8];
 #pragma unroll
-        for (int i = 0; i < H; ++i) P[i] = p.ph[tile * (H * 64) + i * 64 + slot];
+        for (int i = 0; i < H; ++i) P[i] = p.ph[tile * (H * 64) + slot * H + i];
         if constexpr (FULL != 0) {
 #pragma unroll
-            for (int i = 0; i < LP::DW; ++i) Q[i] = p.pl[tile * (LP::DW * 64) + i * 64 + slot];
+            for (int i = 0; i < LP::DW; ++i) Q[i] = p.pl[tile * (LP::DW * 64) + slot * LP::DW + i];
         }
         HighCodec<H>::decode(P, D);
         LP::apply(Q, D);

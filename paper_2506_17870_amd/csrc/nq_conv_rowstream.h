@@ -74,11 +74,11 @@ __global__ void __launch_bounds__(256, 2) k_nested_conv_rowstream(const GemmPara
 #pragma unroll
             for (int s = 0; s < RS_KCAP; ++s) {
 #pragma unroll
-                for (int i = 0; i < H; ++i) W8[c][s][i] = ph[(unsigned)(s * (H * 64) + i * 64 + wslot)];
+                for (int i = 0; i < H; ++i) W8[c][s][i] = ph[(unsigned)(s * (H * 64) + wslot * H + i)];
                 if constexpr (FULL != 0) {
 #pragma unroll
                     for (int i = 0; i < LP::DW; ++i)
-                        W8[c][s][H + i] = pl[(unsigned)(s * (LP::DW * 64) + i * 64 + wslot)];
+                        W8[c][s][H + i] = pl[(unsigned)(s * (LP::DW * 64) + wslot * LP::DW + i)];
                 }
             }
         }

@@ -67,13 +67,13 @@ __global__ void __launch_bounds__(256) k_nested_conv_window(const GemmParams p, 
             const int nb = nb0 + t;
             if (nb < p.NB) {
                 const int64_t tile = (int64_t)nb * p.KB + kb;
-                const uint32_t *src = p.ph + tile * (H * 64) + wslot;
+                const uint32_t *src = p.ph + tile * (H * 64) + wslot * H;
 #pragma unroll
-                for (int i = 0; i < H; ++i) Pd[t][i] = src[i * 64];
+                for (int i = 0; i < H; ++i) Pd[t][i] = src[i];
                 if constexpr (FULL != 0) {
-                    const uint32_t *srcl = p.pl + tile * (LP::DW * 64) + wslot;
+                    const uint32_t *srcl = p.pl + tile * (LP::DW * 64) + wslot * LP::DW;
 #pragma unroll
-                    for (int i = 0; i < LP::DW; ++i) Qd[t][i] = srcl[i * 64];
+                    for (int i = 0; i < LP::DW; ++i) Qd[t][i] = srcl[i];
                 }
             } else {
 #pragma unroll

@@ -38,6 +38,28 @@ typedef unsigned g_v4u __attribute__((ext_vector_type(4)));
 constexpr int GB_BN = 256, GB_KI = 4;                    // K steps of 64 per iteration
 constexpr int GB_ROW = GB_KI * 64;                       // LDS bytes per panel row (swizzled, not padded)
 
+typedef unsigned g_v2u __attribute__((ext_vector_type(2)));
+typedef unsigned g_v3u __attribute__((ext_vector_type(3)));
+
+// Dwords [4 * c, min(4 * c + 4, n_all)) of a slot's n_all packed dwords into dst, as one request.  (A function and not
+// a lambda of the kernel: a lambda called from another lambda there makes the host pass drop the kernel's stub.)
+__device__ __forceinline__ void gb_fetch(uint32_t *dst, const __amdgpu_buffer_rsrc_t &rs, int n_all, int c, int voff, int soff)
+{
+    const int n = n_all - 4 * c >= 4 ? 4 : n_all - 4 * c;
+    if (n == 4) {
+        const g_v4u v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + 16 * c, soff, 0);
+        dst[4 * c] = v[0]; dst[4 * c + 1] = v[1]; dst[4 * c + 2] = v[2]; dst[4 * c + 3] = v[3];
+    } else if (n == 3) {
+        const g_v3u v = __builtin_amdgcn_raw_buffer_load_b96(rs, voff + 16 * c, soff, 0);
+        dst[4 * c] = v[0]; dst[4 * c + 1] = v[1]; dst[4 * c + 2] = v[2];
+    } else if (n == 2) {
+        const g_v2u v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff + 16 * c, soff, 0);
+        dst[4 * c] = v[0]; dst[4 * c + 1] = v[1];
+    } else {
+        dst[4 * c] = __builtin_amdgcn_raw_buffer_load_b32(rs, voff + 16 * c, soff, 0);
+    }
+}
+
 // TM: 32-row tiles per wave (block tile 32*TM x 256); the host picks TM so that the number of
 // blocks fits the 256 compute units with little left over.  TM <= 4 fits two blocks per unit
 // (the element-wise epilogue needs more registers and runs one block per unit rather than spill).
@@ -211,25 +233,29 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
     int trel[TN];
 #pragma unroll
     for (int t = 0; t < TN; ++t) trel[t] = __builtin_amdgcn_readfirstlane((int)(tile0[t] - tile0[0]));
-    // dword j of a pipeline slot: j < TN*H is higher-bit dword (t = j / H, i = j % H), the rest are the
-    // lower-bit dwords; load_b requests the dwords j0 <= j < j1 of K step kb
-    constexpr int NBL = TN * (H + LP::DW);
+    // The packed dwords of a slot are contiguous in the page (slot-major tiles), so a lane fetches them four at a
+    // time: the address unit takes as long over a wave's request for one dword per lane as over one for four, and
+    // with one request per dword it, not the matrix core, set the pace of the K loop.  A pipeline slot of a K step is
+    // NBL requests: for each column tile the pieces of the higher-bit dwords, then those of the lower-bit dwords;
+    // load_b issues the requests j0 <= j < j1 of K step kb.
+    constexpr int CH = (H + 3) / 4, CL = (LP::DW + 3) / 4;          // requests per tile and page
+    constexpr int NBL = TN * (CH + CL);
     auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][LP::ARR], int kb, int j0, int j1) {
         // (the range check covers the lane offset only, so that is where "out of range" goes; the scalar offset
         // always names a real tile)
-        const int voff = (!SOLO || kb < p.KB) ? wslot * 4 : OOR;   // (two blocks per unit hide the useless last refills)
+        const bool real = !SOLO || kb < p.KB;                // (two blocks per unit hide the useless last refills)
+        const int voff_h = real ? wslot * (H * 4) : OOR, voff_l = real ? wslot * (LP::DW * 4) : OOR;
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
             const int tk = trel[t] + min(kb, p.KB - 1);
 #pragma unroll
-            for (int i = 0; i < H; ++i)
-                if (t * H + i >= j0 && t * H + i < j1)
-                    Pd[t][i] = __builtin_amdgcn_raw_buffer_load_b32(hrsrc, voff + i * 256, tk * (H * 256), 0);
+            for (int c = 0; c < CH; ++c)
+                if (t * (CH + CL) + c >= j0 && t * (CH + CL) + c < j1) gb_fetch(Pd[t], hrsrc, H, c, voff_h, tk * (H * 256));
             if constexpr (FULL != 0) {
 #pragma unroll
-                for (int i = 0; i < LP::DW; ++i)
-                    if (TN * H + t * LP::DW + i >= j0 && TN * H + t * LP::DW + i < j1)
-                        Qd[t][i] = __builtin_amdgcn_raw_buffer_load_b32(lrsrc, voff + i * 256, tk * (LP::DW * 256), 0);
+                for (int c = 0; c < CL; ++c)
+                    if (t * (CH + CL) + CH + c >= j0 && t * (CH + CL) + CH + c < j1)
+                        gb_fetch(Qd[t], lrsrc, LP::DW, c, voff_l, tk * (LP::DW * 256));
             }
         }
     };

@@ -132,13 +132,13 @@ __global__ void __launch_bounds__(256) k_nested_gemm(const GemmParams p)
             const int nb = nb0 + t;
             if (nb < p.NB) {
                 const int64_t tile = (int64_t)nb * p.KB + kb;
-                const uint32_t *src = p.ph + tile * (H * 64) + wslot;
+                const uint32_t *src = p.ph + tile * (H * 64) + wslot * H;
 #pragma unroll
-                for (int i = 0; i < H; ++i) P[t][i] = src[i * 64];
+                for (int i = 0; i < H; ++i) P[t][i] = src[i];
                 if constexpr (FULL != 0) {
-                    const uint32_t *srcl = p.pl + tile * (LD * 64) + wslot;
+                    const uint32_t *srcl = p.pl + tile * (LD * 64) + wslot * LD;
 #pragma unroll
-                    for (int i = 0; i < LD; ++i) Q[t][i] = srcl[i * 64];
+                    for (int i = 0; i < LD; ++i) Q[t][i] = srcl[i];
                 }
             } else {
 #pragma unroll

@@ -122,11 +122,11 @@ __device__ __forceinline__ void skinny_block(const GemmParams &p, const int nb, 
         const int kbc = min(kb, p.KB - 1);
         const uint32_t *src = p.ph + (tile0 + kbc) * (H * 64);
 #pragma unroll
-        for (int i = 0; i < H; ++i) P[slot][i] = src[(unsigned)(i * 64 + wslot)];
+        for (int i = 0; i < H; ++i) P[slot][i] = src[(unsigned)(wslot * H + i)];
         if constexpr (FULL != 0) {
             const uint32_t *srcl = p.pl + (tile0 + kbc) * (LP::DW * 64);
 #pragma unroll
-            for (int i = 0; i < LP::DW; ++i) Q[slot][i] = srcl[(unsigned)(i * 64 + wslot)];
+            for (int i = 0; i < LP::DW; ++i) Q[slot][i] = srcl[(unsigned)(wslot * LP::DW + i)];
         }
         if constexpr (!STAGED) {
             const int koff = kb < p.KB ? 64 * kb : 0x7fff0000;

@@ -103,20 +103,18 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
     const int out0 = brow0 * (int)p.N + ch0, n32 = 32 * (int)p.N;
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- per-channel scale and bias (int8 epilogue): the oldest requests of the kernel ----------------
-    // Requested here and turned into the epilogue's constants after everything else has been requested: the
-    // counter of outstanding loads counts in order, so a load that is waited for after the panels have been
-    // requested is a wait for the panels, the whole input of the block, twice over (once per column tile).
+    // ---- per-channel scale and bias (int8 epilogue) and weights: every K step of the wave's two column tiles ----
+    // Scale and bias are requested here and turned into the epilogue's constants after everything else has been
+    // requested: the counter of outstanding loads counts in order, so a load that is waited for after the panels
+    // have been requested is a wait for the panels, the whole input of the block.
     EpiRaw16 craw[EPI == EPI_I8 ? TN : 1];
-    if constexpr (EPI == EPI_I8) {
-#pragma unroll
-        for (int t = 0; t < TN; ++t) epi_cols16_fetch(p, (nb0 + t) * 32 + 16 * (lane >> 5), craw[t]);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-
-    // ---- weights: every K step of the wave's two column tiles ----------------------------------------
     uint32_t W8[TN][KS][H + LP::DW > 8 ? H + LP::DW : 8];    // packed dwords on arrival, decoded afterwards
-    {
+    auto load_weights = [&]() {
+        if constexpr (EPI == EPI_I8) {
+#pragma unroll
+            for (int t = 0; t < TN; ++t) epi_cols16_fetch(p, (nb0 + t) * 32 + 16 * (lane >> 5), craw[t]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         const int wslot = epi_weight_slot<EPI>(lane);        // channel order that suits the epilogue
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
@@ -126,15 +124,21 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
 #pragma unroll
-                for (int i = 0; i < H; ++i) W8[t][s][i] = ph[(unsigned)(s * (H * 64) + i * 64 + wslot)];
+                for (int i = 0; i < H; ++i) W8[t][s][i] = ph[(unsigned)(s * (H * 64) + wslot * H + i)];
                 if constexpr (FULL != 0) {
 #pragma unroll
                     for (int i = 0; i < LP::DW; ++i)
-                        W8[t][s][H + i] = pl[(unsigned)(s * (LP::DW * 64) + i * 64 + wslot)];
+                        W8[t][s][H + i] = pl[(unsigned)(s * (LP::DW * 64) + wslot * LP::DW + i)];
                 }
             }
         }
-    }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // A wave can have 63 memory instructions in flight; its 64 to 80 requests for weights and constants alone
+    // exceed that, and whatever is issued after them waits for the first of them to come back from memory.  With
+    // the int8 epilogue the panels and residual codes (24 requests, the ones that go all the way to memory) are
+    // therefore requested first and the weights (mostly found in L2) behind them.
+    if constexpr (EPI != EPI_I8) load_weights();
 
     // ---- activation panels ------------------------------------------------------------------------
     typedef __attribute__((address_space(3))) void *lds_ptr;
@@ -143,9 +147,11 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
     // requests the rows of this block's i-th tile into panel i % RD; a tile that does not exist is requested
     // out of range into the dump area, so that every wave issues the same loads whatever happens (the waits
     // below count them).  The offset of a request is a scalar (the tile's first row) plus a lane part that never
-    // changes, added on the vector ALU: handed over in the instruction's scalar offset operand instead, the
-    // base of the output tiles gave wrong bytes in four lanes of every sixteen of the blocks that are second on
-    // their compute unit (cause not established), so no request of this kernel uses that operand.
+    // changes, added on the vector ALU and not handed over in the instruction's scalar offset operand.  For the
+    // 16-byte stores of the outputs that operand must stay an immediate: the compiler puts the wait state between
+    // such a store and a vector instruction that overwrites its data registers only when the store has no register
+    // there, and the hardware needs it in both cases (with a register, the first data dword of lanes 12-15 of every
+    // sixteen was stored as the next instruction left it).  The loads of this kernel follow the same form.
     auto load_panel = [&](int i) {
         const bool real = i < nt;
         const int64_t m0 = r_begin + (int64_t)i * r_step;
@@ -214,7 +220,7 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
                                                          NQ_ST_OUT_OFF(RL, BASE, t_, i_), 0, 0, 0);               \
     } while (0)
 
-    __builtin_amdgcn_sched_barrier(0);                       // weights first, then the panels, in this order
+    __builtin_amdgcn_sched_barrier(0);                       // the waits below count on the order of the requests
     if constexpr (EPI == EPI_I8) {
         // the order of a tile of the loop below: residual codes, newest panel, stores (here: NS stores of nothing)
 #pragma unroll
@@ -230,6 +236,7 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
         for (int j = 0; j < NS; ++j)
             __builtin_amdgcn_raw_buffer_store_b128(s_u4v{(unsigned)j, 0u, 0u, 0u}, yrsrc, ST_OOR + 4096 * j + 16 * lane, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
+        load_weights();
     } else {
 #pragma unroll
         for (int i = 0; i < RD; ++i) {
@@ -297,7 +304,8 @@ __global__ void __launch_bounds__(256, EPI == EPI_ANY ? 1 : 2) k_nested_gemm_sta
         __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
     };
     // panel 0 (and the weights before it) are in: everything requested after it may still travel
-    wait_loads(std::integral_constant<int, (RD - 1) * LW + (EPI == EPI_I8 ? 2 * NS : 0)>{});
+    // (int8 epilogue: the weights were requested last, the decoding above has waited for them and with them for everything)
+    wait_loads(std::integral_constant<int, EPI == EPI_I8 ? 0 : (RD - 1) * LW>{});
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
 

@@ -173,13 +173,13 @@ __device__ __forceinline__ void pack_dense_tile(const int8_t *__restrict__ a, co
             uint32_t P[H];
             HighCodec<H>::encode(X, P);
 #pragma unroll
-            for (int i = 0; i < H; ++i) ph[tile * (H * 64) + i * 64 + lane] = P[i];
+            for (int i = 0; i < H; ++i) ph[tile * (H * 64) + lane * H + i] = P[i];
         }
         if (pl) {
             uint32_t Q[L + 1];
             LowCodec<L + 1, S + 1>::encode(XL, Q);
 #pragma unroll
-            for (int i = 0; i < L + 1; ++i) pl[tile * ((L + 1) * 64) + i * 64 + lane] = Q[i];
+            for (int i = 0; i < L + 1; ++i) pl[tile * ((L + 1) * 64) + lane * (L + 1) + i] = Q[i];
         }
         return;
     }
@@ -195,16 +195,16 @@ __device__ __forceinline__ void pack_dense_tile(const int8_t *__restrict__ a, co
     if (ph) {
         uint32_t P[H];
         HighCodec<H>::encode(X, P);
-        uint32_t *dst = ph + tile * (H * 64) + lane;
+        uint32_t *dst = ph + tile * (H * 64) + lane * H;
 #pragma unroll
-        for (int i = 0; i < H; ++i) dst[i * 64] = P[i];
+        for (int i = 0; i < H; ++i) dst[i] = P[i];
     }
     if (pl) {
         uint32_t Q[L];
         LowCodec<L, S>::encode(X, Q);
-        uint32_t *dst = pl + tile * (L * 64) + lane;
+        uint32_t *dst = pl + tile * (L * 64) + lane * L;
 #pragma unroll
-        for (int i = 0; i < L; ++i) dst[i * 64] = Q[i];
+        for (int i = 0; i < L; ++i) dst[i] = Q[i];
     }
 }
 
@@ -345,7 +345,7 @@ __global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict
     if (ph && high) {
         uint32_t P[H], D[8], V[8];
 #pragma unroll
-        for (int i = 0; i < H; ++i) P[i] = ph[tile * (H * 64) + i * 64 + lane];
+        for (int i = 0; i < H; ++i) P[i] = ph[tile * (H * 64) + lane * H + i];
         HighCodec<H>::decode(P, D);
         // a decoded byte is w_high * 2^S: down by S, the neighbour's bits masked off, sign extended from h bits
 #pragma unroll
@@ -355,7 +355,7 @@ __global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict
     if (pl && low && sgn) {
         uint32_t Q[L + 1], D[8], V[8];
 #pragma unroll
-        for (int i = 0; i < L + 1; ++i) Q[i] = pl[tile * ((L + 1) * 64) + i * 64 + lane];
+        for (int i = 0; i < L + 1; ++i) Q[i] = pl[tile * ((L + 1) * 64) + lane * (L + 1) + i];
 #pragma unroll
         for (int j = 0; j < 8; ++j) D[j] = 0;
         LowCodec<L + 1, S + 1>::decode_or(Q, D);
@@ -366,7 +366,7 @@ __global__ void __launch_bounds__(256) k_unpack_dense(const uint32_t *__restrict
     } else if (pl && low) {
         uint32_t Q[L], D[8], V[8];
 #pragma unroll
-        for (int i = 0; i < L; ++i) Q[i] = pl[tile * (L * 64) + i * 64 + lane];
+        for (int i = 0; i < L; ++i) Q[i] = pl[tile * (L * 64) + lane * L + i];
 #pragma unroll
         for (int j = 0; j < 8; ++j) D[j] = 0;
         LowCodec<L, S>::decode_or(Q, D);
