@@ -38,6 +38,28 @@ typedef unsigned g_v4u __attribute__((ext_vector_type(4)));
 constexpr int GB_BN = 256, GB_KI = 4;                    // K steps of 64 per iteration
 constexpr int GB_ROW = GB_KI * 64;                       // LDS bytes per panel row (swizzled, not padded)
 
+// Slot m of a woven K step decodes dword m % 8 of a tile; the dwords past the H-th are gathered from the spare bits of
+// the others and cost three times as many instructions.  gb_pref(H, n, i): the i-th of the n slots in the order in
+// which they should take the step's other work (LDS reads, memory requests): the slots with a cheap dword first.
+constexpr int gb_pref(int H, int n, int i)
+{
+    int seen = 0;
+    for (int pass = 0; pass < 2; ++pass)
+        for (int m = 0; m < n; ++m)
+            if (((m % 8) < H) == (pass == 0)) {
+                if (seen == i) return m;
+                ++seen;
+            }
+    return i % n;
+}
+
+constexpr int gb_light(int H, int n)                      // how many of the n slots decode a cheap dword
+{
+    int c = 0;
+    for (int m = 0; m < n; ++m) c += (m % 8) < H;
+    return c;
+}
+
 typedef unsigned g_v2u __attribute__((ext_vector_type(2)));
 typedef unsigned g_v3u __attribute__((ext_vector_type(3)));
 
@@ -354,10 +376,10 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
         if constexpr (SOLO && TM == 4) {
             // One wave per SIMD: nothing hides a stall, and whatever the wave issues between two MFMAs beyond what
             // fits in the shadow of the first delays the second.  So the K step is woven by hand, one fenced slot
-            // per MFMA: the MFMA, then (every second slot) the LDS read of one fragment of step d + 1, the decoding
-            // of ONE dword of step d + 1's weights (the codec is called whole and everything but that dword is dead
-            // code), one or two refills of the pipeline slot decoded during the previous step, and now and then one
-            // of the next panel's requests.  Left to the scheduler the same work came out in bursts of sixty
+            // per MFMA: the MFMA, the decoding of ONE dword of step d + 1's weights (the codec is called whole and
+            // everything but that dword is dead code), and, in the slots whose dword is cheap to decode, the LDS read
+            // of one fragment of step d + 1 or a refill of the pipeline slot decoded during the previous step; now and
+            // then one of the next panel's requests.  Left to the scheduler the same work came out in bursts of sixty
             // instructions between two MFMAs (3950 -> 3440 clocks per four K steps on a 1024 -> 256 layer).
             constexpr int NF = 2 * TM, NM = NF * TN;
             g_v4i af[2][NF];
@@ -373,9 +395,13 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
                     const int f = m / TN, t = m % TN;
                     __builtin_amdgcn_sched_barrier(0);
                     acc[f % TM][t] = epi_mfma<EPI>(bfr[d & 1][t][f / TM], af[d & 1][f], acc[f % TM][t]);
-                    if (d + 1 < GB_KI && m % TN == 0)
-                        af[(d + 1) & 1][f] = *reinterpret_cast<const g_v4i *>(cur + a_read[d + 1][f / TM] +
-                                                                              (f % TM) * 32 * GB_ROW);
+                    if (d + 1 < GB_KI) {
+#pragma unroll
+                        for (int fr = 0; fr < NF; ++fr)       // fragment fr of step d + 1, in a slot with cheap decoding
+                            if (gb_pref(H, NM, fr) == m)
+                                af[(d + 1) & 1][fr] = *reinterpret_cast<const g_v4i *>(cur + a_read[d + 1][fr / TM] +
+                                                                                       (fr % TM) * 32 * GB_ROW);
+                    }
 #pragma unroll
                     for (int q = m * 8 * TN / NM; q < (m + 1) * 8 * TN / NM; ++q) {   // one dword (TM = 4), or none
                         uint32_t Dn[8];
@@ -383,7 +409,9 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
                         LP::apply(Q[(d + 1) % PD][q / 8], Dn);
                         bfr[(d + 1) & 1][q / 8][(q % 8) / 4][q % 4] = (int)Dn[q % 8];
                     }
-                    load_b(P[d % PD], Q[d % PD], kb + PD, m * NBL / NM, (m + 1) * NBL / NM);
+#pragma unroll
+                    for (int j = 0; j < NBL; ++j)             // refills in the cheap slots after those of the reads
+                        if (gb_pref(H, NM, (NF + j) % gb_light(H, NM)) == m) load_b(P[d % PD], Q[d % PD], kb + PD, j, j + 1);
                     if (d < GB_KI - 1) {
 #pragma unroll
                         for (int k = 0; k < APT; ++k)
