@@ -348,7 +348,8 @@ nq_status nq_gconv_part(const int8_t *d_x, const nq_conv_shape *shape, int group
  *   NQ_TUNE_KERNEL:   1 generic, 2 windowed, 3 register-stationary, 4 large GEMM, 5 few input channels,
  *                     6 few rows, 9 stationary-weights GEMM (short reductions)
  *   NQ_TUNE_BIG_TM:   2..5, rows per block of the large-GEMM kernel = 32 * value; 6 = 128 rows with one block
- *                     per compute unit (the whole register file: deeper weight pipeline)
+ *                     per compute unit (the whole register file: deeper weight pipeline); 7 = blocks of 128 rows
+ *                     x 128 columns (the library's choice for up to 128 output channels)
  *   NQ_TUNE_GC_UNITS: work units the patch planner of the depthwise / grouped kernel aims for
  *   NQ_TUNE_STAT_ROWS: 1 gives every block of the stationary-weights GEMM one run of consecutive rows instead of
  *                     dealing the row tiles to the blocks in turn

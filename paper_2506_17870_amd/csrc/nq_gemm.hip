@@ -455,13 +455,14 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     // output channels; with 512 channels or more out of 512 in, the large kernel's 256-column tiles win
     // (strided 1x1, 28x28x512 -> 1024 at batch 128: 30 us against 48 us)
     if (conv_gemm && w->K <= 576 && !(w->K >= 512 && w->N >= 512)) big_wanted = false;
-    // Filters over up to 128 output channels at stride 1 go to the windowed kernel (64 channels per block): the
-    // large-GEMM kernel's 256-column tile would be half empty (3x3, 28x28x128 -> 128 at batch 128: 38.8 us
-    // against 51.8 us; at stride 2 the large kernel stays ahead, 51 us against 57 us).
+    // Filters over up to 64 output channels at stride 1 go to the windowed kernel (64 channels per block): the
+    // large-GEMM kernel's tiles, 128 columns at the least, would be half empty.  (Up to 128 channels they went there
+    // too while the large kernel had 256-column tiles only; with its 128 x 128 variant, 3x3, 28x28x128 -> 128 at
+    // batch 128 takes 29 us against 42 us, and at stride 2 31 us against 59 us.)
     {
         WindowGeom wg0;
         size_t lds0 = 0;
-        if (conv_gemm && w->N <= 128 && g.stride == 1 && g.KH * g.KW > 1 && plan_window(g, d_x, &wg0, &lds0))
+        if (conv_gemm && w->N <= 64 && g.stride == 1 && g.KH * g.KW > 1 && plan_window(g, d_x, &wg0, &lds0))
             big_wanted = false;
     }
     // short reductions without a filter window: weights stationary in registers, rows streamed

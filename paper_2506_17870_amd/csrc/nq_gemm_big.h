@@ -86,12 +86,15 @@ __device__ __forceinline__ void gb_fetch(uint32_t *dst, const __amdgpu_buffer_rs
 // blocks fits the 256 compute units with little left over.  TM <= 4 fits two blocks per unit
 // (the element-wise epilogue needs more registers and runs one block per unit rather than spill).
 // FULL: 0 part-bit, 1 full-bit (unsigned lower part), 2 full-bit (compensated signed lower part).
-// TMX: 2..5 = TM; 6 = TM 4 with the compute unit to itself (SOLO: 512 registers, the deep weight pipeline).
+// TMX: 2..5 = TM; 6 = TM 4 with the compute unit to itself (SOLO: 512 registers, the deep weight pipeline);
+// 7 = TM 4 with one column tile per wave (NARROW: block tile 128 x 128, for layers of up to 128 output channels whose
+// 256-column tile would be half empty; half the registers, so the deep pipeline and the woven K step fit two blocks per unit).
 template <int H, int L, int FULL, int EPI, int TMX, bool CONV>
-__global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
+__global__ void __launch_bounds__(256, ((TMX <= 4 || TMX == 7) && EPI != EPI_ANY ? 2 : 1)) k_nested_gemm_big(const GemmParams p)
 {
-    constexpr int TM = TMX == 6 ? 4 : TMX;
-    constexpr bool SOLO = TMX >= 5;
+    constexpr int TM = TMX >= 6 ? 4 : TMX;
+    constexpr bool SOLO = TMX == 5 || TMX == 6, NARROW = TMX == 7;
+    constexpr int TN = NARROW ? 1 : 2, BN = 128 * TN;        // column tiles per wave, columns per block
     constexpr int GB_BM = 32 * TM;
     constexpr int GB_PANEL = GB_BM * GB_ROW;             // bytes per LDS panel
     constexpr int S = 8 - H;
@@ -99,7 +102,7 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
     using LP = LowPage<L, S, FULL>;
     // weights are requested PD K steps ahead (registers permitting: TM = 4 shares the compute unit with a
     // second block and has 256 registers, TM >= 5 has 512)
-    constexpr int TN = 2, PD = (TM == 4 && !SOLO && (FULL || H == 7) ? 2 : 4);
+    constexpr int PD = NARROW ? 4 : (TM == 4 && !SOLO && (FULL || H == 7) ? 2 : 4);
     constexpr int APT = 2 * TM;                          // LDS-direct loads per wave and iteration (4 rows each)
 
     extern __shared__ __attribute__((aligned(16))) uint8_t panel[];
@@ -109,10 +112,10 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
     // derived from it (tile numbers, page addresses) lives in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // n tiles vary fastest so that blocks running together share their activation rows
-    const int nblocks = (p.N + GB_BN - 1) / GB_BN;
+    const int nblocks = (p.N + BN - 1) / BN;
     const int bm = blockIdx.x / nblocks, bn = blockIdx.x - bm * nblocks;
     const int64_t m0 = (int64_t)bm * GB_BM;
-    const int n0 = bn * GB_BN;
+    const int n0 = bn * BN;
 
     const int iters = (p.KB + GB_KI - 1) / GB_KI;
 
@@ -161,7 +164,7 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
     // small LDS table behind the panels
     int2 *rowtab = reinterpret_cast<int2 *>(panel + 2 * GB_PANEL);
     // with 96 or 128 rows per block (two blocks share the unit's registers) there is no room for them
-    constexpr bool ROWREG = CONV && (TM <= 2 || SOLO);
+    constexpr bool ROWREG = CONV && (TM <= 2 || SOLO || NARROW);
     int2 rowreg[ROWREG ? APT : 1];
     if constexpr (CONV) {
         if (tid < GB_BM) {
@@ -341,7 +344,7 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
     // the weights of a step are decoded at its start.
     constexpr bool AHEAD = PD >= 4;
     g_v4i bfrag[TN][2];                                   // decoded weights of the current K step
-    constexpr bool WOVEN = SOLO && TM == 4;
+    constexpr bool WOVEN = (SOLO && TM == 4) || NARROW;
     g_v4i bfr[WOVEN ? 2 : 1][TN][2];                      // woven K step: of the current and of the next step
     if constexpr (AHEAD) {
 #pragma unroll
@@ -373,7 +376,7 @@ __global__ void __launch_bounds__(256, (TMX <= 4 && EPI != EPI_ANY ? 2 : 1)) k_n
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (CONV) set_taps(it + 1);
 
-        if constexpr (SOLO && TM == 4) {
+        if constexpr (WOVEN) {
             // One wave per SIMD: nothing hides a stall, and whatever the wave issues between two MFMAs beyond what
             // fits in the shadow of the first delays the second.  So the K step is woven by hand, one fenced slot
             // per MFMA: the MFMA, the decoding of ONE dword of step d + 1's weights (the codec is called whole and
@@ -613,17 +616,20 @@ template <int H, int L>
 void launch_nested_gemm_big(bool full, const GemmParams &p, int tm_forced, int *tm_used, hipStream_t st,
                             void *ev_start, void *ev_stop)
 {
-    const int nblocks = (p.N + GB_BN - 1) / GB_BN;
+    int nblocks = (p.N + GB_BN - 1) / GB_BN;
     const int mode = epi_mode(p);
     int tm = mode == EPI_ANY ? 4 : gemm_big_pick_tm(p.M, p.N, p.conv_big && p.KH * p.KW > 1);   // the element-wise epilogue is built for TM = 4 only
     // 128-row blocks that have a compute unit each anyway take its whole register file (variant 6)
     if (tm == 4 && mode != EPI_ANY && ((p.M + 127) / 128) * nblocks <= 256) tm = 6;
-    if (mode != EPI_ANY && tm_forced >= 2 && tm_forced <= 6) tm = tm_forced;   // test / tuning aid
+    // up to 128 output channels: 128-column blocks (variant 7)
+    if (mode != EPI_ANY && p.N <= 128) tm = 7;
+    if (mode != EPI_ANY && tm_forced >= 2 && tm_forced <= 7) tm = tm_forced;   // test / tuning aid
+    if (tm == 7) nblocks = (p.N + 127) / 128;
     if (tm_used) *tm_used = tm;
 #define NQ_GB_LAUNCH(FULLV, EPIV, TMV, CONVV)                                               \
     do {                                                                                    \
         auto k = k_nested_gemm_big<H, L, FULLV, EPIV, TMV, CONVV>;                          \
-        constexpr int ROWS = 32 * (TMV == 6 ? 4 : TMV);                                     \
+        constexpr int ROWS = 32 * (TMV >= 6 ? 4 : TMV);                                     \
         const size_t lds = 2 * (size_t)ROWS * GB_ROW + (CONVV ? 8 * ROWS : 0);              \
         const int64_t mblocks = (p.M + ROWS - 1) / ROWS;                                    \
         static bool granted = false;                                                        \
@@ -640,6 +646,7 @@ void launch_nested_gemm_big(bool full, const GemmParams &p, int tm_forced, int *
         else if (tm == 3) NQ_GB_LAUNCH(FULLV, EPIV, 3, CONVV);   \
         else if (tm == 5) NQ_GB_LAUNCH(FULLV, EPIV, 5, CONVV);   \
         else if (tm == 6) NQ_GB_LAUNCH(FULLV, EPIV, 6, CONVV);   \
+        else if (tm == 7) NQ_GB_LAUNCH(FULLV, EPIV, 7, CONVV);   \
         else NQ_GB_LAUNCH(FULLV, EPIV, 4, CONVV);                \
     } while (0)
 #define NQ_GB_MODE(FULLV, CONVV)                                         \

@@ -68,8 +68,8 @@ class Case:
 # that does not apply to a shape is not forced, the library's choice runs again).  The large-GEMM kernel is
 # also run with every tile height it is built for (rows per block = 32 * TM, TM = 2..5): the library picks
 # the height from the shape, so without this a parity shape reaches one height only ("tm6": 128 rows with the
-# compute unit to itself).
-KERNEL_CHOICES = ("", "1", "2", "3", "4", "4/tm2", "4/tm3", "4/tm4", "4/tm5", "4/tm6", "5", "6", "9")
+# compute unit to itself; "tm7": 128 rows x 128 columns per block).
+KERNEL_CHOICES = ("", "1", "2", "3", "4", "4/tm2", "4/tm3", "4/tm4", "4/tm5", "4/tm6", "4/tm7", "5", "6", "9")
 
 
 def set_choice(choice):
