@@ -122,15 +122,21 @@ __global__ void __launch_bounds__(256, ((TMX <= 4 || TMX == 7) && EPI != EPI_ANY
     // ---- first touch of the packed pages ----------------------------------------------------------
     // In a network every launch meets weights that no cache holds.  The K loop asks for them four steps
     // ahead, which covers the latency of L2 but not that of memory, and the blocks of a launch move in step:
-    // each new K step would wait for memory once more.  So every wave first touches one dword in each of 64
-    // cache lines of either page, the waves that share an L2 (blocks 8 apart run on the same XCD) covering
-    // the pages between them as far as they reach; the values are not used.
+    // each new K step would wait for memory once more.  So every wave first touches one dword in each of up to
+    // 4 x 64 cache lines of either page, the waves that share an L2 (blocks 8 apart run on the same XCD) covering
+    // the pages between them as far as they reach (3 MB per XCD with 24 blocks: the 2.4 MB pages of the 512-channel
+    // 3x3 layers, which have few rows and therefore few blocks, took 36 us inside the forward and 30 us warm with a
+    // single round of 64 lines); the values are not used.
     uint32_t touch_h = 0, touch_l = 0;
     {
-        const int64_t line = ((int64_t)(blockIdx.x >> 3) * 4 + wave) * 64 + lane;
+        const int64_t waves_xcd = (int64_t)((gridDim.x + 7) >> 3) * 4;
         const int64_t dwords_h = (int64_t)p.NB * p.KB * (H * 64), dwords_l = (int64_t)p.NB * p.KB * (LP::DW * 64);
-        if (line * 32 < dwords_h) touch_h = p.ph[line * 32];
-        if (FULL != 0 && line * 32 < dwords_l) touch_l = p.pl[line * 32];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int64_t line = (r * waves_xcd + (int64_t)(blockIdx.x >> 3) * 4 + wave) * 64 + lane;
+            if (line * 32 < dwords_h) touch_h ^= p.ph[line * 32];
+            if (FULL != 0 && line * 32 < dwords_l) touch_l ^= p.pl[line * 32];
+        }
     }
 
     // ---- activations -------------------------------------------------------------------------
