@@ -444,7 +444,7 @@ nq_status run(bool full, const int8_t *d_x, const Geometry &g, const nq_weight *
     const int64_t x_bytes = (g.M / ((int64_t)g.Ho * g.Wo)) * g.H * g.W * g.Cin;
     const bool conv_gemm = !plain_gemm && g.Cin >= 16 && (g.Cin & (g.Cin - 1)) == 0 && aligned16(d_x) &&
                            x_bytes < 0x7fff0000LL && g.M < (int64_t(1) << 31) && g.H <= 8192 && g.W <= 8192 &&
-                           g.KH * g.KW * g.KW < 65536;
+                           g.KH * g.KW * g.KW < 65536 && g.KH <= 15 && g.KW <= 16;
     p.conv_big = conv_gemm;
     p.cin_shift = 0;
     while ((1 << p.cin_shift) < g.Cin) ++p.cin_shift;

@@ -165,8 +165,8 @@ __global__ void __launch_bounds__(256, ((TMX <= 4 || TMX == 7) && EPI != EPI_ANY
                                             : (int)(rows_here * p.K)),
         0x00020000);
     int a_goff[4];                                       // GEMM: offset of the lane's piece in rows 0..3
-    // CONV: per row of the block, the byte offset of filter tap (0,0) and the packed (ih0, iw0) of the
-    // pixel, worked out once, one row per thread, and handed to the lanes that request the row through a
+    // CONV: per row of the block, the byte offset of filter tap (0,0) and the set of taps that fall into the
+    // image for the pixel, worked out once, one row per thread, and handed to the lanes that request the row through a
     // small LDS table behind the panels
     int2 *rowtab = reinterpret_cast<int2 *>(panel + 2 * GB_PANEL);
     // with 96 or 128 rows per block (two blocks share the unit's registers) there is no room for them
@@ -180,9 +180,14 @@ __global__ void __launch_bounds__(256, ((TMX <= 4 || TMX == 7) && EPI != EPI_ANY
             const int b = mm / HoWo, rem = mm - b * HoWo;
             const int oh = rem / p.Wo, ow = rem - oh * p.Wo;
             const int ih0 = oh * p.stride - p.pad, iw0 = ow * p.stride - p.pad;
-            // rows past M get a row index no tap can bring into the image
+            // which taps fall into the image for this pixel: bit kh (filter rows) and bit 16 + kw (filter
+            // columns); rows past M get no bit at all
+            const int h_lo = max(0, -ih0), h_hi = min(p.KH - 1, p.H - 1 - ih0);
+            const int w_lo = max(0, -iw0), w_hi = min(p.KW - 1, p.W - 1 - iw0);
+            const uint32_t hbits = h_hi >= h_lo ? (2u << h_hi) - (1u << h_lo) : 0u;
+            const uint32_t wbits = w_hi >= w_lo ? (2u << w_hi) - (1u << w_lo) : 0u;
             rowtab[tid] = make_int2(((b * p.H + ih0) * p.W + iw0) * p.Cin,
-                                    (m < p.M ? ih0 : -16384) * 65536 + (iw0 & 0xffff));
+                                    m < p.M ? (int)(hbits | (wbits << 16)) : 0);
         }
         __syncthreads();
         // a lane requests the same APT rows in every iteration: their entries move to registers once (read
@@ -199,16 +204,18 @@ __global__ void __launch_bounds__(256, ((TMX <= 4 || TMX == 7) && EPI != EPI_ANY
     }
     // CONV: where the lane's four pieces of iteration `it` come from: the k index of a piece -> filter tap
     // and channel (Cin is a power of two).  Worked out once per iteration, used by all its requests.
+    // (24-bit multiplications: full rate on the vector ALU, where a 32-bit one takes four issue slots; a filter has
+    // at most 15 x 16 taps and the image at most 8192 columns)
     int tap_off[4], tap_hw[4];
     auto set_taps = [&](int it) {
 #pragma unroll
         for (int par = 0; par < 4; ++par) {
             const int kk = it * (GB_KI * 64) + 16 * piece[par];
             const int tap = kk >> p.cin_shift, ci = kk & (p.Cin - 1);
-            const int kh = (tap * p.kw_magic) >> 16, kw = tap - kh * p.KW;
-            tap_off[par] = (kh * p.W + kw) * p.Cin + ci;
-            // a piece past the end of K gets a tap row that no pixel brings into the image
-            tap_hw[par] = kk < p.K ? (kh << 16) | kw : -16384 * 65536;
+            const int kh = __mul24(tap, p.kw_magic) >> 16, kw = tap - __mul24(kh, p.KW);
+            tap_off[par] = ((__mul24(kh, p.W) + kw) << p.cin_shift) + ci;
+            // the tap's bits in a pixel's table entry; a piece past the end of K gets bit 15, which no pixel has
+            tap_hw[par] = kk < p.K ? (int)((1u << kh) | (0x10000u << kw)) : 0x8000;
         }
     };
     // requests the loads k0 <= k < k1 of iteration `it` (all of them: k0 = 0, k1 = APT); CONV: rows[k - kbase] is
@@ -222,9 +229,7 @@ __global__ void __launch_bounds__(256, ((TMX <= 4 || TMX == 7) && EPI != EPI_ANY
             for (int k = 0; k < APT; ++k) {
                 if (k < k0 || k >= k1) continue;
                 const int2 row = rows[k - kbase];
-                const int ih = (row.y >> 16) + (tap_hw[k & 3] >> 16);
-                const int iw = (int)(int16_t)(row.y & 0xffff) + (tap_hw[k & 3] & 0xffff);
-                const bool in = (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+                const bool in = (row.y & tap_hw[k & 3]) == tap_hw[k & 3];
                 const int off = in ? row.x + tap_off[k & 3] : OOR;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(xrsrc, (lds_ptr)(dst + (wave * APT + k) * 1024), 16, off, 0, 0,
                                                          0);
@@ -272,10 +277,9 @@ __global__ void __launch_bounds__(256, ((TMX <= 4 || TMX == 7) && EPI != EPI_ANY
     constexpr int CH = (H + 3) / 4, CL = (LP::DW + 3) / 4;          // requests per tile and page
     constexpr int NBL = TN * (CH + CL);
     auto load_b = [&](uint32_t (&Pd)[TN][H], uint32_t (&Qd)[TN][LP::ARR], int kb, int j0, int j1) {
-        // (the range check covers the lane offset only, so that is where "out of range" goes; the scalar offset
-        // always names a real tile)
-        const bool real = !SOLO || kb < p.KB;                // (two blocks per unit hide the useless last refills)
-        const int voff_h = real ? wslot * (H * 4) : OOR, voff_l = real ? wslot * (LP::DW * 4) : OOR;
+        // (the last PD refills ask for K steps that do not exist and read the last real tile again: it is in the
+        // cache, and turning them into out-of-range requests costs four instructions per refill all loop long)
+        const int voff_h = wslot * (H * 4), voff_l = wslot * (LP::DW * 4);
 #pragma unroll
         for (int t = 0; t < TN; ++t) {
             const int tk = trel[t] + min(kb, p.KB - 1);
