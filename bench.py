@@ -42,8 +42,8 @@ RIDGE = MFMA_INT8_PEAK_TOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # op per byte above 
 # instantiation they were taken on and by a digest of the kernel's sources at that time: a different kernel or
 # digest reports no traffic.
 TRAFFIC = {   # profiles/gemm_big_conv3x3_b128_counters.txt: FETCH_SIZE x 1.999 KiB, WRITE_SIZE x 1.000 KiB, means per dispatch
-    "k_nested_gemm_big<6,2,full,int8 out,TM=6,filter>": dict(sources="c97b48f286c4aba2", fetch_bytes=13905790, write_bytes=6422528),
-    "k_nested_gemm_big<6,2,part,int8 out,TM=6,filter>": dict(sources="c97b48f286c4aba2", fetch_bytes=12696666, write_bytes=6422528),
+    "k_nested_gemm_big<6,2,full,int8 out,TM=6,filter>": dict(sources="b88b875a50121b2e", fetch_bytes=14220322, write_bytes=6422528),
+    "k_nested_gemm_big<6,2,part,int8 out,TM=6,filter>": dict(sources="b88b875a50121b2e", fetch_bytes=13006169, write_bytes=6422528),
 }
 KERNEL_SOURCES = ("nq_gemm_big.h", "nq_epilogue.h", "nq_codec.h", "nq_gemm_kernel.h")   # what k_nested_gemm_big is made of
 FAMILY = {1: "k_nested_gemm", 2: "k_nested_conv_window", 3: "k_nested_conv_rowstream", 4: "k_nested_gemm_big",
