@@ -89,6 +89,9 @@ def test_epilogue_options(nq):
     # implicit GEMM on the large-GEMM kernel: several row tiles, ragged rows, K not a multiple of 256 or 64
     (2, 14, 14, 256, 256, 3, 3, 1, 1), (3, 15, 13, 32, 96, 3, 3, 2, 1), (1, 9, 9, 16, 130, 5, 5, 1, 2),
     (2, 12, 12, 128, 272, 1, 1, 2, 0),
+    # its pixel table holds one bit per filter row and column: the largest filter it takes (15 x 16), one row too
+    # many (goes to another kernel), a 1 x 7 filter whose padding puts whole output rows outside the image
+    (1, 10, 12, 16, 72, 15, 16, 1, 7), (1, 20, 9, 16, 40, 16, 3, 1, 1), (2, 8, 30, 32, 96, 1, 7, 2, 3),
     # strided 1x1 on the register-stationary kernel (fetches only the pixels it needs): odd sizes, stride 3,
     # several units per image, every K-step count of that kernel
     (2, 13, 11, 64, 64, 1, 1, 2, 0), (1, 57, 57, 256, 96, 1, 1, 2, 0), (2, 9, 10, 512, 40, 1, 1, 3, 0),
