@@ -190,7 +190,7 @@ def main():
                     "concurrently with the part-bit forward (default: on the compute stream)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (the path needs no exchange between GPUs; "
+        sys.exit("bench.py: the library runs on one GPU only (the path needs no exchange between GPUs; "
                  "--gpus must be 1)")
 
     import numpy as np

@@ -230,7 +230,7 @@ def lib():
 
 
 def cpu():
-    """The CPU oracle (plain C loops, -O2, no intrinsics, no BLAS) on the host of the GPU machine: one thread and all
+    """The CPU oracle (plain C loops, -O2, no intrinsics, no BLAS) on the host's cores: one thread and all
     threads OpenMP gives it, integer accumulators only (the part the GPU's TOPS are quoted on)."""
     import ctypes
     import platform
